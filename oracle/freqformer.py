@@ -1,0 +1,429 @@
+"""Plain fp64 numpy oracle of FreqFormer's per-head frequency-domain attention.
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the benchmark's
+CPU-baseline leg.  It shares no code with the HIP library and never calls it.
+
+FreqFormer is an approximation of dense attention (paper section 5), so this file
+follows the method step by step, in the paper's order and notation:
+
+  section 3.2   separable orthonormal DCT-II  F = F_t (x) F_h (x) F_w on Q, K, V
+  section 3.3   partition of the coefficient grid into low / mid / high bands,
+                compression of the low band
+  section 3.4   dense attention on the compressed low band, block-sparse
+                attention on the mid band, sliding-window attention on the high band
+  section 3.5   router: pooled band statistics + timestep embedding -> pi -> heads
+  section 3.6   summary tokens and cross-band residual exchange
+  section 3.7   sum of the bands in the spectral domain, inverse transform
+
+The printed equations of section 3.4 did not survive in the available text of the
+paper; the readings taken for them (and for everything else the paper leaves
+open) are listed in the design notes of this repository and repeated in the
+docstrings below.  Readings that the paper itself cannot confirm are marked
+"parity unpinned (reading)": they are pinned by mathematical invariants only
+(see tests/test_oracle_*.py), not by a value the paper prints.
+
+Pins per function (tests that run without a GPU):
+  dct_matrix / spectral_forward / spectral_inverse : orthonormality, Parseval,
+      round trip <= 1e-10, scipy.fft.dctn(type=2, norm="ortho"), closed forms.
+  band_partition : disjoint cover, closed-form counts, brute-force triple loop,
+      energy split sum_l ||P_l F x||^2 = ||x||^2.
+  low_band_attention : c = 1 equals dense softmax attention; one compressed token
+      returns the mean of V exactly.
+  mid_block_mask / mid_band_attention : all-ones mask equals dense attention,
+      per-row brute force, closed-form nnz for diagonal-only masks.
+  high_band_attention : window >= N equals dense attention, window 0 returns V,
+      per-row brute force, closed-form pair count.
+  summary_tokens / cross_band_exchange : m = 0 no-op, convex-hull bound,
+      permutation invariance.
+  head_forward / forward : head_alloc = 0 returns V, linearity in V for m = 0,
+      head permutation equivariance, band-limited difference for one-hot masks.
+  interaction_count : closed form of section 4.2 (pairs = Nlow_bar^2 + ... ).
+  route_mlp : parity unpinned (reading) apart from softmax / apportionment invariants;
+      router_param_count / router_flops reproduce the paper's 33,283 and 66,304.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+import math
+
+import numpy as np
+
+LOW, MID, HIGH = 0, 1, 2
+BAND_BITS = (1, 2, 4)  # bit l of a head's mask switches band l on
+
+
+@dataclass(frozen=True)
+class BandConfig:
+    """Parameters of the band operators (paper sections 3.3, 3.4, 3.6).
+
+    Band edges are rationals so that membership is decided in integers:
+    low  <=> k_axis * low_den < low_num * n_axis on all three axes,
+    low or mid <=> the same with (mid_num, mid_den), high = the rest.
+    """
+    low_num: int = 1
+    low_den: int = 4
+    mid_num: int = 1
+    mid_den: int = 2
+    low_compress: int = 4      # c: consecutive low-band tokens averaged into one (section 3.3: 4x)
+    mid_block: int = 64        # B: block edge of the mid-band pattern S
+    mid_diag: int = 1          # block-local part: |I - J| <= diag
+    mid_stride: int = 8        # strided part: (I - J) mod stride == 0
+    mid_block0: int = 1        # every query block also sees key block 0
+    high_window: int = 256     # half width w_h: keys i - w_h .. i + w_h
+    n_summary: int = 16        # m summary tokens per band (0 switches the exchange off)
+    softmax_scale: float = 0.0  # 0 -> 1/sqrt(d_k)
+
+
+# --------------------------------------------------------------------------- section 3.2
+def dct_matrix(n: int) -> np.ndarray:
+    """Orthonormal DCT-II matrix F_n (section 3.2: "fixed orthonormal DCT-II").
+
+    F[k, j] = s_k * sqrt(2/n) * cos(pi * (2 j + 1) * k / (2 n)),  s_0 = 1/sqrt(2), s_k = 1 otherwise.
+    Rows are frequencies, columns are positions; F F^T = I.
+    """
+    k = np.arange(n, dtype=np.float64)[:, None]
+    j = np.arange(n, dtype=np.float64)[None, :]
+    F = math.sqrt(2.0 / n) * np.cos(math.pi * (2.0 * j + 1.0) * k / (2.0 * n))
+    F[0, :] *= 1.0 / math.sqrt(2.0)
+    return F
+
+
+def spectral_forward(x: np.ndarray) -> np.ndarray:
+    """x~ = F(x) with F = F_t (x) F_h (x) F_w (section 3.2); x is [T, H, W, d_k], channels untouched."""
+    T, H, W, _ = x.shape
+    x = np.asarray(x, dtype=np.float64)
+    y = np.einsum("at,thwc->ahwc", dct_matrix(T), x)
+    y = np.einsum("bh,ahwc->abwc", dct_matrix(H), y)
+    y = np.einsum("gw,abwc->abgc", dct_matrix(W), y)
+    return y
+
+
+def spectral_inverse(c: np.ndarray) -> np.ndarray:
+    """F^{-1} = F^T per axis (section 3.7; orthonormality, section 5)."""
+    T, H, W, _ = c.shape
+    c = np.asarray(c, dtype=np.float64)
+    y = np.einsum("at,ahwc->thwc", dct_matrix(T), c)
+    y = np.einsum("bh,tbwc->thwc", dct_matrix(H), y)
+    y = np.einsum("gw,thgc->thwc", dct_matrix(W), y)
+    return y
+
+
+# --------------------------------------------------------------------------- section 3.3
+def band_partition(T: int, H: int, W: int, cfg: BandConfig) -> list[np.ndarray]:
+    """Index lists of Omega_low, Omega_mid, Omega_high (section 3.3), each ascending in the
+    flattened index (k_t * H + k_h) * W + k_w ("flattened spectral-token order", section 3.4).
+
+    Reading (the paper gives only band fractions): r = max(k_t/T, k_h/H, k_w/W),
+    low r < low edge, mid low edge <= r < mid edge, high r >= mid edge, decided with
+    integer compares k * den < num * n.
+    """
+    kt = np.arange(T, dtype=np.int64)[:, None, None]
+    kh = np.arange(H, dtype=np.int64)[None, :, None]
+    kw = np.arange(W, dtype=np.int64)[None, None, :]
+
+    def inside(num: int, den: int) -> np.ndarray:
+        return (kt * den < num * T) & (kh * den < num * H) & (kw * den < num * W)
+
+    low = inside(cfg.low_num, cfg.low_den)
+    lowmid = inside(cfg.mid_num, cfg.mid_den)
+    mid = lowmid & ~low
+    high = ~lowmid
+    flat = np.arange(T * H * W, dtype=np.int64).reshape(T, H, W)
+    return [flat[low], flat[mid], flat[high]]  # boolean indexing keeps row-major (ascending) order
+
+
+# --------------------------------------------------------------------------- section 3.4
+def _softmax_rows(s: np.ndarray) -> np.ndarray:
+    """Row softmax; entries equal to -inf get weight 0."""
+    mx = np.max(s, axis=-1, keepdims=True)
+    e = np.exp(s - mx)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def dense_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float) -> np.ndarray:
+    """softmax(scale * Q K^T) V, every query sees every key (textbook scaled dot-product attention)."""
+    return _softmax_rows(scale * (Q @ K.T)) @ V
+
+
+def compress_tokens(X: np.ndarray, c: int) -> np.ndarray:
+    """D_Q = D_K = D_V (section 3.3): mean of c consecutive band tokens; the last group
+    averages over the members it really has.  Reading: the paper names the compressors but
+    not their form (parity unpinned (reading))."""
+    n = X.shape[0]
+    nbar = -(-n // c)
+    out = np.empty((nbar, X.shape[1]), dtype=np.float64)
+    for j in range(nbar):
+        out[j] = X[j * c:min((j + 1) * c, n)].mean(axis=0)
+    return out
+
+
+def low_band_attention(Q, K, V, c: int, scale: float) -> np.ndarray:
+    """Low band (section 3.4.1): dense global attention among the compressed tokens, then every
+    band position takes the output of its group (Y_i = Ybar_{floor(i/c)})."""
+    n = Q.shape[0]
+    Ybar = dense_attention(compress_tokens(Q, c), compress_tokens(K, c), compress_tokens(V, c), scale)
+    return Ybar[np.arange(n) // c]
+
+
+def mid_block_mask(nb: int, diag: int, stride: int, block0: int) -> np.ndarray:
+    """Block pattern S of the mid band (section 3.4.2: "block-local plus strided"):
+    M[I, J] = |I - J| <= diag  or  (I - J) mod stride == 0  or  (block0 and J == 0)."""
+    I = np.arange(nb, dtype=np.int64)[:, None]
+    J = np.arange(nb, dtype=np.int64)[None, :]
+    m = (np.abs(I - J) <= diag) | ((I - J) % stride == 0)
+    if block0:
+        m = m | (J == 0)
+    return m
+
+
+def mid_block_csr(nb: int, diag: int, stride: int, block0: int):
+    """The same pattern as (row_ptr[nb+1], col_idx[nnz]) with ascending columns in a row."""
+    m = mid_block_mask(nb, diag, stride, block0)
+    row_ptr = np.zeros(nb + 1, dtype=np.int32)
+    cols = []
+    for I in range(nb):
+        js = np.nonzero(m[I])[0]
+        cols.append(js)
+        row_ptr[I + 1] = row_ptr[I] + len(js)
+    col_idx = np.concatenate(cols).astype(np.int32) if cols else np.zeros(0, np.int32)
+    return row_ptr, col_idx
+
+
+def mid_band_attention(Q, K, V, cfg: BandConfig, scale: float) -> np.ndarray:
+    """Mid band (section 3.4.2): query i sees key j iff M[floor(i/B), floor(j/B)]; softmax over
+    exactly those keys.  Non-causal; the last block may be partial."""
+    n = Q.shape[0]
+    B = cfg.mid_block
+    nb = -(-n // B)
+    mask = mid_block_mask(nb, cfg.mid_diag, cfg.mid_stride, cfg.mid_block0)
+    Y = np.empty_like(np.asarray(V, dtype=np.float64))
+    key_block = np.arange(n) // B
+    for I in range(nb):
+        rows = slice(I * B, min((I + 1) * B, n))
+        keys = np.nonzero(mask[I][key_block])[0]
+        Y[rows] = dense_attention(Q[rows], K[keys], V[keys], scale)
+    return Y
+
+
+def high_band_attention(Q, K, V, w: int, scale: float, chunk: int = 256) -> np.ndarray:
+    """High band (section 3.4.3): query i sees keys max(0, i - w) .. min(n - 1, i + w) in band order.
+    Queries are taken `chunk` at a time only to bound memory; every row is an independent softmax
+    over its own key set."""
+    n = Q.shape[0]
+    Y = np.empty_like(np.asarray(V, dtype=np.float64))
+    for i0 in range(0, n, chunk):
+        i1 = min(i0 + chunk, n)
+        j0, j1 = max(0, i0 - w), min(n, i1 + w)
+        i = np.arange(i0, i1)[:, None]
+        j = np.arange(j0, j1)[None, :]
+        s = scale * (Q[i0:i1] @ K[j0:j1].T)
+        s = np.where(np.abs(i - j) <= w, s, -np.inf)
+        Y[i0:i1] = _softmax_rows(s) @ V[j0:j1]
+    return Y
+
+
+# --------------------------------------------------------------------------- section 3.6
+def summary_tokens(Y: np.ndarray, m: int) -> np.ndarray:
+    """S = Pool(Y) (section 3.6 with U = I): m_eff = min(m, n) means over contiguous near-equal
+    chunks [floor(u n / m_eff), floor((u + 1) n / m_eff)) of the band order.
+    Reading: chunking rule and U = I are not fixed by the paper (parity unpinned (reading))."""
+    n = Y.shape[0]
+    m_eff = min(m, n)
+    S = np.empty((m_eff, Y.shape[1]), dtype=np.float64)
+    for u in range(m_eff):
+        S[u] = Y[(u * n) // m_eff:((u + 1) * n) // m_eff].mean(axis=0)
+    return S
+
+
+def cross_band_exchange(Y: np.ndarray, C: np.ndarray, scale: float) -> np.ndarray:
+    """Delta Y = Attn_summary(Y, C) (section 3.6): queries are the band's own outputs, keys and
+    values are both the other bands' summary tokens C."""
+    return dense_attention(Y, C, C, scale)
+
+
+# --------------------------------------------------------------------------- whole head
+def resolve_scale(cfg: BandConfig, d_k: int) -> float:
+    return cfg.softmax_scale if cfg.softmax_scale > 0 else 1.0 / math.sqrt(d_k)
+
+
+def head_forward(q, k, v, cfg: BandConfig, mask: int, return_parts: bool = False):
+    """One (batch, head): q, k, v are [T, H, W, d_k] in token space; returns [T, H, W, d_k].
+
+    Steps: transform (3.2) -> gather bands (3.3) -> band operators on the bands whose bit is set
+    in `mask`, pass-through of V~ on the others (reading of "allocating heads to bands") ->
+    summaries of all three bands from the pre-exchange outputs, exchange on active bands (3.6)
+    -> scatter (disjoint supports, so the sum of 3.7 is a scatter) -> inverse transform (3.7).
+    """
+    T, H, W, d = q.shape
+    N = T * H * W
+    scale = resolve_scale(cfg, d)
+    qs = spectral_forward(q).reshape(N, d)
+    ks = spectral_forward(k).reshape(N, d)
+    vs = spectral_forward(v).reshape(N, d)
+    bands = band_partition(T, H, W, cfg)
+
+    Y = []
+    for l, idx in enumerate(bands):
+        Ql, Kl, Vl = qs[idx], ks[idx], vs[idx]
+        if not (mask & BAND_BITS[l]) or len(idx) == 0:
+            Y.append(Vl.copy())
+        elif l == LOW:
+            Y.append(low_band_attention(Ql, Kl, Vl, cfg.low_compress, scale))
+        elif l == MID:
+            Y.append(mid_band_attention(Ql, Kl, Vl, cfg, scale))
+        else:
+            Y.append(high_band_attention(Ql, Kl, Vl, cfg.high_window, scale))
+
+    Yhat = [y.copy() for y in Y]
+    if cfg.n_summary > 0:
+        S = [summary_tokens(y, cfg.n_summary) if len(y) else np.zeros((0, d)) for y in Y]
+        for l in range(3):
+            if (mask & BAND_BITS[l]) and len(Y[l]):
+                C = np.concatenate([S[o] for o in range(3) if o != l], axis=0)
+                if len(C):
+                    Yhat[l] = Y[l] + cross_band_exchange(Y[l], C, scale)
+
+    spec = np.empty((N, d), dtype=np.float64)
+    for idx, y in zip(bands, Yhat):
+        spec[idx] = y
+    out = spectral_inverse(spec.reshape(T, H, W, d))
+    if return_parts:
+        return out, {"qs": qs, "ks": ks, "vs": vs, "bands": bands, "Y": Y, "Yhat": Yhat}
+    return out
+
+
+def forward(q, k, v, grid, cfg: BandConfig, head_alloc) -> np.ndarray:
+    """q, k, v: [batch, heads, N, d_k] with N = (t * H + h) * W + w; head_alloc[h] is the band
+    bit mask of head h.  Every (batch, head) is independent (section 3.1)."""
+    T, H, W = grid
+    Bsz, nh, N, d = q.shape
+    assert N == T * H * W and len(head_alloc) == nh
+    out = np.empty((Bsz, nh, N, d), dtype=np.float64)
+    for b in range(Bsz):
+        for h in range(nh):
+            f = lambda a: np.asarray(a[b, h], dtype=np.float64).reshape(T, H, W, d)
+            out[b, h] = head_forward(f(q), f(k), f(v), cfg, int(head_alloc[h])).reshape(N, d)
+    return out
+
+
+def dense_reference(q, k, v, scale: float | None = None) -> np.ndarray:
+    """Plain dense attention over all N tokens of one head (the comparison of section 4: N^2 pairs)."""
+    q = np.asarray(q, dtype=np.float64)
+    if scale is None:
+        scale = 1.0 / math.sqrt(q.shape[-1])
+    return dense_attention(q, np.asarray(k, dtype=np.float64), np.asarray(v, dtype=np.float64), scale)
+
+
+# --------------------------------------------------------------------------- section 4.2
+def interaction_count(T, H, W, cfg: BandConfig, mask: int = 7) -> int:
+    """Query-key pairs evaluated by the band operators of one head, counted pair by pair
+    (section 4.2: I = Nlow_bar^2 + N_mid k_mid + N_high w, with the exact degrees of this pattern)."""
+    n_low, n_mid, n_high = (len(ix) for ix in band_partition(T, H, W, cfg))
+    total = 0
+    if mask & 1:
+        nbar = -(-n_low // cfg.low_compress)
+        total += nbar * nbar
+    if mask & 2:
+        B = cfg.mid_block
+        nb = -(-n_mid // B)
+        m = mid_block_mask(nb, cfg.mid_diag, cfg.mid_stride, cfg.mid_block0)
+        size = np.minimum(B, n_mid - np.arange(nb) * B)
+        total += int((m * size[:, None] * size[None, :]).sum())
+    if mask & 4:
+        w = cfg.high_window
+        for i in range(n_high):
+            total += min(i + w, n_high - 1) - max(i - w, 0) + 1
+    return total
+
+
+# --------------------------------------------------------------------------- section 3.5
+ROUTER_DR = 64      # pooled statistics per band (d_r)
+ROUTER_DT = 64      # timestep embedding width (d_t); 3 d_r + d_t = 256 as in section 3.5
+ROUTER_KAPPA = 1.5  # strength of the timestep prior added to the logits (reading)
+ROUTER_EPS = 1e-6
+
+
+def router_param_count(d_in: int = 256, hidden: int = 128, n_out: int = 3) -> int:
+    """Section 3.5: d_in * hidden + hidden + hidden * n_out + n_out."""
+    return d_in * hidden + hidden + hidden * n_out + n_out
+
+
+def router_flops(d_in: int = 256, hidden: int = 128, n_out: int = 3) -> int:
+    """Section 3.5: 2 (d_in * hidden) + 2 (hidden * n_out)."""
+    return 2 * d_in * hidden + 2 * hidden * n_out
+
+
+def band_statistics(q, k, v, grid, cfg: BandConfig) -> np.ndarray:
+    """g in R^{3 d_r} (section 3.5, "pooled statistics from the three spectral bands").
+    Reading: for band l and channel group r (d_k / d_r adjacent channels), the mean over batch,
+    heads, the band's coefficients and the three tensors Q~, K~, V~ of the squared coefficient,
+    then log(eps + .), centred by the mean of the 3 d_r values so that only the relative spectral shape
+    reaches the router (a common gain on Q, K, V changes nothing).  parity unpinned (reading)."""
+    T, H, W = grid
+    Bsz, nh, N, d = q.shape
+    assert d % ROUTER_DR == 0
+    bands = band_partition(T, H, W, cfg)
+    acc = np.zeros((3, d), dtype=np.float64)
+    for x in (q, k, v):
+        for b in range(Bsz):
+            for h in range(nh):
+                xs = spectral_forward(np.asarray(x[b, h], dtype=np.float64).reshape(T, H, W, d)).reshape(N, d)
+                for l, idx in enumerate(bands):
+                    acc[l] += (xs[idx] ** 2).sum(axis=0)
+    g = np.empty((3, ROUTER_DR), dtype=np.float64)
+    for l, idx in enumerate(bands):
+        per_channel = acc[l] / max(1, 3 * Bsz * nh * len(idx))
+        g[l] = per_channel.reshape(ROUTER_DR, d // ROUTER_DR).mean(axis=1)
+    logs = np.log(ROUTER_EPS + g).reshape(-1)
+    return logs - logs.mean()
+
+
+def timestep_embedding(t: float) -> np.ndarray:
+    """e(t) in R^{d_t}: sin then cos of 1000 t * 10000^(-2 i / d_t), i = 0 .. d_t/2 - 1 (sinusoidal reading)."""
+    i = np.arange(ROUTER_DT // 2, dtype=np.float64)
+    ang = 1000.0 * t * np.power(10000.0, -2.0 * i / ROUTER_DT)
+    return np.concatenate([np.sin(ang), np.cos(ang)])
+
+
+def router_probabilities(g, t: float, w1, b1, w2, b2) -> np.ndarray:
+    """pi = softmax(R([g; e(t)])) (section 3.5) for a two-layer ReLU MLP with given weights
+    (w1 [256, hidden], w2 [hidden, 3]), plus the prior kappa (2 t - 1) (+1, 0, -1) on the logits so that
+    early timesteps (t near 1) favour the low band and late ones the high band (section 7.6)."""
+    x = np.concatenate([np.asarray(g, dtype=np.float64), timestep_embedding(t)])
+    hdn = np.maximum(x @ np.asarray(w1, dtype=np.float64) + np.asarray(b1, dtype=np.float64), 0.0)
+    z = hdn @ np.asarray(w2, dtype=np.float64) + np.asarray(b2, dtype=np.float64)
+    z = z + ROUTER_KAPPA * (2.0 * t - 1.0) * np.array([1.0, 0.0, -1.0])
+    z = z - z.max()
+    e = np.exp(z)
+    return e / e.sum()
+
+
+def apportion_heads(pi, n_heads: int) -> np.ndarray:
+    """pi -> integer heads per band.  With n_heads >= 3 every band first gets one head (the spirit of
+    the load-balancing term of section 3.5), the rest is shared by largest remainder of pi * rest,
+    ties to the lower band.  parity unpinned (reading)."""
+    pi = np.asarray(pi, dtype=np.float64)
+    base = 1 if n_heads >= 3 else 0
+    rest = n_heads - 3 * base
+    quota = pi * rest
+    counts = np.floor(quota).astype(np.int64)
+    rem = quota - counts
+    for _ in range(rest - int(counts.sum())):
+        l = int(np.argmax(rem))  # argmax returns the first (lowest band) among equals
+        counts[l] += 1
+        rem[l] = -1.0
+    return counts + base
+
+
+def route_fixed(n_heads: int, n_low: int, n_mid: int, n_high: int) -> np.ndarray:
+    """Fixed allocation: heads are handed out contiguously, low first, then mid, then high."""
+    assert n_low + n_mid + n_high == n_heads
+    return np.array([1] * n_low + [2] * n_mid + [4] * n_high, dtype=np.int32)
+
+
+def route_mlp(q, k, v, grid, cfg: BandConfig, t: float, w1, b1, w2, b2):
+    """Router of section 3.5 end to end: statistics -> pi -> head counts -> one-hot masks per head."""
+    g = band_statistics(q, k, v, grid, cfg)
+    pi = router_probabilities(g, t, w1, b1, w2, b2)
+    counts = apportion_heads(pi, q.shape[1])
+    return route_fixed(q.shape[1], *[int(c) for c in counts]), pi

@@ -1,0 +1,133 @@
+"""Pins for the whole per-head path (paper sections 3.2-3.7) and the pair counter (section 4.2)."""
+import numpy as np
+import pytest
+
+from oracle import freqformer as O
+
+GRID = (4, 8, 8)
+D = 8
+
+
+def rand_head(seed, grid=GRID, d=D):
+    rng = np.random.default_rng(seed)
+    return [rng.standard_normal(grid + (d,)) for _ in range(3)]
+
+
+def cfg_tiny(**kw):
+    base = dict(mid_block=16, mid_diag=1, mid_stride=4, mid_block0=1, high_window=32, n_summary=4)
+    base.update(kw)
+    return O.BandConfig(**base)
+
+
+def test_no_active_band_returns_v():
+    q, k, v = rand_head(0)
+    assert np.abs(O.head_forward(q, k, v, cfg_tiny(), 0) - v).max() < 1e-10
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 3, 7])
+def test_linear_in_v_without_exchange(mask):
+    q, k, v1 = rand_head(1)
+    v2 = rand_head(2)[2]
+    cfg = cfg_tiny(n_summary=0)
+    f = lambda v: O.head_forward(q, k, v, cfg, mask)
+    assert np.abs(f(v1 + 2.5 * v2) - (f(v1) + 2.5 * f(v2))).max() < 1e-10
+
+
+@pytest.mark.parametrize("mask,band", [(1, 0), (2, 1), (4, 2)])
+def test_one_hot_mask_changes_only_its_band(mask, band):
+    q, k, v = rand_head(3)
+    cfg = cfg_tiny()
+    diff = O.spectral_forward(O.head_forward(q, k, v, cfg, mask) - v).reshape(-1, D)
+    bands = O.band_partition(*GRID, cfg)
+    for l, idx in enumerate(bands):
+        if l == band:
+            assert np.abs(diff[idx]).max() > 1e-3
+        else:
+            assert np.abs(diff[idx]).max() < 1e-10
+
+
+def test_full_pipeline_by_hand_from_parts():
+    """Re-assemble the output from independently computed pieces (library DCT, per-band operators, explicit exchange)."""
+    from scipy.fft import dctn, idctn
+    q, k, v = rand_head(4)
+    cfg = cfg_tiny()
+    mask = 7
+    scale = 1 / np.sqrt(D)
+    N = int(np.prod(GRID))
+    spec = lambda x: dctn(x, type=2, norm="ortho", axes=(0, 1, 2)).reshape(N, D)
+    qs, ks, vs = spec(q), spec(k), spec(v)
+    bands = O.band_partition(*GRID, cfg)
+    Y = [O.low_band_attention(qs[bands[0]], ks[bands[0]], vs[bands[0]], 4, scale),
+         O.mid_band_attention(qs[bands[1]], ks[bands[1]], vs[bands[1]], cfg, scale),
+         O.high_band_attention(qs[bands[2]], ks[bands[2]], vs[bands[2]], 32, scale)]
+    S = [O.summary_tokens(y, 4) for y in Y]
+    full = np.zeros((N, D))
+    for l in range(3):
+        C = np.concatenate([S[o] for o in range(3) if o != l])
+        full[bands[l]] = Y[l] + O.dense_attention(Y[l], C, C, scale)
+    want = idctn(full.reshape(GRID + (D,)), type=2, norm="ortho", axes=(0, 1, 2))
+    got, parts = O.head_forward(q, k, v, cfg, mask, return_parts=True)
+    assert np.abs(got - want).max() < 1e-10
+    # summaries come from pre-exchange outputs of all bands, also of inactive ones (pass-through V~)
+    got2, parts2 = O.head_forward(q, k, v, cfg, 4, return_parts=True)
+    assert np.abs(parts2["Y"][0] - vs[bands[0]]).max() < 1e-10 and np.abs(parts2["Yhat"][1] - vs[bands[1]]).max() < 1e-10
+    C = np.concatenate([O.summary_tokens(vs[bands[0]], 4), O.summary_tokens(vs[bands[1]], 4)])
+    assert np.abs(parts2["Yhat"][2] - (Y[2] + O.dense_attention(Y[2], C, C, scale))).max() < 1e-10
+
+
+def test_exchange_off_equals_m0_and_scale_override():
+    q, k, v = rand_head(5)
+    a = O.head_forward(q, k, v, cfg_tiny(n_summary=0), 7)
+    b = O.head_forward(q, k, v, cfg_tiny(n_summary=4), 7)
+    assert np.abs(a - b).max() > 1e-4
+    c = O.head_forward(q, k, v, cfg_tiny(softmax_scale=1 / np.sqrt(D)), 7)
+    assert np.abs(b - c).max() < 1e-12
+
+
+def test_heads_and_batches_are_independent():
+    rng = np.random.default_rng(6)
+    N = int(np.prod(GRID))
+    q, k, v = (rng.standard_normal((2, 3, N, D)) for _ in range(3))
+    cfg = cfg_tiny()
+    alloc = np.array([1, 2, 4])
+    out = O.forward(q, k, v, GRID, cfg, alloc)
+    perm = [2, 0, 1]
+    outp = O.forward(q[:, perm], k[:, perm], v[:, perm], GRID, cfg, alloc[perm])
+    assert np.abs(outp - out[:, perm]).max() < 1e-12
+    assert np.abs(O.forward(q[::-1], k[::-1], v[::-1], GRID, cfg, alloc) - out[::-1]).max() < 1e-12
+    one = O.head_forward(*(x[1, 2].reshape(GRID + (D,)) for x in (q, k, v)), cfg, 4).reshape(N, D)
+    assert np.abs(one - out[1, 2]).max() < 1e-12
+
+
+def test_degenerate_parameters_collapse_to_dense_attention_per_band():
+    """Section 5: with c = 1, the full pattern and w >= N_high every band runs exact dense attention on its band."""
+    q, k, v = rand_head(7)
+    cfg = cfg_tiny(low_compress=1, mid_stride=1, high_window=10 ** 6, n_summary=0)
+    out, parts = O.head_forward(q, k, v, cfg, 7, return_parts=True)
+    scale = 1 / np.sqrt(D)
+    for l, idx in enumerate(parts["bands"]):
+        want = O.dense_attention(parts["qs"][idx], parts["ks"][idx], parts["vs"][idx], scale)
+        assert np.abs(parts["Y"][l] - want).max() < 1e-12
+
+
+@pytest.mark.parametrize("grid,kw", [((4, 8, 8), dict(mid_block=16, mid_diag=1, mid_stride=4, high_window=32)),
+                                     ((16, 32, 32), dict(mid_block=64, mid_diag=1, mid_stride=8, high_window=256))])
+def test_interaction_count_closed_form(grid, kw):
+    cfg = O.BandConfig(**kw)
+    n_low, n_mid, n_high = (len(b) for b in O.band_partition(*grid, cfg))
+    nbar = -(-n_low // 4)
+    B = cfg.mid_block
+    nb = -(-n_mid // B)
+    rp, ci = O.mid_block_csr(nb, cfg.mid_diag, cfg.mid_stride, 1)
+    size = lambda J: min(B, n_mid - J * B)
+    mid = sum(size(I) * size(int(J)) for I in range(nb) for J in ci[rp[I]:rp[I + 1]])
+    w = cfg.high_window
+    # sum_i (min(i+w, n-1) - max(i-w, 0) + 1) = n (2w+1) - w (w+1) when n > 2 w, else n^2 if w >= n - 1
+    high = n_high * (2 * w + 1) - w * (w + 1) if n_high > 2 * w else None
+    total = O.interaction_count(*grid, cfg, 7)
+    if high is not None:
+        assert total == nbar * nbar + mid + high
+    assert O.interaction_count(*grid, cfg, 1) == nbar * nbar
+    assert O.interaction_count(*grid, cfg, 2) == mid
+    if grid == (16, 32, 32):   # 16K configuration: 64^2 low pairs, 177 full blocks, window average 508.4
+        assert nbar == 64 and mid == 177 * 64 * 64 and abs((total - 4096 - mid) / n_high - 508.4) < 0.05
