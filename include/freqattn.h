@@ -1,0 +1,160 @@
+/*
+ * freqattn -- FreqFormer's per-head frequency-domain heterogeneous attention on one AMD Instinct MI355X (gfx950).
+ *
+ * The library computes, for every (batch, head) independently (paper section 3.1):
+ *   section 3.2  X~ = F(X) for X in {Q, K, V}, F = F_t (x) F_h (x) F_w, orthonormal DCT-II per token-grid axis
+ *   section 3.3  split of the coefficient grid into low / mid / high bands, compression of the low band
+ *   section 3.4  dense attention on the compressed low band, block-sparse attention on the mid band,
+ *                sliding-window attention on the high band (in band order = ascending flat coefficient index)
+ *   section 3.6  m summary tokens per band, every active band attends to the other bands' summaries (residual)
+ *   section 3.7  scatter of the bands back to the grid (disjoint supports) and inverse transform
+ * and, as a stand-in for the router of section 3.5, a fixed or small-MLP head allocator.
+ *
+ * All entry points are plain C.  Pointers are marked HOST or DEVICE.  Nothing here allocates on behalf of the
+ * caller except freqattn_create (tables and scratch, owned by the context, released by freqattn_destroy).
+ * Errors are returned as codes; freqattn_last_error gives the text of the last failure on a context.
+ * A context must be used from one host thread at a time and with one stream at a time.
+ */
+#ifndef FREQATTN_H
+#define FREQATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct freqattn_ctx freqattn_ctx; /* opaque, library-owned */
+
+typedef enum {
+  FREQATTN_OK = 0,
+  FREQATTN_EINVAL = 1,       /* bad argument; nothing was launched */
+  FREQATTN_ENOMEM = 2,       /* host or device allocation failed in freqattn_create */
+  FREQATTN_EHIP = 3,         /* a HIP runtime call failed */
+  FREQATTN_EUNSUPPORTED = 4  /* valid request that this build has no kernel for */
+} freqattn_status;
+
+typedef enum { FREQATTN_F32 = 0, FREQATTN_BF16 = 1 } freqattn_dtype;
+
+/* Problem shape (section 3.1): q, k, v, out are [batch, heads, N, head_dim] with N = T*H*W and token index
+ * n = (t*H + h)*W + w; head_dim is contiguous.  dtype is the type of q, k, v and out. */
+typedef struct {
+  int32_t batch, heads, head_dim, T, H, W;
+  int32_t dtype; /* freqattn_dtype */
+} freqattn_shape;
+
+/* Band operators (sections 3.3, 3.4, 3.6).  Band edges are rationals so that membership is decided with integer
+ * compares: a coefficient (kt, kh, kw) is in the low band iff k*low_den < low_num*n on all three axes, in low or mid
+ * iff the same holds with (mid_num, mid_den), and in the high band otherwise. */
+typedef struct {
+  int32_t low_num, low_den, mid_num, mid_den;
+  int32_t low_compress; /* c >= 1: c consecutive low-band tokens are averaged into one (section 3.3 uses 4)          */
+  int32_t mid_block;    /* B: block edge of the mid-band pattern                                                   */
+  int32_t mid_diag;     /* query block I sees key block J if |I-J| <= mid_diag ...                                  */
+  int32_t mid_stride;   /* ... or (I-J) mod mid_stride == 0 ...                                                     */
+  int32_t mid_block0;   /* ... or (mid_block0 != 0 and J == 0)                                                      */
+  int32_t high_window;  /* w_h: query i sees keys i-w_h .. i+w_h of the high band (clipped, two-sided)              */
+  int32_t n_summary;    /* m summary tokens per band; 0 switches the cross-band exchange off                        */
+  float softmax_scale;  /* <= 0 selects 1/sqrt(head_dim)                                                            */
+} freqattn_band_cfg;
+
+/* How the three band branches are launched (paper section 6.2: one launch for all branches vs one per branch). */
+typedef enum { FREQATTN_LAUNCH_FUSED = 0, FREQATTN_LAUNCH_SEPARATE = 1 } freqattn_launch_mode;
+/* Which kernels run: AUTO picks the MFMA kernels when dtype is BF16 and the shape allows them (T, H, W multiples
+ * of 16 and at most 128, head_dim 64 or 128, mid_block a multiple of 64), otherwise the generic fp32 kernels. */
+typedef enum {
+  FREQATTN_PATH_AUTO = 0,
+  FREQATTN_PATH_GENERIC = 1,
+  FREQATTN_PATH_MFMA = 2,
+  FREQATTN_PATH_TABLES_ONLY = 3 /* host tables only: no device is touched, only the introspection calls work */
+} freqattn_path;
+
+/* Builds the per-axis DCT matrices, band index lists, block list of the mid band and summary chunk bounds (host,
+ * then uploaded) and allocates all device scratch on the current HIP device.  `path` is a freqattn_path.
+ * Returns EINVAL for non-positive dimensions, edges not satisfying 0 < low < mid <= 1, low_compress < 1,
+ * mid_block < 1, mid_stride < 1, mid_diag < 0, high_window < 0, n_summary < 0, unknown dtype or NULL pointers;
+ * EUNSUPPORTED if FREQATTN_PATH_MFMA is forced on a shape it cannot run; ENOMEM / EHIP on allocation failure. */
+freqattn_status freqattn_create(const freqattn_shape* shape /*HOST*/, const freqattn_band_cfg* cfg /*HOST*/,
+                                int32_t path, freqattn_ctx** out_ctx /*HOST*/);
+
+/* Whole hot path (sections 3.2-3.7) for all batches and heads.
+ *   q, k, v   DEVICE, contiguous [batch, heads, N, head_dim] of shape.dtype, read only
+ *   band_cfg  HOST; must equal the configuration given to freqattn_create in every field except softmax_scale
+ *   head_alloc HOST [heads]; bit 0 / 1 / 2 of entry h switch the low / mid / high operator of head h on.  A band whose
+ *             bit is clear passes V~ through unchanged on that band (it still contributes summary tokens).
+ *   out       DEVICE, same shape and type as q; must not overlap q, k, v
+ *   stream    hipStream_t (NULL = default stream)
+ * Asynchronous: work is enqueued on `stream` and the call returns.  The one exception is a call whose head_alloc
+ * differs from the previous call's on this context: it first waits for `stream` so that the work lists of earlier
+ * calls are no longer in use.  Allocates nothing.  EINVAL: NULL pointer, head_alloc entry outside 0..7, band_cfg
+ * mismatch.  EHIP: a launch failed. */
+freqattn_status freqattn_forward(freqattn_ctx* ctx, const void* q, const void* k, const void* v,
+                                 const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out, void* stream);
+
+/* Releases everything the context owns.  freqattn_destroy(NULL) is a no-op.  The caller must have synchronised. */
+void freqattn_destroy(freqattn_ctx* ctx);
+
+/* Text of the last error on this context (or of the last failed freqattn_create when ctx is NULL). Never NULL. */
+const char* freqattn_last_error(const freqattn_ctx* ctx);
+
+/* FREQATTN_LAUNCH_FUSED (default): low, mid and high work items run in one persistent launch (section 6.2).
+ * FREQATTN_LAUNCH_SEPARATE: one launch per branch (the unfused comparison of section 6.6). */
+freqattn_status freqattn_set_launch_mode(freqattn_ctx* ctx, int32_t mode);
+/* Returns the path the context resolved to (FREQATTN_PATH_GENERIC or FREQATTN_PATH_MFMA). */
+int32_t freqattn_get_path(const freqattn_ctx* ctx);
+
+/* ---- introspection of the integer tables (section 3.3 band lists, section 3.4.2 block pattern) ---------------- */
+/* n[l] = number of coefficients in band l (0 low, 1 mid, 2 high); HOST out. */
+freqattn_status freqattn_band_sizes(const freqattn_ctx* ctx, int64_t n[3]);
+/* Flat coefficient indices (kt*H + kh)*W + kw of band `band`, ascending; host_out HOST [n[band]]. */
+freqattn_status freqattn_band_index(const freqattn_ctx* ctx, int32_t band, int32_t* host_out);
+/* Block list of the mid band in CSR form, columns ascending in a row.  *nnz is always written; row_ptr (HOST
+ * [nb+1], nb = ceil(n_mid / mid_block)) and col_idx (HOST [nnz]) are filled when not NULL. */
+freqattn_status freqattn_mid_blocks(const freqattn_ctx* ctx, int32_t* row_ptr, int32_t* col_idx, int64_t* nnz);
+/* Per-axis transform matrix as used on the device, widened to double: axis 0/1/2 = T/H/W, HOST out [n*n] row-major
+ * (row = frequency). */
+freqattn_status freqattn_dct_matrix(const freqattn_ctx* ctx, int32_t axis, double* host_out);
+
+/* ---- intermediate results of the last forward, for stage-wise checks ------------------------------------------
+ * Copies one band of one (batch*heads + head) slice of a spectral buffer to HOST as float [n[band], head_dim],
+ * after synchronising `stream`.  which: 0 = Q~, 1 = K~, 2 = V~ (section 3.2/3.3, band-major),
+ * 3 = band outputs after the exchange, Y^ (section 3.6).  Rows follow freqattn_band_index.  Q~ and K~ of a band
+ * that is inactive for the slice are not defined (they are not computed when not needed). */
+freqattn_status freqattn_read_spectral(freqattn_ctx* ctx, int32_t which, int32_t slice, int32_t band, float* host_out,
+                                       void* stream);
+
+/* ---- head allocation (section 3.5 stand-in) -------------------------------------------------------------------- */
+/* Fixed allocation: the first n_low heads get mask 1, the next n_mid mask 2, the last n_high mask 4.  HOST out. */
+freqattn_status freqattn_route_fixed(int32_t heads, int32_t n_low, int32_t n_mid, int32_t n_high, int32_t* head_alloc);
+/* Router: band statistics g (per band, 64 channel groups: log(1e-6 + mean squared coefficient over batch, heads,
+ * band and Q~/K~/V~), centred by the mean of the 192 values), sinusoidal timestep embedding of width 64, two-layer ReLU
+ * MLP with the given weights (HOST float: w1 [256, hidden] row-major, b1 [hidden], w2 [hidden, 3], b2 [3]), the
+ * prior 1.5*(2t-1)*(+1, 0, -1) on the logits, softmax -> pi[3]; heads per band = 1 + largest-remainder share of
+ * (heads-3) (plain largest remainder if heads < 3), handed out contiguously low, mid, high.
+ * q, k, v DEVICE as in freqattn_forward.  Synchronous: transforms Q, K, V on `stream`, waits, then runs the MLP on
+ * the host.  head_alloc HOST [heads] and pi HOST [3] are outputs; stats_out HOST [192] may be NULL. */
+freqattn_status freqattn_route_mlp(freqattn_ctx* ctx, const void* q, const void* k, const void* v, float t,
+                                   int32_t hidden, const float* w1, const float* b1, const float* w2, const float* b2,
+                                   int32_t* head_alloc, float pi[3], float* stats_out, void* stream);
+
+/* ---- dense comparison (section 4: N^2 pairs per head) ----------------------------------------------------------
+ * Plain softmax(scale * Q K^T) V over all N tokens of every head with the library's own flash-style MFMA kernel;
+ * BF16 contexts on the MFMA path only.  Same pointer conventions as freqattn_forward.  Asynchronous. */
+freqattn_status freqattn_dense_forward(freqattn_ctx* ctx, const void* q, const void* k, const void* v, void* out,
+                                       void* stream);
+
+/* ---- per-stage timing of the forward ---------------------------------------------------------------------------
+ * When enabled, freqattn_forward records HIP events on its stream around each stage.  freqattn_stage_times waits
+ * for the last forward's events and returns, for stage s < *n_stages, its name and the milliseconds between its
+ * events.  names_out HOST [max_stages] receives pointers to static strings; ms_out HOST [max_stages]. */
+freqattn_status freqattn_set_stage_timing(freqattn_ctx* ctx, int32_t enabled);
+freqattn_status freqattn_stage_times(freqattn_ctx* ctx, int32_t max_stages, const char** names_out, float* ms_out,
+                                     int32_t* n_stages);
+
+/* Device bytes owned by the context (tables + scratch). */
+int64_t freqattn_workspace_bytes(const freqattn_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FREQATTN_H */

@@ -1,0 +1,1 @@
+"""freqattn: FreqFormer's frequency-domain heterogeneous attention for one MI355X (HIP library + ctypes binding)."""

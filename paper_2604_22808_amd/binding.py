@@ -1,0 +1,210 @@
+"""ctypes binding of libfreqattn.so: the same entry points as include/freqattn.h, argument marshalling only.
+
+Device tensors are torch tensors (torch is used for device memory and streams, nothing else); every computation
+happens inside the library.  Loading fails loudly when the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfreqattn.so")
+
+OK, EINVAL, ENOMEM, EHIP, EUNSUPPORTED = 0, 1, 2, 3, 4
+F32, BF16 = 0, 1
+LAUNCH_FUSED, LAUNCH_SEPARATE = 0, 1
+PATH_AUTO, PATH_GENERIC, PATH_MFMA, PATH_TABLES_ONLY = 0, 1, 2, 3
+
+
+class Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("batch", "heads", "head_dim", "T", "H", "W", "dtype")]
+
+
+class BandCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("low_num", "low_den", "mid_num", "mid_den", "low_compress", "mid_block",
+                                         "mid_diag", "mid_stride", "mid_block0", "high_window", "n_summary")] + \
+               [("softmax_scale", C.c_float)]
+
+
+EXPORTS = {
+    "freqattn_create": (C.c_int, [C.POINTER(Shape), C.POINTER(BandCfg), C.c_int32, C.POINTER(C.c_void_p)]),
+    "freqattn_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(BandCfg),
+                                   C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]),
+    "freqattn_destroy": (None, [C.c_void_p]),
+    "freqattn_last_error": (C.c_char_p, [C.c_void_p]),
+    "freqattn_set_launch_mode": (C.c_int, [C.c_void_p, C.c_int32]),
+    "freqattn_get_path": (C.c_int32, [C.c_void_p]),
+    "freqattn_band_sizes": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
+    "freqattn_band_index": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
+    "freqattn_mid_blocks": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
+    "freqattn_dct_matrix": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
+    "freqattn_read_spectral": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.c_void_p]),
+    "freqattn_route_fixed": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
+    "freqattn_route_mlp": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_int32,
+                                     C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                     C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_float),
+                                     C.POINTER(C.c_float), C.c_void_p]),
+    "freqattn_dense_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "freqattn_set_stage_timing": (C.c_int, [C.c_void_p, C.c_int32]),
+    "freqattn_stage_times": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
+                                       C.POINTER(C.c_int32)]),
+    "freqattn_workspace_bytes": (C.c_int64, [C.c_void_p]),
+}
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(or python paper_2604_22808_amd/build.py) first")
+        # torch ships its own HIP runtime (same soname): load it first so that the library binds to the runtime
+        # that owns torch's device memory and streams instead of bringing a second one into the process.
+        import torch  # noqa: F401
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(l, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = l
+    return _lib
+
+
+class FreqAttnError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"freqattn status {status}: {msg}")
+        self.status = status
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_cfg(**kw) -> BandCfg:
+    base = dict(low_num=1, low_den=4, mid_num=1, mid_den=2, low_compress=4, mid_block=64, mid_diag=1, mid_stride=8,
+                mid_block0=1, high_window=256, n_summary=16, softmax_scale=0.0)
+    base.update(kw)
+    return BandCfg(**base)
+
+
+class Context:
+    """Owns one freqattn_ctx.  Methods carry the names of the C entry points without the prefix."""
+
+    def __init__(self, batch, heads, head_dim, grid, dtype, cfg: BandCfg, path=PATH_AUTO):
+        self.shape = Shape(batch, heads, head_dim, grid[0], grid[1], grid[2], dtype)
+        self.cfg = cfg
+        self._h = C.c_void_p()
+        st = lib().freqattn_create(C.byref(self.shape), C.byref(cfg), path, C.byref(self._h))
+        if st != OK:
+            raise FreqAttnError(st, lib().freqattn_last_error(None).decode())
+
+    def _check(self, st):
+        if st != OK:
+            raise FreqAttnError(st, lib().freqattn_last_error(self._h).decode())
+
+    def destroy(self):
+        if self._h:
+            lib().freqattn_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # ---- hot path
+    def forward(self, q, k, v, head_alloc, out, cfg=None):
+        ha = np.ascontiguousarray(head_alloc, dtype=np.int32)
+        cfg = cfg or self.cfg
+        self._check(lib().freqattn_forward(self._h, _ptr(q), _ptr(k), _ptr(v), C.byref(cfg),
+                                           ha.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(out), _stream()))
+        return out
+
+    def dense_forward(self, q, k, v, out):
+        self._check(lib().freqattn_dense_forward(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _stream()))
+        return out
+
+    def route_mlp(self, q, k, v, t, w1, b1, w2, b2):
+        hidden = int(w1.shape[1])
+        f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+        w1, b1, w2, b2 = f(w1), f(b1), f(w2), f(b2)
+        alloc = np.zeros(self.shape.heads, np.int32)
+        pi = np.zeros(3, np.float32)
+        stats = np.zeros(192, np.float32)
+        P = lambda a: a.ctypes.data_as(C.POINTER(C.c_float))
+        self._check(lib().freqattn_route_mlp(self._h, _ptr(q), _ptr(k), _ptr(v), float(t), hidden, P(w1), P(b1), P(w2),
+                                             P(b2), alloc.ctypes.data_as(C.POINTER(C.c_int32)), P(pi), P(stats),
+                                             _stream()))
+        return alloc, pi, stats
+
+    # ---- options and introspection
+    def set_launch_mode(self, mode):
+        self._check(lib().freqattn_set_launch_mode(self._h, mode))
+
+    def get_path(self):
+        return lib().freqattn_get_path(self._h)
+
+    def workspace_bytes(self):
+        return lib().freqattn_workspace_bytes(self._h)
+
+    def band_sizes(self):
+        n = (C.c_int64 * 3)()
+        self._check(lib().freqattn_band_sizes(self._h, n))
+        return [int(x) for x in n]
+
+    def band_index(self, band):
+        out = np.zeros(self.band_sizes()[band], np.int32)
+        self._check(lib().freqattn_band_index(self._h, band, out.ctypes.data_as(C.POINTER(C.c_int32))))
+        return out
+
+    def mid_blocks(self):
+        nnz = C.c_int64()
+        self._check(lib().freqattn_mid_blocks(self._h, None, None, C.byref(nnz)))
+        nb = -(-self.band_sizes()[1] // self.cfg.mid_block)
+        rp = np.zeros(nb + 1, np.int32)
+        ci = np.zeros(nnz.value, np.int32)
+        self._check(lib().freqattn_mid_blocks(self._h, rp.ctypes.data_as(C.POINTER(C.c_int32)),
+                                              ci.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nnz)))
+        return rp, ci
+
+    def dct_matrix(self, axis):
+        n = (self.shape.T, self.shape.H, self.shape.W)[axis]
+        out = np.zeros((n, n), np.float64)
+        self._check(lib().freqattn_dct_matrix(self._h, axis, out.ctypes.data_as(C.POINTER(C.c_double))))
+        return out
+
+    def read_spectral(self, which, slice_, band):
+        out = np.zeros((self.band_sizes()[band], self.shape.head_dim), np.float32)
+        self._check(lib().freqattn_read_spectral(self._h, which, slice_, band, out.ctypes.data_as(C.POINTER(C.c_float)),
+                                                 _stream()))
+        return out
+
+    def set_stage_timing(self, enabled):
+        self._check(lib().freqattn_set_stage_timing(self._h, int(enabled)))
+
+    def stage_times(self):
+        names = (C.c_char_p * 16)()
+        ms = (C.c_float * 16)()
+        n = C.c_int32()
+        self._check(lib().freqattn_stage_times(self._h, 16, names, ms, C.byref(n)))
+        return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
+
+
+def route_fixed(heads, n_low, n_mid, n_high):
+    out = np.zeros(heads, np.int32)
+    st = lib().freqattn_route_fixed(heads, n_low, n_mid, n_high, out.ctypes.data_as(C.POINTER(C.c_int32)))
+    if st != OK:
+        raise FreqAttnError(st, "freqattn_route_fixed: bad arguments")
+    return out

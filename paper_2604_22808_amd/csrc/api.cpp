@@ -1,0 +1,724 @@
+// C-ABI entry points of libfreqattn and the host-side orchestration of the hot path.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "ctx.h"
+
+using namespace fa;
+
+struct freqattn_ctx : public fa::Ctx {};
+
+static thread_local std::string g_create_error;
+
+static freqattn_status fail(freqattn_ctx* c, freqattn_status s, const std::string& msg) {
+  if (c) c->err = msg; else g_create_error = msg;
+  return s;
+}
+
+#define HIP_TRY(ctx, expr)                                                                         \
+  do {                                                                                             \
+    hipError_t e__ = (expr);                                                                       \
+    if (e__ != hipSuccess)                                                                         \
+      return fail(ctx, FREQATTN_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__));        \
+  } while (0)
+
+static size_t esize(const Ctx& c) { return c.path == FREQATTN_PATH_MFMA ? sizeof(half_t) : sizeof(float); }
+static int io_kind(const Ctx& c) { return c.shape.dtype == FREQATTN_BF16 ? 1 : 0; }
+
+static bool mfma_shape_ok(const freqattn_shape& s, const freqattn_band_cfg& g) {
+  auto ax = [](int n) { return n % 16 == 0 && n >= 16 && n <= 128; };
+  return s.dtype == FREQATTN_BF16 && ax(s.T) && ax(s.H) && ax(s.W) && (s.head_dim == 64 || s.head_dim == 128) &&
+         g.mid_block % 64 == 0;
+}
+
+template <typename T>
+static hipError_t dev_alloc(Ctx& c, T** p, size_t count) {
+  *p = nullptr;
+  if (count == 0) count = 1;
+  hipError_t e = hipMalloc((void**)p, count * sizeof(T));
+  if (e == hipSuccess) c.dev_bytes += (int64_t)(count * sizeof(T));
+  return e;
+}
+static hipError_t dev_alloc_bytes(Ctx& c, void** p, size_t bytes) {
+  *p = nullptr;
+  if (bytes == 0) bytes = 16;
+  hipError_t e = hipMalloc(p, bytes);
+  if (e == hipSuccess) c.dev_bytes += (int64_t)bytes;
+  return e;
+}
+
+static void free_all(Ctx* c) {
+  auto F = [](void* p) { if (p) (void)hipFree(p); };
+  F(c->d_perm); F(c->d_row_ptr); F(c->d_col_idx);
+  for (int a = 0; a < 3; ++a) { F(c->d_F32[a]); F(c->d_Ft32[a]); F(c->d_F16[a]); F(c->d_Ft16[a]); }
+  F(c->specQ); F(c->specK); F(c->specV); F(c->Y); F(c->tmp0); F(c->tmp1);
+  F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_lists);
+  if (c->h_lists) (void)hipHostFree(c->h_lists);
+  if (c->h_stats) (void)hipHostFree(c->h_stats);
+  if (c->ev_created)
+    for (int i = 0; i <= Ctx::MAX_STAGES; ++i) (void)hipEventDestroy(c->ev[i]);
+}
+
+static int items_per_slice_max(const Ctx& c, int rows) {
+  auto cd = [](int64_t a, int64_t b) { return (int)((a + b - 1) / b); };
+  return cd(c.nbar, rows) + cd(c.band_n[MID], rows) + cd(c.band_n[HIGH], rows) + 3;
+}
+
+extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const freqattn_band_cfg* cfg, int32_t path,
+                                           freqattn_ctx** out_ctx) {
+  if (!shape || !cfg || !out_ctx) return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: NULL argument");
+  *out_ctx = nullptr;
+  const freqattn_shape& s = *shape;
+  const freqattn_band_cfg& g = *cfg;
+  if (s.batch < 1 || s.heads < 1 || s.head_dim < 1 || s.T < 1 || s.H < 1 || s.W < 1)
+    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: dimensions must be positive");
+  if (s.head_dim > 256) return fail(nullptr, FREQATTN_EUNSUPPORTED, "freqattn_create: head_dim > 256");
+  if (s.dtype != FREQATTN_F32 && s.dtype != FREQATTN_BF16)
+    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: unknown dtype");
+  if ((int64_t)s.T * s.H * s.W > (int64_t)1 << 30 ||
+      (int64_t)s.batch * s.heads * s.T * s.H * s.W > (int64_t)2000000000)
+    return fail(nullptr, FREQATTN_EUNSUPPORTED, "freqattn_create: token count too large for 32-bit row indices");
+  if (g.low_num < 1 || g.low_den < 1 || g.mid_num < 1 || g.mid_den < 1 ||
+      !((int64_t)g.low_num * g.mid_den < (int64_t)g.mid_num * g.low_den) || g.mid_num > g.mid_den)
+    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: band edges must satisfy 0 < low < mid <= 1");
+  if (g.low_compress < 1 || g.mid_block < 1 || g.mid_stride < 1 || g.mid_diag < 0 || g.high_window < 0 ||
+      g.n_summary < 0)
+    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: band operator parameter out of range");
+  if (path != FREQATTN_PATH_AUTO && path != FREQATTN_PATH_GENERIC && path != FREQATTN_PATH_MFMA &&
+      path != FREQATTN_PATH_TABLES_ONLY)
+    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: unknown path");
+  const bool mfma_ok = mfma_shape_ok(s, g);
+  if (path == FREQATTN_PATH_MFMA && !mfma_ok)
+    return fail(nullptr, FREQATTN_EUNSUPPORTED,
+                "freqattn_create: MFMA path needs bf16, T/H/W multiples of 16 in [16,128], head_dim 64 or 128, "
+                "mid_block multiple of 64");
+
+  freqattn_ctx* c = new (std::nothrow) freqattn_ctx();
+  if (!c) return fail(nullptr, FREQATTN_ENOMEM, "freqattn_create: host allocation failed");
+  c->shape = s;
+  c->cfg = g;
+  c->path = (path == FREQATTN_PATH_AUTO) ? (mfma_ok ? FREQATTN_PATH_MFMA : FREQATTN_PATH_GENERIC) : path;
+  c->launch_mode = FREQATTN_LAUNCH_FUSED;
+  c->slices = s.batch * s.heads;
+  c->N = (int64_t)s.T * s.H * s.W;
+  c->d = s.head_dim;
+
+  try {
+    build_bands(*c);
+    build_mid_blocks(*c);
+    const int dims[3] = {s.T, s.H, s.W};
+    for (int a = 0; a < 3; ++a) build_dct_matrix(dims[a], c->h_F[a]);
+  } catch (const std::bad_alloc&) {
+    delete c;
+    return fail(nullptr, FREQATTN_ENOMEM, "freqattn_create: host allocation failed");
+  }
+  c->nbar = (c->band_n[LOW] + g.low_compress - 1) / g.low_compress;
+  for (int l = 0; l < 3; ++l) c->m_eff[l] = (int)std::min<int64_t>(g.n_summary, c->band_n[l]);
+  for (int l = 0; l < 3; ++l) {
+    c->n_c[l] = 0;
+    for (int o = 0; o < 3; ++o)
+      if (o != l) c->n_c[l] += c->m_eff[o];
+  }
+  const bool mf = c->path == FREQATTN_PATH_MFMA;
+  if (mf && 2 * g.n_summary > 1024) {
+    delete c;
+    return fail(nullptr, FREQATTN_EUNSUPPORTED, "freqattn_create: n_summary > 512 on the MFMA path");
+  }
+  c->attn_rows = (g.mid_block % 128 == 0) ? 128 : 64;
+  if (c->path == FREQATTN_PATH_TABLES_ONLY) {
+    *out_ctx = c;
+    return FREQATTN_OK;
+  }
+
+  hipDeviceProp_t prop;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    delete c;
+    return fail(nullptr, FREQATTN_EHIP, "freqattn_create: no usable HIP device");
+  }
+  c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+  // ---- device tables
+  hipError_t e = hipSuccess;
+  auto up = [&](void* dst, const void* src, size_t bytes) {
+    if (e == hipSuccess && bytes) e = hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
+  };
+  auto A = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  A(dev_alloc(*c, &c->d_perm, (size_t)c->N));
+  up(c->d_perm, c->h_perm.data(), (size_t)c->N * 4);
+  A(dev_alloc(*c, &c->d_row_ptr, c->h_row_ptr.size()));
+  up(c->d_row_ptr, c->h_row_ptr.data(), c->h_row_ptr.size() * 4);
+  A(dev_alloc(*c, &c->d_col_idx, c->h_col_idx.size()));
+  up(c->d_col_idx, c->h_col_idx.data(), c->h_col_idx.size() * 4);
+  {
+    const int dims[3] = {s.T, s.H, s.W};
+    for (int a = 0; a < 3 && e == hipSuccess; ++a) {
+      const int n = dims[a];
+      std::vector<double>& F = c->h_F[a];
+      if (mf) {
+        std::vector<half_t> f16((size_t)n * n), ft16((size_t)n * n);
+        for (int k = 0; k < n; ++k)
+          for (int j = 0; j < n; ++j) {
+            const half_t hv = (half_t)F[(size_t)k * n + j];
+            f16[(size_t)k * n + j] = hv;
+            ft16[(size_t)j * n + k] = hv;
+            F[(size_t)k * n + j] = (double)hv;  // what the device really multiplies with
+          }
+        A(dev_alloc(*c, &c->d_F16[a], (size_t)n * n));
+        up(c->d_F16[a], f16.data(), (size_t)n * n * sizeof(half_t));
+        A(dev_alloc(*c, &c->d_Ft16[a], (size_t)n * n));
+        up(c->d_Ft16[a], ft16.data(), (size_t)n * n * sizeof(half_t));
+      } else {
+        std::vector<float> f32((size_t)n * n), ft32((size_t)n * n);
+        for (int k = 0; k < n; ++k)
+          for (int j = 0; j < n; ++j) {
+            const float fv = (float)F[(size_t)k * n + j];
+            f32[(size_t)k * n + j] = fv;
+            ft32[(size_t)j * n + k] = fv;
+            F[(size_t)k * n + j] = (double)fv;
+          }
+        A(dev_alloc(*c, &c->d_F32[a], (size_t)n * n));
+        up(c->d_F32[a], f32.data(), (size_t)n * n * 4);
+        A(dev_alloc(*c, &c->d_Ft32[a], (size_t)n * n));
+        up(c->d_Ft32[a], ft32.data(), (size_t)n * n * 4);
+      }
+    }
+  }
+  // ---- scratch
+  const size_t es = esize(*c);
+  const size_t slab = (size_t)c->slices * (size_t)c->N * (size_t)c->d * es;
+  const size_t lowb = (size_t)c->slices * (size_t)std::max<int64_t>(c->nbar, 1) * (size_t)c->d * es;
+  A(dev_alloc_bytes(*c, &c->specQ, slab));
+  A(dev_alloc_bytes(*c, &c->specK, slab));
+  A(dev_alloc_bytes(*c, &c->specV, slab));
+  A(dev_alloc_bytes(*c, &c->Y, slab));
+  A(dev_alloc_bytes(*c, &c->tmp0, slab));
+  A(dev_alloc_bytes(*c, &c->tmp1, slab));
+  A(dev_alloc_bytes(*c, &c->lowQ, lowb));
+  A(dev_alloc_bytes(*c, &c->lowK, lowb));
+  A(dev_alloc_bytes(*c, &c->lowV, lowb));
+  A(dev_alloc_bytes(*c, &c->lowY, lowb));
+  A(dev_alloc_bytes(*c, &c->Cbuf, (size_t)c->slices * 3 * 2 * (size_t)std::max(g.n_summary, 1) * c->d * es));
+  const size_t stats_floats = (size_t)3 * c->d * (1 + 64);
+  A(dev_alloc(*c, &c->d_stats, stats_floats));
+  if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_stats, 3 * c->d * sizeof(float), hipHostMallocDefault);
+
+  // ---- per-forward lists
+  {
+    const int rows = c->attn_rows;
+    const size_t per_slice = (size_t)items_per_slice_max(*c, rows);
+    const size_t xchg_per_slice = (size_t)((c->N + rows - 1) / rows + 3);
+    size_t ints = 0;
+    c->off_masks = ints; ints += (size_t)c->slices;
+    for (int l = 0; l < 3; ++l) { c->off_list[l] = ints; ints += (size_t)c->slices; }
+    ints = (ints + 3) & ~(size_t)3;
+    c->off_items = ints; ints += 4 * per_slice * c->slices;
+    for (int l = 0; l < 3; ++l) { c->off_items_kind[l] = ints; ints += 4 * per_slice * c->slices; }
+    c->off_items_xchg = ints; ints += 4 * xchg_per_slice * c->slices;
+    c->off_items_dense = ints; ints += 4 * xchg_per_slice * c->slices;
+    c->lists_bytes = ints * 4;
+    A(dev_alloc_bytes(*c, (void**)&c->d_lists, c->lists_bytes));
+    if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_lists, c->lists_bytes, hipHostMallocDefault);
+  }
+  if (e == hipSuccess) {
+    for (int i = 0; i <= Ctx::MAX_STAGES && e == hipSuccess; ++i) e = hipEventCreate(&c->ev[i]);
+    c->ev_created = (e == hipSuccess);
+  }
+  if (e != hipSuccess) {
+    const bool oom = (e == hipErrorOutOfMemory);
+    std::string msg = std::string("freqattn_create: ") + hipGetErrorString(e);
+    free_all(c);
+    delete c;
+    (void)hipGetLastError();
+    return fail(nullptr, oom ? FREQATTN_ENOMEM : FREQATTN_EHIP, msg);
+  }
+  *out_ctx = c;
+  return FREQATTN_OK;
+}
+
+extern "C" void freqattn_destroy(freqattn_ctx* c) {
+  if (!c) return;
+  free_all(c);
+  delete c;
+}
+
+extern "C" const char* freqattn_last_error(const freqattn_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+extern "C" freqattn_status freqattn_set_launch_mode(freqattn_ctx* c, int32_t mode) {
+  if (!c) return FREQATTN_EINVAL;
+  if (mode != FREQATTN_LAUNCH_FUSED && mode != FREQATTN_LAUNCH_SEPARATE)
+    return fail(c, FREQATTN_EINVAL, "freqattn_set_launch_mode: unknown mode");
+  c->launch_mode = mode;
+  return FREQATTN_OK;
+}
+extern "C" int32_t freqattn_get_path(const freqattn_ctx* c) { return c ? c->path : -1; }
+extern "C" int64_t freqattn_workspace_bytes(const freqattn_ctx* c) { return c ? c->dev_bytes : 0; }
+
+extern "C" freqattn_status freqattn_band_sizes(const freqattn_ctx* c, int64_t n[3]) {
+  if (!c || !n) return FREQATTN_EINVAL;
+  for (int l = 0; l < 3; ++l) n[l] = c->band_n[l];
+  return FREQATTN_OK;
+}
+extern "C" freqattn_status freqattn_band_index(const freqattn_ctx* c, int32_t band, int32_t* host_out) {
+  if (!c || !host_out || band < 0 || band > 2) return FREQATTN_EINVAL;
+  std::memcpy(host_out, c->h_band_index[band].data(), c->h_band_index[band].size() * sizeof(int32_t));
+  return FREQATTN_OK;
+}
+extern "C" freqattn_status freqattn_mid_blocks(const freqattn_ctx* c, int32_t* row_ptr, int32_t* col_idx, int64_t* nnz) {
+  if (!c || !nnz) return FREQATTN_EINVAL;
+  *nnz = (int64_t)c->h_col_idx.size();
+  if (row_ptr) std::memcpy(row_ptr, c->h_row_ptr.data(), c->h_row_ptr.size() * sizeof(int32_t));
+  if (col_idx) std::memcpy(col_idx, c->h_col_idx.data(), c->h_col_idx.size() * sizeof(int32_t));
+  return FREQATTN_OK;
+}
+extern "C" freqattn_status freqattn_dct_matrix(const freqattn_ctx* c, int32_t axis, double* host_out) {
+  if (!c || !host_out || axis < 0 || axis > 2) return FREQATTN_EINVAL;
+  std::memcpy(host_out, c->h_F[axis].data(), c->h_F[axis].size() * sizeof(double));
+  return FREQATTN_OK;
+}
+
+extern "C" freqattn_status freqattn_route_fixed(int32_t heads, int32_t n_low, int32_t n_mid, int32_t n_high,
+                                                int32_t* head_alloc) {
+  if (!head_alloc || heads < 1 || n_low < 0 || n_mid < 0 || n_high < 0 || n_low + n_mid + n_high != heads)
+    return FREQATTN_EINVAL;
+  int h = 0;
+  for (int i = 0; i < n_low; ++i) head_alloc[h++] = 1;
+  for (int i = 0; i < n_mid; ++i) head_alloc[h++] = 2;
+  for (int i = 0; i < n_high; ++i) head_alloc[h++] = 4;
+  return FREQATTN_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ work lists
+static bool same_cfg(const freqattn_band_cfg& a, const freqattn_band_cfg& b) {
+  return a.low_num == b.low_num && a.low_den == b.low_den && a.mid_num == b.mid_num && a.mid_den == b.mid_den &&
+         a.low_compress == b.low_compress && a.mid_block == b.mid_block && a.mid_diag == b.mid_diag &&
+         a.mid_stride == b.mid_stride && (a.mid_block0 != 0) == (b.mid_block0 != 0) &&
+         a.high_window == b.high_window && a.n_summary == b.n_summary;
+}
+
+static void build_lists(Ctx& c, const int32_t* head_alloc) {
+  int32_t* L = c.h_lists;
+  const int heads = c.shape.heads;
+  for (int l = 0; l < 3; ++l) c.n_list[l] = 0;
+  for (int s = 0; s < c.slices; ++s) {
+    const int mask = head_alloc[s % heads];
+    L[c.off_masks + s] = mask;
+    for (int l = 0; l < 3; ++l)
+      if (((mask >> l) & 1) && c.band_n[l] > 0) L[c.off_list[l] + c.n_list[l]++] = s;
+  }
+  const int rows = c.attn_rows;
+  const int KT = 64;  // key tile of the MFMA attention kernel
+  std::vector<AttnItem> kind[3], xchg;
+  auto cd = [](int64_t a, int64_t b) { return (a + b - 1) / b; };
+  for (int s = 0; s < c.slices; ++s) {
+    const int mask = L[c.off_masks + s];
+    if ((mask & 1) && c.band_n[LOW] > 0)
+      for (int64_t q0 = 0; q0 < c.nbar; q0 += rows)
+        kind[0].push_back({0 | (LOW << 8), s, (int32_t)q0, (int32_t)cd(c.nbar, KT)});
+    if ((mask & 2) && c.band_n[MID] > 0)
+      for (int64_t q0 = 0; q0 < c.band_n[MID]; q0 += rows) {
+        const int64_t I = q0 / c.cfg.mid_block;
+        const int nblk = c.h_row_ptr[I + 1] - c.h_row_ptr[I];
+        kind[1].push_back({1 | (MID << 8), s, (int32_t)q0, (int32_t)(nblk * cd(c.cfg.mid_block, KT))});
+      }
+    if ((mask & 4) && c.band_n[HIGH] > 0)
+      for (int64_t q0 = 0; q0 < c.band_n[HIGH]; q0 += rows) {
+        const int64_t k0 = std::max<int64_t>(0, q0 - c.cfg.high_window);
+        const int64_t k1 = std::min<int64_t>(c.band_n[HIGH] - 1, q0 + rows - 1 + (int64_t)c.cfg.high_window);
+        kind[2].push_back({2 | (HIGH << 8), s, (int32_t)q0, (int32_t)(k1 / KT - k0 / KT + 1)});
+      }
+    if (c.cfg.n_summary > 0)
+      for (int l = 0; l < 3; ++l)
+        if (((mask >> l) & 1) && c.band_n[l] > 0 && c.n_c[l] > 0)
+          for (int64_t q0 = 0; q0 < c.band_n[l]; q0 += rows)
+            xchg.push_back({3 | (l << 8), s, (int32_t)q0, (int32_t)cd(c.n_c[l], KT)});
+  }
+  std::vector<AttnItem> fused;
+  for (int k = 0; k < 3; ++k) fused.insert(fused.end(), kind[k].begin(), kind[k].end());
+  std::stable_sort(fused.begin(), fused.end(), [](const AttnItem& a, const AttnItem& b) { return a.cost > b.cost; });
+  c.n_items_branch = (int)fused.size();
+  if (!fused.empty()) std::memcpy(L + c.off_items, fused.data(), fused.size() * sizeof(AttnItem));
+  for (int k = 0; k < 3; ++k) {
+    c.n_items_kind[k] = (int)kind[k].size();
+    if (!kind[k].empty()) std::memcpy(L + c.off_items_kind[k], kind[k].data(), kind[k].size() * sizeof(AttnItem));
+  }
+  c.n_items_xchg = (int)xchg.size();
+  if (!xchg.empty()) std::memcpy(L + c.off_items_xchg, xchg.data(), xchg.size() * sizeof(AttnItem));
+  // dense baseline items (do not depend on the allocation)
+  std::vector<AttnItem> dense;
+  for (int s = 0; s < c.slices; ++s)
+    for (int64_t q0 = 0; q0 < c.N; q0 += rows) dense.push_back({4, s, (int32_t)q0, (int32_t)cd(c.N, KT)});
+  c.n_items_dense = (int)dense.size();
+  if (!dense.empty()) std::memcpy(L + c.off_items_dense, dense.data(), dense.size() * sizeof(AttnItem));
+}
+
+static freqattn_status ensure_lists(freqattn_ctx* c, const int32_t* head_alloc, hipStream_t st) {
+  const int heads = c->shape.heads;
+  if (c->alloc_valid && std::memcmp(c->h_alloc.data(), head_alloc, heads * sizeof(int32_t)) == 0) return FREQATTN_OK;
+  HIP_TRY(c, hipStreamSynchronize(st));  // earlier forwards may still read the lists
+  build_lists(*c, head_alloc);
+  HIP_TRY(c, hipMemcpyAsync(c->d_lists, c->h_lists, c->lists_bytes, hipMemcpyHostToDevice, st));
+  c->h_alloc.assign(head_alloc, head_alloc + heads);
+  c->alloc_valid = true;
+  return FREQATTN_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ transforms
+// Forward transform of one [slices, N, d] tensor into a band-major spectral buffer (sections 3.2, 3.3).
+static hipError_t forward_transform(Ctx& c, const void* x, void* spec, hipStream_t st) {
+  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
+  hipError_t e;
+  if (c.path == FREQATTN_PATH_MFMA) {
+    DctPassArgs a{};
+    a.d = d; a.Ntok = c.N; a.slice_mod = c.slices;
+    a.in = x; a.out = c.tmp0; a.M = c.d_F16[0]; a.n = T; a.inner = (int64_t)H * W * d; a.outer = 1;
+    a.nslab = c.slices; a.in_bf16 = 1; a.out_bf16 = 0;
+    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
+    a.in = c.tmp0; a.out = c.tmp1; a.M = c.d_F16[1]; a.n = H; a.inner = (int64_t)W * d; a.outer = T;
+    a.nslab = (int64_t)c.slices * T; a.in_bf16 = 0;
+    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
+    a.in = c.tmp1; a.out = spec; a.M = c.d_F16[2]; a.n = W; a.inner = d; a.outer = (int64_t)T * H;
+    a.nslab = (int64_t)c.slices * T * H; a.perm_out = c.d_perm;
+    return launch_mfma_dct_pass(a, c.num_cu, st);
+  }
+  AxisPassArgs a{};
+  a.Ntok = c.N; a.slice_mod = c.slices;
+  a.in = x; a.out = c.tmp0; a.M = c.d_F32[0]; a.n = a.n_out = T; a.inner = (int64_t)H * W * d; a.outer = 1;
+  a.nslab = c.slices; a.in_kind = io_kind(c); a.out_kind = 0;
+  if ((e = launch_generic_axis_pass(a, st)) != hipSuccess) return e;
+  a.in = c.tmp0; a.out = c.tmp1; a.M = c.d_F32[1]; a.n = a.n_out = H; a.inner = (int64_t)W * d; a.outer = T;
+  a.nslab = (int64_t)c.slices * T; a.in_kind = 0;
+  if ((e = launch_generic_axis_pass(a, st)) != hipSuccess) return e;
+  a.in = c.tmp1; a.out = spec; a.M = c.d_F32[2]; a.n = a.n_out = W; a.inner = d; a.outer = (int64_t)T * H;
+  a.nslab = (int64_t)c.slices * T * H; a.perm_out = c.d_perm;
+  return launch_generic_axis_pass(a, st);
+}
+
+// Inverse transform (section 3.7): rows of band l of slice s are read from Y when the band is active for s, else
+// from V~; W axis first (it reads the band-major rows), then H, then T, which writes `out` in the I/O type.
+static hipError_t inverse_transform(Ctx& c, void* out, hipStream_t st) {
+  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
+  const int32_t* masks = c.d_lists + c.off_masks;
+  hipError_t e;
+  if (c.path == FREQATTN_PATH_MFMA) {
+    DctPassArgs a{};
+    a.d = d; a.Ntok = c.N; a.slice_mod = c.slices;
+    a.in = c.Y; a.in_alt = c.specV; a.masks = masks; a.band_off1 = (int32_t)c.band_off[1];
+    a.band_off2 = (int32_t)c.band_off[2]; a.perm_in = c.d_perm;
+    a.out = c.tmp0; a.M = c.d_Ft16[2]; a.n = W; a.inner = d; a.outer = (int64_t)T * H;
+    a.nslab = (int64_t)c.slices * T * H;
+    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
+    a.perm_in = nullptr; a.masks = nullptr; a.in_alt = nullptr;
+    a.in = c.tmp0; a.out = c.tmp1; a.M = c.d_Ft16[1]; a.n = H; a.inner = (int64_t)W * d; a.outer = T;
+    a.nslab = (int64_t)c.slices * T;
+    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
+    a.in = c.tmp1; a.out = out; a.M = c.d_Ft16[0]; a.n = T; a.inner = (int64_t)H * W * d; a.outer = 1;
+    a.nslab = c.slices; a.out_bf16 = 1;
+    return launch_mfma_dct_pass(a, c.num_cu, st);
+  }
+  AxisPassArgs a{};
+  a.Ntok = c.N; a.slice_mod = c.slices;
+  a.in = c.Y; a.in_alt = c.specV; a.masks = masks; a.band_off1 = (int32_t)c.band_off[1];
+  a.band_off2 = (int32_t)c.band_off[2]; a.perm_in = c.d_perm;
+  a.out = c.tmp0; a.M = c.d_Ft32[2]; a.n = a.n_out = W; a.inner = d; a.outer = (int64_t)T * H;
+  a.nslab = (int64_t)c.slices * T * H; a.in_kind = 0; a.out_kind = 0;
+  if ((e = launch_generic_axis_pass(a, st)) != hipSuccess) return e;
+  a.perm_in = nullptr; a.masks = nullptr; a.in_alt = nullptr;
+  a.in = c.tmp0; a.out = c.tmp1; a.M = c.d_Ft32[1]; a.n = a.n_out = H; a.inner = (int64_t)W * d; a.outer = T;
+  a.nslab = (int64_t)c.slices * T;
+  if ((e = launch_generic_axis_pass(a, st)) != hipSuccess) return e;
+  a.in = c.tmp1; a.out = out; a.M = c.d_Ft32[0]; a.n = a.n_out = T; a.inner = (int64_t)H * W * d; a.outer = 1;
+  a.nslab = c.slices; a.out_kind = io_kind(c);
+  return launch_generic_axis_pass(a, st);
+}
+
+static void fill_attn_params(const Ctx& c, AttnParams& p, float scale) {
+  std::memset(&p, 0, sizeof(p));
+  p.specQ = c.specQ; p.specK = c.specK; p.specV = c.specV; p.Y = c.Y;
+  p.lowQ = c.lowQ; p.lowK = c.lowK; p.lowV = c.lowV; p.lowY = c.lowY; p.C = c.Cbuf;
+  p.mid_row_ptr = c.d_row_ptr; p.mid_col_idx = c.d_col_idx;
+  for (int l = 0; l < 3; ++l) {
+    p.band_off[l] = (int32_t)c.band_off[l];
+    p.band_n[l] = (int32_t)c.band_n[l];
+    p.n_c[l] = c.n_c[l];
+  }
+  p.N = (int32_t)c.N; p.d = c.d; p.nbar = (int32_t)c.nbar; p.m2 = 2 * std::max(c.cfg.n_summary, 1);
+  p.mid_block = c.cfg.mid_block; p.high_window = c.cfg.high_window; p.scale = scale;
+}
+
+struct StageTimer {
+  Ctx& c; hipStream_t st; bool on;
+  StageTimer(Ctx& c_, hipStream_t s) : c(c_), st(s), on(c_.timing) {
+    if (on) { c.n_stages = 0; (void)hipEventRecord(c.ev[0], st); }
+  }
+  void done(const char* name) {
+    if (on && c.n_stages < Ctx::MAX_STAGES) {
+      c.stage_name[c.n_stages] = name;
+      (void)hipEventRecord(c.ev[c.n_stages + 1], st);
+      ++c.n_stages;
+    }
+  }
+};
+
+extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, const void* k, const void* v,
+                                            const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,
+                                            void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  if (!q || !k || !v || !band_cfg || !head_alloc || !out) return fail(c, FREQATTN_EINVAL, "freqattn_forward: NULL argument");
+  if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward: tables-only context");
+  if (!same_cfg(*band_cfg, c->cfg))
+    return fail(c, FREQATTN_EINVAL, "freqattn_forward: band_cfg differs from the one given to freqattn_create");
+  for (int h = 0; h < c->shape.heads; ++h)
+    if (head_alloc[h] < 0 || head_alloc[h] > 7) return fail(c, FREQATTN_EINVAL, "freqattn_forward: head_alloc entry outside 0..7");
+  if (out == q || out == k || out == v) return fail(c, FREQATTN_EINVAL, "freqattn_forward: out aliases an input");
+  hipStream_t st = (hipStream_t)stream;
+  const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
+  freqattn_status fs = ensure_lists(c, head_alloc, st);
+  if (fs != FREQATTN_OK) return fs;
+  const bool mf = c->path == FREQATTN_PATH_MFMA;
+  const int is_half = mf ? 1 : 0;
+  const int32_t* L = c->d_lists;
+  StageTimer tm(*c, st);
+
+  // sections 3.2 / 3.3: spectral transform of Q, K, V into band-major buffers
+  HIP_TRY(c, forward_transform(*c, q, c->specQ, st));
+  HIP_TRY(c, forward_transform(*c, k, c->specK, st));
+  HIP_TRY(c, forward_transform(*c, v, c->specV, st));
+  tm.done("forward_transform");
+
+  // section 3.3: compression of the low band
+  if (c->n_list[LOW] > 0) {
+    const int32_t* lst = L + c->off_list[LOW];
+    HIP_TRY(c, launch_pool_low(c->specQ, c->lowQ, lst, c->n_list[LOW], c->N, c->d, c->band_n[LOW], c->nbar, c->cfg.low_compress, is_half, st));
+    HIP_TRY(c, launch_pool_low(c->specK, c->lowK, lst, c->n_list[LOW], c->N, c->d, c->band_n[LOW], c->nbar, c->cfg.low_compress, is_half, st));
+    HIP_TRY(c, launch_pool_low(c->specV, c->lowV, lst, c->n_list[LOW], c->N, c->d, c->band_n[LOW], c->nbar, c->cfg.low_compress, is_half, st));
+  }
+  tm.done("low_compress");
+
+  // section 3.4: the three band operators
+  AttnParams ap;
+  fill_attn_params(*c, ap, scale);
+  if (mf) {
+    if (c->launch_mode == FREQATTN_LAUNCH_FUSED) {
+      HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(L + c->off_items), c->n_items_branch, c->attn_rows, c->num_cu, st));
+      tm.done("band_attention_fused");
+    } else {
+      static const char* nm[3] = {"low_attention", "mid_attention", "high_attention"};
+      for (int kd = 0; kd < 3; ++kd) {
+        HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(L + c->off_items_kind[kd]), c->n_items_kind[kd], c->attn_rows, c->num_cu, st));
+        tm.done(nm[kd]);
+      }
+    }
+  } else {
+    const int64_t Nd = c->N * c->d;
+    GenericAttnArgs g{};
+    g.d = c->d; g.scale = scale;
+    if (c->n_list[LOW] > 0) {
+      g.Q = (const float*)c->lowQ; g.K = (const float*)c->lowK; g.V = (const float*)c->lowV; g.O = (float*)c->lowY;
+      g.slice_list = L + c->off_list[LOW]; g.n_slices = c->n_list[LOW];
+      g.slice_stride = g.kv_slice_stride = c->nbar * c->d; g.nq = g.nk = (int)c->nbar; g.mode = 0;
+      HIP_TRY(c, launch_generic_attn(g, st));
+    }
+    tm.done("low_attention");
+    if (c->n_list[MID] > 0) {
+      const int64_t o = c->band_off[MID] * c->d;
+      g.Q = (const float*)c->specQ + o; g.K = (const float*)c->specK + o; g.V = (const float*)c->specV + o;
+      g.O = (float*)c->Y + o; g.slice_list = L + c->off_list[MID]; g.n_slices = c->n_list[MID];
+      g.slice_stride = g.kv_slice_stride = Nd; g.nq = g.nk = (int)c->band_n[MID]; g.mode = 1;
+      g.row_ptr = c->d_row_ptr; g.col_idx = c->d_col_idx; g.block = c->cfg.mid_block;
+      HIP_TRY(c, launch_generic_attn(g, st));
+    }
+    tm.done("mid_attention");
+    if (c->n_list[HIGH] > 0) {
+      const int64_t o = c->band_off[HIGH] * c->d;
+      g.Q = (const float*)c->specQ + o; g.K = (const float*)c->specK + o; g.V = (const float*)c->specV + o;
+      g.O = (float*)c->Y + o; g.slice_list = L + c->off_list[HIGH]; g.n_slices = c->n_list[HIGH];
+      g.slice_stride = g.kv_slice_stride = Nd; g.nq = g.nk = (int)c->band_n[HIGH]; g.mode = 2;
+      g.window = c->cfg.high_window;
+      HIP_TRY(c, launch_generic_attn(g, st));
+    }
+    tm.done("high_attention");
+  }
+  if (c->n_list[LOW] > 0)
+    HIP_TRY(c, launch_expand_low(c->lowY, c->Y, L + c->off_list[LOW], c->n_list[LOW], c->N, c->d, c->band_n[LOW], c->nbar, c->cfg.low_compress, is_half, st));
+  tm.done("low_expand");
+
+  // section 3.6: summary tokens of all bands, then the exchange on the active bands
+  if (c->cfg.n_summary > 0) {
+    HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, st));
+    tm.done("summaries");
+    if (mf) {
+      HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(L + c->off_items_xchg), c->n_items_xchg, c->attn_rows, c->num_cu, st));
+    } else {
+      for (int l = 0; l < 3; ++l) {
+        if (c->n_list[l] == 0 || c->n_c[l] == 0) continue;
+        GenericAttnArgs g{};
+        g.d = c->d; g.scale = scale; g.mode = 0; g.residual = 1;
+        g.Q = (const float*)c->Y + c->band_off[l] * c->d; g.O = (float*)c->Y + c->band_off[l] * c->d;
+        g.K = g.V = (const float*)c->Cbuf + (int64_t)l * ap.m2 * c->d;
+        g.slice_list = L + c->off_list[l]; g.n_slices = c->n_list[l];
+        g.slice_stride = c->N * c->d; g.kv_slice_stride = (int64_t)3 * ap.m2 * c->d;
+        g.nq = (int)c->band_n[l]; g.nk = c->n_c[l];
+        HIP_TRY(c, launch_generic_attn(g, st));
+      }
+    }
+    tm.done("exchange");
+  }
+
+  // section 3.7: scatter + inverse transform
+  HIP_TRY(c, inverse_transform(*c, out, st));
+  tm.done("inverse_transform");
+  return FREQATTN_OK;
+}
+
+extern "C" freqattn_status freqattn_dense_forward(freqattn_ctx* c, const void* q, const void* k, const void* v, void* out,
+                                                  void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  if (!q || !k || !v || !out) return fail(c, FREQATTN_EINVAL, "freqattn_dense_forward: NULL argument");
+  if (c->path != FREQATTN_PATH_MFMA) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_dense_forward: MFMA path only");
+  hipStream_t st = (hipStream_t)stream;
+  if (!c->alloc_valid) {
+    std::vector<int32_t> zero(c->shape.heads, 0);
+    freqattn_status fs = ensure_lists(c, zero.data(), st);
+    if (fs != FREQATTN_OK) return fs;
+  }
+  AttnParams ap;
+  const float scale = c->cfg.softmax_scale > 0.f ? c->cfg.softmax_scale : 1.0f / std::sqrt((float)c->d);
+  fill_attn_params(*c, ap, scale);
+  ap.denseQ = q; ap.denseK = k; ap.denseV = v; ap.denseO = out; ap.dense_bf16 = 1;
+  StageTimer tm(*c, st);
+  HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(c->d_lists + c->off_items_dense), c->n_items_dense, c->attn_rows, c->num_cu, st));
+  tm.done("dense_attention");
+  return FREQATTN_OK;
+}
+
+extern "C" freqattn_status freqattn_read_spectral(freqattn_ctx* c, int32_t which, int32_t slice, int32_t band,
+                                                  float* host_out, void* stream) {
+  if (!c || !host_out || which < 0 || which > 3 || slice < 0 || slice >= c->slices || band < 0 || band > 2)
+    return FREQATTN_EINVAL;
+  if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_read_spectral: tables-only context");
+  HIP_TRY(c, hipStreamSynchronize((hipStream_t)stream));
+  const void* src = which == 0 ? c->specQ : which == 1 ? c->specK : which == 2 ? c->specV : c->Y;
+  if (which == 3) {
+    if (!c->alloc_valid) return fail(c, FREQATTN_EINVAL, "freqattn_read_spectral: no forward has run");
+    if (!((c->h_alloc[slice % c->shape.heads] >> band) & 1)) src = c->specV;
+  }
+  const size_t cnt = (size_t)c->band_n[band] * c->d;
+  const size_t off = ((size_t)slice * c->N + c->band_off[band]) * c->d;
+  if (cnt == 0) return FREQATTN_OK;
+  if (c->path == FREQATTN_PATH_MFMA) {
+    std::vector<half_t> tmp(cnt);
+    HIP_TRY(c, hipMemcpy(tmp.data(), (const half_t*)src + off, cnt * sizeof(half_t), hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < cnt; ++i) host_out[i] = (float)tmp[i];
+  } else {
+    HIP_TRY(c, hipMemcpy(host_out, (const float*)src + off, cnt * sizeof(float), hipMemcpyDeviceToHost));
+  }
+  return FREQATTN_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ router
+extern "C" freqattn_status freqattn_route_mlp(freqattn_ctx* c, const void* q, const void* k, const void* v, float t,
+                                              int32_t hidden, const float* w1, const float* b1, const float* w2,
+                                              const float* b2, int32_t* head_alloc, float pi[3], float* stats_out,
+                                              void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  if (!q || !k || !v || !w1 || !b1 || !w2 || !b2 || !head_alloc || !pi || hidden < 1)
+    return fail(c, FREQATTN_EINVAL, "freqattn_route_mlp: NULL argument or hidden < 1");
+  const int d = c->d, DR = 64, DT = 64;
+  if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: tables-only context");
+  if (d % DR != 0) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: head_dim must be a multiple of 64");
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(c, forward_transform(*c, q, c->specQ, st));
+  HIP_TRY(c, forward_transform(*c, k, c->specK, st));
+  HIP_TRY(c, forward_transform(*c, v, c->specV, st));
+  HIP_TRY(c, launch_band_energy(c->specQ, c->specK, c->specV, c->d_stats, c->slices, c->N, d, c->band_off, c->band_n,
+                                c->path == FREQATTN_PATH_MFMA ? 1 : 0, st));
+  HIP_TRY(c, hipMemcpyAsync(c->h_stats, c->d_stats, 3 * d * sizeof(float), hipMemcpyDeviceToHost, st));
+  HIP_TRY(c, hipStreamSynchronize(st));
+  // g: log(eps + mean energy) per band and channel group, centred (section 3.5 "pooled statistics")
+  double x[3 * 64 + 64];
+  const int per = d / DR;
+  double mean_log = 0.0;
+  for (int l = 0; l < 3; ++l)
+    for (int r = 0; r < DR; ++r) {
+      double sum = 0.0;
+      for (int u = 0; u < per; ++u) sum += (double)c->h_stats[l * d + r * per + u];
+      const double cnt = 3.0 * c->slices * (double)std::max<int64_t>(c->band_n[l], 1);
+      const double e = sum / cnt / per;
+      x[l * DR + r] = std::log(1e-6 + e);
+      mean_log += x[l * DR + r];
+    }
+  mean_log /= 3.0 * DR;
+  for (int i = 0; i < 3 * DR; ++i) x[i] -= mean_log;
+  if (stats_out)
+    for (int i = 0; i < 3 * DR; ++i) stats_out[i] = (float)x[i];
+  // e(t): sin then cos of 1000 t 10000^(-2i/64)
+  for (int i = 0; i < DT / 2; ++i) {
+    const double ang = 1000.0 * (double)t * std::pow(10000.0, -2.0 * i / DT);
+    x[3 * DR + i] = std::sin(ang);
+    x[3 * DR + DT / 2 + i] = std::cos(ang);
+  }
+  const int DIN = 3 * DR + DT;
+  std::vector<double> hdn(hidden);
+  for (int j = 0; j < hidden; ++j) {
+    double s = b1[j];
+    for (int i = 0; i < DIN; ++i) s += x[i] * (double)w1[(size_t)i * hidden + j];
+    hdn[j] = s > 0 ? s : 0;
+  }
+  double z[3];
+  const double prior[3] = {1.0, 0.0, -1.0};
+  for (int o = 0; o < 3; ++o) {
+    double s = b2[o];
+    for (int j = 0; j < hidden; ++j) s += hdn[j] * (double)w2[(size_t)j * 3 + o];
+    z[o] = s + 1.5 * (2.0 * (double)t - 1.0) * prior[o];
+  }
+  const double zm = std::max(z[0], std::max(z[1], z[2]));
+  double p[3], ps = 0;
+  for (int o = 0; o < 3; ++o) { p[o] = std::exp(z[o] - zm); ps += p[o]; }
+  for (int o = 0; o < 3; ++o) { p[o] /= ps; pi[o] = (float)p[o]; }
+  // apportionment: one head per band when heads >= 3, the rest by largest remainder, ties to the lower band
+  const int heads = c->shape.heads;
+  const int base = heads >= 3 ? 1 : 0;
+  const int rest = heads - 3 * base;
+  int cnt[3]; double rem[3]; int given = 0;
+  for (int o = 0; o < 3; ++o) {
+    const double quota = p[o] * rest;
+    cnt[o] = (int)std::floor(quota);
+    rem[o] = quota - cnt[o];
+    given += cnt[o];
+  }
+  for (int r = given; r < rest; ++r) {
+    int best = 0;
+    for (int o = 1; o < 3; ++o)
+      if (rem[o] > rem[best]) best = o;
+    cnt[best] += 1;
+    rem[best] = -1.0;
+  }
+  return freqattn_route_fixed(heads, cnt[0] + base, cnt[1] + base, cnt[2] + base, head_alloc);
+}
+
+// ------------------------------------------------------------------------------------------------ stage timing
+extern "C" freqattn_status freqattn_set_stage_timing(freqattn_ctx* c, int32_t enabled) {
+  if (!c) return FREQATTN_EINVAL;
+  c->timing = enabled != 0;
+  c->n_stages = 0;
+  return FREQATTN_OK;
+}
+
+extern "C" freqattn_status freqattn_stage_times(freqattn_ctx* c, int32_t max_stages, const char** names_out, float* ms_out,
+                                                int32_t* n_stages) {
+  if (!c || !names_out || !ms_out || !n_stages) return FREQATTN_EINVAL;
+  *n_stages = 0;
+  if (!c->timing || c->n_stages == 0) return FREQATTN_OK;
+  HIP_TRY(c, hipEventSynchronize(c->ev[c->n_stages]));
+  const int n = std::min<int>(c->n_stages, max_stages);
+  for (int i = 0; i < n; ++i) {
+    names_out[i] = c->stage_name[i];
+    HIP_TRY(c, hipEventElapsedTime(&ms_out[i], c->ev[i], c->ev[i + 1]));
+  }
+  *n_stages = n;
+  return FREQATTN_OK;
+}

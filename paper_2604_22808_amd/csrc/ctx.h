@@ -1,0 +1,177 @@
+// Internal definitions shared by the host side and the kernel launchers of libfreqattn.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "freqattn.h"
+
+namespace fa {
+
+typedef _Float16 half_t;
+
+enum { LOW = 0, MID = 1, HIGH = 2 };
+
+// Work item of the attention kernels: a tile of query rows of one branch of one (batch*heads) slice.
+// kind: 0 low (compressed tokens), 1 mid (block list), 2 high (window), 3 exchange on band `band`, 4 dense baseline.
+struct AttnItem {
+  int32_t kind_band;  // kind | band << 8
+  int32_t slice;      // batch*heads index
+  int32_t q0;         // first query row of the tile, in band order
+  int32_t cost;       // key tiles the item visits (used for ordering only)
+};
+
+// Everything the attention kernels need besides the item list (device pointers into context-owned memory).
+struct AttnParams {
+  const void* specQ;  // [slices][N][d] band-major, band l starts at row band_off[l]
+  const void* specK;
+  const void* specV;
+  void* Y;            // [slices][N][d] band-major band outputs
+  const void* lowQ;   // [slices][nbar][d] compressed low band
+  const void* lowK;
+  const void* lowV;
+  void* lowY;
+  const void* C;      // [slices][3][2m][d] summary tokens seen by band l
+  const int32_t* mid_row_ptr;
+  const int32_t* mid_col_idx;
+  int32_t band_off[3];
+  int32_t band_n[3];
+  int32_t n_c[3];     // valid rows of C per band
+  int32_t N, d, nbar, m2;  // m2 = 2m = rows reserved per band in C
+  int32_t mid_block, high_window;
+  float scale;
+  // dense baseline
+  const void* denseQ; const void* denseK; const void* denseV; void* denseO;
+  int32_t dense_bf16;
+};
+
+struct Ctx {
+  freqattn_shape shape;
+  freqattn_band_cfg cfg;
+  int path;         // resolved freqattn_path
+  int launch_mode;
+  int slices;       // batch*heads
+  int64_t N;
+  int d;
+  int64_t band_n[3], band_off[3];
+  int64_t nbar, nb_mid;
+  int m_eff[3], n_c[3];
+  std::string err;
+
+  // host tables
+  std::vector<int32_t> h_band_index[3];
+  std::vector<int32_t> h_perm;       // flat coefficient index -> band-major row
+  std::vector<int32_t> h_row_ptr, h_col_idx;
+  std::vector<double> h_F[3];        // per-axis DCT matrices as rounded for the device, [n][n]
+  std::vector<int32_t> h_alloc;      // last head_alloc seen (size heads), empty before the first forward
+  bool alloc_valid = false;
+
+  // device tables
+  int32_t* d_perm = nullptr;
+  int32_t* d_row_ptr = nullptr;
+  int32_t* d_col_idx = nullptr;
+  float* d_F32[3] = {nullptr, nullptr, nullptr};    // F  [n][n] fp32 (generic path)
+  float* d_Ft32[3] = {nullptr, nullptr, nullptr};   // F^T
+  half_t* d_F16[3] = {nullptr, nullptr, nullptr};   // F  fp16 (MFMA path)
+  half_t* d_Ft16[3] = {nullptr, nullptr, nullptr};  // F^T fp16
+
+  // device scratch (element type float on the generic path, fp16 on the MFMA path)
+  void* specQ = nullptr; void* specK = nullptr; void* specV = nullptr; void* Y = nullptr;
+  void* tmp0 = nullptr; void* tmp1 = nullptr;     // transform ping-pong, 3*slices*N*d
+  void* lowQ = nullptr; void* lowK = nullptr; void* lowV = nullptr; void* lowY = nullptr;
+  void* Cbuf = nullptr;
+  float* d_stats = nullptr;                       // router statistics [3][d]
+  float* h_stats = nullptr;                       // pinned mirror
+
+  // per-forward lists (device + pinned host mirror)
+  int32_t* d_lists = nullptr; int32_t* h_lists = nullptr; size_t lists_bytes = 0;
+  // layout inside lists (int32 units)
+  size_t off_masks = 0;               // [slices] band mask per slice
+  size_t off_list[3] = {0, 0, 0};     // [slices] slices with band l active
+  int n_list[3] = {0, 0, 0};
+  size_t off_items = 0;               // AttnItem array (fused order: all branches), then exchange items
+  int n_items_branch = 0;             // low+mid+high items in cost order
+  int n_items_kind[3] = {0, 0, 0};    // per-branch sub-lists follow at off_items_kind
+  size_t off_items_kind[3] = {0, 0, 0};
+  size_t off_items_xchg = 0; int n_items_xchg = 0;
+  size_t off_items_dense = 0; int n_items_dense = 0;
+  int attn_rows = 0;                  // query rows per attention item on the MFMA path
+  int num_cu = 256;
+
+  // stage timing
+  bool timing = false;
+  static const int MAX_STAGES = 16;
+  hipEvent_t ev[MAX_STAGES + 1];
+  const char* stage_name[MAX_STAGES];
+  int n_stages = 0;
+  bool ev_created = false;
+
+  int64_t dev_bytes = 0;
+};
+
+// ---- host tables (tables.cpp) --------------------------------------------------------------------------------
+void build_dct_matrix(int n, std::vector<double>& F);  // [n][n], row = frequency
+void build_bands(Ctx& c);
+void build_mid_blocks(Ctx& c);
+
+// ---- generic fp32 kernels (generic_kernels.hip) -----------------------------------------------------------------
+struct AxisPassArgs {
+  const void* in; void* out;
+  const float* M;           // [n_out][n]: out[k] = sum_j M[k][j] in[j]
+  int n, n_out;
+  int64_t inner, outer;     // element index ((s*n + j)*inner + i), s in [0, nslab), slab s belongs to slice s/outer
+  int64_t nslab;
+  const int32_t* perm_in;   // when set (axis W only, inner == d): input row of token (s%outer)*n + j is perm[token]
+  const int32_t* perm_out;  // same for output rows
+  int64_t Ntok;
+  // input source selection per band for the first inverse pass (perm_in set): rows of band l of slice hb come from
+  // `in` when bit l of masks[hb] is set, else from `in_alt`.
+  const void* in_alt; const int32_t* masks; int32_t band_off1, band_off2;
+  int in_kind, out_kind;    // 0 float, 1 bf16, 2 fp16
+  int slice_mod;            // number of slices the masks array covers (slab slice index is taken modulo this)
+};
+hipError_t launch_generic_axis_pass(const AxisPassArgs& a, hipStream_t st);
+
+struct GenericAttnArgs {
+  const float* Q; const float* K; const float* V; float* O;
+  const int32_t* slice_list; int n_slices;
+  int64_t slice_stride;     // elements between slices for Q/K/V/O
+  int64_t kv_slice_stride;  // elements between slices for K/V (differs from Q for the exchange)
+  int nq, nk, d;
+  int mode;                 // 0 dense, 1 block list, 2 window
+  const int32_t* row_ptr; const int32_t* col_idx; int block; int window;
+  int residual;             // O = Q + attention (exchange)
+  float scale;
+};
+hipError_t launch_generic_attn(const GenericAttnArgs& a, hipStream_t st);
+
+hipError_t launch_pool_low(const void* spec, void* low, const int32_t* slice_list, int n_slices, int64_t N, int d,
+                           int64_t n_low, int64_t nbar, int c, int is_half, hipStream_t st);
+hipError_t launch_expand_low(const void* lowY, void* Y, const int32_t* slice_list, int n_slices, int64_t N, int d,
+                             int64_t n_low, int64_t nbar, int c, int is_half, hipStream_t st);
+// Summary tokens of all bands of all slices, written into the C slots of the two other bands.
+hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
+                            const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2, int is_half,
+                            hipStream_t st);
+// Router statistics: per band and channel, sum of squares over slices and the three spectral buffers.
+hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, float* stats /*[3][d], zeroed inside*/,
+                              int slices, int64_t N, int d, const int64_t band_off[3], const int64_t band_n[3],
+                              int is_half, hipStream_t st);
+
+// ---- MFMA kernels (mfma_dct.hip, mfma_attn.hip) -------------------------------------------------------------------
+struct DctPassArgs {
+  const void* in; void* out;
+  const half_t* M;          // [n_out][n] fp16, out[k] = sum_j M[k][j] in[j]
+  int n;
+  int64_t inner, outer, nslab;
+  const int32_t* perm_in; const int32_t* perm_out; int64_t Ntok;
+  const void* in_alt; const int32_t* masks; int32_t band_off1, band_off2; int slice_mod;
+  int in_bf16, out_bf16;    // element type of in / out: bf16 when set, else fp16
+  int d;
+};
+hipError_t launch_mfma_dct_pass(const DctPassArgs& a, int num_cu, hipStream_t st);
+hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_items, int rows_per_item, int num_cu,
+                            hipStream_t st);
+
+}  // namespace fa

@@ -1,0 +1,338 @@
+// Generic kernels of libfreqattn: plain fp32 arithmetic for any shape (the fp32 configuration and every shape the
+// MFMA kernels do not cover), plus the small helper kernels both paths share (pooling, summaries, band energy).
+#include <hip/hip_runtime.h>
+
+#include "ctx.h"
+
+namespace fa {
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_as_f32(const void* p, int64_t i, int kind) {
+  if (kind == 0) return ((const float*)p)[i];
+  if (kind == 1) return bf16_to_f32(((const uint16_t*)p)[i]);
+  return (float)((const half_t*)p)[i];
+}
+__device__ __forceinline__ void store_from_f32(void* p, int64_t i, float v, int kind) {
+  if (kind == 0) ((float*)p)[i] = v;
+  else if (kind == 1) ((uint16_t*)p)[i] = f32_to_bf16(v);
+  else ((half_t*)p)[i] = (half_t)v;
+}
+
+// One 1-D transform along one grid axis (section 3.2 / 3.7): out[s, k, i] = sum_j M[k][j] in[s, j, i].
+// One thread per output element.  With perm_in / perm_out the rows of the W-axis pass are looked up in the
+// band-major order (section 3.3), and with masks set the row's source buffer is chosen per band (section 3.7:
+// bands that were not processed contribute V~ unchanged).
+__global__ void k_axis_pass(AxisPassArgs a, int64_t total) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int64_t i = idx % a.inner;
+  const int64_t r = idx / a.inner;
+  const int k = (int)(r % a.n_out);
+  const int64_t s = r / a.n_out;
+  const int64_t slice = s / a.outer;
+  const int64_t o = s % a.outer;
+  const float* Mrow = a.M + (int64_t)k * a.n;
+  float acc = 0.f;
+  for (int j = 0; j < a.n; ++j) {
+    int64_t e;
+    const void* src = a.in;
+    if (a.perm_in) {
+      const int32_t row = a.perm_in[o * a.n + j];
+      if (a.masks) {
+        const int band = row < a.band_off1 ? 0 : (row < a.band_off2 ? 1 : 2);
+        if (!((a.masks[slice % a.slice_mod] >> band) & 1)) src = a.in_alt;
+      }
+      e = (slice * a.Ntok + row) * a.inner + i;
+    } else {
+      e = (s * a.n + j) * a.inner + i;
+    }
+    acc = fmaf(Mrow[j], load_as_f32(src, e, a.in_kind), acc);
+  }
+  int64_t eo;
+  if (a.perm_out) eo = (slice * a.Ntok + a.perm_out[o * a.n_out + k]) * a.inner + i;
+  else eo = (s * a.n_out + k) * a.inner + i;
+  store_from_f32(a.out, eo, acc, a.out_kind);
+}
+
+hipError_t launch_generic_axis_pass(const AxisPassArgs& a, hipStream_t st) {
+  const int64_t total = a.nslab * a.n_out * a.inner;
+  if (total == 0) return hipSuccess;
+  const int bs = 256;
+  const int64_t nb = (total + bs - 1) / bs;
+  hipLaunchKernelGGL(k_axis_pass, dim3((unsigned)nb), dim3(bs), 0, st, a, total);
+  return hipGetLastError();
+}
+
+// Attention of one query row per wave over a list of contiguous key ranges (sections 3.4.1-3.4.3, 3.6).
+// Lanes first take one key each (dot product over the channels), the wave does the running softmax, then lanes
+// take channels for the weighted sum of values.
+#define GATT_MAXC 4  // channels per lane: head_dim <= 256
+__global__ void __launch_bounds__(64) k_generic_attn(GenericAttnArgs a) {
+  __shared__ float qs[64 * GATT_MAXC];
+  const int lane = threadIdx.x;
+  const int64_t i = blockIdx.x;  // query row
+  const int slice = a.slice_list ? a.slice_list[blockIdx.y] : (int)blockIdx.y;
+  const float* Q = a.Q + (int64_t)slice * a.slice_stride;
+  const float* K = a.K + (int64_t)slice * a.kv_slice_stride;
+  const float* V = a.V + (int64_t)slice * a.kv_slice_stride;
+  float* O = a.O + (int64_t)slice * a.slice_stride;
+  const int d = a.d;
+  for (int c = lane; c < d; c += 64) qs[c] = Q[i * d + c];
+  __syncthreads();
+
+  float acc[GATT_MAXC];
+#pragma unroll
+  for (int u = 0; u < GATT_MAXC; ++u) acc[u] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  int n_ranges = 1, e0 = 0;
+  if (a.mode == 1) {
+    const int I = (int)(i / a.block);
+    e0 = a.row_ptr[I];
+    n_ranges = a.row_ptr[I + 1] - e0;
+  }
+  for (int rg = 0; rg < n_ranges; ++rg) {
+    int64_t k0, k1;
+    if (a.mode == 0) { k0 = 0; k1 = a.nk; }
+    else if (a.mode == 1) {
+      const int64_t J = a.col_idx[e0 + rg];
+      k0 = J * a.block;
+      k1 = k0 + a.block < a.nk ? k0 + a.block : a.nk;
+    } else {
+      k0 = i - a.window > 0 ? i - a.window : 0;
+      k1 = (i + a.window + 1 < a.nk) ? i + a.window + 1 : a.nk;
+    }
+    for (int64_t kb = k0; kb < k1; kb += 64) {
+      const int64_t key = kb + lane;
+      const bool valid = key < k1;
+      float s = -INFINITY;
+      if (valid) {
+        const float* kr = K + key * d;
+        float dot = 0.f;
+        for (int c = 0; c < d; ++c) dot = fmaf(qs[c], kr[c], dot);
+        s = dot * a.scale;
+      }
+      float mx = s;
+      for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+      const float m_new = fmaxf(m_run, mx);
+      const float p = valid ? expf(s - m_new) : 0.f;
+      float ps = p;
+      for (int off = 32; off > 0; off >>= 1) ps += __shfl_xor(ps, off);
+      const float alpha = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
+      l_run = l_run * alpha + ps;
+      m_run = m_new;
+#pragma unroll
+      for (int u = 0; u < GATT_MAXC; ++u) acc[u] *= alpha;
+      const int cnt = (int)((k1 - kb) < 64 ? (k1 - kb) : 64);
+      for (int j = 0; j < cnt; ++j) {
+        const float pj = __shfl(p, j);
+        const float* vr = V + (kb + j) * d;
+#pragma unroll
+        for (int u = 0; u < GATT_MAXC; ++u) {
+          const int c = lane + 64 * u;
+          if (c < d) acc[u] = fmaf(pj, vr[c], acc[u]);
+        }
+      }
+    }
+  }
+  const float inv = 1.f / l_run;
+#pragma unroll
+  for (int u = 0; u < GATT_MAXC; ++u) {
+    const int c = lane + 64 * u;
+    if (c < d) {
+      float r = acc[u] * inv;
+      if (a.residual) r += qs[c];
+      O[i * d + c] = r;
+    }
+  }
+}
+
+hipError_t launch_generic_attn(const GenericAttnArgs& a, hipStream_t st) {
+  if (a.nq <= 0 || a.n_slices <= 0 || a.nk <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_generic_attn, dim3((unsigned)a.nq, (unsigned)a.n_slices), dim3(64), 0, st, a);
+  return hipGetLastError();
+}
+
+// Low-band compression (section 3.3): mean of c consecutive band rows.  T is float or fp16.
+template <typename T>
+__global__ void k_pool_low(const T* spec, T* low, const int32_t* slice_list, int64_t N, int d, int64_t n_low,
+                           int64_t nbar, int c, int64_t total) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int ch = (int)(idx % d);
+  const int64_t j = (idx / d) % nbar;
+  const int li = (int)(idx / ((int64_t)d * nbar));
+  const int slice = slice_list[li];
+  const int64_t r0 = j * c;
+  const int64_t r1 = r0 + c < n_low ? r0 + c : n_low;
+  float s = 0.f;
+  for (int64_t r = r0; r < r1; ++r) s += (float)spec[((int64_t)slice * N + r) * d + ch];
+  low[((int64_t)slice * nbar + j) * d + ch] = (T)(s / (float)(r1 - r0));
+}
+
+hipError_t launch_pool_low(const void* spec, void* low, const int32_t* slice_list, int n_slices, int64_t N, int d,
+                           int64_t n_low, int64_t nbar, int c, int is_half, hipStream_t st) {
+  const int64_t total = (int64_t)n_slices * nbar * d;
+  if (total == 0) return hipSuccess;
+  const unsigned nb = (unsigned)((total + 255) / 256);
+  if (is_half)
+    hipLaunchKernelGGL(k_pool_low<half_t>, dim3(nb), dim3(256), 0, st, (const half_t*)spec, (half_t*)low, slice_list, N,
+                       d, n_low, nbar, c, total);
+  else
+    hipLaunchKernelGGL(k_pool_low<float>, dim3(nb), dim3(256), 0, st, (const float*)spec, (float*)low, slice_list, N, d,
+                       n_low, nbar, c, total);
+  return hipGetLastError();
+}
+
+// Every low-band position takes the output of its group (section 3.4.1 reading: Y_i = Ybar_{floor(i/c)}).
+template <typename T>
+__global__ void k_expand_low(const T* lowY, T* Y, const int32_t* slice_list, int64_t N, int d, int64_t n_low,
+                             int64_t nbar, int c, int64_t total) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int ch = (int)(idx % d);
+  const int64_t i = (idx / d) % n_low;
+  const int li = (int)(idx / ((int64_t)d * n_low));
+  const int slice = slice_list[li];
+  Y[((int64_t)slice * N + i) * d + ch] = lowY[((int64_t)slice * nbar + i / c) * d + ch];
+}
+
+hipError_t launch_expand_low(const void* lowY, void* Y, const int32_t* slice_list, int n_slices, int64_t N, int d,
+                             int64_t n_low, int64_t nbar, int c, int is_half, hipStream_t st) {
+  const int64_t total = (int64_t)n_slices * n_low * d;
+  if (total == 0) return hipSuccess;
+  const unsigned nb = (unsigned)((total + 255) / 256);
+  if (is_half)
+    hipLaunchKernelGGL(k_expand_low<half_t>, dim3(nb), dim3(256), 0, st, (const half_t*)lowY, (half_t*)Y, slice_list, N,
+                       d, n_low, nbar, c, total);
+  else
+    hipLaunchKernelGGL(k_expand_low<float>, dim3(nb), dim3(256), 0, st, (const float*)lowY, (float*)Y, slice_list, N, d,
+                       n_low, nbar, c, total);
+  return hipGetLastError();
+}
+
+// Summary tokens (section 3.6, U = I): chunk u of band l covers band rows [floor(u n / m), floor((u+1) n / m)).
+// One workgroup per (slice, band, chunk); threads split the chunk's rows 256/d ways and the partial sums are added in
+// a fixed order, so the result does not depend on scheduling.  The mean is written to the C rows of the two other
+// bands (band l sees the summaries of the other bands, ascending band order).
+template <typename T>
+__global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C, const int32_t* masks, int64_t N, int d,
+                                                   int64_t off0, int64_t off1, int64_t off2, int64_t n0, int64_t n1,
+                                                   int64_t n2, int m0, int m1, int m2e, int mmax, int m2rows) {
+  __shared__ float part[256];
+  const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x;
+  const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
+  const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
+  const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
+  if (u >= me) return;
+  const T* src = ((masks[slice] >> band) & 1) ? Y : V;
+  const int64_t r0 = ((int64_t)u * n) / me, r1 = ((int64_t)(u + 1) * n) / me;
+  const int groups = 256 / d;  // head_dim <= 256
+  const int tid = threadIdx.x;
+  const int ch = tid % d, grp = tid / d;
+  float s = 0.f;
+  if (grp < groups)
+    for (int64_t r = r0 + grp; r < r1; r += groups) s += (float)src[((int64_t)slice * N + off + r) * d + ch];
+  part[tid] = s;
+  __syncthreads();
+  if (grp == 0) {
+    float t = 0.f;
+    for (int g2 = 0; g2 < groups; ++g2) t += part[g2 * d + ch];
+    const T mean = (T)(t / (float)(r1 - r0));
+    // destination rows: in C of band b != band, the summaries of the lower other band come first
+    for (int b = 0; b < 3; ++b) {
+      if (b == band) continue;
+      int pos = u;
+      for (int o = 0; o < band; ++o)
+        if (o != b) pos += (o == 0 ? m0 : o == 1 ? m1 : m2e);
+      C[(((int64_t)slice * 3 + b) * m2rows + pos) * d + ch] = mean;
+    }
+  }
+  (void)mmax;
+}
+
+hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
+                            const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2rows,
+                            int is_half, hipStream_t st) {
+  int mmax = m_eff[0] > m_eff[1] ? m_eff[0] : m_eff[1];
+  if (m_eff[2] > mmax) mmax = m_eff[2];
+  if (mmax == 0 || slices == 0) return hipSuccess;
+  dim3 grid((unsigned)mmax, 3, (unsigned)slices);
+  if (is_half)
+    hipLaunchKernelGGL(k_summaries<half_t>, grid, dim3(256), 0, st, (const half_t*)Y, (const half_t*)V, (half_t*)C,
+                       masks, N, d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0],
+                       m_eff[1], m_eff[2], mmax, m2rows);
+  else
+    hipLaunchKernelGGL(k_summaries<float>, grid, dim3(256), 0, st, (const float*)Y, (const float*)V, (float*)C, masks, N,
+                       d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0], m_eff[1],
+                       m_eff[2], mmax, m2rows);
+  return hipGetLastError();
+}
+
+// Router statistics (section 3.5): per band and channel, the sum of squared coefficients over all slices and the
+// three spectral tensors.  Workgroup (chunk, band) adds its rows in a fixed order into part[chunk][band][d]; the
+// second kernel adds the chunks in order.  No floating-point atomics, so the result is reproducible.
+#define BE_CHUNKS 64
+template <typename T>
+__global__ void __launch_bounds__(256) k_band_energy(const T* sq, const T* sk, const T* sv, float* part, int slices,
+                                                     int64_t N, int d, int64_t off0, int64_t off1, int64_t off2,
+                                                     int64_t n0, int64_t n1, int64_t n2) {
+  __shared__ float red[256];
+  const int chunk = blockIdx.x, band = blockIdx.y;
+  const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
+  const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
+  const int64_t rows = n * slices;  // virtual row index: slice-major
+  const int64_t r0 = (chunk * rows) / BE_CHUNKS, r1 = ((chunk + 1) * rows) / BE_CHUNKS;
+  const int tid = threadIdx.x;
+  const int groups = 256 / d, ch = tid % d, grp = tid / d;
+  float s = 0.f;
+  if (grp < groups)
+    for (int64_t r = r0 + grp; r < r1; r += groups) {
+      const int64_t slice = r / n, row = r % n;
+      const int64_t e = ((int64_t)slice * N + off + row) * d + ch;
+      const float a = (float)sq[e], b = (float)sk[e], c = (float)sv[e];
+      s += a * a + b * b + c * c;
+    }
+  red[tid] = s;
+  __syncthreads();
+  if (grp == 0) {
+    float t = 0.f;
+    for (int g2 = 0; g2 < groups; ++g2) t += red[g2 * d + ch];
+    part[((int64_t)chunk * 3 + band) * d + ch] = t;
+  }
+}
+__global__ void k_band_energy_final(const float* part, float* stats, int d) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= 3 * d) return;
+  float t = 0.f;
+  for (int c = 0; c < BE_CHUNKS; ++c) t += part[(int64_t)c * 3 * d + idx];
+  stats[idx] = t;
+}
+
+hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, float* stats, int slices, int64_t N, int d,
+                              const int64_t band_off[3], const int64_t band_n[3], int is_half, hipStream_t st) {
+  // stats holds [3][d] results followed by BE_CHUNKS*3*d partial sums
+  float* part = stats + 3 * d;
+  dim3 grid(BE_CHUNKS, 3);
+  if (is_half)
+    hipLaunchKernelGGL(k_band_energy<half_t>, grid, dim3(256), 0, st, (const half_t*)sq, (const half_t*)sk,
+                       (const half_t*)sv, part, slices, N, d, band_off[0], band_off[1], band_off[2], band_n[0],
+                       band_n[1], band_n[2]);
+  else
+    hipLaunchKernelGGL(k_band_energy<float>, grid, dim3(256), 0, st, (const float*)sq, (const float*)sk,
+                       (const float*)sv, part, slices, N, d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1],
+                       band_n[2]);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_band_energy_final, dim3((3 * d + 255) / 256), dim3(256), 0, st, part, stats, d);
+  return hipGetLastError();
+}
+
+}  // namespace fa

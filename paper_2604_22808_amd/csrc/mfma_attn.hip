@@ -1,0 +1,310 @@
+// Band attention on the gfx950 matrix cores (paper sections 3.4.1-3.4.3, 3.6, 6.2).
+//
+// One kernel serves every branch.  A work item is a tile of 32*NW query rows of one branch of one (batch, head)
+// slice; the branches differ only in which 64-key tiles the item visits and how scores are masked:
+//   low   all tiles of the compressed low band            (dense global attention)
+//   mid   the tiles of the key blocks listed for the query block (block-sparse pattern)
+//   high  the tiles overlapping [q - w, q + w]            (sliding window, element mask on the edge tiles)
+//   exchange  the <= 2m summary tokens of the other bands, result added to the query row (residual)
+//   dense all tiles of the untransformed sequence         (comparison baseline)
+// The launch is persistent: workgroups stride over the item list, which the host orders by decreasing cost, so the
+// three branches are co-scheduled in one launch.
+//
+// Per 64-key tile, with S^T = K Q^T kept transposed so that a lane owns one query column:
+//   K tile   -> LDS row-major, A operand of v_mfma_f32_32x32x16_f16 (lane = key, 8 consecutive channels)
+//   Q        -> registers, B operand (lane = query, 8 consecutive channels), loaded once per item
+//   softmax  -> running max / sum per lane (one query per lane; the two lane halves hold different keys)
+//   V tile   -> LDS transposed [channel][key] with the key order of the S^T accumulator, so that the
+//               accumulator registers, converted to fp16, are the B operand of O^T += V^T P^T directly.
+#include <hip/hip_runtime.h>
+
+#include "ctx.h"
+
+namespace fa {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+
+#define KT 64  // keys per tile
+
+__device__ __forceinline__ uint16_t at_f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint4v at_bf16x8_to_f16x8(uint4v v) {
+  uint4v r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const _Float16 hl = (_Float16)__uint_as_float(v[i] << 16);
+    const _Float16 hh = (_Float16)__uint_as_float(v[i] & 0xffff0000u);
+    r[i] = (uint32_t)__builtin_bit_cast(uint16_t, hl) | ((uint32_t)__builtin_bit_cast(uint16_t, hh) << 16);
+  }
+  return r;
+}
+__device__ __forceinline__ uint32_t pack_h2(float a, float b) {
+  const _Float16 ha = (_Float16)a, hb = (_Float16)b;
+  return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
+}
+
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW) k_attn(AttnParams p, const AttnItem* __restrict__ items, int n_items) {
+  constexpr int KS = D + 8;     // row stride of the K tile in LDS (halfs)
+  constexpr int VS = KT + 8;    // row stride of the transposed V tile (halfs)
+  constexpr int DT = D / 32;    // 32-channel tiles of the output
+  constexpr int DK = D / 16;    // MFMA steps over the channels for S
+  constexpr int NT = 64 * NW;
+  __shared__ __attribute__((aligned(16))) half_t Ks[KT * KS];
+  __shared__ __attribute__((aligned(16))) half_t Vt[D * VS];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nn = lane & 31, g = lane >> 5;
+  const float c2 = p.scale * 1.4426950408889634f;  // scores are kept in units of log2
+
+  for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+    const AttnItem item = items[it];
+    const int kind = item.kind_band & 0xff, band = item.kind_band >> 8;
+    const int64_t slice = item.slice;
+    const int q0 = item.q0;
+    const uint16_t *Qp, *Kp, *Vp;
+    uint16_t* Op;
+    int nq, nk;
+    bool in_bf16 = false;
+    if (kind == 0) {
+      const int64_t o = slice * p.nbar * D;
+      Qp = (const uint16_t*)p.lowQ + o; Kp = (const uint16_t*)p.lowK + o; Vp = (const uint16_t*)p.lowV + o;
+      Op = (uint16_t*)p.lowY + o; nq = nk = p.nbar;
+    } else if (kind == 1 || kind == 2) {
+      const int64_t o = (slice * p.N + p.band_off[band]) * D;
+      Qp = (const uint16_t*)p.specQ + o; Kp = (const uint16_t*)p.specK + o; Vp = (const uint16_t*)p.specV + o;
+      Op = (uint16_t*)p.Y + o; nq = nk = p.band_n[band];
+    } else if (kind == 3) {
+      const int64_t o = (slice * p.N + p.band_off[band]) * D;
+      Qp = (const uint16_t*)p.Y + o; Op = (uint16_t*)p.Y + o; nq = p.band_n[band];
+      Kp = Vp = (const uint16_t*)p.C + ((slice * 3 + band) * p.m2) * (int64_t)D; nk = p.n_c[band];
+    } else {
+      const int64_t o = slice * p.N * D;
+      Qp = (const uint16_t*)p.denseQ + o; Kp = (const uint16_t*)p.denseK + o; Vp = (const uint16_t*)p.denseV + o;
+      Op = (uint16_t*)p.denseO + o; nq = nk = p.N; in_bf16 = p.dense_bf16 != 0;
+    }
+    const int w = p.high_window;
+    const int r0 = q0 + 32 * wave;      // first query row of this wave
+    const int row = r0 + nn;            // this lane's query row
+    const bool valid_q = row < nq;
+
+    // Q operand: lane holds channels 16*ks + 8*g .. +8 of its query row
+    half8 Qr[DK];
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      uint4v v = {0u, 0u, 0u, 0u};
+      if (valid_q) v = *(const uint4v*)(Qp + (int64_t)row * D + ks * 16 + g * 8);
+      if (in_bf16) v = at_bf16x8_to_f16x8(v);
+      Qr[ks] = __builtin_bit_cast(half8, v);
+    }
+
+    float16v O[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    // tile iteration space of the item
+    int n_outer = 1, e0 = 0, sub_n = 1, t_lo = 0, t_hi = 0;
+    if (kind == 1) {
+      const int I = q0 / p.mid_block;
+      e0 = p.mid_row_ptr[I];
+      n_outer = p.mid_row_ptr[I + 1] - e0;
+      sub_n = p.mid_block / KT;
+    } else if (kind == 2) {
+      const int klo = q0 - w > 0 ? q0 - w : 0;
+      int khi = q0 + 32 * NW - 1 + w;
+      if (khi > nk - 1) khi = nk - 1;
+      t_lo = klo / KT; t_hi = khi / KT;
+      n_outer = t_hi - t_lo + 1;
+    } else {
+      n_outer = (nk + KT - 1) / KT;
+    }
+
+    for (int eo = 0; eo < n_outer; ++eo) {
+      int tbase = (kind == 1) ? p.mid_col_idx[e0 + eo] * sub_n : (kind == 2 ? t_lo + eo : eo);
+      for (int sub = 0; sub < sub_n; ++sub) {
+        const int key0 = (tbase + sub) * KT;
+        if (key0 >= nk) continue;  // uniform over the workgroup
+        __syncthreads();
+        // ---- stage K: rows key0 .. key0+63, 16 bytes per thread per step
+        for (int e = tid; e < KT * (D / 8); e += NT) {
+          const int kr = e / (D / 8), c8 = e % (D / 8);
+          uint4v v = {0u, 0u, 0u, 0u};
+          if (key0 + kr < nk) v = *(const uint4v*)(Kp + (int64_t)(key0 + kr) * D + c8 * 8);
+          if (in_bf16) v = at_bf16x8_to_f16x8(v);
+          *(uint4v*)(Ks + kr * KS + c8 * 8) = v;
+        }
+        // ---- stage V transposed: unit = 4 keys x 8 channels
+        for (int e = tid; e < (KT / 4) * (D / 8); e += NT) {
+          const int kg = e / (D / 8), c8 = e % (D / 8);
+          uint4v rws[4];
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const int key = key0 + kg * 4 + b;
+            uint4v v = {0u, 0u, 0u, 0u};
+            if (key < nk) v = *(const uint4v*)(Vp + (int64_t)key * D + c8 * 8);
+            if (in_bf16) v = at_bf16x8_to_f16x8(v);
+            rws[b] = v;
+          }
+          // tile-local key kk = 4*kg + b = 32*t2 + 16*s + 8*a + 4*gg + b  ->  position 32*t2 + 16*s + 8*gg + 4*a + b
+          const int kk = kg * 4;
+          const int pos = (kk & ~15) | ((kk & 4) << 1) | ((kk & 8) >> 1);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int wd = i >> 1;
+            uint2v o2;
+            if (i & 1) {
+              o2[0] = (rws[0][wd] >> 16) | (rws[1][wd] & 0xffff0000u);
+              o2[1] = (rws[2][wd] >> 16) | (rws[3][wd] & 0xffff0000u);
+            } else {
+              o2[0] = (rws[0][wd] & 0xffffu) | (rws[1][wd] << 16);
+              o2[1] = (rws[2][wd] & 0xffffu) | (rws[3][wd] << 16);
+            }
+            *(uint2v*)(Vt + (c8 * 8 + i) * VS + pos) = o2;
+          }
+        }
+        __syncthreads();
+
+        // ---- does this wave need the tile at all (window), and does it need the element mask
+        const int key_hi = key0 + KT - 1;
+        bool need = true, need_mask = key_hi >= nk;
+        if (kind == 2) {
+          need = !(key_hi < r0 - w || key0 > r0 + 31 + w);
+          need_mask = need_mask || (key0 < r0 + 31 - w) || (key_hi > r0 + w);
+        }
+        if (!need) continue;  // uniform per wave; barriers are only at the top of the tile body
+
+        // ---- S^T = K Q^T for the two 32-key halves of the tile
+        float16v S[2];
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) S[t2][r] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < DK; ++ks) {
+            const half8 A = *(const half8*)(Ks + (t2 * 32 + nn) * KS + ks * 16 + g * 8);
+            S[t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Qr[ks], S[t2], 0, 0, 0);
+          }
+        }
+        // ---- scale, mask, running softmax (lane = query row; registers = keys)
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float s = S[t2][r] * c2;
+            if (need_mask) {
+              const int key = key0 + t2 * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+              bool ok = key < nk;
+              if (kind == 2) ok = ok && (key >= row - w) && (key <= row + w);
+              if (!ok) s = -INFINITY;
+            }
+            S[t2][r] = s;
+            mx = fmaxf(mx, s);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        m_run = m_new;
+        float psum = 0.f;
+        half8 P[2][2];
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            float pv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              pv[j] = __builtin_amdgcn_exp2f(S[t2][s2 * 8 + j] - m_safe);
+              psum += pv[j];
+            }
+            uint4v pk;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pk[j] = pack_h2(pv[2 * j], pv[2 * j + 1]);
+            P[t2][s2] = __builtin_bit_cast(half8, pk);
+          }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+              const half8 A = *(const half8*)(Vt + (dt * 32 + nn) * VS + t2 * 32 + s2 * 16 + g * 8);
+              O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[t2][s2], O[dt], 0, 0, 0);
+            }
+      }
+    }
+
+    // ---- epilogue: normalise, optional residual, store 4 consecutive channels per register group
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    if (valid_q) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4) {
+          const int dd = dt * 32 + a4 * 8 + g * 4;
+          float o[4];
+#pragma unroll
+          for (int b = 0; b < 4; ++b) o[b] = O[dt][a4 * 4 + b] * inv;
+          uint16_t* dst = Op + (int64_t)row * D + dd;
+          if (kind == 3) {
+            const uint2v y = *(const uint2v*)(Qp + (int64_t)row * D + dd);
+            const half4 yh = __builtin_bit_cast(half4, y);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) o[b] += (float)yh[b];
+          }
+          uint2v st2;
+          if (in_bf16) {
+            st2[0] = (uint32_t)at_f32_to_bf16(o[0]) | ((uint32_t)at_f32_to_bf16(o[1]) << 16);
+            st2[1] = (uint32_t)at_f32_to_bf16(o[2]) | ((uint32_t)at_f32_to_bf16(o[3]) << 16);
+          } else {
+            st2[0] = pack_h2(o[0], o[1]);
+            st2[1] = pack_h2(o[2], o[3]);
+          }
+          *(uint2v*)dst = st2;
+        }
+    }
+  }
+}
+
+template <int D, int NW>
+static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_items, int num_cu, hipStream_t st) {
+  int occ = 0;
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_attn<D, NW>, 64 * NW, 0);
+  if (e != hipSuccess) return e;
+  if (occ < 1) occ = 1;
+  int64_t blocks = (int64_t)num_cu * occ;
+  if (blocks > n_items) blocks = n_items;
+  hipLaunchKernelGGL((k_attn<D, NW>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
+  return hipGetLastError();
+}
+
+hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_items, int rows_per_item, int num_cu,
+                            hipStream_t st) {
+  if (n_items <= 0) return hipSuccess;
+  if (p.d == 64 && rows_per_item == 64) return launch_dn<64, 2>(p, items, n_items, num_cu, st);
+  if (p.d == 64 && rows_per_item == 128) return launch_dn<64, 4>(p, items, n_items, num_cu, st);
+  if (p.d == 128 && rows_per_item == 64) return launch_dn<128, 2>(p, items, n_items, num_cu, st);
+  if (p.d == 128 && rows_per_item == 128) return launch_dn<128, 4>(p, items, n_items, num_cu, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace fa

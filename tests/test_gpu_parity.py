@@ -1,0 +1,200 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 oracle on the same seeded inputs.
+
+Tolerances: bf16 I/O with fp16 matrix-core operands and fp32 accumulation: max-abs <= 2e-2 and relative L2 <= 5e-3;
+fp32 configuration: 1e-5 for both.  Integer tables must be bit-exact.
+"""
+import numpy as np
+import pytest
+
+from oracle import freqformer as O
+from paper_2604_22808_amd import binding as B
+from paper_2604_22808_amd import workloads as WL
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(wl, heads=None):
+    q, k, v = WL.qkv_numpy(wl, heads=heads)
+    return [WL.round_to_io(x, wl.dtype) for x in (q, k, v)]
+
+
+def _check(got, want, dtype, what=""):
+    mx, rl = U.errors(got, want)
+    tol_abs, tol_rel = U.TOL[dtype]
+    print(f"{what}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+    assert mx <= tol_abs and rl <= tol_rel, (what, mx, rl)
+
+
+# ------------------------------------------------------------------ fp32 configuration (generic kernels)
+@pytest.mark.parametrize("masks", [(1, 4), (2, 7), (0, 3), (5, 6)])
+def test_tiny_f32_matches_oracle(masks):
+    wl = WL.WORKLOADS["tiny_f32"]
+    q, k, v = _inputs(wl)
+    ctx, band = U.make_ctx(wl)
+    assert ctx.get_path() == B.PATH_GENERIC
+    got = U.run_forward(ctx, q, k, v, wl.dtype, masks)
+    want = O.forward(q, k, v, wl.grid, U.oracle_cfg(band), masks)
+    _check(got, want, "f32", f"tiny_f32 masks={masks}")
+
+
+def test_tiny_f32_unit_rms_stress():
+    """Inputs rescaled to unit RMS: the low band becomes argmax-like (DC variance ~86); fp32 only."""
+    wl = WL.WORKLOADS["tiny_f32"]
+    q, k, v = (x / x.std() for x in WL.qkv_numpy(wl))
+    q, k, v = (WL.round_to_io(x, "f32") for x in (q, k, v))
+    ctx, band = U.make_ctx(wl)
+    got = U.run_forward(ctx, q, k, v, "f32", (7, 7))
+    want = O.forward(q, k, v, wl.grid, U.oracle_cfg(band), (7, 7))
+    mx, rl = U.errors(got, want)
+    print(f"unit-rms stress: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+    assert mx <= 1e-4 and rl <= 1e-4   # logits reach O(100): fp32 products lose ~1e-5 absolute before the exponential
+
+
+@pytest.mark.parametrize("grid,d,band", [
+    ((3, 5, 7), 8, dict(mid_block=5, mid_diag=1, mid_stride=3, mid_block0=0, high_window=4, n_summary=3, low_compress=2)),
+    ((2, 4, 4), 16, dict(mid_block=4, mid_diag=0, mid_stride=2, mid_block0=1, high_window=100, n_summary=50, low_compress=1)),
+    ((1, 1, 1), 4, dict(mid_block=4, high_window=1, n_summary=2)),
+    ((4, 8, 8), 64, dict(mid_block=16, mid_diag=1, mid_stride=1, high_window=0, n_summary=0)),
+    ((4, 8, 8), 160, dict(mid_block=16, mid_diag=1, mid_stride=4, high_window=32, n_summary=4, softmax_scale=0.2)),
+])
+def test_generic_edge_shapes_f32(grid, d, band):
+    """Ragged grids, empty bands (1x1x1 has only a low band), m larger than a band, window 0 and >= N, all-ones mask."""
+    rng = np.random.default_rng(11)
+    N = int(np.prod(grid))
+    q, k, v = (WL.round_to_io(rng.standard_normal((2, 3, N, d)), "f32") for _ in range(3))
+    cfgd = dict(WL.WORKLOADS["tiny_f32"].band)
+    cfgd.update(band)
+    ctx = B.Context(2, 3, d, grid, B.F32, B.make_cfg(**cfgd))
+    alloc = (7, 2, 5)
+    got = U.run_forward(ctx, q, k, v, "f32", alloc)
+    want = O.forward(q, k, v, grid, O.BandConfig(**cfgd), alloc)
+    _check(got, want, "f32", f"edge {grid} d={d}")
+
+
+def test_no_active_band_returns_v_on_gpu():
+    wl = WL.WORKLOADS["tiny_f32"]
+    q, k, v = _inputs(wl)
+    ctx, _ = U.make_ctx(wl)
+    got = U.run_forward(ctx, q, k, v, "f32", (0, 0))
+    assert np.abs(got - v).max() < 1e-5
+
+
+def test_forward_rejects_bad_arguments():
+    import torch
+    wl = WL.WORKLOADS["tiny_f32"]
+    ctx, band = U.make_ctx(wl)
+    q = torch.zeros((1, 2, 256, 64), device="cuda")
+    out = torch.empty_like(q)
+    with pytest.raises(B.FreqAttnError) as e:
+        ctx.forward(q, q, q, (1, 9), out)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.FreqAttnError) as e:
+        ctx.forward(q, q, q, (1, 4), q)            # out aliases an input
+    assert e.value.status == B.EINVAL
+    other = dict(band); other["high_window"] = 31
+    with pytest.raises(B.FreqAttnError) as e:
+        ctx.forward(q, q, q, (1, 4), out, cfg=B.make_cfg(**other))
+    assert e.value.status == B.EINVAL
+    ctx.forward(q, q, q, (1, 4), out)              # the context is still usable
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ bf16 configurations (MFMA kernels)
+def _stagewise(ctx, wl, band, q, k, v, alloc, out_gpu):
+    """Per-slice, per-stage report against the oracle's intermediate results."""
+    cfg = U.oracle_cfg(band)
+    T, H, W = wl.grid
+    for s in range(q.shape[1]):
+        f = lambda a: a[0, s].reshape(T, H, W, -1)
+        want, parts = O.head_forward(f(q), f(k), f(v), cfg, int(alloc[s]), return_parts=True)
+        for l in range(3):
+            idx = parts["bands"][l]
+            if (alloc[s] >> l) & 1:
+                for which, name in ((0, "qs"), (1, "ks")):
+                    mx, rl = U.errors(ctx.read_spectral(which, s, l), parts[name][idx])
+                    print(f"  slice {s} band {l} {name}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+            mx, rl = U.errors(ctx.read_spectral(2, s, l), parts["vs"][idx])
+            print(f"  slice {s} band {l} vs: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+            mx, rl = U.errors(ctx.read_spectral(3, s, l), parts["Yhat"][l])
+            print(f"  slice {s} band {l} Yhat: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+        mx, rl = U.errors(out_gpu[0, s], want.reshape(-1, want.shape[-1]))
+        print(f"  slice {s} mask {alloc[s]} out: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("path", [B.PATH_MFMA, B.PATH_GENERIC])
+def test_16k_bf16_matches_oracle(path):
+    wl = WL.WORKLOADS["16k"]
+    heads = [0, 2, 5, 7]                       # one low, one mid, two high heads of the 2/3/3 allocation
+    alloc_full = B.route_fixed(wl.heads, *wl.alloc["counts"])
+    alloc = [int(alloc_full[h]) for h in heads]
+    alloc[3] = 7                               # and one head that runs every band (the paper's literal equations)
+    q, k, v = _inputs(wl, heads=heads)
+    ctx, band = U.make_ctx(wl, path=path, heads=len(heads))
+    assert ctx.get_path() == path
+    got = U.run_forward(ctx, q, k, v, wl.dtype, alloc)
+    _stagewise(ctx, wl, band, q, k, v, alloc, got)
+    want = O.forward(q, k, v, wl.grid, U.oracle_cfg(band), alloc)
+    _check(got, want, "bf16", f"16k path={path}")
+    for s in range(len(heads)):
+        _check(got[0, s], want[0, s], "bf16", f"16k path={path} slice {s}")
+
+
+def test_16k_tables_bit_exact_on_device_context():
+    wl = WL.WORKLOADS["16k"]
+    ctx, band = U.make_ctx(wl)
+    want = O.band_partition(*wl.grid, U.oracle_cfg(band))
+    for l in range(3):
+        assert np.array_equal(ctx.band_index(l).astype(np.int64), want[l])
+    rp, ci = ctx.mid_blocks()
+    wrp, wci = O.mid_block_csr(len(rp) - 1, band["mid_diag"], band["mid_stride"], band["mid_block0"])
+    assert np.array_equal(rp, wrp) and np.array_equal(ci, wci)
+
+
+def test_16k_fused_and_separate_launches_agree():
+    import torch
+    wl = WL.WORKLOADS["16k"]
+    q, k, v = (U.to_device(x, "bf16") for x in _inputs(wl, heads=[0, 3, 6]))
+    ctx, _ = U.make_ctx(wl, heads=3)
+    a = torch.empty_like(q); b = torch.empty_like(q)
+    ctx.forward(q, k, v, (1, 2, 4), a)
+    ctx.set_launch_mode(B.LAUNCH_SEPARATE)
+    ctx.forward(q, k, v, (1, 2, 4), b)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)                      # same kernels, same per-item arithmetic: bitwise equal
+    ctx.set_launch_mode(B.LAUNCH_FUSED)
+    ctx.forward(q, k, v, (1, 2, 4), b)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)                      # and run-to-run deterministic
+
+
+@pytest.mark.parametrize("band", [
+    dict(mid_stride=1, high_window=20000, low_compress=1, n_summary=0),     # every branch degenerates to dense attention
+    dict(mid_block=128, mid_diag=0, mid_stride=3, mid_block0=0, high_window=100, n_summary=5, low_compress=3),
+    dict(mid_block=192, mid_diag=1, mid_stride=2, high_window=0, n_summary=300),
+])
+def test_16k_bf16_parameter_edges(band):
+    wl = WL.WORKLOADS["16k"]
+    q, k, v = _inputs(wl, heads=[1, 4])
+    ctx, bandd = U.make_ctx(wl, heads=2, **band)
+    assert ctx.get_path() == B.PATH_MFMA
+    alloc = (3, 6)
+    got = U.run_forward(ctx, q, k, v, wl.dtype, alloc)
+    want = O.forward(q, k, v, wl.grid, U.oracle_cfg(bandd), alloc)
+    _check(got, want, "bf16", f"16k edges {band}")
+
+
+def test_mfma_ragged_grid_bf16():
+    """Grid 16x48x80 (axis lengths that are not powers of two), head_dim 128, ragged tails in every band."""
+    grid, d = (16, 48, 80), 128
+    rng = np.random.default_rng(5)
+    N = int(np.prod(grid))
+    q, k, v = (WL.round_to_io(0.3 * rng.standard_normal((1, 2, N, d)), "bf16") for _ in range(3))
+    band = dict(WL.WORKLOADS["16k"].band)
+    band.update(mid_block=128, mid_diag=1, mid_stride=5, high_window=200, n_summary=7, low_compress=4)
+    ctx = B.Context(1, 2, d, grid, B.BF16, B.make_cfg(**band))
+    assert ctx.get_path() == B.PATH_MFMA
+    alloc = (7, 4)
+    got = U.run_forward(ctx, q, k, v, "bf16", alloc)
+    want = O.forward(q, k, v, grid, O.BandConfig(**band), alloc)
+    _check(got, want, "bf16", "ragged 16x48x80")

@@ -1,0 +1,105 @@
+"""Host-side checks of libfreqattn that need no GPU: the library loads, exports every declared symbol, rejects bad
+arguments, and its integer tables (paper sections 3.3, 3.4.2) equal the oracle's bit for bit."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import freqformer as O
+from paper_2604_22808_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "freqattn.h")).read()
+    declared = set(re.findall(r"\b(freqattn_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    raw = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(raw, name), name
+
+
+def tables_ctx(grid, d=64, dtype=B.F32, **kw):
+    return B.Context(1, 2, d, grid, dtype, B.make_cfg(**kw), path=B.PATH_TABLES_ONLY)
+
+
+@pytest.mark.parametrize("grid", [(4, 8, 8), (16, 32, 32), (3, 5, 7), (1, 1, 1), (16, 64, 64), (2, 6, 10)])
+def test_band_lists_bit_exact(grid):
+    ctx = tables_ctx(grid)
+    want = O.band_partition(*grid, O.BandConfig())
+    assert ctx.band_sizes() == [len(w) for w in want]
+    for l in range(3):
+        got = ctx.band_index(l)
+        assert got.dtype == np.int32 and np.array_equal(got.astype(np.int64), want[l])
+
+
+def test_band_lists_other_edges():
+    kw = dict(low_num=1, low_den=8, mid_num=3, mid_den=4)
+    ctx = tables_ctx((8, 8, 16), **kw)
+    want = O.band_partition(8, 8, 16, O.BandConfig(**kw))
+    for l in range(3):
+        assert np.array_equal(ctx.band_index(l).astype(np.int64), want[l])
+
+
+@pytest.mark.parametrize("grid,block,diag,stride,b0", [((4, 8, 8), 16, 1, 4, 1), ((16, 32, 32), 64, 1, 8, 1),
+                                                       ((16, 64, 64), 64, 1, 8, 1), ((64, 64, 64), 128, 2, 16, 1),
+                                                       ((8, 8, 8), 5, 0, 3, 0), ((8, 8, 8), 7, 3, 1, 0)])
+def test_mid_block_list_bit_exact(grid, block, diag, stride, b0):
+    ctx = tables_ctx(grid, mid_block=block, mid_diag=diag, mid_stride=stride, mid_block0=b0)
+    n_mid = ctx.band_sizes()[1]
+    nb = -(-n_mid // block)
+    rp, ci = ctx.mid_blocks()
+    wrp, wci = O.mid_block_csr(nb, diag, stride, b0)
+    assert np.array_equal(rp, wrp) and np.array_equal(ci, wci)
+
+
+def test_mid_block_counts_of_the_benchmark_configurations():
+    for grid, block, diag, stride, nnz in [((16, 32, 32), 64, 1, 8, 177), ((16, 64, 64), 64, 1, 8, 1887),
+                                           ((64, 64, 64), 128, 2, 16, 4234)]:
+        ctx = tables_ctx(grid, mid_block=block, mid_diag=diag, mid_stride=stride)
+        assert len(ctx.mid_blocks()[1]) == nnz
+
+
+@pytest.mark.parametrize("n", [1, 4, 8, 16, 64, 128])
+def test_dct_matrix_matches_oracle(n):
+    ctx = tables_ctx((n, 4, 4))
+    assert np.abs(ctx.dct_matrix(0) - O.dct_matrix(n)).max() < 1e-14
+
+
+def test_route_fixed():
+    assert list(B.route_fixed(8, 2, 3, 3)) == list(O.route_fixed(8, 2, 3, 3))
+    with pytest.raises(B.FreqAttnError):
+        B.route_fixed(8, 2, 3, 4)
+
+
+@pytest.mark.parametrize("bad", [dict(low_compress=0), dict(mid_block=0), dict(mid_stride=0), dict(mid_diag=-1),
+                                 dict(high_window=-1), dict(n_summary=-1), dict(low_num=1, low_den=2, mid_num=1, mid_den=2),
+                                 dict(mid_num=3, mid_den=2), dict(low_num=0)])
+def test_create_rejects_bad_band_cfg(bad):
+    with pytest.raises(B.FreqAttnError) as e:
+        tables_ctx((4, 8, 8), **bad)
+    assert e.value.status == B.EINVAL
+
+
+def test_create_rejects_bad_shapes_and_paths():
+    for shape in [(0, 2, 64, (4, 8, 8), B.F32), (1, 2, 64, (4, 0, 8), B.F32), (1, 2, 64, (4, 8, 8), 7)]:
+        with pytest.raises(B.FreqAttnError) as e:
+            B.Context(*shape, B.make_cfg(), path=B.PATH_TABLES_ONLY)
+        assert e.value.status == B.EINVAL
+    with pytest.raises(B.FreqAttnError) as e:      # MFMA path cannot take fp32 I/O or a 4x8x8 grid
+        B.Context(1, 2, 64, (4, 8, 8), B.F32, B.make_cfg(), path=B.PATH_MFMA)
+    assert e.value.status == B.EUNSUPPORTED
+    assert B.lib().freqattn_create(None, None, 0, None) == B.EINVAL
+    B.lib().freqattn_destroy(None)   # no-op
+
+
+def test_tables_only_context_refuses_compute():
+    ctx = tables_ctx((4, 8, 8))
+    cfg = ctx.cfg
+    ha = (C.c_int32 * 2)(1, 4)
+    dummy = C.c_void_p(16)
+    st = B.lib().freqattn_forward(ctx._h, dummy, dummy, dummy, C.byref(cfg), ha, C.c_void_p(32), None)
+    assert st == B.EUNSUPPORTED and b"tables-only" in B.lib().freqattn_last_error(ctx._h)
