@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the freqattn hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic Q/K/V already resident in HBM: head
+allocation (router MLP in the loop for the MLP workloads), forward transforms, band split, the three band
+operators, summary exchange, inverse transform.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1m|256k|64k|16k] [--dense] [--separate]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 matrix-core peak
+
+
+def algorithmic_work(wl, ctx, alloc):
+    """Algorithmic bytes / flops per stage of one forward (what the method itself must move or multiply)."""
+    N, d, S = wl.n_tokens, wl.head_dim, wl.batch * wl.heads
+    n_low, n_mid, n_high = ctx.band_sizes()
+    band = wl.band
+    c = band["low_compress"]
+    nbar = -(-n_low // c)
+    rp, ci = ctx.mid_blocks()
+    B = band["mid_block"]
+    nb = len(rp) - 1
+    size = lambda J: min(B, n_mid - J * B)
+    mid_pairs = sum(size(I) * size(int(J)) for I in range(nb) for J in ci[rp[I]:rp[I + 1]])
+    w = band["high_window"]
+    high_pairs = n_high * (2 * w + 1) - w * (w + 1) if n_high > 2 * w else n_high * n_high
+    pairs = [nbar * nbar, mid_pairs, high_pairs]
+    m = band["n_summary"]
+    m_eff = [min(m, n) for n in (n_low, n_mid, n_high)]
+    n_c = [sum(m_eff) - m_eff[l] for l in range(3)]
+    attn_flops = [0.0, 0.0, 0.0]
+    xchg_flops = 0.0
+    for b in range(wl.batch):
+        for h in range(wl.heads):
+            for l, n in enumerate((n_low, n_mid, n_high)):
+                if (int(alloc[h]) >> l) & 1:
+                    attn_flops[l] += 4.0 * d * pairs[l]
+                    xchg_flops += 4.0 * d * n * n_c[l]
+    io = 2  # bytes per bf16 element
+    return {
+        "forward_transform": ("hbm", 3 * S * N * d * io * 2.0, 9),     # 3 tensors, one read + one write each; 9 launches
+        "inverse_transform": ("hbm", S * N * d * io * 2.0, 3),
+        "band_attention_fused": ("mfma", sum(attn_flops), 1),
+        "low_attention": ("mfma", attn_flops[0], 1),
+        "mid_attention": ("mfma", attn_flops[1], 1),
+        "high_attention": ("mfma", attn_flops[2], 1),
+        "exchange": ("mfma", xchg_flops, 1),
+        "summaries": ("hbm", S * N * d * io * 1.0, 1),
+        "dense_attention": ("mfma", 4.0 * d * float(N) * N * S, 1),
+    }
+
+
+def cpu_baseline(wl, alloc):
+    """Times the fp64 oracle on the host cores on a bounded sample: one head per distinct band mask, on a reduced
+    token grid with the workload's head_dim and band parameters; scaled to whole-forward tokens/s."""
+    import numpy as np
+    from oracle import freqformer as O
+    from paper_2604_22808_amd import workloads as WL
+    T, H, W = wl.grid
+    sample_grid = (min(T, 16), min(H, 32), min(W, 64))
+    ns = sample_grid[0] * sample_grid[1] * sample_grid[2]
+    cfg = O.BandConfig(**wl.band)
+    masks = sorted(set(int(a) for a in alloc))
+    per_mask = {}
+    for mk in masks:
+        x = [WL.round_to_io(WL.field_numpy(sample_grid, wl.head_dim, wl.seed, s, mk), wl.dtype).reshape(sample_grid + (wl.head_dim,))
+             for s in range(3)]
+        t0 = time.perf_counter()
+        O.head_forward(x[0], x[1], x[2], cfg, mk)
+        per_mask[mk] = time.perf_counter() - t0
+    total_s = sum(per_mask[int(a)] for a in alloc) * wl.batch      # all heads at sample size
+    tokens = ns * wl.batch
+    cores = len(os.sched_getaffinity(0))
+    return {"value": tokens / total_s, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"fp64 numpy oracle, one head per distinct band mask {masks} on a {sample_grid[0]}x{sample_grid[1]}x"
+                      f"{sample_grid[2]} grid ({ns} of {wl.n_tokens} tokens per head) with the workload's head_dim and band "
+                      f"parameters; seconds summed over the {wl.heads} heads of the allocation ({total_s:.2f} s of CPU work)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="1m")
+    ap.add_argument("--dense", action="store_true", help="also time the dense flash-style baseline (one iteration)")
+    ap.add_argument("--separate", action="store_true", help="one launch per branch instead of the fused launch")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (every (batch, head) is independent; see DESIGN.md for how "
+                 "the path would shard); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2604_22808_amd import binding as B
+    from paper_2604_22808_amd import workloads as WL
+
+    B.lib()  # fails loudly when the HIP library has not been built
+    wl = WL.WORKLOADS[args.workload]
+    assert wl.dtype == "bf16", "the benchmark runs the bf16 workloads"
+    torch.cuda.set_device(0)
+    q, k, v = WL.qkv_torch(wl, "cuda")
+    out = torch.empty_like(q)
+    cfg = B.make_cfg(**wl.band)
+    ctx = B.Context(wl.batch, wl.heads, wl.head_dim, wl.grid, B.BF16, cfg)
+    if args.separate:
+        ctx.set_launch_mode(B.LAUNCH_SEPARATE)
+    router = None
+    if wl.alloc["kind"] == "mlp":
+        router = WL.router_weights(wl.alloc["hidden"], wl.alloc["seed"])
+        t_step = wl.alloc["t"]
+        alloc, pi, _ = ctx.route_mlp(q, k, v, t_step, *router)
+    else:
+        alloc = B.route_fixed(wl.heads, *wl.alloc["counts"])
+        pi = None
+
+    def step():
+        if router is not None:
+            ctx.forward_routed(q, k, v, t_step, *router, out)
+        else:
+            ctx.forward(q, k, v, alloc, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.set_stage_timing(True)       # HIP events on the launch stream around every stage of every timed step
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stages = ctx.stage_times()
+    ctx.set_stage_timing(False)
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens = wl.batch * wl.n_tokens
+    value = tokens / (elapsed / args.steps)
+
+    work = algorithmic_work(wl, ctx, alloc)
+    stage_report = {}
+    for name, ms in stages:
+        entry = {"ms": round(ms, 4)}
+        if name in work and ms > 0:
+            bound, amount, launches = work[name]
+            if bound == "hbm":
+                entry.update(bound="hbm", achieved_GBs=round(amount / (ms * 1e-3) / 1e9, 1), launches=launches)
+            else:
+                entry.update(bound="mfma", achieved_TFLOPs=round(amount / (ms * 1e-3) / 1e12, 2), launches=launches)
+        stage_report[name] = entry
+    dom = max((s for s in stages if s[0] in work), key=lambda s: s[1])
+    bound, amount, launches = work[dom[0]]
+    per_launch_s = dom[1] * 1e-3 / launches
+    if bound == "hbm":
+        achieved, peak, unit = amount / launches / per_launch_s / 1e9, HBM_PEAK_GBS, "GB/s"
+    else:
+        achieved, peak, unit = amount / launches / per_launch_s / 1e12, MFMA_PEAK_TFLOPS, "TFLOP/s"
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{wl.name}.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(dom[0])
+    roofline = {"bound": bound, "kernel": dom[0], "launches_per_step": launches,
+                "avg_launch_ms": round(per_launch_s * 1e3, 4), "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": traffic}
+
+    result = {
+        "metric": "tokens/s per forward", "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 I/O, fp16 MFMA operands, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "heads": wl.heads, "head_dim": wl.head_dim,
+                   "grid": list(wl.grid), "tokens": wl.n_tokens, "band": wl.band, "alloc": wl.alloc,
+                   "head_alloc": [int(a) for a in alloc], "pi": None if pi is None else [round(float(p), 4) for p in pi],
+                   "launch": "separate" if args.separate else "fused"},
+        "roofline": roofline, "stages": stage_report,
+    }
+    if args.dense:
+        dout = torch.empty_like(q)
+        ctx.set_stage_timing(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.dense_forward(q, k, v, dout)
+        torch.cuda.synchronize()
+        dense_s = time.perf_counter() - t0
+        ctx.set_stage_timing(False)
+        dflops = work["dense_attention"][1]
+        result["dense_baseline"] = {"ms": round(dense_s * 1e3, 3), "tokens_per_s": round(tokens / dense_s, 1),
+                                    "achieved_TFLOPs": round(dflops / dense_s / 1e12, 2),
+                                    "speedup_of_freqattn": round(dense_s * 1e3 / ms_per_step, 2)}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, alloc)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

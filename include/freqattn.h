@@ -137,6 +137,16 @@ freqattn_status freqattn_route_mlp(freqattn_ctx* ctx, const void* q, const void*
                                    int32_t hidden, const float* w1, const float* b1, const float* w2, const float* b2,
                                    int32_t* head_alloc, float pi[3], float* stats_out, void* stream);
 
+/* Whole hot path with the router in the loop (sections 3.2-3.7 including 3.5): transforms Q, K, V once, reduces the
+ * band statistics on the device, waits for them (the single host synchronisation of the call), evaluates the MLP
+ * and the apportionment on the host exactly as freqattn_route_mlp does, then runs the band operators, the exchange
+ * and the inverse transform with that allocation.  Arguments as in freqattn_forward and freqattn_route_mlp;
+ * head_alloc_out HOST [heads] and pi_out HOST [3] receive the allocation that was used. */
+freqattn_status freqattn_forward_routed(freqattn_ctx* ctx, const void* q, const void* k, const void* v,
+                                        const freqattn_band_cfg* band_cfg, float t, int32_t hidden, const float* w1,
+                                        const float* b1, const float* w2, const float* b2, void* out,
+                                        int32_t* head_alloc_out, float pi_out[3], void* stream);
+
 /* ---- dense comparison (section 4: N^2 pairs per head) ----------------------------------------------------------
  * Plain softmax(scale * Q K^T) V over all N tokens of every head with the library's own flash-style MFMA kernel;
  * BF16 contexts on the MFMA path only.  Same pointer conventions as freqattn_forward.  Asynchronous. */
@@ -144,9 +154,10 @@ freqattn_status freqattn_dense_forward(freqattn_ctx* ctx, const void* q, const v
                                        void* stream);
 
 /* ---- per-stage timing of the forward ---------------------------------------------------------------------------
- * When enabled, freqattn_forward records HIP events on its stream around each stage.  freqattn_stage_times waits
- * for the last forward's events and returns, for stage s < *n_stages, its name and the milliseconds between its
- * events.  names_out HOST [max_stages] receives pointers to static strings; ms_out HOST [max_stages]. */
+ * When enabled, every forward records HIP events on its stream around each stage (the last 64 forwards are kept).
+ * freqattn_stage_times waits for the last forward's events and returns, for stage s < *n_stages, its name and the
+ * milliseconds between its events averaged over the kept forwards since timing was enabled.  names_out HOST
+ * [max_stages] receives pointers to static strings; ms_out HOST [max_stages]. */
 freqattn_status freqattn_set_stage_timing(freqattn_ctx* ctx, int32_t enabled);
 freqattn_status freqattn_stage_times(freqattn_ctx* ctx, int32_t max_stages, const char** names_out, float* ms_out,
                                      int32_t* n_stages);

@@ -47,6 +47,10 @@ EXPORTS = {
                                      C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float),
                                      C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_float),
                                      C.POINTER(C.c_float), C.c_void_p]),
+    "freqattn_forward_routed": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(BandCfg), C.c_float,
+                                          C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                          C.POINTER(C.c_float), C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float),
+                                          C.c_void_p]),
     "freqattn_dense_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "freqattn_set_stage_timing": (C.c_int, [C.c_void_p, C.c_int32]),
     "freqattn_stage_times": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
@@ -131,6 +135,19 @@ class Context:
         self._check(lib().freqattn_forward(self._h, _ptr(q), _ptr(k), _ptr(v), C.byref(cfg),
                                            ha.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(out), _stream()))
         return out
+
+    def forward_routed(self, q, k, v, t, w1, b1, w2, b2, out, cfg=None):
+        hidden = int(w1.shape[1])
+        f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+        w1, b1, w2, b2 = f(w1), f(b1), f(w2), f(b2)
+        alloc = np.zeros(self.shape.heads, np.int32)
+        pi = np.zeros(3, np.float32)
+        P = lambda a: a.ctypes.data_as(C.POINTER(C.c_float))
+        cfg = cfg or self.cfg
+        self._check(lib().freqattn_forward_routed(self._h, _ptr(q), _ptr(k), _ptr(v), C.byref(cfg), float(t), hidden,
+                                                  P(w1), P(b1), P(w2), P(b2), _ptr(out),
+                                                  alloc.ctypes.data_as(C.POINTER(C.c_int32)), P(pi), _stream()))
+        return alloc, pi
 
     def dense_forward(self, q, k, v, out):
         self._check(lib().freqattn_dense_forward(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _stream()))

@@ -59,7 +59,8 @@ static void free_all(Ctx* c) {
   if (c->h_lists) (void)hipHostFree(c->h_lists);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
   if (c->ev_created)
-    for (int i = 0; i <= Ctx::MAX_STAGES; ++i) (void)hipEventDestroy(c->ev[i]);
+    for (int t = 0; t < Ctx::MAX_TIMED; ++t)
+      for (int i = 0; i <= Ctx::MAX_STAGES; ++i) (void)hipEventDestroy(c->ev[t][i]);
 }
 
 static int items_per_slice_max(const Ctx& c, int rows) {
@@ -224,8 +225,17 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_lists, c->lists_bytes, hipHostMallocDefault);
   }
   if (e == hipSuccess) {
-    for (int i = 0; i <= Ctx::MAX_STAGES && e == hipSuccess; ++i) e = hipEventCreate(&c->ev[i]);
-    c->ev_created = (e == hipSuccess);
+    bool all = true;
+    for (int t = 0; t < Ctx::MAX_TIMED; ++t)
+      for (int i = 0; i <= Ctx::MAX_STAGES; ++i) {
+        if (e == hipSuccess) e = hipEventCreate(&c->ev[t][i]);
+        if (e != hipSuccess && all) {  // destroy what exists, leave the rest untouched
+          all = false;
+          for (int t2 = 0; t2 <= t; ++t2)
+            for (int i2 = 0; i2 <= Ctx::MAX_STAGES && (t2 < t || i2 < i); ++i2) (void)hipEventDestroy(c->ev[t2][i2]);
+        }
+      }
+    c->ev_created = all;
   }
   if (e != hipSuccess) {
     const bool oom = (e == hipErrorOutOfMemory);
@@ -450,45 +460,38 @@ static void fill_attn_params(const Ctx& c, AttnParams& p, float scale) {
 }
 
 struct StageTimer {
-  Ctx& c; hipStream_t st; bool on;
-  StageTimer(Ctx& c_, hipStream_t s) : c(c_), st(s), on(c_.timing) {
-    if (on) { c.n_stages = 0; (void)hipEventRecord(c.ev[0], st); }
+  Ctx& c; hipStream_t st; bool on; int slot;
+  StageTimer(Ctx& c_, hipStream_t s) : c(c_), st(s), on(c_.timing), slot(0) {
+    if (on) {
+      slot = (int)(c.timed_steps % Ctx::MAX_TIMED);
+      c.n_stages = 0;
+      (void)hipEventRecord(c.ev[slot][0], st);
+    }
   }
   void done(const char* name) {
     if (on && c.n_stages < Ctx::MAX_STAGES) {
       c.stage_name[c.n_stages] = name;
-      (void)hipEventRecord(c.ev[c.n_stages + 1], st);
+      (void)hipEventRecord(c.ev[slot][c.n_stages + 1], st);
       ++c.n_stages;
     }
   }
+  ~StageTimer() { if (on) ++c.timed_steps; }
 };
 
-extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, const void* k, const void* v,
-                                            const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,
-                                            void* stream) {
-  if (!c) return FREQATTN_EINVAL;
-  if (!q || !k || !v || !band_cfg || !head_alloc || !out) return fail(c, FREQATTN_EINVAL, "freqattn_forward: NULL argument");
-  if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward: tables-only context");
-  if (!same_cfg(*band_cfg, c->cfg))
-    return fail(c, FREQATTN_EINVAL, "freqattn_forward: band_cfg differs from the one given to freqattn_create");
-  for (int h = 0; h < c->shape.heads; ++h)
-    if (head_alloc[h] < 0 || head_alloc[h] > 7) return fail(c, FREQATTN_EINVAL, "freqattn_forward: head_alloc entry outside 0..7");
-  if (out == q || out == k || out == v) return fail(c, FREQATTN_EINVAL, "freqattn_forward: out aliases an input");
-  hipStream_t st = (hipStream_t)stream;
-  const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
-  freqattn_status fs = ensure_lists(c, head_alloc, st);
-  if (fs != FREQATTN_OK) return fs;
-  const bool mf = c->path == FREQATTN_PATH_MFMA;
-  const int is_half = mf ? 1 : 0;
-  const int32_t* L = c->d_lists;
-  StageTimer tm(*c, st);
-
+static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const void* k, const void* v, hipStream_t st,
+                                        StageTimer& tm) {
   // sections 3.2 / 3.3: spectral transform of Q, K, V into band-major buffers
   HIP_TRY(c, forward_transform(*c, q, c->specQ, st));
   HIP_TRY(c, forward_transform(*c, k, c->specK, st));
   HIP_TRY(c, forward_transform(*c, v, c->specV, st));
   tm.done("forward_transform");
+  return FREQATTN_OK;
+}
 
+static freqattn_status bands_phase(freqattn_ctx* c, float scale, void* out, hipStream_t st, StageTimer& tm) {
+  const bool mf = c->path == FREQATTN_PATH_MFMA;
+  const int is_half = mf ? 1 : 0;
+  const int32_t* L = c->d_lists;
   // section 3.3: compression of the low band
   if (c->n_list[LOW] > 0) {
     const int32_t* lst = L + c->off_list[LOW];
@@ -574,6 +577,63 @@ extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, cons
   return FREQATTN_OK;
 }
 
+static freqattn_status check_forward_args(freqattn_ctx* c, const void* q, const void* k, const void* v,
+                                          const freqattn_band_cfg* band_cfg, const void* out, const char* who) {
+  if (!q || !k || !v || !band_cfg || !out) return fail(c, FREQATTN_EINVAL, std::string(who) + ": NULL argument");
+  if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, std::string(who) + ": tables-only context");
+  if (!same_cfg(*band_cfg, c->cfg))
+    return fail(c, FREQATTN_EINVAL, std::string(who) + ": band_cfg differs from the one given to freqattn_create");
+  if (out == q || out == k || out == v) return fail(c, FREQATTN_EINVAL, std::string(who) + ": out aliases an input");
+  return FREQATTN_OK;
+}
+
+extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, const void* k, const void* v,
+                                            const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,
+                                            void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  if (!head_alloc) return fail(c, FREQATTN_EINVAL, "freqattn_forward: NULL argument");
+  freqattn_status fs = check_forward_args(c, q, k, v, band_cfg, out, "freqattn_forward");
+  if (fs != FREQATTN_OK) return fs;
+  for (int h = 0; h < c->shape.heads; ++h)
+    if (head_alloc[h] < 0 || head_alloc[h] > 7) return fail(c, FREQATTN_EINVAL, "freqattn_forward: head_alloc entry outside 0..7");
+  hipStream_t st = (hipStream_t)stream;
+  const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
+  fs = ensure_lists(c, head_alloc, st);
+  if (fs != FREQATTN_OK) return fs;
+  StageTimer tm(*c, st);
+  fs = transforms_phase(c, q, k, v, st, tm);
+  if (fs != FREQATTN_OK) return fs;
+  return bands_phase(c, scale, out, st, tm);
+}
+
+static freqattn_status router_from_spectral(freqattn_ctx* c, float t, int32_t hidden, const float* w1, const float* b1,
+                                            const float* w2, const float* b2, int32_t* head_alloc, float pi[3],
+                                            float* stats_out, hipStream_t st);
+
+extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* q, const void* k, const void* v,
+                                                   const freqattn_band_cfg* band_cfg, float t, int32_t hidden,
+                                                   const float* w1, const float* b1, const float* w2, const float* b2,
+                                                   void* out, int32_t* head_alloc_out, float pi_out[3], void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  if (!w1 || !b1 || !w2 || !b2 || !head_alloc_out || !pi_out || hidden < 1)
+    return fail(c, FREQATTN_EINVAL, "freqattn_forward_routed: NULL argument or hidden < 1");
+  freqattn_status fs = check_forward_args(c, q, k, v, band_cfg, out, "freqattn_forward_routed");
+  if (fs != FREQATTN_OK) return fs;
+  if (c->d % 64 != 0) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_routed: head_dim must be a multiple of 64");
+  hipStream_t st = (hipStream_t)stream;
+  const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
+  StageTimer tm(*c, st);
+  fs = transforms_phase(c, q, k, v, st, tm);
+  if (fs != FREQATTN_OK) return fs;
+  fs = router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc_out, pi_out, nullptr, st);
+  if (fs != FREQATTN_OK) return fs;
+  fs = ensure_lists(c, head_alloc_out, st);
+  if (fs != FREQATTN_OK) return fs;
+  tm.done("router");
+  return bands_phase(c, scale, out, st, tm);
+}
+
+
 extern "C" freqattn_status freqattn_dense_forward(freqattn_ctx* c, const void* q, const void* k, const void* v, void* out,
                                                   void* stream) {
   if (!c) return FREQATTN_EINVAL;
@@ -620,20 +680,10 @@ extern "C" freqattn_status freqattn_read_spectral(freqattn_ctx* c, int32_t which
 }
 
 // ------------------------------------------------------------------------------------------------ router
-extern "C" freqattn_status freqattn_route_mlp(freqattn_ctx* c, const void* q, const void* k, const void* v, float t,
-                                              int32_t hidden, const float* w1, const float* b1, const float* w2,
-                                              const float* b2, int32_t* head_alloc, float pi[3], float* stats_out,
-                                              void* stream) {
-  if (!c) return FREQATTN_EINVAL;
-  if (!q || !k || !v || !w1 || !b1 || !w2 || !b2 || !head_alloc || !pi || hidden < 1)
-    return fail(c, FREQATTN_EINVAL, "freqattn_route_mlp: NULL argument or hidden < 1");
+static freqattn_status router_from_spectral(freqattn_ctx* c, float t, int32_t hidden, const float* w1, const float* b1,
+                                            const float* w2, const float* b2, int32_t* head_alloc, float pi[3],
+                                            float* stats_out, hipStream_t st) {
   const int d = c->d, DR = 64, DT = 64;
-  if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: tables-only context");
-  if (d % DR != 0) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: head_dim must be a multiple of 64");
-  hipStream_t st = (hipStream_t)stream;
-  HIP_TRY(c, forward_transform(*c, q, c->specQ, st));
-  HIP_TRY(c, forward_transform(*c, k, c->specK, st));
-  HIP_TRY(c, forward_transform(*c, v, c->specV, st));
   HIP_TRY(c, launch_band_energy(c->specQ, c->specK, c->specV, c->d_stats, c->slices, c->N, d, c->band_off, c->band_n,
                                 c->path == FREQATTN_PATH_MFMA ? 1 : 0, st));
   HIP_TRY(c, hipMemcpyAsync(c->h_stats, c->d_stats, 3 * d * sizeof(float), hipMemcpyDeviceToHost, st));
@@ -700,11 +750,29 @@ extern "C" freqattn_status freqattn_route_mlp(freqattn_ctx* c, const void* q, co
   return freqattn_route_fixed(heads, cnt[0] + base, cnt[1] + base, cnt[2] + base, head_alloc);
 }
 
+
+extern "C" freqattn_status freqattn_route_mlp(freqattn_ctx* c, const void* q, const void* k, const void* v, float t,
+                                              int32_t hidden, const float* w1, const float* b1, const float* w2,
+                                              const float* b2, int32_t* head_alloc, float pi[3], float* stats_out,
+                                              void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  if (!q || !k || !v || !w1 || !b1 || !w2 || !b2 || !head_alloc || !pi || hidden < 1)
+    return fail(c, FREQATTN_EINVAL, "freqattn_route_mlp: NULL argument or hidden < 1");
+  if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: tables-only context");
+  if (c->d % 64 != 0) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: head_dim must be a multiple of 64");
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(c, forward_transform(*c, q, c->specQ, st));
+  HIP_TRY(c, forward_transform(*c, k, c->specK, st));
+  HIP_TRY(c, forward_transform(*c, v, c->specV, st));
+  return router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc, pi, stats_out, st);
+}
+
 // ------------------------------------------------------------------------------------------------ stage timing
 extern "C" freqattn_status freqattn_set_stage_timing(freqattn_ctx* c, int32_t enabled) {
   if (!c) return FREQATTN_EINVAL;
   c->timing = enabled != 0;
   c->n_stages = 0;
+  c->timed_steps = 0;
   return FREQATTN_OK;
 }
 
@@ -712,12 +780,20 @@ extern "C" freqattn_status freqattn_stage_times(freqattn_ctx* c, int32_t max_sta
                                                 int32_t* n_stages) {
   if (!c || !names_out || !ms_out || !n_stages) return FREQATTN_EINVAL;
   *n_stages = 0;
-  if (!c->timing || c->n_stages == 0) return FREQATTN_OK;
-  HIP_TRY(c, hipEventSynchronize(c->ev[c->n_stages]));
+  if (!c->timing || c->n_stages == 0 || c->timed_steps == 0) return FREQATTN_OK;
+  const int last = (int)((c->timed_steps - 1) % Ctx::MAX_TIMED);
+  HIP_TRY(c, hipEventSynchronize(c->ev[last][c->n_stages]));
   const int n = std::min<int>(c->n_stages, max_stages);
+  const int kept = (int)std::min<int64_t>(c->timed_steps, Ctx::MAX_TIMED);
   for (int i = 0; i < n; ++i) {
     names_out[i] = c->stage_name[i];
-    HIP_TRY(c, hipEventElapsedTime(&ms_out[i], c->ev[i], c->ev[i + 1]));
+    double sum = 0.0;
+    for (int t = 0; t < kept; ++t) {
+      float ms = 0.f;
+      HIP_TRY(c, hipEventElapsedTime(&ms, c->ev[t][i], c->ev[t][i + 1]));
+      sum += ms;
+    }
+    ms_out[i] = (float)(sum / kept);
   }
   *n_stages = n;
   return FREQATTN_OK;

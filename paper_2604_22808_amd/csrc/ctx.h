@@ -102,9 +102,11 @@ struct Ctx {
   // stage timing
   bool timing = false;
   static const int MAX_STAGES = 16;
-  hipEvent_t ev[MAX_STAGES + 1];
+  static const int MAX_TIMED = 64;                // forwards whose events are kept (ring)
+  hipEvent_t ev[MAX_TIMED][MAX_STAGES + 1];
   const char* stage_name[MAX_STAGES];
-  int n_stages = 0;
+  int n_stages = 0;                               // stages of the last timed forward
+  int64_t timed_steps = 0;                        // timed forwards since timing was switched on
   bool ev_created = false;
 
   int64_t dev_bytes = 0;

@@ -198,3 +198,37 @@ def test_mfma_ragged_grid_bf16():
     got = U.run_forward(ctx, q, k, v, "bf16", alloc)
     want = O.forward(q, k, v, grid, O.BandConfig(**band), alloc)
     _check(got, want, "bf16", "ragged 16x48x80")
+
+
+def test_64k_router_in_the_loop_matches_oracle():
+    """64K configuration, four of its heads: the device router (statistics on fp16 spectra, MLP on the host) must give
+    the oracle's probabilities and the same integer allocation; the routed forward must match the oracle run with it."""
+    import torch
+    wl = WL.WORKLOADS["64k"]
+    heads = [0, 1, 2, 3]
+    q, k, v = _inputs(wl, heads=heads)
+    ctx, band = U.make_ctx(wl, heads=len(heads))
+    cfg = U.oracle_cfg(band)
+    w = WL.router_weights(wl.alloc["hidden"], wl.alloc["seed"])
+    dq, dk, dv = (U.to_device(x, "bf16") for x in (q, k, v))
+    for t in (0.9, 0.1):
+        want_alloc, want_pi = O.route_mlp(q, k, v, wl.grid, cfg, t, *w)
+        got_alloc, got_pi, got_stats = ctx.route_mlp(dq, dk, dv, t, *w)
+        want_stats = O.band_statistics(q, k, v, wl.grid, cfg)
+        print(f"t={t}: pi gpu {got_pi} oracle {want_pi} alloc {got_alloc}; stats max diff "
+              f"{np.abs(got_stats - want_stats).max():.2e}", flush=True)
+        assert np.abs(got_stats - want_stats).max() < 5e-3
+        assert np.abs(got_pi - want_pi).max() < 2e-3
+        assert np.array_equal(got_alloc, want_alloc)
+    out = torch.empty_like(dq)
+    alloc, pi = ctx.forward_routed(dq, dk, dv, 0.9, *w, out)
+    torch.cuda.synchronize()
+    want_alloc, _ = O.route_mlp(q, k, v, wl.grid, cfg, 0.9, *w)
+    assert np.array_equal(alloc, want_alloc)
+    want = O.forward(q, k, v, wl.grid, cfg, want_alloc)
+    _check(U.to_host64(out), want, "bf16", f"64k routed alloc={list(alloc)}")
+    # the same allocation through the plain entry point gives the same bits
+    out2 = torch.empty_like(dq)
+    ctx.forward(dq, dk, dv, alloc, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
