@@ -2,6 +2,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -55,7 +56,7 @@ static void free_all(Ctx* c) {
   F(c->d_perm); F(c->d_row_ptr); F(c->d_col_idx);
   for (int a = 0; a < 3; ++a) { F(c->d_F32[a]); F(c->d_Ft32[a]); F(c->d_F16[a]); F(c->d_Ft16[a]); }
   F(c->specQ); F(c->specK); F(c->specV); F(c->Y); F(c->tmp0); F(c->tmp1);
-  F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_lists);
+  F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_lists); F(c->d_energy_part);
   if (c->h_lists) (void)hipHostFree(c->h_lists);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
   if (c->ev_created)
@@ -205,6 +206,15 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
   A(dev_alloc_bytes(*c, &c->Cbuf, (size_t)c->slices * 3 * 2 * (size_t)std::max(g.n_summary, 1) * c->d * es));
   const size_t stats_floats = (size_t)3 * c->d * (1 + 64);
   A(dev_alloc(*c, &c->d_stats, stats_floats));
+  if (mf) A(dev_alloc(*c, &c->d_energy_part, (size_t)3 * DCT_MAX_WAVES * 3 * 64));
+  {
+    auto box = [](int64_t num, int64_t den, int n) { return (int)((num * n + den - 1) / den); };  // #k with k*den < num*n
+    const int dims[3] = {s.T, s.H, s.W};
+    for (int a = 0; a < 3; ++a) {
+      c->low_box[a] = std::min(dims[a], box(g.low_num, g.low_den, dims[a]));
+      c->mid_box[a] = std::min(dims[a], box(g.mid_num, g.mid_den, dims[a]));
+    }
+  }
   if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_stats, 3 * c->d * sizeof(float), hipHostMallocDefault);
 
   // ---- per-forward lists
@@ -378,22 +388,107 @@ static freqattn_status ensure_lists(freqattn_ctx* c, const int32_t* head_alloc, 
 
 // ------------------------------------------------------------------------------------------------ transforms
 // Forward transform of one [slices, N, d] tensor into a band-major spectral buffer (sections 3.2, 3.3).
-static hipError_t forward_transform(Ctx& c, const void* x, void* spec, hipStream_t st) {
+// The three axis passes of the MFMA path are chained over units small enough for the intermediates to stay in the
+// 256 MB last-level cache: as many whole slices as fit the budget, or, when one slice is larger, groups of t-planes
+// for the W and H passes (the T pass then runs once per slice).  The scratch regions are reused by every unit.
+struct ChainPlan { int ns; int G; };  // slices per unit; planes per W/H launch (T when ns >= 1 whole slices)
+static ChainPlan chain_plan(const Ctx& c) {
+  static int64_t budget = -1;
+  if (budget < 0) {
+    const char* e = getenv("FREQATTN_CHAIN_MB");
+    budget = (e && atoi(e) > 0 ? (int64_t)atoi(e) : ((int64_t)1 << 40)) << 20;
+  }
+  const int64_t slice_bytes = c.N * c.d * (int64_t)sizeof(half_t);
+  ChainPlan p;
+  if (slice_bytes <= budget) {
+    p.ns = (int)std::min<int64_t>(c.slices, std::max<int64_t>(1, budget / slice_bytes));
+    p.G = c.shape.T;
+  } else {
+    const int64_t plane_bytes = slice_bytes / c.shape.T;
+    int64_t g = std::max<int64_t>(1, budget / plane_bytes);
+    if (g > c.shape.T) g = c.shape.T;
+    while (c.shape.T % g) --g;
+    p.ns = 1;
+    p.G = (int)g;
+  }
+  return p;
+}
+
+// MFMA path, forward: W axis (tmp0), H axis (tmp1, left in [h][t] order so that the rows of the T pass are W*d
+// elements apart), T axis, which scatters into the band-major spectral buffer and, when asked to, adds up the
+// router statistics.
+static hipError_t forward_transform_mfma(Ctx& c, const void* x, void* spec, hipStream_t st, int energy_slot) {
+  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
+  const int64_t plane = (int64_t)H * W * d, Nd = c.N * d;
+  const ChainPlan cp = chain_plan(c);
+  hipError_t e;
+  for (int s0 = 0; s0 < c.slices; s0 += cp.ns) {
+    const int ns = std::min(cp.ns, c.slices - s0);
+    const uint16_t* xs = (const uint16_t*)x + (int64_t)s0 * Nd;
+    for (int t0 = 0; t0 < T; t0 += cp.G) {
+      DctPassArgs a{};
+      a.d = d; a.Ntok = c.N;
+      a.in = xs + (int64_t)t0 * plane; a.out = c.tmp0; a.M = c.d_F16[2]; a.n = W; a.inner = d;
+      a.nslab = (int64_t)ns * cp.G * H; a.outer = a.nslab; a.in_bf16 = 1;
+      if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
+      a.in = c.tmp0; a.out = c.tmp1; a.M = c.d_F16[1]; a.n = H; a.inner = (int64_t)W * d;
+      a.nslab = (int64_t)ns * cp.G; a.outer = a.nslab; a.in_bf16 = 0;
+      a.out_swap = 1; a.sw = cp.G; a.sw_total = T; a.sw_off = t0;
+      if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
+    }
+    DctPassArgs a{};
+    a.d = d; a.Ntok = c.N;
+    a.in = c.tmp1; a.out = (uint16_t*)spec + (int64_t)s0 * Nd; a.M = c.d_F16[0]; a.n = T; a.inner = (int64_t)W * d;
+    a.nslab = (int64_t)ns * H; a.outer = H; a.perm_out = c.d_perm; a.perm_k = (int64_t)H * W; a.perm_o = W;
+    if (energy_slot >= 0) {
+      a.energy_part = c.d_energy_part + (size_t)energy_slot * DCT_MAX_WAVES * 3 * 64;
+      a.en_omul = W; a.en_div = W;  // the tile's other coordinates are (kh, kw)
+      a.low_u = c.low_box[1]; a.low_v = c.low_box[2]; a.low_a = c.low_box[0];
+      a.mid_u = c.mid_box[1]; a.mid_v = c.mid_box[2]; a.mid_a = c.mid_box[0];
+    }
+    if ((e = launch_mfma_dct_pass(a, c.num_cu, st, &c.energy_waves)) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// MFMA path, inverse (section 3.7): the T axis pass gathers band-major rows (from Y where the band is active for
+// the slice, else from V~) into tmp1 in [h][t] order, then H axis (tmp1 -> tmp0) and W axis (tmp0 -> out).
+static hipError_t inverse_transform_mfma(Ctx& c, void* out, hipStream_t st) {
+  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
+  const int64_t plane = (int64_t)H * W * d, Nd = c.N * d;
+  const ChainPlan cp = chain_plan(c);
+  const int32_t* masks = c.d_lists + c.off_masks;
+  hipError_t e;
+  for (int s0 = 0; s0 < c.slices; s0 += cp.ns) {
+    const int ns = std::min(cp.ns, c.slices - s0);
+    DctPassArgs a{};
+    a.d = d; a.Ntok = c.N;
+    a.in = (const uint16_t*)c.Y + (int64_t)s0 * Nd; a.in_alt = (const uint16_t*)c.specV + (int64_t)s0 * Nd;
+    a.masks = masks + s0; a.band_off1 = (int32_t)c.band_off[1]; a.band_off2 = (int32_t)c.band_off[2];
+    a.perm_in = c.d_perm; a.perm_k = (int64_t)H * W; a.perm_o = W;
+    a.out = c.tmp1; a.M = c.d_Ft16[0]; a.n = T; a.inner = (int64_t)W * d; a.nslab = (int64_t)ns * H; a.outer = H;
+    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
+    for (int t0 = 0; t0 < T; t0 += cp.G) {
+      DctPassArgs b{};
+      b.d = d; b.Ntok = c.N;
+      b.in = c.tmp1; b.out = c.tmp0; b.M = c.d_Ft16[1]; b.n = H; b.inner = (int64_t)W * d;
+      b.nslab = (int64_t)ns * cp.G; b.outer = b.nslab;
+      b.in_swap = 1; b.sw = cp.G; b.sw_total = T; b.sw_off = t0;
+      if ((e = launch_mfma_dct_pass(b, c.num_cu, st)) != hipSuccess) return e;
+      b.in_swap = 0;
+      b.in = c.tmp0; b.out = (uint16_t*)out + (int64_t)s0 * Nd + (int64_t)t0 * plane; b.M = c.d_Ft16[2]; b.n = W;
+      b.inner = d; b.nslab = (int64_t)ns * cp.G * H; b.outer = b.nslab; b.out_bf16 = 1;
+      if ((e = launch_mfma_dct_pass(b, c.num_cu, st)) != hipSuccess) return e;
+    }
+  }
+  return hipSuccess;
+}
+
+// Forward transform of one [slices, N, d] tensor into a band-major spectral buffer (sections 3.2, 3.3).
+static hipError_t forward_transform(Ctx& c, const void* x, void* spec, hipStream_t st, int energy_slot = -1) {
   const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
   hipError_t e;
-  if (c.path == FREQATTN_PATH_MFMA) {
-    DctPassArgs a{};
-    a.d = d; a.Ntok = c.N; a.slice_mod = c.slices;
-    a.in = x; a.out = c.tmp0; a.M = c.d_F16[0]; a.n = T; a.inner = (int64_t)H * W * d; a.outer = 1;
-    a.nslab = c.slices; a.in_bf16 = 1; a.out_bf16 = 0;
-    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
-    a.in = c.tmp0; a.out = c.tmp1; a.M = c.d_F16[1]; a.n = H; a.inner = (int64_t)W * d; a.outer = T;
-    a.nslab = (int64_t)c.slices * T; a.in_bf16 = 0;
-    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
-    a.in = c.tmp1; a.out = spec; a.M = c.d_F16[2]; a.n = W; a.inner = d; a.outer = (int64_t)T * H;
-    a.nslab = (int64_t)c.slices * T * H; a.perm_out = c.d_perm;
-    return launch_mfma_dct_pass(a, c.num_cu, st);
-  }
+  if (c.path == FREQATTN_PATH_MFMA) return forward_transform_mfma(c, x, spec, st, energy_slot);
   AxisPassArgs a{};
   a.Ntok = c.N; a.slice_mod = c.slices;
   a.in = x; a.out = c.tmp0; a.M = c.d_F32[0]; a.n = a.n_out = T; a.inner = (int64_t)H * W * d; a.outer = 1;
@@ -413,22 +508,7 @@ static hipError_t inverse_transform(Ctx& c, void* out, hipStream_t st) {
   const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
   const int32_t* masks = c.d_lists + c.off_masks;
   hipError_t e;
-  if (c.path == FREQATTN_PATH_MFMA) {
-    DctPassArgs a{};
-    a.d = d; a.Ntok = c.N; a.slice_mod = c.slices;
-    a.in = c.Y; a.in_alt = c.specV; a.masks = masks; a.band_off1 = (int32_t)c.band_off[1];
-    a.band_off2 = (int32_t)c.band_off[2]; a.perm_in = c.d_perm;
-    a.out = c.tmp0; a.M = c.d_Ft16[2]; a.n = W; a.inner = d; a.outer = (int64_t)T * H;
-    a.nslab = (int64_t)c.slices * T * H;
-    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
-    a.perm_in = nullptr; a.masks = nullptr; a.in_alt = nullptr;
-    a.in = c.tmp0; a.out = c.tmp1; a.M = c.d_Ft16[1]; a.n = H; a.inner = (int64_t)W * d; a.outer = T;
-    a.nslab = (int64_t)c.slices * T;
-    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
-    a.in = c.tmp1; a.out = out; a.M = c.d_Ft16[0]; a.n = T; a.inner = (int64_t)H * W * d; a.outer = 1;
-    a.nslab = c.slices; a.out_bf16 = 1;
-    return launch_mfma_dct_pass(a, c.num_cu, st);
-  }
+  if (c.path == FREQATTN_PATH_MFMA) return inverse_transform_mfma(c, out, st);
   AxisPassArgs a{};
   a.Ntok = c.N; a.slice_mod = c.slices;
   a.in = c.Y; a.in_alt = c.specV; a.masks = masks; a.band_off1 = (int32_t)c.band_off[1];
@@ -478,13 +558,22 @@ struct StageTimer {
   ~StageTimer() { if (on) ++c.timed_steps; }
 };
 
+// sections 3.2 / 3.3: spectral transform of Q, K, V into band-major buffers; with_stats also leaves the router's
+// band statistics (section 3.5) in d_stats.
 static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const void* k, const void* v, hipStream_t st,
-                                        StageTimer& tm) {
-  // sections 3.2 / 3.3: spectral transform of Q, K, V into band-major buffers
-  HIP_TRY(c, forward_transform(*c, q, c->specQ, st));
-  HIP_TRY(c, forward_transform(*c, k, c->specK, st));
-  HIP_TRY(c, forward_transform(*c, v, c->specV, st));
-  tm.done("forward_transform");
+                                        bool with_stats) {
+  const bool fused_stats = with_stats && c->path == FREQATTN_PATH_MFMA;
+  if (fused_stats) {
+    c->energy_waves = 0;
+    HIP_TRY(c, launch_fill_zero(c->d_energy_part, (int64_t)3 * DCT_MAX_WAVES * 3 * 64, st));
+  }
+  HIP_TRY(c, forward_transform(*c, q, c->specQ, st, fused_stats ? 0 : -1));
+  HIP_TRY(c, forward_transform(*c, k, c->specK, st, fused_stats ? 1 : -1));
+  HIP_TRY(c, forward_transform(*c, v, c->specV, st, fused_stats ? 2 : -1));
+  if (fused_stats) HIP_TRY(c, launch_energy_reduce(c->d_energy_part, c->d_stats, c->d, c->energy_waves, st));
+  else if (with_stats)
+    HIP_TRY(c, launch_band_energy(c->specQ, c->specK, c->specV, c->d_stats, c->slices, c->N, c->d, c->band_off, c->band_n,
+                                  0, st));
   return FREQATTN_OK;
 }
 
@@ -601,8 +690,9 @@ extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, cons
   fs = ensure_lists(c, head_alloc, st);
   if (fs != FREQATTN_OK) return fs;
   StageTimer tm(*c, st);
-  fs = transforms_phase(c, q, k, v, st, tm);
+  fs = transforms_phase(c, q, k, v, st, false);
   if (fs != FREQATTN_OK) return fs;
+  tm.done("forward_transform");
   return bands_phase(c, scale, out, st, tm);
 }
 
@@ -623,8 +713,9 @@ extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* 
   hipStream_t st = (hipStream_t)stream;
   const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
   StageTimer tm(*c, st);
-  fs = transforms_phase(c, q, k, v, st, tm);
+  fs = transforms_phase(c, q, k, v, st, true);
   if (fs != FREQATTN_OK) return fs;
+  tm.done("forward_transform");
   fs = router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc_out, pi_out, nullptr, st);
   if (fs != FREQATTN_OK) return fs;
   fs = ensure_lists(c, head_alloc_out, st);
@@ -684,8 +775,6 @@ static freqattn_status router_from_spectral(freqattn_ctx* c, float t, int32_t hi
                                             const float* w2, const float* b2, int32_t* head_alloc, float pi[3],
                                             float* stats_out, hipStream_t st) {
   const int d = c->d, DR = 64, DT = 64;
-  HIP_TRY(c, launch_band_energy(c->specQ, c->specK, c->specV, c->d_stats, c->slices, c->N, d, c->band_off, c->band_n,
-                                c->path == FREQATTN_PATH_MFMA ? 1 : 0, st));
   HIP_TRY(c, hipMemcpyAsync(c->h_stats, c->d_stats, 3 * d * sizeof(float), hipMemcpyDeviceToHost, st));
   HIP_TRY(c, hipStreamSynchronize(st));
   // g: log(eps + mean energy) per band and channel group, centred (section 3.5 "pooled statistics")
@@ -761,9 +850,8 @@ extern "C" freqattn_status freqattn_route_mlp(freqattn_ctx* c, const void* q, co
   if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: tables-only context");
   if (c->d % 64 != 0) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: head_dim must be a multiple of 64");
   hipStream_t st = (hipStream_t)stream;
-  HIP_TRY(c, forward_transform(*c, q, c->specQ, st));
-  HIP_TRY(c, forward_transform(*c, k, c->specK, st));
-  HIP_TRY(c, forward_transform(*c, v, c->specV, st));
+  freqattn_status fs = transforms_phase(c, q, k, v, st, true);
+  if (fs != FREQATTN_OK) return fs;
   return router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc, pi, stats_out, st);
 }
 

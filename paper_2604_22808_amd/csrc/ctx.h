@@ -81,7 +81,10 @@ struct Ctx {
   void* tmp0 = nullptr; void* tmp1 = nullptr;     // transform ping-pong, 3*slices*N*d
   void* lowQ = nullptr; void* lowK = nullptr; void* lowV = nullptr; void* lowY = nullptr;
   void* Cbuf = nullptr;
-  float* d_stats = nullptr;                       // router statistics [3][d]
+  float* d_stats = nullptr;                       // router statistics [3][d] (+ partial sums of the generic kernel)
+  float* d_energy_part = nullptr;                 // per-wave partial sums of the fused statistics (MFMA path)
+  int energy_waves = 0;                           // waves that wrote partial sums in the last fused pass
+  int low_box[3] = {0, 0, 0}, mid_box[3] = {0, 0, 0};  // extent of the low / low+mid box per axis
   float* h_stats = nullptr;                       // pinned mirror
 
   // per-forward lists (device + pinned host mirror)
@@ -160,6 +163,10 @@ hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t
 hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, float* stats /*[3][d], zeroed inside*/,
                               int slices, int64_t N, int d, const int64_t band_off[3], const int64_t band_n[3],
                               int is_half, hipStream_t st);
+// Adds up the per-wave partial sums of the three fused W-axis passes in a fixed order: stats[band][channel].
+hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
+hipError_t launch_energy_reduce(const float* energy_part /*[3][DCT_MAX_WAVES][3][64]*/, float* stats, int d,
+                                int n_waves, hipStream_t st);
 
 // ---- MFMA kernels (mfma_dct.hip, mfma_attn.hip) -------------------------------------------------------------------
 struct DctPassArgs {
@@ -167,12 +174,26 @@ struct DctPassArgs {
   const half_t* M;          // [n_out][n] fp16, out[k] = sum_j M[k][j] in[j]
   int n;
   int64_t inner, outer, nslab;
-  const int32_t* perm_in; const int32_t* perm_out; int64_t Ntok;
-  const void* in_alt; const int32_t* masks; int32_t band_off1, band_off2; int slice_mod;
+  // Band-major side (section 3.3): with perm_in / perm_out set, row j (k) of the tile at slab s = slice*outer + o and
+  // first column col0 is the band-major row perm[j*perm_k + o*perm_o + col0/d] of slice `slice`.
+  const int32_t* perm_in; const int32_t* perm_out; int64_t Ntok, perm_k, perm_o;
+  const void* in_alt; const int32_t* masks; int32_t band_off1, band_off2;
   int in_bf16, out_bf16;    // element type of in / out: bf16 when set, else fp16
   int d;
+  // Swapped scratch layout: with out_swap (in_swap) set, slab s = a*sw + b writes (reads) row k at
+  // (((a*n + k)*sw_total) + b + sw_off)*inner instead of (s*n + k)*inner, i.e. the slab index b becomes the inner of the
+  // two row indices.  The H-axis pass uses it to leave [h][t] order behind so that the T-axis pass finds its rows
+  // W*d elements apart instead of H*W*d.
+  int in_swap, out_swap, sw, sw_total, sw_off;
+  // Router statistics fused into the forward pass that scatters into the band-major buffer (perm_out set): every
+  // wave adds the squares of its fp32 results per band and column to energy_part[global wave][3][64].  With (u, v) the
+  // coordinates of the tile on the two axes the pass does not transform (flat index = u*en_div + v), rows [0, t1) are
+  // low, [t1, t2) mid and the rest high, t1 = low_a if u < low_u and v < low_v else 0, t2 likewise from the mid box.
+  float* energy_part;
+  int en_omul, en_div, low_u, low_v, low_a, mid_u, mid_v, mid_a;  // flat index of the tile = o*en_omul + col0/d
 };
-hipError_t launch_mfma_dct_pass(const DctPassArgs& a, int num_cu, hipStream_t st);
+#define DCT_MAX_WAVES 4096   // upper bound of waves in one launch of the DCT pass (sizes energy_part)
+hipError_t launch_mfma_dct_pass(const DctPassArgs& a, int num_cu, hipStream_t st, int* waves_out = nullptr);
 hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_items, int rows_per_item, int num_cu,
                             hipStream_t st);
 

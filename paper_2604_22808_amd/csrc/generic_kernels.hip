@@ -335,4 +335,42 @@ hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, fl
   return hipGetLastError();
 }
 
+__global__ void k_fill_zero(float* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n);
+  return hipGetLastError();
+}
+
+// Fixed-order sum of the per-wave partial statistics written by the fused forward passes of Q, K and V.
+// Wave w of a launch worked on column chunk w % (d/64) only.  One workgroup per (band, channel): 256 threads take
+// the (tensor, wave) terms round-robin and a fixed tree adds their partial sums.
+__global__ void __launch_bounds__(256) k_energy_reduce(const float* part, float* stats, int d, int n_waves) {
+  __shared__ float red[256];
+  const int idx = blockIdx.x, tid = threadIdx.x;
+  const int band = idx / d, ch = idx % d;
+  const int chunks = d / 64, chunk = ch / 64, col = ch % 64;
+  const int per = (n_waves - chunk + chunks - 1) / chunks;   // waves of this chunk
+  float t = 0.f;
+  for (int i = tid; i < 3 * per; i += 256) {
+    const int tensor = i / per, w = chunk + (i % per) * chunks;
+    t += part[(((size_t)tensor * DCT_MAX_WAVES + w) * 3 + band) * 64 + col];
+  }
+  red[tid] = t;
+  __syncthreads();
+  for (int sft = 128; sft > 0; sft >>= 1) {
+    if (tid < sft) red[tid] += red[tid + sft];
+    __syncthreads();
+  }
+  if (tid == 0) stats[idx] = red[0];
+}
+
+hipError_t launch_energy_reduce(const float* energy_part, float* stats, int d, int n_waves, hipStream_t st) {
+  hipLaunchKernelGGL(k_energy_reduce, dim3(3 * d), dim3(256), 0, st, energy_part, stats, d, n_waves);
+  return hipGetLastError();
+}
+
 }  // namespace fa

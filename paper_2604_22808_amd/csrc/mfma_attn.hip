@@ -287,9 +287,9 @@ __global__ void __launch_bounds__(64 * NW) k_attn(AttnParams p, const AttnItem* 
 
 template <int D, int NW>
 static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_items, int num_cu, hipStream_t st) {
-  int occ = 0;
-  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_attn<D, NW>, 64 * NW, 0);
-  if (e != hipSuccess) return e;
+  // resident workgroups per CU: register-limited (D = 128 holds one wave per SIMD, D = 64 two), 4 SIMDs per CU
+  const int waves_per_simd = D == 128 ? 1 : 2;
+  int occ = waves_per_simd * 4 / NW;
   if (occ < 1) occ = 1;
   int64_t blocks = (int64_t)num_cu * occ;
   if (blocks > n_items) blocks = n_items;
