@@ -92,9 +92,9 @@ def spectral_forward(x: np.ndarray) -> np.ndarray:
     """x~ = F(x) with F = F_t (x) F_h (x) F_w (section 3.2); x is [T, H, W, d_k], channels untouched."""
     T, H, W, _ = x.shape
     x = np.asarray(x, dtype=np.float64)
-    y = np.einsum("at,thwc->ahwc", dct_matrix(T), x)
-    y = np.einsum("bh,ahwc->abwc", dct_matrix(H), y)
-    y = np.einsum("gw,abwc->abgc", dct_matrix(W), y)
+    y = np.einsum("at,thwc->ahwc", dct_matrix(T), x, optimize=True)
+    y = np.einsum("bh,ahwc->abwc", dct_matrix(H), y, optimize=True)
+    y = np.einsum("gw,abwc->abgc", dct_matrix(W), y, optimize=True)
     return y
 
 
@@ -102,9 +102,9 @@ def spectral_inverse(c: np.ndarray) -> np.ndarray:
     """F^{-1} = F^T per axis (section 3.7; orthonormality, section 5)."""
     T, H, W, _ = c.shape
     c = np.asarray(c, dtype=np.float64)
-    y = np.einsum("at,ahwc->thwc", dct_matrix(T), c)
-    y = np.einsum("bh,tbwc->thwc", dct_matrix(H), y)
-    y = np.einsum("gw,thgc->thwc", dct_matrix(W), y)
+    y = np.einsum("at,ahwc->thwc", dct_matrix(T), c, optimize=True)
+    y = np.einsum("bh,tbwc->thwc", dct_matrix(H), y, optimize=True)
+    y = np.einsum("gw,thgc->thwc", dct_matrix(W), y, optimize=True)
     return y
 
 
