@@ -258,6 +258,65 @@ __global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C,
   (void)mmax;
 }
 
+// fp16 variant with 16-byte loads: a thread owns 8 adjacent channels, 256 / (d/8) row groups per workgroup, four rows
+// in flight per thread.  Same chunk rule, same fixed summation order per (row group, then groups ascending).
+__global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const half_t* V, half_t* C, const int32_t* masks,
+                                                      int64_t N, int d, int64_t off0, int64_t off1, int64_t off2,
+                                                      int64_t n0, int64_t n1, int64_t n2, int m0, int m1, int m2e,
+                                                      int m2rows) {
+  typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+  __shared__ float part[256 * 8];
+  const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x;
+  const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
+  const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
+  const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
+  if (u >= me) return;
+  const half_t* src = (((masks[slice] >> band) & 1) ? Y : V) + ((int64_t)slice * N + off) * d;
+  const int64_t r0 = ((int64_t)u * n) / me, r1 = ((int64_t)(u + 1) * n) / me;
+  const int tpr = d / 8;               // threads per row
+  const int groups = 256 / tpr;        // rows per workgroup step
+  const int tid = threadIdx.x;
+  const int c8 = tid % tpr, grp = tid / tpr;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (grp < groups) {
+    int64_t r = r0 + grp;
+    for (; r + 3 * (int64_t)groups < r1; r += 4 * (int64_t)groups) {
+      h8 x[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) x[k] = *(const h8*)(src + (r + (int64_t)k * groups) * d + c8 * 8);
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += (float)x[k][j];
+    }
+    for (; r < r1; r += groups) {
+      const h8 x = *(const h8*)(src + r * d + c8 * 8);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += (float)x[j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) part[tid * 8 + j] = acc[j];
+  __syncthreads();
+  if (grp == 0) {
+    const float inv = 1.f / (float)(r1 - r0);
+    h8 mean;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float t = 0.f;
+      for (int g2 = 0; g2 < groups; ++g2) t += part[(g2 * tpr + c8) * 8 + j];
+      mean[j] = (_Float16)(t * inv);
+    }
+    for (int b = 0; b < 3; ++b) {
+      if (b == band) continue;
+      int pos = u;
+      for (int o = 0; o < band; ++o)
+        if (o != b) pos += (o == 0 ? m0 : o == 1 ? m1 : m2e);
+      *(h8*)(C + (((int64_t)slice * 3 + b) * m2rows + pos) * d + c8 * 8) = mean;
+    }
+  }
+}
+
 hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
                             const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2rows,
                             int is_half, hipStream_t st) {
@@ -265,7 +324,11 @@ hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t
   if (m_eff[2] > mmax) mmax = m_eff[2];
   if (mmax == 0 || slices == 0) return hipSuccess;
   dim3 grid((unsigned)mmax, 3, (unsigned)slices);
-  if (is_half)
+  if (is_half && d % 8 == 0 && 256 % (d / 8) == 0)
+    hipLaunchKernelGGL(k_summaries_h8, grid, dim3(256), 0, st, (const half_t*)Y, (const half_t*)V, (half_t*)C, masks, N,
+                       d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0], m_eff[1],
+                       m_eff[2], m2rows);
+  else if (is_half)
     hipLaunchKernelGGL(k_summaries<half_t>, grid, dim3(256), 0, st, (const half_t*)Y, (const half_t*)V, (half_t*)C,
                        masks, N, d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0],
                        m_eff[1], m_eff[2], mmax, m2rows);

@@ -51,19 +51,23 @@ __device__ __forceinline__ uint32_t pack_h2(float a, float b) {
   return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
 }
 
-template <int D, int NW>
-__global__ void __launch_bounds__(64 * NW) k_attn(AttnParams p, const AttnItem* __restrict__ items, int n_items) {
-  constexpr int KS = D + 8;     // row stride of the K tile in LDS (halfs)
+template <int D, int NW, int QT>
+__global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2 : 1) k_attn(AttnParams p, const AttnItem* __restrict__ items, int n_items) {
+  constexpr int KS = D + 8;     // row stride of the K tile in LDS (halfs): rows shift by 16 bytes against the banks
   constexpr int VS = KT + 8;    // row stride of the transposed V tile (halfs)
   constexpr int DT = D / 32;    // 32-channel tiles of the output
   constexpr int DK = D / 16;    // MFMA steps over the channels for S
   constexpr int NT = 64 * NW;
+  constexpr int ROWS = 32 * QT * NW;  // query rows per item
+  constexpr int WROWS = 32 * QT;      // query rows per wave
+  constexpr bool QLDS = QT > 1;  // with two query tiles per wave the Q operands live in (wave-private) LDS, not registers
   __shared__ __attribute__((aligned(16))) half_t Ks[KT * KS];
   __shared__ __attribute__((aligned(16))) half_t Vt[D * VS];
+  __shared__ __attribute__((aligned(16))) half_t Qs[QLDS ? ROWS * KS : 8];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nn = lane & 31, g = lane >> 5;
-  const float c2 = p.scale * 1.4426950408889634f;  // scores are kept in units of log2
+  const float c2 = p.scale * 1.4426950408889634f;  // folded into Q: scores come out of the MFMA in units of log2
 
   for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
     const AttnItem item = items[it];
@@ -92,26 +96,38 @@ __global__ void __launch_bounds__(64 * NW) k_attn(AttnParams p, const AttnItem* 
       Op = (uint16_t*)p.denseO + o; nq = nk = p.N; in_bf16 = p.dense_bf16 != 0;
     }
     const int w = p.high_window;
-    const int r0 = q0 + 32 * wave;      // first query row of this wave
-    const int row = r0 + nn;            // this lane's query row
-    const bool valid_q = row < nq;
+    const int r0 = q0 + WROWS * wave;   // first query row of this wave
 
-    // Q operand: lane holds channels 16*ks + 8*g .. +8 of its query row
-    half8 Qr[DK];
+    // Q operand: lane holds channels 16*ks + 8*g .. +8 of its query rows (one per 32-row tile), pre-scaled
+    half8 Qr[QLDS ? 1 : QT][QLDS ? 1 : DK];
+    half_t* Qw = Qs + (QLDS ? wave * WROWS * KS : 0);
+    if (QLDS) __builtin_amdgcn_wave_barrier();   // the previous item's reads of this wave's Q rows are done
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      uint4v v = {0u, 0u, 0u, 0u};
-      if (valid_q) v = *(const uint4v*)(Qp + (int64_t)row * D + ks * 16 + g * 8);
-      if (in_bf16) v = at_bf16x8_to_f16x8(v);
-      Qr[ks] = __builtin_bit_cast(half8, v);
+    for (int qt = 0; qt < QT; ++qt) {
+      const int row = r0 + 32 * qt + nn;
+#pragma unroll
+      for (int ks = 0; ks < DK; ++ks) {
+        uint4v v = {0u, 0u, 0u, 0u};
+        if (row < nq) v = *(const uint4v*)(Qp + (int64_t)row * D + ks * 16 + g * 8);
+        if (in_bf16) v = at_bf16x8_to_f16x8(v);
+        half8 h = __builtin_bit_cast(half8, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = (_Float16)((float)h[j] * c2);
+        if (QLDS) *(half8*)(Qw + (32 * qt + nn) * KS + ks * 16 + g * 8) = h;   // each lane re-reads only what it wrote
+        else Qr[qt][ks] = h;
+      }
     }
 
-    float16v O[DT];
+    float16v O[QT][DT];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+    for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) O[qt][dt][r] = 0.f;
+    float m_run[QT], l_run[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
 
     // tile iteration space of the item
     int n_outer = 1, e0 = 0, sub_n = 1, t_lo = 0, t_hi = 0;
@@ -122,7 +138,7 @@ __global__ void __launch_bounds__(64 * NW) k_attn(AttnParams p, const AttnItem* 
       sub_n = p.mid_block / KT;
     } else if (kind == 2) {
       const int klo = q0 - w > 0 ? q0 - w : 0;
-      int khi = q0 + 32 * NW - 1 + w;
+      int khi = q0 + ROWS - 1 + w;
       if (khi > nk - 1) khi = nk - 1;
       t_lo = klo / KT; t_hi = khi / KT;
       n_outer = t_hi - t_lo + 1;
@@ -130,35 +146,63 @@ __global__ void __launch_bounds__(64 * NW) k_attn(AttnParams p, const AttnItem* 
       n_outer = (nk + KT - 1) / KT;
     }
 
-    for (int eo = 0; eo < n_outer; ++eo) {
-      int tbase = (kind == 1) ? p.mid_col_idx[e0 + eo] * sub_n : (kind == 2 ? t_lo + eo : eo);
-      for (int sub = 0; sub < sub_n; ++sub) {
-        const int key0 = (tbase + sub) * KT;
-        if (key0 >= nk) continue;  // uniform over the workgroup
-        __syncthreads();
-        // ---- stage K: rows key0 .. key0+63, 16 bytes per thread per step
-        for (int e = tid; e < KT * (D / 8); e += NT) {
-          const int kr = e / (D / 8), c8 = e % (D / 8);
-          uint4v v = {0u, 0u, 0u, 0u};
-          if (key0 + kr < nk) v = *(const uint4v*)(Kp + (int64_t)(key0 + kr) * D + c8 * 8);
-          if (in_bf16) v = at_bf16x8_to_f16x8(v);
-          *(uint4v*)(Ks + kr * KS + c8 * 8) = v;
-        }
-        // ---- stage V transposed: unit = 4 keys x 8 channels
-        for (int e = tid; e < (KT / 4) * (D / 8); e += NT) {
-          const int kg = e / (D / 8), c8 = e % (D / 8);
-          uint4v rws[4];
+    // Tiles are staged through registers: the global loads of tile i+1 are issued before the arithmetic of tile i, so
+    // their latency hides behind it; the registers are written to LDS after the barrier that ends tile i.
+    constexpr int KPT = (KT * (D / 8) + NT - 1) / NT;          // 16-byte K pieces per thread
+    constexpr int VPT = ((KT / 4) * (D / 8) + NT - 1) / NT;    // (4 keys x 8 channels) V units per thread
+    uint4v Kreg[KPT];
+    uint4v Vreg[VPT][4];
+    const int n_tt = n_outer * sub_n;
+    auto key0_of = [&](int idx) -> int {
+      if (kind == 1) return (p.mid_col_idx[e0 + idx / sub_n] * sub_n + idx % sub_n) * KT;
+      return (t_lo + idx) * KT;
+    };
+    auto load_tile = [&](int key0) {
 #pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const int key = key0 + kg * 4 + b;
-            uint4v v = {0u, 0u, 0u, 0u};
-            if (key < nk) v = *(const uint4v*)(Vp + (int64_t)key * D + c8 * 8);
-            if (in_bf16) v = at_bf16x8_to_f16x8(v);
-            rws[b] = v;
-          }
-          // tile-local key kk = 4*kg + b = 32*t2 + 16*s + 8*a + 4*gg + b  ->  position 32*t2 + 16*s + 8*gg + 4*a + b
-          const int kk = kg * 4;
-          const int pos = (kk & ~15) | ((kk & 4) << 1) | ((kk & 8) >> 1);
+      for (int u = 0; u < KPT; ++u) {
+        const int e = tid + u * NT;
+        const int kr = e / (D / 8), c8 = e % (D / 8);
+        uint4v v = {0u, 0u, 0u, 0u};
+        if (e < KT * (D / 8) && key0 + kr < nk) v = *(const uint4v*)(Kp + (int64_t)(key0 + kr) * D + c8 * 8);
+        Kreg[u] = v;
+      }
+#pragma unroll
+      for (int u = 0; u < VPT; ++u) {
+        const int e = tid + u * NT;
+        const int kg = e / (D / 8), c8 = e % (D / 8);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int key = key0 + kg * 4 + b;
+          uint4v v = {0u, 0u, 0u, 0u};
+          if (e < (KT / 4) * (D / 8) && key < nk) v = *(const uint4v*)(Vp + (int64_t)key * D + c8 * 8);
+          Vreg[u][b] = v;
+        }
+      }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+      for (int u = 0; u < KPT; ++u) {
+        const int e = tid + u * NT;
+        const int kr = e / (D / 8), c8 = e % (D / 8);
+        uint4v v = Kreg[u];
+        if (in_bf16) v = at_bf16x8_to_f16x8(v);
+        if (e < KT * (D / 8)) *(uint4v*)(Ks + kr * KS + c8 * 8) = v;
+      }
+#pragma unroll
+      for (int u = 0; u < VPT; ++u) {
+        const int e = tid + u * NT;
+        const int kg = e / (D / 8), c8 = e % (D / 8);
+        uint4v rws[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) rws[b] = in_bf16 ? at_bf16x8_to_f16x8(Vreg[u][b]) : Vreg[u][b];
+        // tile-local key kk = 4*kg + b = 32*t2 + 16*s + 8*a + 4*gg + b lives in 16-byte chunk x = 4*t2 + 2*s + gg of its
+        // channel row, half a of the chunk; chunks are XOR-swizzled with the row's channel octet so that the 8-byte
+        // stores of a wave (rows 8 apart) spread over the banks.
+        const int kk = kg * 4;
+        const int x = ((kk >> 4) << 1) | ((kk >> 2) & 1);
+        const int ahalf = (kk >> 3) & 1;
+        const int pos = ((x ^ (c8 & 7)) << 3) | (ahalf << 2);
+        if (e < (KT / 4) * (D / 8)) {
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             const int wd = i >> 1;
@@ -173,52 +217,75 @@ __global__ void __launch_bounds__(64 * NW) k_attn(AttnParams p, const AttnItem* 
             *(uint2v*)(Vt + (c8 * 8 + i) * VS + pos) = o2;
           }
         }
-        __syncthreads();
+      }
+    };
 
-        // ---- does this wave need the tile at all (window), and does it need the element mask
-        const int key_hi = key0 + KT - 1;
-        bool need = true, need_mask = key_hi >= nk;
-        if (kind == 2) {
-          need = !(key_hi < r0 - w || key0 > r0 + 31 + w);
-          need_mask = need_mask || (key0 < r0 + 31 - w) || (key_hi > r0 + w);
-        }
-        if (!need) continue;  // uniform per wave; barriers are only at the top of the tile body
+    if (n_tt > 0) load_tile(key0_of(0));
+    for (int idx = 0; idx < n_tt; ++idx) {
+      const int key0 = key0_of(idx);
+      __syncthreads();
+      store_tile();
+      __syncthreads();
+      if (idx + 1 < n_tt) load_tile(key0_of(idx + 1));
+      if (key0 >= nk) continue;  // block tail beyond the band (uniform over the workgroup)
 
-        // ---- S^T = K Q^T for the two 32-key halves of the tile
-        float16v S[2];
+      // ---- does this wave need the tile at all (window), and does it need the element mask
+      const int key_hi = key0 + KT - 1;
+      bool need = true, need_mask = key_hi >= nk;
+      if (kind == 2) {
+        need = !(key_hi < r0 - w || key0 > r0 + WROWS - 1 + w);
+        need_mask = need_mask || (key0 < r0 + WROWS - 1 - w) || (key_hi > r0 + w);
+      }
+      if (!need) continue;  // uniform per wave; barriers are only at the top of the tile body
+
+      // ---- S^T = K Q^T for the two 32-key halves of the tile; a K operand feeds all query tiles of the wave
+      float16v S[QT][2];
 #pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
+      for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) S[t2][r] = 0.f;
+        for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-          for (int ks = 0; ks < DK; ++ks) {
-            const half8 A = *(const half8*)(Ks + (t2 * 32 + nn) * KS + ks * 16 + g * 8);
-            S[t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Qr[ks], S[t2], 0, 0, 0);
+          for (int r = 0; r < 16; ++r) S[qt][t2][r] = 0.f;
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int ks = 0; ks < DK; ++ks) {
+          const half8 A = *(const half8*)(Ks + (t2 * 32 + nn) * KS + ks * 16 + g * 8);
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt) {
+            const half8 Bq = QLDS ? *(const half8*)(Qw + (32 * qt + nn) * KS + ks * 16 + g * 8) : Qr[QLDS ? 0 : qt][QLDS ? 0 : ks];
+            S[qt][t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Bq, S[qt][t2], 0, 0, 0);
           }
         }
-        // ---- scale, mask, running softmax (lane = query row; registers = keys)
+      // ---- mask, running softmax (lane = query row; registers = keys)
+      half8 P[QT][2][2];
+      bool any_rescale = false;
+      float alpha[QT];
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        const int row = r0 + 32 * qt + nn;
         float mx = -INFINITY;
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float s = S[t2][r] * c2;
+            float sv = S[qt][t2][r];
             if (need_mask) {
               const int key = key0 + t2 * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
               bool ok = key < nk;
               if (kind == 2) ok = ok && (key >= row - w) && (key <= row + w);
-              if (!ok) s = -INFINITY;
+              if (!ok) sv = -INFINITY;
+              S[qt][t2][r] = sv;
             }
-            S[t2][r] = s;
-            mx = fmaxf(mx, s);
+            mx = fmaxf(mx, sv);
           }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
+        const float m_new = fmaxf(m_run[qt], mx);
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-        m_run = m_new;
+        alpha[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_safe);
+        any_rescale = any_rescale || (m_new != m_run[qt]);
+        m_run[qt] = m_new;
         float psum = 0.f;
-        half8 P[2][2];
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
@@ -226,84 +293,97 @@ __global__ void __launch_bounds__(64 * NW) k_attn(AttnParams p, const AttnItem* 
             float pv[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-              pv[j] = __builtin_amdgcn_exp2f(S[t2][s2 * 8 + j] - m_safe);
+              pv[j] = __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + j] - m_safe);
               psum += pv[j];
             }
             uint4v pk;
 #pragma unroll
             for (int j = 0; j < 4; ++j) pk[j] = pack_h2(pv[2 * j], pv[2 * j + 1]);
-            P[t2][s2] = __builtin_bit_cast(half8, pk);
+            P[qt][t2][s2] = __builtin_bit_cast(half8, pk);
           }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
-        // ---- O^T += V^T P^T
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-              const half8 A = *(const half8*)(Vt + (dt * 32 + nn) * VS + t2 * 32 + s2 * 16 + g * 8);
-              O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[t2][s2], O[dt], 0, 0, 0);
-            }
+        l_run[qt] = l_run[qt] * alpha[qt] + psum;
       }
+      // the running maximum rarely moves after the first tiles: rescale the accumulators only when some lane needs it
+      if (__builtin_amdgcn_ballot_w64(any_rescale) != 0) {
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) O[qt][dt][r] *= alpha[qt];
+      }
+      // ---- O^T += V^T P^T; a V operand feeds all query tiles of the wave
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            const int vrow = dt * 32 + nn;
+            const int x = (t2 * 2 + s2) * 2 + g;
+            const half8 A = *(const half8*)(Vt + vrow * VS + ((x ^ ((vrow >> 3) & 7)) << 3));
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+              O[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[qt][t2][s2], O[qt][dt], 0, 0, 0);
+          }
     }
 
     // ---- epilogue: normalise, optional residual, store 4 consecutive channels per register group
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (valid_q) {
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+    for (int qt = 0; qt < QT; ++qt) {
+      const int row = r0 + 32 * qt + nn;
+      const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32);
+      const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+      if (row < nq) {
 #pragma unroll
-        for (int a4 = 0; a4 < 4; ++a4) {
-          const int dd = dt * 32 + a4 * 8 + g * 4;
-          float o[4];
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int b = 0; b < 4; ++b) o[b] = O[dt][a4 * 4 + b] * inv;
-          uint16_t* dst = Op + (int64_t)row * D + dd;
-          if (kind == 3) {
-            const uint2v y = *(const uint2v*)(Qp + (int64_t)row * D + dd);
-            const half4 yh = __builtin_bit_cast(half4, y);
+          for (int a4 = 0; a4 < 4; ++a4) {
+            const int dd = dt * 32 + a4 * 8 + g * 4;
+            float o[4];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) o[b] += (float)yh[b];
+            for (int b = 0; b < 4; ++b) o[b] = O[qt][dt][a4 * 4 + b] * inv;
+            uint16_t* dst = Op + (int64_t)row * D + dd;
+            if (kind == 3) {
+              const uint2v y = *(const uint2v*)(Qp + (int64_t)row * D + dd);
+              const half4 yh = __builtin_bit_cast(half4, y);
+#pragma unroll
+              for (int b = 0; b < 4; ++b) o[b] += (float)yh[b];
+            }
+            uint2v st2;
+            if (in_bf16) {
+              st2[0] = (uint32_t)at_f32_to_bf16(o[0]) | ((uint32_t)at_f32_to_bf16(o[1]) << 16);
+              st2[1] = (uint32_t)at_f32_to_bf16(o[2]) | ((uint32_t)at_f32_to_bf16(o[3]) << 16);
+            } else {
+              st2[0] = pack_h2(o[0], o[1]);
+              st2[1] = pack_h2(o[2], o[3]);
+            }
+            *(uint2v*)dst = st2;
           }
-          uint2v st2;
-          if (in_bf16) {
-            st2[0] = (uint32_t)at_f32_to_bf16(o[0]) | ((uint32_t)at_f32_to_bf16(o[1]) << 16);
-            st2[1] = (uint32_t)at_f32_to_bf16(o[2]) | ((uint32_t)at_f32_to_bf16(o[3]) << 16);
-          } else {
-            st2[0] = pack_h2(o[0], o[1]);
-            st2[1] = pack_h2(o[2], o[3]);
-          }
-          *(uint2v*)dst = st2;
-        }
+      }
     }
   }
 }
 
-template <int D, int NW>
+template <int D, int NW, int QT>
 static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_items, int num_cu, hipStream_t st) {
-  // resident workgroups per CU: register-limited (D = 128 holds one wave per SIMD, D = 64 two), 4 SIMDs per CU
-  const int waves_per_simd = D == 128 ? 1 : 2;
+  // resident workgroups per CU: register-limited waves per SIMD (accumulators of QT query tiles), 4 SIMDs per CU
+  const int waves_per_simd = (QT == 1 && (D == 64 || NW == 4)) ? 2 : 1;   // matches the kernel's launch bounds
   int occ = waves_per_simd * 4 / NW;
   if (occ < 1) occ = 1;
   int64_t blocks = (int64_t)num_cu * occ;
   if (blocks > n_items) blocks = n_items;
-  hipLaunchKernelGGL((k_attn<D, NW>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
+  hipLaunchKernelGGL((k_attn<D, NW, QT>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
   return hipGetLastError();
 }
 
 hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_items, int rows_per_item, int num_cu,
                             hipStream_t st) {
   if (n_items <= 0) return hipSuccess;
-  if (p.d == 64 && rows_per_item == 64) return launch_dn<64, 2>(p, items, n_items, num_cu, st);
-  if (p.d == 64 && rows_per_item == 128) return launch_dn<64, 4>(p, items, n_items, num_cu, st);
-  if (p.d == 128 && rows_per_item == 64) return launch_dn<128, 2>(p, items, n_items, num_cu, st);
-  if (p.d == 128 && rows_per_item == 128) return launch_dn<128, 4>(p, items, n_items, num_cu, st);
+  if (p.d == 64 && rows_per_item == 64) return launch_dn<64, 2, 1>(p, items, n_items, num_cu, st);
+  if (p.d == 64 && rows_per_item == 128) return launch_dn<64, 4, 1>(p, items, n_items, num_cu, st);
+  if (p.d == 128 && rows_per_item == 64) return launch_dn<128, 2, 1>(p, items, n_items, num_cu, st);
+  if (p.d == 128 && rows_per_item == 128) return launch_dn<128, 4, 1>(p, items, n_items, num_cu, st);
   return hipErrorInvalidValue;
 }
 
