@@ -10,7 +10,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfreqattn.so")
-SOURCES = ["api.cpp", "tables.cpp", "generic_kernels.hip", "mfma_dct.hip", "mfma_attn.hip"]
+SOURCES = ["mfma_dct_plain.hip", "mfma_dct_plain_tot.hip", "mfma_dct_scatter.hip", "mfma_dct_scatter_en.hip",
+           "mfma_dct_gather.hip", "mfma_attn.hip", "api.cpp", "tables.cpp", "generic_kernels.hip", "mfma_dct.hip"]
 
 
 def hipcc() -> str:
@@ -20,7 +21,7 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False, jobs: int = 5) -> str:
+def build(verbose: bool = False, jobs: int = 6) -> str:
     """Compiles every source to an object (in parallel) and links the shared library.  Always recompiles."""
     objdir = os.path.join(PKG, "_build")
     os.makedirs(objdir, exist_ok=True)

@@ -57,6 +57,7 @@ static void free_all(Ctx* c) {
   for (int a = 0; a < 3; ++a) { F(c->d_F32[a]); F(c->d_Ft32[a]); F(c->d_F16[a]); F(c->d_Ft16[a]); }
   F(c->specQ); F(c->specK); F(c->specV); F(c->Y); F(c->tmp0); F(c->tmp1);
   F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_lists); F(c->d_energy_part);
+  F(c->d_tot_part);
   if (c->h_lists) (void)hipHostFree(c->h_lists);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
   if (c->ev_created)
@@ -207,6 +208,7 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
   const size_t stats_floats = (size_t)3 * c->d * (1 + 64);
   A(dev_alloc(*c, &c->d_stats, stats_floats));
   if (mf) A(dev_alloc(*c, &c->d_energy_part, (size_t)3 * DCT_MAX_WAVES * 3 * 64));
+  if (mf) A(dev_alloc(*c, &c->d_tot_part, (size_t)2 * DCT_MAX_WAVES * 64));
   {
     auto box = [](int64_t num, int64_t den, int n) { return (int)((num * n + den - 1) / den); };  // #k with k*den < num*n
     const int dims[3] = {s.T, s.H, s.W};
@@ -225,6 +227,7 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
     size_t ints = 0;
     c->off_masks = ints; ints += (size_t)c->slices;
     for (int l = 0; l < 3; ++l) { c->off_list[l] = ints; ints += (size_t)c->slices; }
+    for (int k = 0; k < 4; ++k) { c->off_cls[k] = ints; ints += (size_t)c->slices; }
     ints = (ints + 3) & ~(size_t)3;
     c->off_items = ints; ints += 4 * per_slice * c->slices;
     for (int l = 0; l < 3; ++l) { c->off_items_kind[l] = ints; ints += 4 * per_slice * c->slices; }
@@ -323,9 +326,15 @@ static void build_lists(Ctx& c, const int32_t* head_alloc) {
   int32_t* L = c.h_lists;
   const int heads = c.shape.heads;
   for (int l = 0; l < 3; ++l) c.n_list[l] = 0;
+  for (int k = 0; k < 4; ++k) c.n_cls[k] = 0;
   for (int s = 0; s < c.slices; ++s) {
     const int mask = head_alloc[s % heads];
     L[c.off_masks + s] = mask;
+    int eff = 0;   // bands that really run (a band without coefficients runs nothing)
+    for (int l = 0; l < 3; ++l)
+      if (((mask >> l) & 1) && c.band_n[l] > 0) eff |= 1 << l;
+    const int cls = (eff & 4) ? 2 : (eff & 2) ? 1 : (eff & 1) ? 0 : 3;
+    L[c.off_cls[cls] + c.n_cls[cls]++] = s;
     for (int l = 0; l < 3; ++l)
       if (((mask >> l) & 1) && c.band_n[l] > 0) L[c.off_list[l] + c.n_list[l]++] = s;
   }
@@ -387,6 +396,88 @@ static freqattn_status ensure_lists(freqattn_ctx* c, const int32_t* head_alloc, 
 }
 
 // ------------------------------------------------------------------------------------------------ transforms
+// Forward transform of one [slices, N, d] tensor into a band-major spectral buffer (sections 3.2, 3.3).
+// Coefficients kept per axis when only the box [0, box) of an axis is needed: rounded up to the kernel's granularity,
+// or the full axis when the rectangular pass is not available for that pair of sizes.
+static int keep_rows(int box, int n) {
+  const int r = std::min(n, (box + 15) / 16 * 16);
+  return (r < n && mfma_dct_supported(n, r) && mfma_dct_supported(r, n)) ? r : n;
+}
+
+// MFMA path, forward, for `ns` slices (slice_list on the device, NULL = slices 0..ns-1): W axis (tmp0), H axis (tmp1,
+// left in [h][t] order so that the rows of the T pass are W*d elements apart), T axis, which scatters into the
+// band-major spectral buffer.  keep[] = coefficients computed per axis (T, H, W): a head that only runs the low (low
+// and mid) band needs Q~ and K~ on that box only, and every pass after the first then moves a fraction of the tensor.
+// energy_slot >= 0 adds up the router's band statistics in the T pass, tot_slot >= 0 the input's sum of squares in
+// the W pass.
+static hipError_t forward_transform_mfma(Ctx& c, const void* x, void* spec, hipStream_t st, const int32_t* slice_list,
+                                         int ns, const int keep[3], int energy_slot, int tot_slot) {
+  if (ns <= 0) return hipSuccess;
+  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
+  const int kt = keep[0], kh = keep[1], kw = keep[2];
+  hipError_t e;
+  DctPassArgs a{};
+  a.d = d; a.Ntok = c.N; a.slice_elems = c.N * d;
+  a.in = x; a.slice_list = slice_list; a.list_in = 1; a.out = c.tmp0; a.M = c.d_F16[2]; a.ldm = W; a.n = W; a.n_out = kw;
+  a.inner = d; a.outer = (int64_t)T * H; a.nslab = (int64_t)ns * T * H; a.in_bf16 = 1;
+  if (tot_slot >= 0) a.tot_part = c.d_tot_part + (size_t)tot_slot * DCT_MAX_WAVES * 64;
+  if ((e = launch_mfma_dct_pass(a, c.num_cu, st, &c.tot_waves)) != hipSuccess) return e;
+
+  DctPassArgs b{};
+  b.d = d; b.Ntok = c.N;
+  b.in = c.tmp0; b.out = c.tmp1; b.M = c.d_F16[1]; b.ldm = H; b.n = H; b.n_out = kh; b.inner = (int64_t)kw * d;
+  b.nslab = (int64_t)ns * T; b.outer = b.nslab; b.out_swap = 1; b.sw = T; b.sw_total = T; b.sw_off = 0;
+  if ((e = launch_mfma_dct_pass(b, c.num_cu, st)) != hipSuccess) return e;
+
+  DctPassArgs t{};
+  t.d = d; t.Ntok = c.N;
+  t.in = c.tmp1; t.out = spec; t.M = c.d_F16[0]; t.ldm = T; t.n = T; t.n_out = kt; t.inner = (int64_t)kw * d;
+  t.nslab = (int64_t)ns * kh; t.outer = kh; t.slice_list = slice_list;
+  t.perm_out = c.d_perm; t.perm_k = (int64_t)H * W; t.perm_o = W;
+  if (energy_slot >= 0) {
+    t.energy_part = c.d_energy_part + (size_t)energy_slot * DCT_MAX_WAVES * 3 * 64;
+    t.en_omul = W; t.en_div = W;  // the tile's other coordinates are (kh, kw)
+    t.low_u = c.low_box[1]; t.low_v = c.low_box[2]; t.low_a = c.low_box[0];
+    t.mid_u = c.mid_box[1]; t.mid_v = c.mid_box[2]; t.mid_a = c.mid_box[0];
+  }
+  return launch_mfma_dct_pass(t, c.num_cu, st, &c.energy_waves);
+}
+
+// MFMA path, inverse (section 3.7) for `ns` slices: the T axis pass gathers band-major rows into tmp1 in [h][t]
+// order, then H axis (tmp1 -> tmp0) and W axis (tmp0 -> out, bf16).  Two forms:
+//   select (delta = false): rows come from Y where the band is active for the slice, else from V~;
+//   delta  (delta = true):  rows are Y - V~ on the active bands and zero elsewhere, restricted to the box keep[] that
+//                           contains the active bands, and the last pass adds the input V:  out = V + F^-1(Y^ - V~),
+//                           which is the same sum because F^-1(V~) = V.
+static hipError_t inverse_transform_mfma(Ctx& c, void* out, const void* v_in, hipStream_t st, const int32_t* slice_list,
+                                         int ns, const int keep[3], bool delta) {
+  if (ns <= 0) return hipSuccess;
+  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
+  const int kt = keep[0], kh = keep[1], kw = keep[2];
+  hipError_t e;
+  DctPassArgs a{};
+  a.d = d; a.Ntok = c.N;
+  a.in = c.Y; a.in_alt = c.specV; a.masks = c.d_lists + c.off_masks; a.slice_list = slice_list; a.delta = delta ? 1 : 0;
+  a.band_off1 = (int32_t)c.band_off[1]; a.band_off2 = (int32_t)c.band_off[2];
+  a.perm_in = c.d_perm; a.perm_k = (int64_t)H * W; a.perm_o = W;
+  a.out = c.tmp1; a.M = c.d_Ft16[0]; a.ldm = T; a.n = kt; a.n_out = T; a.inner = (int64_t)kw * d;
+  a.nslab = (int64_t)ns * kh; a.outer = kh;
+  if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
+
+  DctPassArgs b{};
+  b.d = d; b.Ntok = c.N;
+  b.in = c.tmp1; b.out = c.tmp0; b.M = c.d_Ft16[1]; b.ldm = H; b.n = kh; b.n_out = H; b.inner = (int64_t)kw * d;
+  b.nslab = (int64_t)ns * T; b.outer = b.nslab; b.in_swap = 1; b.sw = T; b.sw_total = T; b.sw_off = 0;
+  if ((e = launch_mfma_dct_pass(b, c.num_cu, st)) != hipSuccess) return e;
+
+  DctPassArgs w{};
+  w.d = d; w.Ntok = c.N; w.slice_elems = c.N * d;
+  w.in = c.tmp0; w.out = out; w.M = c.d_Ft16[2]; w.ldm = W; w.n = kw; w.n_out = W; w.inner = d;
+  w.nslab = (int64_t)ns * T * H; w.outer = (int64_t)T * H; w.slice_list = slice_list; w.list_out = 1; w.out_bf16 = 1;
+  w.resid = delta ? v_in : nullptr;
+  return launch_mfma_dct_pass(w, c.num_cu, st);
+}
+
 // Forward transform of one [slices, N, d] tensor into a band-major spectral buffer (sections 3.2, 3.3).
 // The three axis passes of the MFMA path are chained over units small enough for the intermediates to stay in the
 // 256 MB last-level cache: as many whole slices as fit the budget, or, when one slice is larger, groups of t-planes
@@ -488,7 +579,10 @@ static hipError_t inverse_transform_mfma(Ctx& c, void* out, hipStream_t st) {
 static hipError_t forward_transform(Ctx& c, const void* x, void* spec, hipStream_t st, int energy_slot = -1) {
   const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
   hipError_t e;
-  if (c.path == FREQATTN_PATH_MFMA) return forward_transform_mfma(c, x, spec, st, energy_slot);
+  if (c.path == FREQATTN_PATH_MFMA) {
+    const int full[3] = {T, H, W};
+    return forward_transform_mfma(c, x, spec, st, nullptr, c.slices, full, energy_slot, -1);
+  }
   AxisPassArgs a{};
   a.Ntok = c.N; a.slice_mod = c.slices;
   a.in = x; a.out = c.tmp0; a.M = c.d_F32[0]; a.n = a.n_out = T; a.inner = (int64_t)H * W * d; a.outer = 1;
@@ -504,11 +598,22 @@ static hipError_t forward_transform(Ctx& c, const void* x, void* spec, hipStream
 
 // Inverse transform (section 3.7): rows of band l of slice s are read from Y when the band is active for s, else
 // from V~; W axis first (it reads the band-major rows), then H, then T, which writes `out` in the I/O type.
-static hipError_t inverse_transform(Ctx& c, void* out, hipStream_t st) {
+static hipError_t inverse_transform(Ctx& c, void* out, const void* v_in, hipStream_t st) {
   const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
   const int32_t* masks = c.d_lists + c.off_masks;
   hipError_t e;
-  if (c.path == FREQATTN_PATH_MFMA) return inverse_transform_mfma(c, out, st);
+  if (c.path == FREQATTN_PATH_MFMA) {
+    // slices grouped by what they ran: low only / low+mid -> delta form on the box, high -> select form on the whole
+    // grid, nothing -> the output is V itself
+    const int full[3] = {T, H, W};
+    int low[3], mid[3];
+    for (int a = 0; a < 3; ++a) { low[a] = keep_rows(c.low_box[a], full[a]); mid[a] = keep_rows(c.mid_box[a], full[a]); }
+    const int32_t* L = c.d_lists;
+    if ((e = inverse_transform_mfma(c, out, v_in, st, L + c.off_cls[0], c.n_cls[0], low, true)) != hipSuccess) return e;
+    if ((e = inverse_transform_mfma(c, out, v_in, st, L + c.off_cls[1], c.n_cls[1], mid, true)) != hipSuccess) return e;
+    if ((e = inverse_transform_mfma(c, out, v_in, st, L + c.off_cls[2], c.n_cls[2], full, false)) != hipSuccess) return e;
+    return launch_copy_slices(v_in, out, L + c.off_cls[3], c.n_cls[3], c.N * c.d * 2, st);
+  }
   AxisPassArgs a{};
   a.Ntok = c.N; a.slice_mod = c.slices;
   a.in = c.Y; a.in_alt = c.specV; a.masks = masks; a.band_off1 = (int32_t)c.band_off[1];
@@ -567,6 +672,22 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
     c->energy_waves = 0;
     HIP_TRY(c, launch_fill_zero(c->d_energy_part, (int64_t)3 * DCT_MAX_WAVES * 3 * 64, st));
   }
+  if (c->path == FREQATTN_PATH_MFMA && !with_stats) {
+    // allocation known: Q~ and K~ are only needed on the bands a slice runs (none at all for an idle slice)
+    const int full[3] = {c->shape.T, c->shape.H, c->shape.W};
+    int low[3], mid[3];
+    for (int a = 0; a < 3; ++a) { low[a] = keep_rows(c->low_box[a], full[a]); mid[a] = keep_rows(c->mid_box[a], full[a]); }
+    const int32_t* L = c->d_lists;
+    const void* xs[2] = {q, k};
+    void* sp[2] = {c->specQ, c->specK};
+    for (int i = 0; i < 2; ++i) {
+      HIP_TRY(c, forward_transform_mfma(*c, xs[i], sp[i], st, L + c->off_cls[0], c->n_cls[0], low, -1, -1));
+      HIP_TRY(c, forward_transform_mfma(*c, xs[i], sp[i], st, L + c->off_cls[1], c->n_cls[1], mid, -1, -1));
+      HIP_TRY(c, forward_transform_mfma(*c, xs[i], sp[i], st, L + c->off_cls[2], c->n_cls[2], full, -1, -1));
+    }
+    HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, full, -1, -1));
+    return FREQATTN_OK;
+  }
   HIP_TRY(c, forward_transform(*c, q, c->specQ, st, fused_stats ? 0 : -1));
   HIP_TRY(c, forward_transform(*c, k, c->specK, st, fused_stats ? 1 : -1));
   HIP_TRY(c, forward_transform(*c, v, c->specV, st, fused_stats ? 2 : -1));
@@ -577,7 +698,8 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
   return FREQATTN_OK;
 }
 
-static freqattn_status bands_phase(freqattn_ctx* c, float scale, void* out, hipStream_t st, StageTimer& tm) {
+static freqattn_status bands_phase(freqattn_ctx* c, float scale, const void* v_in, void* out, hipStream_t st,
+                                   StageTimer& tm) {
   const bool mf = c->path == FREQATTN_PATH_MFMA;
   const int is_half = mf ? 1 : 0;
   const int32_t* L = c->d_lists;
@@ -661,7 +783,7 @@ static freqattn_status bands_phase(freqattn_ctx* c, float scale, void* out, hipS
   }
 
   // section 3.7: scatter + inverse transform
-  HIP_TRY(c, inverse_transform(*c, out, st));
+  HIP_TRY(c, inverse_transform(*c, out, v_in, st));
   tm.done("inverse_transform");
   return FREQATTN_OK;
 }
@@ -693,7 +815,7 @@ extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, cons
   fs = transforms_phase(c, q, k, v, st, false);
   if (fs != FREQATTN_OK) return fs;
   tm.done("forward_transform");
-  return bands_phase(c, scale, out, st, tm);
+  return bands_phase(c, scale, v, out, st, tm);
 }
 
 static freqattn_status router_from_spectral(freqattn_ctx* c, float t, int32_t hidden, const float* w1, const float* b1,
@@ -721,7 +843,7 @@ extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* 
   fs = ensure_lists(c, head_alloc_out, st);
   if (fs != FREQATTN_OK) return fs;
   tm.done("router");
-  return bands_phase(c, scale, out, st, tm);
+  return bands_phase(c, scale, v, out, st, tm);
 }
 
 

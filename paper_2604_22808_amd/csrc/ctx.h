@@ -83,6 +83,8 @@ struct Ctx {
   void* Cbuf = nullptr;
   float* d_stats = nullptr;                       // router statistics [3][d] (+ partial sums of the generic kernel)
   float* d_energy_part = nullptr;                 // per-wave partial sums of the fused statistics (MFMA path)
+  float* d_tot_part = nullptr;                    // per-wave partial sums of the inputs' squares (Q, K), MFMA path
+  int tot_waves = 0;
   int energy_waves = 0;                           // waves that wrote partial sums in the last fused pass
   int low_box[3] = {0, 0, 0}, mid_box[3] = {0, 0, 0};  // extent of the low / low+mid box per axis
   float* h_stats = nullptr;                       // pinned mirror
@@ -93,6 +95,8 @@ struct Ctx {
   size_t off_masks = 0;               // [slices] band mask per slice
   size_t off_list[3] = {0, 0, 0};     // [slices] slices with band l active
   int n_list[3] = {0, 0, 0};
+  size_t off_cls[4] = {0, 0, 0, 0};   // [slices] slices by class: 0 low only, 1 mid (no high), 2 high, 3 nothing active
+  int n_cls[4] = {0, 0, 0, 0};
   size_t off_items = 0;               // AttnItem array (fused order: all branches), then exchange items
   int n_items_branch = 0;             // low+mid+high items in cost order
   int n_items_kind[3] = {0, 0, 0};    // per-branch sub-lists follow at off_items_kind
@@ -165,14 +169,24 @@ hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, fl
                               int is_half, hipStream_t st);
 // Adds up the per-wave partial sums of the three fused W-axis passes in a fixed order: stats[band][channel].
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
+// out[slice] = in[slice] for the listed slices (slice_bytes each, a multiple of 16).
+hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_list, int n_slices, int64_t slice_bytes,
+                              hipStream_t st);
 hipError_t launch_energy_reduce(const float* energy_part /*[3][DCT_MAX_WAVES][3][64]*/, float* stats, int d,
                                 int n_waves, hipStream_t st);
 
 // ---- MFMA kernels (mfma_dct.hip, mfma_attn.hip) -------------------------------------------------------------------
 struct DctPassArgs {
   const void* in; void* out;
-  const half_t* M;          // [n_out][n] fp16, out[k] = sum_j M[k][j] in[j]
-  int n;
+  const half_t* M;          // fp16, row stride ldm: out[k] = sum_{j < n} M[k*ldm + j] in[j], k < n_out
+  int n, n_out, ldm;        // rows contracted (multiple of 16, <= 128), rows produced (<= 128)
+  // Slices of the caller's tensors: with slice_list set, slice sl of this launch is slice_list[sl] of q/k/v/out, of the
+  // band-major buffers and of masks; list_in / list_out make the regular-layout input / output use it too
+  // (element offset slice*slice_elems + slab_in_slice*rows*inner), otherwise those are compact scratch.
+  const int32_t* slice_list; int list_in, list_out; int64_t slice_elems;
+  int delta;                // gather side: read (in - in_alt) on active bands and zero elsewhere instead of selecting
+  const void* resid;        // bf16, addressed like out: out = resid + result (the sum is formed in fp32)
+  float* tot_part;          // [global wave][64]: sum of squares of the input per column (pass with inner == d only)
   int64_t inner, outer, nslab;
   // Band-major side (section 3.3): with perm_in / perm_out set, row j (k) of the tile at slab s = slice*outer + o and
   // first column col0 is the band-major row perm[j*perm_k + o*perm_o + col0/d] of slice `slice`.
@@ -194,6 +208,7 @@ struct DctPassArgs {
 };
 #define DCT_MAX_WAVES 4096   // upper bound of waves in one launch of the DCT pass (sizes energy_part)
 hipError_t launch_mfma_dct_pass(const DctPassArgs& a, int num_cu, hipStream_t st, int* waves_out = nullptr);
+bool mfma_dct_supported(int n_in, int n_out);
 hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_items, int rows_per_item, int num_cu,
                             hipStream_t st);
 

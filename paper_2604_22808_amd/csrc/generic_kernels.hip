@@ -2,6 +2,8 @@
 // MFMA kernels do not cover), plus the small helper kernels both paths share (pooling, summaries, band energy).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "ctx.h"
 
 namespace fa {
@@ -405,6 +407,22 @@ __global__ void k_fill_zero(float* p, int64_t n) {
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n);
+  return hipGetLastError();
+}
+
+__global__ void k_copy_slices(const uint4* in, uint4* out, const int32_t* slice_list, int64_t vec_per_slice) {
+  const int64_t base = (int64_t)slice_list[blockIdx.y] * vec_per_slice;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < vec_per_slice; i += (int64_t)gridDim.x * blockDim.x)
+    out[base + i] = in[base + i];
+}
+hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_list, int n_slices, int64_t slice_bytes,
+                              hipStream_t st) {
+  if (n_slices <= 0 || slice_bytes <= 0) return hipSuccess;
+  if (slice_bytes % 16) return hipErrorInvalidValue;
+  const int64_t vec = slice_bytes / 16;
+  const unsigned gx = (unsigned)std::min<int64_t>((vec + 255) / 256, 2048);
+  hipLaunchKernelGGL(k_copy_slices, dim3(gx, (unsigned)n_slices), dim3(256), 0, st, (const uint4*)in, (uint4*)out,
+                     slice_list, vec);
   return hipGetLastError();
 }
 

@@ -1,0 +1,375 @@
+#pragma once
+// One axis of the separable DCT (paper sections 3.2, 3.7) as a batched small-matrix contraction on the gfx950
+// matrix cores:  out[s, k, i] = sum_j M[k][j] * in[s, j, i],  s = slab, j/k = position/frequency along the axis,
+// i = everything that is contiguous behind the axis (trailing grid axes times head_dim).
+//
+// Work decomposition: a wave owns a tile of all n rows x 64 contiguous columns.  Rows arrive as coalesced 128-byte
+// segments, are parked row-major in a wave-private LDS buffer 32 rows at a time, and are read back column-wise as
+// the B operand of v_mfma_f32_32x32x16_f16 (lane = column, 8 consecutive j per lane); the A operand is the fp16
+// transform matrix, staged once per workgroup in LDS.  The next 32 rows (of this tile or of the wave's next tile)
+// are fetched while the current 32 are multiplied.  Accumulators are fp32; results go back through the same LDS
+// buffer so that global stores are again full 128-byte rows.  The kernel is bandwidth-bound by design: every element
+// is read once and written once per axis.
+//
+// The pass that touches the band-major spectral buffers (section 3.3) looks rows up through the coefficient ->
+// band-row permutation: on output for the forward transform (scatter), on input for the inverse (gather, with the
+// source buffer chosen per band, section 3.7).  The same forward pass can add up the router's band statistics
+// (section 3.5) from its fp32 results.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+
+#include "ctx.h"
+
+namespace fa {
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+
+#define DCT_WAVES 4
+#define DCT_XS_STRIDE 72  // halfs per staged row: 64 columns + 8 pad (144 bytes keeps 16-byte alignment)
+
+__device__ __forceinline__ uint16_t dct_f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// eight bf16 (as four dwords) -> eight fp16 (exact for every bf16 value inside the fp16 range)
+__device__ __forceinline__ uint4v bf16x8_to_f16x8(uint4v v) {
+  uint4v r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = __uint_as_float(v[i] << 16);
+    const float hi = __uint_as_float(v[i] & 0xffff0000u);
+    const _Float16 hl = (_Float16)lo, hh = (_Float16)hi;
+    r[i] = (uint32_t)__builtin_bit_cast(uint16_t, hl) | ((uint32_t)__builtin_bit_cast(uint16_t, hh) << 16);
+  }
+  return r;
+}
+
+// MODE selects what the pass touches besides plain row-major tensors, so that each variant carries only its own
+// addressing in registers: 0 plain, 1 plain + sum of squares of the input, 2 scatter into the band-major buffer,
+// 3 scatter + router statistics, 4 gather from the band-major buffers.
+enum { DCT_PLAIN = 0, DCT_PLAIN_TOT = 1, DCT_SCATTER = 2, DCT_SCATTER_EN = 3, DCT_GATHER = 4 };
+
+template <int NI, int MT, int MODE>
+__global__ void __launch_bounds__(64 * DCT_WAVES) __attribute__((amdgpu_waves_per_eu(2)))
+k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
+  // NI input rows are contracted into up to 32*MT output rows, of which the first a.n_out are stored.
+  constexpr int RC = (NI % 32 == 0) ? 32 : 16;  // rows staged per step
+  constexpr int NCH = NI / RC;                  // staging steps per tile
+  constexpr int FS = NI + 8;                    // row stride of the matrix in LDS (halfs)
+  constexpr int LPC = RC / 8;                   // 16-byte loads per lane per staging step
+  __shared__ __attribute__((aligned(16))) half_t Fs[32 * MT * FS];
+  __shared__ __attribute__((aligned(16))) half_t Xs_all[DCT_WAVES][32 * DCT_XS_STRIDE];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: tile addressing stays in scalar registers
+  const int nn = lane & 31, g = lane >> 5;
+  constexpr bool PERM_IN = MODE == DCT_GATHER, PERM_OUT = MODE == DCT_SCATTER || MODE == DCT_SCATTER_EN;
+  constexpr bool ENERGY = MODE == DCT_SCATTER_EN, TOT = MODE == DCT_PLAIN_TOT;
+  const int NO = a.n_out;
+  // transform matrix -> LDS, rows beyond n_out zero
+  for (int e = tid; e < 32 * MT * (NI / 8); e += 64 * DCT_WAVES) {
+    const int row = e / (NI / 8), c8 = e % (NI / 8);
+    uint4v v = {0u, 0u, 0u, 0u};
+    if (row < NO) v = *(const uint4v*)(a.M + (size_t)row * a.ldm + c8 * 8);
+    *(uint4v*)(Fs + row * FS + c8 * 8) = v;
+  }
+  __syncthreads();
+
+  half_t* Xs = Xs_all[wave];
+  const int lrow = lane >> 3, lcol = (lane & 7) * 8;  // this lane's row (within 8) and first column of a row segment
+  float en[3][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};  // band x column tile, this lane's rows only
+  float te[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // sum of squares of the input, this lane's 8 columns
+
+  // Per-tile addressing, computed once per tile: rows of a tile are `stride` elements apart from `base`, except on the
+  // band-major side where every row is looked up through the permutation.
+  struct TileAddr {
+    const uint16_t* in_base; int64_t in_stride;   // regular / swapped input
+    int64_t out_off, out_stride;                  // regular / swapped output (element offset into out / resid)
+    int64_t bm_off;                               // band-major side: slice*Ntok (rows), and
+    int32_t pidx, dcol, mask;                     // o*perm_o + col0/d, col0 % d, band mask of the slice
+  };
+  auto tile_addr = [&](uint32_t tile) -> TileAddr {
+    TileAddr t;
+    const uint32_t s = tile / (uint32_t)chunks_per_slab;
+    const int32_t col0 = (int32_t)(tile % (uint32_t)chunks_per_slab) * 64;
+    const uint32_t sl = s / (uint32_t)a.outer;              // slice within this launch
+    const int32_t o = (int32_t)(s % (uint32_t)a.outer);     // slab within the slice
+    const int64_t slice = a.slice_list ? a.slice_list[sl] : (int64_t)sl;   // slice of the caller's tensors
+    t.dcol = 0; t.pidx = 0; t.bm_off = 0; t.mask = 7; t.in_base = nullptr; t.in_stride = 0; t.out_off = 0; t.out_stride = 0;
+    if (PERM_IN || PERM_OUT) {
+      const int32_t ctok = col0 / a.d;
+      t.dcol = col0 - ctok * a.d;
+      t.pidx = o * (int32_t)a.perm_o + ctok;
+      t.bm_off = slice * a.Ntok;
+      if (PERM_IN) t.mask = a.masks[slice];
+    }
+    if (PERM_IN) {
+    } else if (a.in_swap) {
+      const uint32_t sa = s / (uint32_t)a.sw, sb = s % (uint32_t)a.sw;
+      t.in_base = (const uint16_t*)a.in + (((int64_t)sa * NI * a.sw_total + sb + a.sw_off) * a.inner + col0);
+      t.in_stride = (int64_t)a.sw_total * a.inner;
+    } else if (a.list_in) {
+      t.in_base = (const uint16_t*)a.in + (slice * a.slice_elems + (int64_t)o * NI * a.inner + col0);
+      t.in_stride = a.inner;
+    } else {
+      t.in_base = (const uint16_t*)a.in + ((int64_t)s * NI * a.inner + col0);
+      t.in_stride = a.inner;
+    }
+    if (PERM_OUT) {
+    } else if (a.out_swap) {
+      const uint32_t sa = s / (uint32_t)a.sw, sb = s % (uint32_t)a.sw;
+      t.out_off = ((int64_t)sa * NO * a.sw_total + sb + a.sw_off) * a.inner + col0;
+      t.out_stride = (int64_t)a.sw_total * a.inner;
+    } else if (a.list_out) {
+      t.out_off = slice * a.slice_elems + (int64_t)o * NO * a.inner + col0;
+      t.out_stride = a.inner;
+    } else {
+      t.out_off = (int64_t)s * NO * a.inner + col0;
+      t.out_stride = a.inner;
+    }
+    return t;
+  };
+  // this lane's 16-byte piece of input row j
+  auto load_piece = [&](const TileAddr& t, int j) -> uint4v {
+    if (PERM_IN) {
+      const int32_t row = a.perm_in[(int64_t)j * a.perm_k + t.pidx];
+      const int band = row < a.band_off1 ? 0 : (row < a.band_off2 ? 1 : 2);
+      const bool active = (t.mask >> band) & 1;
+      const int64_t off = (t.bm_off + row) * a.d + t.dcol + lcol;
+      if (a.delta) {   // change of the active bands against V~ (zero elsewhere)
+        uint4v r = {0u, 0u, 0u, 0u};
+        if (active) {
+          const half8 y = *(const half8*)((const uint16_t*)a.in + off);
+          const half8 v = *(const half8*)((const uint16_t*)a.in_alt + off);
+          r = __builtin_bit_cast(uint4v, y - v);
+        }
+        return r;
+      }
+      return *(const uint4v*)((const uint16_t*)(active ? a.in : a.in_alt) + off);
+    }
+    return *(const uint4v*)(t.in_base + (int64_t)j * t.in_stride + lcol);
+  };
+
+  const uint32_t tile_step = gridDim.x * DCT_WAVES;
+  uint32_t tile = blockIdx.x * DCT_WAVES + wave;
+  const uint32_t n_tiles32 = (uint32_t)n_tiles;
+  // staging steps requested ahead of their use (of this tile, then of the next); step c lives in R[c % PD], which
+  // carries over to the next tile only when PD divides NCH
+  constexpr int PD = (NCH % 2 == 0) ? 2 : 1;
+  uint4v R[PD][LPC];
+  TileAddr cur, nxt;
+  if (tile < n_tiles32) {
+    cur = tile_addr(tile);
+#pragma unroll
+    for (int ch = 0; ch < PD; ++ch)
+#pragma unroll
+      for (int it = 0; it < LPC; ++it) R[ch][it] = load_piece(cur, ch * RC + it * 8 + lrow);
+  }
+
+  for (; tile < n_tiles32; tile += tile_step) {
+    const bool has_next = tile + tile_step < n_tiles32;
+    if (has_next) nxt = tile_addr(tile + tile_step);
+
+    float16v acc[MT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.f;
+
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int it = 0; it < LPC; ++it) {
+        uint4v v = R[ch % PD][it];
+        if (a.in_bf16) v = bf16x8_to_f16x8(v);
+        if (TOT) {
+          const half8 h = __builtin_bit_cast(half8, v);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) te[j] = fmaf((float)h[j], (float)h[j], te[j]);
+        }
+        *(uint4v*)(Xs + (it * 8 + lrow) * DCT_XS_STRIDE + lcol) = v;
+      }
+      if (ch + PD < NCH) {
+#pragma unroll
+        for (int it = 0; it < LPC; ++it) R[ch % PD][it] = load_piece(cur, (ch + PD) * RC + it * 8 + lrow);
+      } else if (has_next) {
+#pragma unroll
+        for (int it = 0; it < LPC; ++it) R[ch % PD][it] = load_piece(nxt, (ch + PD - NCH) * RC + it * 8 + lrow);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int ks = 0; ks < RC / 16; ++ks) {
+        half8 B[2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int jj = 0; jj < 8; ++jj) B[nt][jj] = Xs[(ks * 16 + g * 8 + jj) * DCT_XS_STRIDE + nt * 32 + nn];
+        const int kglob = ch * RC + ks * 16 + g * 8;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const half8 A = *(const half8*)(Fs + (mt * 32 + nn) * FS + kglob);
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, B[nt], acc[mt][nt], 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    }
+
+    if (ENERGY) {
+      // flat index over the two axes the pass does not transform (perm_o == tokens per slab row on this pass)
+      const int32_t other = cur.pidx;
+      const int u = other / a.en_div, v = other % a.en_div;
+      const int t1 = (u < a.low_u && v < a.low_v) ? a.low_a : 0;
+      const int t2 = (u < a.mid_u && v < a.mid_v) ? a.mid_a : 0;
+      const float f1 = (float)(t1 - 4 * g), f2 = (float)(t2 - 4 * g);
+      // en[0] collects rows below t1, en[1] rows below t2, en[2] all rows; the bands are differences of these
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          // row = rc + 4*g; row < t  <=>  clamp(t - row, 0, 1) == 1 for integers (kept in floats: no lane masks to hold)
+          const float rc = (float)(mt * 32 + 8 * (r >> 2) + (r & 3));
+          const float w1 = __builtin_amdgcn_fmed3f(f1 - rc, 0.f, 1.f), w2 = __builtin_amdgcn_fmed3f(f2 - rc, 0.f, 1.f);
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt) {
+            const float v2 = acc[mt][nt][r] * acc[mt][nt][r];   // rows >= n_out hold exact zeros
+            en[0][nt] = fmaf(v2, w1, en[0][nt]);
+            en[1][nt] = fmaf(v2, w2, en[1][nt]);
+            en[2][nt] += v2;
+          }
+        }
+    }
+
+    // epilogue: 32 output rows at a time through the staging buffer
+    uint16_t* Xo = (uint16_t*)Xs;
+    const bool stage_bf16 = a.out_bf16 && (PERM_OUT || !a.resid);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      if (mt * 32 >= NO) break;
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = 8 * (r >> 2) + 4 * g + (r & 3);
+          const float val = acc[mt][nt][r];
+          uint16_t bits;
+          if (stage_bf16) bits = dct_f32_to_bf16(val);
+          else { const _Float16 hv = (_Float16)val; bits = __builtin_bit_cast(uint16_t, hv); }
+          Xo[row * DCT_XS_STRIDE + nt * 32 + nn] = bits;
+        }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int k = mt * 32 + it * 8 + lrow;
+        if (k < NO) {
+          uint4v v = *(const uint4v*)(Xo + (it * 8 + lrow) * DCT_XS_STRIDE + lcol);
+          int64_t off;
+          if (PERM_OUT) off = (cur.bm_off + a.perm_out[(int64_t)k * a.perm_k + cur.pidx]) * a.d + cur.dcol;
+          else off = cur.out_off + (int64_t)k * cur.out_stride;
+          if (!PERM_OUT && a.resid) {   // out = resid + result, both bf16 in memory, the sum formed in fp32
+            const uint4v rs = *(const uint4v*)((const uint16_t*)a.resid + off + lcol);
+            const half8 h = __builtin_bit_cast(half8, v);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float lo = __uint_as_float(rs[i] << 16) + (float)h[2 * i];
+              const float hi = __uint_as_float(rs[i] & 0xffff0000u) + (float)h[2 * i + 1];
+              v[i] = (uint32_t)dct_f32_to_bf16(lo) | ((uint32_t)dct_f32_to_bf16(hi) << 16);
+            }
+          }
+          *(uint4v*)((uint16_t*)a.out + off + lcol) = v;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    }
+    cur = nxt;
+  }
+  if (ENERGY || TOT) {
+    const int gwave = blockIdx.x * DCT_WAVES + wave;
+    if (ENERGY) {
+#pragma unroll
+      for (int b = 0; b < 3; ++b)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          // band sums from the prefix sums: low = below t1, mid = below t2 minus below t1, high = all minus below t2
+          const float mine = b == 0 ? en[0][nt] : b == 1 ? en[1][nt] - en[0][nt] : en[2][nt] - en[1][nt];
+          const float tot = mine + __shfl_xor(mine, 32);
+          float* slot = a.energy_part + ((size_t)gwave * 3 + b) * 64 + nt * 32 + nn;
+          if (g == 0) *slot = *slot + tot;   // launches on one stream are ordered: no other writer of this slot
+        }
+    }
+    if (TOT) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float t = te[j];
+        t += __shfl_xor(t, 8); t += __shfl_xor(t, 16); t += __shfl_xor(t, 32);   // lanes that share lane & 7
+        float* slot = a.tot_part + (size_t)gwave * 64 + lcol + j;
+        if (lane < 8) *slot = *slot + t;
+      }
+    }
+  }
+}
+
+template <int NI, int MT, int MODE>
+static hipError_t launch_n(const DctPassArgs& a, int num_cu, hipStream_t st, int* waves_out) {
+  const int chunks = (int)(a.inner / 64);
+  const int64_t n_tiles = a.nslab * chunks;
+  if (n_tiles == 0) return hipSuccess;
+  if (n_tiles > 0x7fffffff) return hipErrorInvalidValue;
+  // workgroups per CU: bounded by the 160 KB of LDS of a gfx950 CU (the runtime's occupancy query assumes 64 KB)
+  constexpr int lds_bytes = (32 * MT * (NI + 8) + DCT_WAVES * 32 * DCT_XS_STRIDE) * 2;
+  static int occ = 0;
+  if (occ == 0) {
+    const char* e = getenv("FREQATTN_DCT_OCC");
+    occ = (e && atoi(e) > 0) ? atoi(e) : std::min(4, (160 * 1024) / lds_bytes);
+  }
+  int64_t blocks = (n_tiles + DCT_WAVES - 1) / DCT_WAVES;
+  int64_t cap = (int64_t)num_cu * occ;
+  if (cap * DCT_WAVES > DCT_MAX_WAVES) cap = DCT_MAX_WAVES / DCT_WAVES;
+  if (blocks > cap) blocks = cap;
+  if (MODE == DCT_SCATTER_EN || MODE == DCT_PLAIN_TOT) {
+    // every wave must keep one column chunk for all its tiles: the tile stride has to be a multiple of the chunks
+    // per head_dim (columns of a token).  The partial-sum slots are accumulated into; the caller zeroes them first.
+    const int cpt = a.d / 64;
+    if ((blocks * DCT_WAVES) % cpt != 0 || !waves_out || (a.energy_part && !a.perm_out) || (a.tot_part && a.inner != a.d))
+      return hipErrorInvalidValue;
+    if ((int)(blocks * DCT_WAVES) > *waves_out) *waves_out = (int)(blocks * DCT_WAVES);
+  }
+  hipLaunchKernelGGL((k_dct_pass<NI, MT, MODE>), dim3((unsigned)blocks), dim3(64 * DCT_WAVES), 0, st, a, n_tiles, chunks);
+  return hipGetLastError();
+}
+
+
+// Size dispatch of one mode; every translation unit that includes this file instantiates one mode.
+template <int MODE>
+static hipError_t dispatch_mode(const DctPassArgs& a, int num_cu, hipStream_t st, int* waves_out) {
+  int mt = (a.n_out + 31) / 32;
+  if (mt == 3 && (a.n == 16 || a.n == 32 || a.n == 64 || a.n == 128)) mt = 4;
+#define FA_DCT_CASE(NI_, MT_) if (a.n == NI_ && mt == MT_) return launch_n<NI_, MT_, MODE>(a, num_cu, st, waves_out);
+  FA_DCT_CASE(16, 1) FA_DCT_CASE(16, 2) FA_DCT_CASE(16, 4)
+  FA_DCT_CASE(32, 1) FA_DCT_CASE(32, 2) FA_DCT_CASE(32, 4)
+  FA_DCT_CASE(64, 1) FA_DCT_CASE(64, 2) FA_DCT_CASE(64, 4)
+  FA_DCT_CASE(128, 1) FA_DCT_CASE(128, 2) FA_DCT_CASE(128, 4)
+  FA_DCT_CASE(48, 2) FA_DCT_CASE(80, 3) FA_DCT_CASE(96, 3) FA_DCT_CASE(112, 4)
+#undef FA_DCT_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+}  // namespace fa

@@ -232,3 +232,19 @@ def test_64k_router_in_the_loop_matches_oracle():
     ctx.forward(dq, dk, dv, alloc, out2)
     torch.cuda.synchronize()
     assert torch.equal(out, out2)
+
+
+def test_16k_mask_classes_bf16():
+    """Every class of band mask on the MFMA path: idle head (out = V exactly), low+high, low+mid, mid+high, and the
+    one-hot masks, in one context (heads that only run the low / low+mid bands take the pruned transforms)."""
+    wl = WL.WORKLOADS["16k"]
+    heads = [0, 1, 2, 3, 4, 5, 6]
+    alloc = (0, 5, 3, 6, 1, 2, 4)
+    q, k, v = _inputs(wl, heads=heads)
+    ctx, band = U.make_ctx(wl, heads=len(heads))
+    assert ctx.get_path() == B.PATH_MFMA
+    got = U.run_forward(ctx, q, k, v, wl.dtype, alloc)
+    want = O.forward(q, k, v, wl.grid, U.oracle_cfg(band), alloc)
+    assert np.array_equal(got[0, 0], v[0, 0])          # nothing active: the library returns V itself
+    for s in range(len(heads)):
+        _check(got[0, s], want[0, s], "bf16", f"16k mask {alloc[s]}")
