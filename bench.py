@@ -159,6 +159,27 @@ def main():
     value = tokens / (elapsed / args.steps)
 
     work = algorithmic_work(wl, ctx, alloc)
+    # the forward transform may be split in two stages (completion of Q~/K~ for the heads routed to the high band)
+    merged, extra = [], 0.0
+    for name, ms in stages:
+        if name == "forward_transform_high_qk":
+            extra += ms
+        else:
+            merged.append([name, ms])
+    for e in merged:
+        if e[0] == "forward_transform":
+            e[1] += extra
+    stages = [tuple(e) for e in merged]
+    masks = [int(a) for a in alloc]
+    cls_present = [any((m & 4) == 0 and (m & 2) == 0 and (m & 1) for m in masks), any((m & 4) == 0 and (m & 2) for m in masks),
+                   any(m & 4 for m in masks)]
+    if router is not None:
+        fwd_launches = 9 + (6 if cls_present[2] else 0)
+    else:
+        fwd_launches = 3 + 6 * sum(cls_present)
+    inv_launches = 3 * sum(cls_present) + (1 if any(m == 0 for m in masks) else 0)
+    work["forward_transform"] = (work["forward_transform"][0], work["forward_transform"][1], fwd_launches)
+    work["inverse_transform"] = (work["inverse_transform"][0], work["inverse_transform"][1], max(1, inv_launches))
     stage_report = {}
     for name, ms in stages:
         entry = {"ms": round(ms, 4)}

@@ -669,8 +669,22 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
                                         bool with_stats) {
   const bool fused_stats = with_stats && c->path == FREQATTN_PATH_MFMA;
   if (fused_stats) {
-    c->energy_waves = 0;
+    // Router in the loop: the allocation is not known yet.  V~ is needed everywhere; Q~ and K~ are computed on the
+    // low+mid box only, which gives their low and mid statistics exactly and their high-band energy by Parseval;
+    // slices that turn out to run the high band get their Q~ and K~ completed afterwards (complete_qk_for_high).
+    const int full[3] = {c->shape.T, c->shape.H, c->shape.W};
+    int mid[3];
+    bool pruned = false;
+    for (int a = 0; a < 3; ++a) { mid[a] = keep_rows(c->mid_box[a], full[a]); pruned = pruned || mid[a] < full[a]; }
+    c->energy_waves = 0; c->tot_waves = 0; c->qk_on_mid_box = pruned;
     HIP_TRY(c, launch_fill_zero(c->d_energy_part, (int64_t)3 * DCT_MAX_WAVES * 3 * 64, st));
+    if (pruned) HIP_TRY(c, launch_fill_zero(c->d_tot_part, (int64_t)2 * DCT_MAX_WAVES * 64, st));
+    HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, nullptr, c->slices, pruned ? mid : full, 0, pruned ? 0 : -1));
+    HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, nullptr, c->slices, pruned ? mid : full, 1, pruned ? 1 : -1));
+    HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, full, 2, -1));
+    HIP_TRY(c, launch_energy_reduce(c->d_energy_part, pruned ? c->d_tot_part : nullptr, c->d_stats, c->d, c->energy_waves,
+                                    c->tot_waves, st));
+    return FREQATTN_OK;
   }
   if (c->path == FREQATTN_PATH_MFMA && !with_stats) {
     // allocation known: Q~ and K~ are only needed on the bands a slice runs (none at all for an idle slice)
@@ -688,13 +702,22 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
     HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, full, -1, -1));
     return FREQATTN_OK;
   }
-  HIP_TRY(c, forward_transform(*c, q, c->specQ, st, fused_stats ? 0 : -1));
-  HIP_TRY(c, forward_transform(*c, k, c->specK, st, fused_stats ? 1 : -1));
-  HIP_TRY(c, forward_transform(*c, v, c->specV, st, fused_stats ? 2 : -1));
-  if (fused_stats) HIP_TRY(c, launch_energy_reduce(c->d_energy_part, c->d_stats, c->d, c->energy_waves, st));
-  else if (with_stats)
+  HIP_TRY(c, forward_transform(*c, q, c->specQ, st));
+  HIP_TRY(c, forward_transform(*c, k, c->specK, st));
+  HIP_TRY(c, forward_transform(*c, v, c->specV, st));
+  if (with_stats)
     HIP_TRY(c, launch_band_energy(c->specQ, c->specK, c->specV, c->d_stats, c->slices, c->N, c->d, c->band_off, c->band_n,
                                   0, st));
+  return FREQATTN_OK;
+}
+
+// After routing with Q~ and K~ on the low+mid box only: the slices that run the high band get the full transforms.
+static freqattn_status complete_qk_for_high(freqattn_ctx* c, const void* q, const void* k, hipStream_t st) {
+  if (c->path != FREQATTN_PATH_MFMA || !c->qk_on_mid_box || c->n_cls[2] == 0) return FREQATTN_OK;
+  const int full[3] = {c->shape.T, c->shape.H, c->shape.W};
+  const int32_t* list = c->d_lists + c->off_cls[2];
+  HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, list, c->n_cls[2], full, -1, -1));
+  HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, list, c->n_cls[2], full, -1, -1));
   return FREQATTN_OK;
 }
 
@@ -843,6 +866,9 @@ extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* 
   fs = ensure_lists(c, head_alloc_out, st);
   if (fs != FREQATTN_OK) return fs;
   tm.done("router");
+  fs = complete_qk_for_high(c, q, k, st);
+  if (fs != FREQATTN_OK) return fs;
+  tm.done("forward_transform_high_qk");
   return bands_phase(c, scale, v, out, st, tm);
 }
 

@@ -85,6 +85,7 @@ struct Ctx {
   float* d_energy_part = nullptr;                 // per-wave partial sums of the fused statistics (MFMA path)
   float* d_tot_part = nullptr;                    // per-wave partial sums of the inputs' squares (Q, K), MFMA path
   int tot_waves = 0;
+  bool qk_on_mid_box = false;                     // the last routed transforms left Q~, K~ on the low+mid box only
   int energy_waves = 0;                           // waves that wrote partial sums in the last fused pass
   int low_box[3] = {0, 0, 0}, mid_box[3] = {0, 0, 0};  // extent of the low / low+mid box per axis
   float* h_stats = nullptr;                       // pinned mirror
@@ -172,8 +173,9 @@ hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 // out[slice] = in[slice] for the listed slices (slice_bytes each, a multiple of 16).
 hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_list, int n_slices, int64_t slice_bytes,
                               hipStream_t st);
-hipError_t launch_energy_reduce(const float* energy_part /*[3][DCT_MAX_WAVES][3][64]*/, float* stats, int d,
-                                int n_waves, hipStream_t st);
+hipError_t launch_energy_reduce(const float* energy_part /*[3][DCT_MAX_WAVES][3][64]*/,
+                                const float* tot_part /*[2][DCT_MAX_WAVES][64] or NULL*/, float* stats, int d,
+                                int n_waves, int n_waves_tot, hipStream_t st);
 
 // ---- MFMA kernels (mfma_dct.hip, mfma_attn.hip) -------------------------------------------------------------------
 struct DctPassArgs {

@@ -429,16 +429,29 @@ hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_li
 // Fixed-order sum of the per-wave partial statistics written by the fused forward passes of Q, K and V.
 // Wave w of a launch worked on column chunk w % (d/64) only.  One workgroup per (band, channel): 256 threads take
 // the (tensor, wave) terms round-robin and a fixed tree adds their partial sums.
-__global__ void __launch_bounds__(256) k_energy_reduce(const float* part, float* stats, int d, int n_waves) {
+// With tot_part set, Q~ and K~ (tensors 0 and 1) were only computed on the low+mid box: their high-band energy is the
+// energy of the input (Parseval, the transform is orthonormal) minus their low and mid energies.
+__global__ void __launch_bounds__(256) k_energy_reduce(const float* part, const float* tot_part, float* stats, int d,
+                                                       int n_waves, int n_waves_tot) {
   __shared__ float red[256];
   const int idx = blockIdx.x, tid = threadIdx.x;
   const int band = idx / d, ch = idx % d;
   const int chunks = d / 64, chunk = ch / 64, col = ch % 64;
   const int per = (n_waves - chunk + chunks - 1) / chunks;   // waves of this chunk
+  const bool parseval = tot_part != nullptr && band == 2;
   float t = 0.f;
   for (int i = tid; i < 3 * per; i += 256) {
     const int tensor = i / per, w = chunk + (i % per) * chunks;
-    t += part[(((size_t)tensor * DCT_MAX_WAVES + w) * 3 + band) * 64 + col];
+    const float* p3 = part + (((size_t)tensor * DCT_MAX_WAVES + w) * 3) * 64 + col;
+    if (parseval && tensor < 2) t -= p3[0] + p3[64];
+    else t += p3[band * 64];
+  }
+  if (parseval) {
+    const int per_t = (n_waves_tot - chunk + chunks - 1) / chunks;
+    for (int i = tid; i < 2 * per_t; i += 256) {
+      const int tensor = i / per_t, w = chunk + (i % per_t) * chunks;
+      t += tot_part[((size_t)tensor * DCT_MAX_WAVES + w) * 64 + col];
+    }
   }
   red[tid] = t;
   __syncthreads();
@@ -449,8 +462,9 @@ __global__ void __launch_bounds__(256) k_energy_reduce(const float* part, float*
   if (tid == 0) stats[idx] = red[0];
 }
 
-hipError_t launch_energy_reduce(const float* energy_part, float* stats, int d, int n_waves, hipStream_t st) {
-  hipLaunchKernelGGL(k_energy_reduce, dim3(3 * d), dim3(256), 0, st, energy_part, stats, d, n_waves);
+hipError_t launch_energy_reduce(const float* energy_part, const float* tot_part, float* stats, int d, int n_waves,
+                                int n_waves_tot, hipStream_t st) {
+  hipLaunchKernelGGL(k_energy_reduce, dim3(3 * d), dim3(256), 0, st, energy_part, tot_part, stats, d, n_waves, n_waves_tot);
   return hipGetLastError();
 }
 
