@@ -51,7 +51,7 @@ __device__ __forceinline__ uint32_t pack_h2(float a, float b) {
   return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
 }
 
-template <int D, int NW, int QT>
+template <int D, int NW, int QT, bool BF16IN>
 __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2 : 1) k_attn(AttnParams p, const AttnItem* __restrict__ items, int n_items) {
   constexpr int KS = D + 8;     // row stride of the K tile in LDS (halfs): rows shift by 16 bytes against the banks
   constexpr int VS = KT + 8;    // row stride of the transposed V tile (halfs)
@@ -77,7 +77,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
     const uint16_t *Qp, *Kp, *Vp;
     uint16_t* Op;
     int nq, nk;
-    bool in_bf16 = false;
+    constexpr bool in_bf16 = BF16IN;   // only the dense comparison reads bf16 tensors
     if (kind == 0) {
       const int64_t o = slice * p.nbar * D;
       Qp = (const uint16_t*)p.lowQ + o; Kp = (const uint16_t*)p.lowK + o; Vp = (const uint16_t*)p.lowV + o;
@@ -93,7 +93,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
     } else {
       const int64_t o = slice * p.N * D;
       Qp = (const uint16_t*)p.denseQ + o; Kp = (const uint16_t*)p.denseK + o; Vp = (const uint16_t*)p.denseV + o;
-      Op = (uint16_t*)p.denseO + o; nq = nk = p.N; in_bf16 = p.dense_bf16 != 0;
+      Op = (uint16_t*)p.denseO + o; nq = nk = p.N;
     }
     const int w = p.high_window;
     const int r0 = q0 + WROWS * wave;   // first query row of this wave
@@ -157,7 +157,28 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       if (kind == 1) return (p.mid_col_idx[e0 + idx / sub_n] * sub_n + idx % sub_n) * KT;
       return (t_lo + idx) * KT;
     };
+    // Per-thread staging geometry, fixed for the whole item: piece u of the K tile is row krow[u], 16-byte column kc8;
+    // V unit u is the four keys 4*vkg[u] .. +3 of channel octet vc8.  Tiles inside the band take the fast path (no
+    // bounds tests, one 64-bit add per load).
+    const int kc8 = tid % (D / 8), krow0 = tid / (D / 8);
+    constexpr int KROWS_PER_STEP = NT / (D / 8);
+    const uint16_t* kthread = Kp + (int64_t)krow0 * D + kc8 * 8;
+    const uint16_t* vthread = Vp + (int64_t)(krow0 * 4) * D + kc8 * 8;   // V units use the same (row group, octet) split
     auto load_tile = [&](int key0) {
+      if (key0 + KT <= nk) {
+        const uint16_t* kp = kthread + (int64_t)key0 * D;
+        const uint16_t* vp = vthread + (int64_t)key0 * D;
+#pragma unroll
+        for (int u = 0; u < KPT; ++u)
+          if (KT * (D / 8) % NT == 0 || tid + u * NT < KT * (D / 8)) Kreg[u] = *(const uint4v*)(kp + (int64_t)u * KROWS_PER_STEP * D);
+#pragma unroll
+        for (int u = 0; u < VPT; ++u)
+          if ((KT / 4) * (D / 8) % NT == 0 || tid + u * NT < (KT / 4) * (D / 8)) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) Vreg[u][b] = *(const uint4v*)(vp + (int64_t)(u * KROWS_PER_STEP * 4 + b) * D);
+          }
+        return;
+      }
 #pragma unroll
       for (int u = 0; u < KPT; ++u) {
         const int e = tid + u * NT;
@@ -179,41 +200,37 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
         }
       }
     };
+    // LDS destinations of this thread's pieces (constant for the item)
+    half_t* ks_dst = Ks + krow0 * KS + kc8 * 8;
     auto store_tile = [&]() {
 #pragma unroll
       for (int u = 0; u < KPT; ++u) {
-        const int e = tid + u * NT;
-        const int kr = e / (D / 8), c8 = e % (D / 8);
         uint4v v = Kreg[u];
         if (in_bf16) v = at_bf16x8_to_f16x8(v);
-        if (e < KT * (D / 8)) *(uint4v*)(Ks + kr * KS + c8 * 8) = v;
+        if (KT * (D / 8) % NT == 0 || tid + u * NT < KT * (D / 8)) *(uint4v*)(ks_dst + u * KROWS_PER_STEP * KS) = v;
       }
 #pragma unroll
       for (int u = 0; u < VPT; ++u) {
-        const int e = tid + u * NT;
-        const int kg = e / (D / 8), c8 = e % (D / 8);
+        const int kg = krow0 + u * KROWS_PER_STEP, c8 = kc8;
         uint4v rws[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) rws[b] = in_bf16 ? at_bf16x8_to_f16x8(Vreg[u][b]) : Vreg[u][b];
         // tile-local key kk = 4*kg + b = 32*t2 + 16*s + 8*a + 4*gg + b lives in 16-byte chunk x = 4*t2 + 2*s + gg of its
-        // channel row, half a of the chunk; chunks are XOR-swizzled with the row's channel octet so that the 8-byte
-        // stores of a wave (rows 8 apart) spread over the banks.
+        // channel row, half a of the chunk.  Chunks are XOR-swizzled with bits 4..6 of the row: the 16 lanes of an
+        // operand read (16 consecutive rows) share one swizzle and stay conflict-free, while the 8-byte stores of a
+        // wave (rows 8 apart) spread over all banks.
         const int kk = kg * 4;
         const int x = ((kk >> 4) << 1) | ((kk >> 2) & 1);
         const int ahalf = (kk >> 3) & 1;
-        const int pos = ((x ^ (c8 & 7)) << 3) | (ahalf << 2);
-        if (e < (KT / 4) * (D / 8)) {
+        const int pos = ((x ^ ((c8 >> 1) & 7)) << 3) | (ahalf << 2);
+        if ((KT / 4) * (D / 8) % NT == 0 || tid + u * NT < (KT / 4) * (D / 8)) {
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             const int wd = i >> 1;
-            uint2v o2;
-            if (i & 1) {
-              o2[0] = (rws[0][wd] >> 16) | (rws[1][wd] & 0xffff0000u);
-              o2[1] = (rws[2][wd] >> 16) | (rws[3][wd] & 0xffff0000u);
-            } else {
-              o2[0] = (rws[0][wd] & 0xffffu) | (rws[1][wd] << 16);
-              o2[1] = (rws[2][wd] & 0xffffu) | (rws[3][wd] << 16);
-            }
+            uint2v o2;   // halves i of rows 0..3: byte selectors pick the low (0x05040100) or high (0x07060302) halves
+            const unsigned sel = (i & 1) ? 0x07060302u : 0x05040100u;
+            o2[0] = __builtin_amdgcn_perm(rws[1][wd], rws[0][wd], sel);
+            o2[1] = __builtin_amdgcn_perm(rws[3][wd], rws[2][wd], sel);
             *(uint2v*)(Vt + (c8 * 8 + i) * VS + pos) = o2;
           }
         }
@@ -246,17 +263,35 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
           for (int r = 0; r < 16; ++r) S[qt][t2][r] = 0.f;
+      // K operands are requested PF steps ahead of the MFMA that consumes them, so LDS latency overlaps the matrix core
+      constexpr int PF = 4;
+      {
+        constexpr int NS = 2 * DK;
+        half8 Abuf[PF];
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
+        for (int i = 0; i < PF; ++i) Abuf[i] = *(const half8*)(Ks + ((i / DK) * 32 + nn) * KS + (i % DK) * 16 + g * 8);
 #pragma unroll
-        for (int ks = 0; ks < DK; ++ks) {
-          const half8 A = *(const half8*)(Ks + (t2 * 32 + nn) * KS + ks * 16 + g * 8);
+        for (int i = 0; i < NS; ++i) {
+          const int t2 = i / DK, ks = i % DK;
+          const half8 A = Abuf[i % PF];
+          if (i + PF < NS)
+            Abuf[i % PF] = *(const half8*)(Ks + (((i + PF) / DK) * 32 + nn) * KS + ((i + PF) % DK) * 16 + g * 8);
 #pragma unroll
           for (int qt = 0; qt < QT; ++qt) {
             const half8 Bq = QLDS ? *(const half8*)(Qw + (32 * qt + nn) * KS + ks * 16 + g * 8) : Qr[QLDS ? 0 : qt][QLDS ? 0 : ks];
             S[qt][t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Bq, S[qt][t2], 0, 0, 0);
           }
         }
+        if (!QLDS) {   // pin the order: PF reads up front, then one read per MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
+#pragma unroll
+          for (int i = 0; i < NS - PF; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, QT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, PF * QT, 0);
+        }
+      }
       // ---- mask, running softmax (lane = query row; registers = keys)
       half8 P[QT][2][2];
       bool any_rescale = false;
@@ -313,19 +348,27 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
             for (int r = 0; r < 16; ++r) O[qt][dt][r] *= alpha[qt];
       }
       // ---- O^T += V^T P^T; a V operand feeds all query tiles of the wave
+      {
+        constexpr int NS = 4 * DT;   // (t2, s2, dt) flattened, dt fastest
+        auto vptr = [&](int i) -> const half8* {
+          const int dt = i % DT, ts = i / DT;   // ts = t2 * 2 + s2
+          const int vrow = dt * 32 + nn;
+          const int x = ts * 2 + g;
+          return (const half8*)(Vt + vrow * VS + ((x ^ ((vrow >> 4) & 7)) << 3));
+        };
+        half8 Abuf[PF];
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
+        for (int i = 0; i < PF; ++i) Abuf[i] = *vptr(i);
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
+        for (int i = 0; i < NS; ++i) {
+          const int dt = i % DT, ts = i / DT;
+          const half8 A = Abuf[i % PF];
+          if (i + PF < NS) Abuf[i % PF] = *vptr(i + PF);
 #pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            const int vrow = dt * 32 + nn;
-            const int x = (t2 * 2 + s2) * 2 + g;
-            const half8 A = *(const half8*)(Vt + vrow * VS + ((x ^ ((vrow >> 3) & 7)) << 3));
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt)
-              O[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[qt][t2][s2], O[qt][dt], 0, 0, 0);
-          }
+          for (int qt = 0; qt < QT; ++qt)
+            O[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[qt][ts >> 1][ts & 1], O[qt][dt], 0, 0, 0);
+        }
+      }
     }
 
     // ---- epilogue: normalise, optional residual, store 4 consecutive channels per register group
@@ -365,7 +408,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
   }
 }
 
-template <int D, int NW, int QT>
+template <int D, int NW, int QT, bool BF16IN>
 static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_items, int num_cu, hipStream_t st) {
   // resident workgroups per CU: register-limited waves per SIMD (accumulators of QT query tiles), 4 SIMDs per CU
   const int waves_per_simd = (QT == 1 && (D == 64 || NW == 4)) ? 2 : 1;   // matches the kernel's launch bounds
@@ -373,17 +416,19 @@ static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_it
   if (occ < 1) occ = 1;
   int64_t blocks = (int64_t)num_cu * occ;
   if (blocks > n_items) blocks = n_items;
-  hipLaunchKernelGGL((k_attn<D, NW, QT>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
+  hipLaunchKernelGGL((k_attn<D, NW, QT, BF16IN>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
   return hipGetLastError();
 }
 
 hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_items, int rows_per_item, int num_cu,
                             hipStream_t st) {
   if (n_items <= 0) return hipSuccess;
-  if (p.d == 64 && rows_per_item == 64) return launch_dn<64, 2, 1>(p, items, n_items, num_cu, st);
-  if (p.d == 64 && rows_per_item == 128) return launch_dn<64, 4, 1>(p, items, n_items, num_cu, st);
-  if (p.d == 128 && rows_per_item == 64) return launch_dn<128, 2, 1>(p, items, n_items, num_cu, st);
-  if (p.d == 128 && rows_per_item == 128) return launch_dn<128, 4, 1>(p, items, n_items, num_cu, st);
+  const bool bf = p.denseQ != nullptr && p.dense_bf16;   // the dense comparison reads the caller's bf16 tensors
+#define FA_ATTN_CASE(D_, R_, NW_) \
+  if (p.d == D_ && rows_per_item == R_) \
+    return bf ? launch_dn<D_, NW_, 1, true>(p, items, n_items, num_cu, st) : launch_dn<D_, NW_, 1, false>(p, items, n_items, num_cu, st);
+  FA_ATTN_CASE(64, 64, 2) FA_ATTN_CASE(64, 128, 4) FA_ATTN_CASE(128, 64, 2) FA_ATTN_CASE(128, 128, 4)
+#undef FA_ATTN_CASE
   return hipErrorInvalidValue;
 }
 
