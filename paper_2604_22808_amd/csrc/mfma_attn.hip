@@ -24,6 +24,7 @@ namespace fa {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
@@ -61,15 +62,22 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
   constexpr int ROWS = 32 * QT * NW;  // query rows per item
   constexpr int WROWS = 32 * QT;      // query rows per wave
   constexpr bool QLDS = QT > 1;  // with two query tiles per wave the Q operands live in (wave-private) LDS, not registers
-  __shared__ __attribute__((aligned(16))) half_t Ks[KT * KS];
-  __shared__ __attribute__((aligned(16))) half_t Vt[D * VS];
+  // two copies of the K / V^T tiles: tile i+1 is written while tile i is still being read, one barrier per tile
+  __shared__ __attribute__((aligned(16))) half_t Ks2[2][KT * KS];
+  __shared__ __attribute__((aligned(16))) half_t Vt2[2][D * VS];
   __shared__ __attribute__((aligned(16))) half_t Qs[QLDS ? ROWS * KS : 8];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nn = lane & 31, g = lane >> 5;
   const float c2 = p.scale * 1.4426950408889634f;  // folded into Q: scores come out of the MFMA in units of log2
 
-  for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+  // Workgroups are dealt to the 8 XCDs round-robin by blockIdx, and each XCD has its own L2.  Consecutive items are
+  // neighbouring query tiles of one slice, which visit largely the same K/V tiles (all of them in the dense branches,
+  // most of the window in the high band): each round of gridDim.x items is cut into 8 contiguous runs, one per XCD,
+  // so that those tiles are fetched into one L2 once instead of into all eight.
+  int it_first = blockIdx.x;
+  if ((gridDim.x & 7) == 0) it_first = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  for (int it = it_first; it < n_items; it += gridDim.x) {
     const AttnItem item = items[it];
     const int kind = item.kind_band & 0xff, band = item.kind_band >> 8;
     const int64_t slice = item.slice;
@@ -201,8 +209,9 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       }
     };
     // LDS destinations of this thread's pieces (constant for the item)
-    half_t* ks_dst = Ks + krow0 * KS + kc8 * 8;
-    auto store_tile = [&]() {
+    auto store_tile = [&](int buf) {
+      half_t* ks_dst = Ks2[buf] + krow0 * KS + kc8 * 8;
+      half_t* Vt = Vt2[buf];
 #pragma unroll
       for (int u = 0; u < KPT; ++u) {
         uint4v v = Kreg[u];
@@ -237,13 +246,23 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       }
     };
 
-    if (n_tt > 0) load_tile(key0_of(0));
-    for (int idx = 0; idx < n_tt; ++idx) {
+    // Pipeline: at the top of iteration i the registers hold tile i+1 (requested one iteration ago); it goes into the
+    // LDS copy that tile i-1 used - free since the barrier that ended iteration i-1 - and the loads of tile i+2 are
+    // issued, a whole iteration ahead of their use.  The barrier at the end of the iteration publishes tile i+1.
+    if (n_tt > 0) {   // (the barrier that ended the previous item's last tile already freed both copies)
+      load_tile(key0_of(0));
+      store_tile(0);
+      if (n_tt > 1) load_tile(key0_of(1));
+    }
+    __syncthreads();
+    for (int idx = 0; idx < n_tt; ++idx, __syncthreads()) {
       const int key0 = key0_of(idx);
-      __syncthreads();
-      store_tile();
-      __syncthreads();
-      if (idx + 1 < n_tt) load_tile(key0_of(idx + 1));
+      const half_t* Ks = Ks2[idx & 1];
+      const half_t* Vt = Vt2[idx & 1];
+      if (idx + 1 < n_tt) {
+        store_tile((idx + 1) & 1);
+        if (idx + 2 < n_tt) load_tile(key0_of(idx + 2));
+      }
       if (key0 >= nk) continue;  // block tail beyond the band (uniform over the workgroup)
 
       // ---- does this wave need the tile at all (window), and does it need the element mask
@@ -253,16 +272,21 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
         need = !(key_hi < r0 - w || key0 > r0 + WROWS - 1 + w);
         need_mask = need_mask || (key0 < r0 + WROWS - 1 - w) || (key_hi > r0 + w);
       }
-      if (!need) continue;  // uniform per wave; barriers are only at the top of the tile body
+      if (!need) continue;  // uniform per wave; the tile's barrier sits in the loop increment, which `continue` still runs
 
       // ---- S^T = K Q^T for the two 32-key halves of the tile; a K operand feeds all query tiles of the wave
+      // The accumulators start at minus the lane's reference maximum, so the matrix core delivers the scores already
+      // shifted: in the common case (no new maximum) they go into exp2 without a subtraction.
       float16v S[QT][2];
+      float s_init[QT];
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) s_init[qt] = (m_run[qt] == -INFINITY) ? 0.f : -m_run[qt];
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) S[qt][t2][r] = 0.f;
+          for (int r = 0; r < 16; ++r) S[qt][t2][r] = s_init[qt];
       // K operands are requested PF steps ahead of the MFMA that consumes them, so LDS latency overlaps the matrix core
       constexpr int PF = 4;
       {
@@ -292,60 +316,76 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
           __builtin_amdgcn_sched_group_barrier(0x008, PF * QT, 0);
         }
       }
-      // ---- mask, running softmax (lane = query row; registers = keys)
+      // ---- mask, running softmax (lane = query row; registers = keys).  m_run is a reference maximum, not the exact
+      // one: it moves only when a score exceeds it by more than 2^kBump (or when the row sees its first valid key), so
+      // probabilities stay within [0, 2^kBump] - exact in the ratio P / sum(P) - and the rescale is rare.
+      constexpr float kBump = 8.f;
       half8 P[QT][2][2];
-      bool any_rescale = false;
-      float alpha[QT];
+      bool bump[QT], any_bump = false;
+      float mx[QT];
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) {
         const int row = r0 + 32 * qt + nn;
-        float mx = -INFINITY;
+        if (need_mask) {
 #pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
+          for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float sv = S[qt][t2][r];
-            if (need_mask) {
+            for (int r = 0; r < 16; ++r) {
               const int key = key0 + t2 * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
               bool ok = key < nk;
               if (kind == 2) ok = ok && (key >= row - w) && (key <= row + w);
-              if (!ok) sv = -INFINITY;
-              S[qt][t2][r] = sv;
+              if (!ok) S[qt][t2][r] = -INFINITY;
             }
-            mx = fmaxf(mx, sv);
-          }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[qt], mx);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        alpha[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_safe);
-        any_rescale = any_rescale || (m_new != m_run[qt]);
-        m_run[qt] = m_new;
+        }
+        float m0 = -INFINITY;
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) m0 = __builtin_fmaxf(__builtin_fmaxf(m0, S[qt][t2][r]), S[qt][t2][r + 1]);
+        m0 = fmaxf(m0, __shfl_xor(m0, 32));
+        mx[qt] = m0;
+        bump[qt] = (m_run[qt] == -INFINITY) ? (m0 > -INFINITY) : (m0 > kBump);
+        any_bump = any_bump || bump[qt];
+      }
+      if (__builtin_amdgcn_ballot_w64(any_bump) != 0) {
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+          const bool fresh = m_run[qt] == -INFINITY;
+          const float delta = bump[qt] ? mx[qt] : 0.f;
+          const float alpha = (bump[qt] && !fresh) ? __builtin_amdgcn_exp2f(-delta) : 1.f;
+          if (bump[qt]) m_run[qt] = fresh ? delta : m_run[qt] + delta;
+          l_run[qt] *= alpha;
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) S[qt][t2][r] -= delta;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) O[qt][dt][r] *= alpha;
+        }
+      }
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
         float psum = 0.f;
+        const half2v ones = {(_Float16)1.f, (_Float16)1.f};
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
           for (int s2 = 0; s2 < 2; ++s2) {
-            float pv[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              pv[j] = __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + j] - m_safe);
-              psum += pv[j];
-            }
             uint4v pk;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) pk[j] = pack_h2(pv[2 * j], pv[2 * j + 1]);
+            for (int j = 0; j < 4; ++j) {
+              // two probabilities per register, rounded toward zero; the row sum is taken over the rounded values (the
+              // ones the matrix core multiplies), so the rounding direction cancels in P / sum(P)
+              const half2v h2 = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(
+                  __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + 2 * j]), __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + 2 * j + 1])));
+              psum = __builtin_amdgcn_fdot2(h2, ones, psum, false);
+              pk[j] = __builtin_bit_cast(uint32_t, h2);
+            }
             P[qt][t2][s2] = __builtin_bit_cast(half8, pk);
           }
-        l_run[qt] = l_run[qt] * alpha[qt] + psum;
-      }
-      // the running maximum rarely moves after the first tiles: rescale the accumulators only when some lane needs it
-      if (__builtin_amdgcn_ballot_w64(any_rescale) != 0) {
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) O[qt][dt][r] *= alpha[qt];
+        l_run[qt] += psum;
       }
       // ---- O^T += V^T P^T; a V operand feeds all query tiles of the wave
       {
@@ -411,11 +451,12 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
 template <int D, int NW, int QT, bool BF16IN>
 static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_items, int num_cu, hipStream_t st) {
   // resident workgroups per CU: register-limited waves per SIMD (accumulators of QT query tiles), 4 SIMDs per CU
-  const int waves_per_simd = (QT == 1 && (D == 64 || NW == 4)) ? 2 : 1;   // matches the kernel's launch bounds
+  const int waves_per_simd = (QT == 1 && (D == 64 || NW == 4 || NW == 8)) ? 2 : 1;   // matches the kernel's launch bounds
   int occ = waves_per_simd * 4 / NW;
   if (occ < 1) occ = 1;
   int64_t blocks = (int64_t)num_cu * occ;
   if (blocks > n_items) blocks = n_items;
+  if (blocks > 8) blocks -= blocks % 8;   // whole runs per XCD (see the kernel's item mapping)
   hipLaunchKernelGGL((k_attn<D, NW, QT, BF16IN>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
   return hipGetLastError();
 }
@@ -427,7 +468,7 @@ hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_it
 #define FA_ATTN_CASE(D_, R_, NW_) \
   if (p.d == D_ && rows_per_item == R_) \
     return bf ? launch_dn<D_, NW_, 1, true>(p, items, n_items, num_cu, st) : launch_dn<D_, NW_, 1, false>(p, items, n_items, num_cu, st);
-  FA_ATTN_CASE(64, 64, 2) FA_ATTN_CASE(64, 128, 4) FA_ATTN_CASE(128, 64, 2) FA_ATTN_CASE(128, 128, 4)
+  FA_ATTN_CASE(64, 64, 2) FA_ATTN_CASE(64, 128, 4) FA_ATTN_CASE(128, 64, 2) FA_ATTN_CASE(128, 128, 4) FA_ATTN_CASE(128, 256, 8)
 #undef FA_ATTN_CASE
   return hipErrorInvalidValue;
 }
