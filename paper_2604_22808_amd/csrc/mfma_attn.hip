@@ -259,11 +259,20 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       const int key0 = key0_of(idx);
       const half_t* Ks = Ks2[idx & 1];
       const half_t* Vt = Vt2[idx & 1];
-      if (idx + 1 < n_tt) {
-        store_tile((idx + 1) & 1);
-        if (idx + 2 < n_tt) load_tile(key0_of(idx + 2));
+      // Staging of the next tiles.  Half of the waves do it before the score MFMAs and half after them, so that the
+      // workgroup's LDS stores and global loads do not all queue up behind one barrier.
+      auto stage = [&]() {
+        if (idx + 1 < n_tt) {
+          store_tile((idx + 1) & 1);
+          if (idx + 2 < n_tt) load_tile(key0_of(idx + 2));
+        }
+      };
+      const bool stage_early = (wave & 1) == 0;
+      if (stage_early) stage();
+      if (key0 >= nk) {  // block tail beyond the band (uniform over the workgroup)
+        if (!stage_early) stage();
+        continue;
       }
-      if (key0 >= nk) continue;  // block tail beyond the band (uniform over the workgroup)
 
       // ---- does this wave need the tile at all (window), and does it need the element mask
       const int key_hi = key0 + KT - 1;
@@ -272,7 +281,10 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
         need = !(key_hi < r0 - w || key0 > r0 + WROWS - 1 + w);
         need_mask = need_mask || (key0 < r0 + WROWS - 1 - w) || (key_hi > r0 + w);
       }
-      if (!need) continue;  // uniform per wave; the tile's barrier sits in the loop increment, which `continue` still runs
+      if (!need) {  // uniform per wave; the tile's barrier sits in the loop increment, which `continue` still runs
+        if (!stage_early) stage();
+        continue;
+      }
 
       // ---- S^T = K Q^T for the two 32-key halves of the tile; a K operand feeds all query tiles of the wave
       // The accumulators start at minus the lane's reference maximum, so the matrix core delivers the scores already
@@ -316,6 +328,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
           __builtin_amdgcn_sched_group_barrier(0x008, PF * QT, 0);
         }
       }
+      if (!stage_early) stage();
       // ---- mask, running softmax (lane = query row; registers = keys).  m_run is a reference maximum, not the exact
       // one: it moves only when a score exceeds it by more than 2^kBump (or when the row sees its first valid key), so
       // probabilities stay within [0, 2^kBump] - exact in the ratio P / sum(P) - and the rescale is rare.
