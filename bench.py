@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 matrix-core peak
 # HBM bytes per launch of a stage's kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the plain-copy
 # calibration (profiles/hbm_traffic_bench_1m.md); None where no counter run exists for the workload.
-MEASURED_TRAFFIC = {"1m": {"forward_transform": 8.59e9, "inverse_transform": 8.80e9}}
+MEASURED_TRAFFIC = {"1m": {"forward_transform": 4.15e9, "inverse_transform": 1.88e9, "band_attention_fused": 17.4e9}}
 
 
 def algorithmic_work(wl, ctx, alloc):
@@ -205,12 +205,13 @@ def main():
     result = {
         "metric": "tokens/s per forward", "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 I/O, fp16 MFMA operands, fp32 accumulate",
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "heads": wl.heads, "head_dim": wl.head_dim,
                    "grid": list(wl.grid), "tokens": wl.n_tokens, "band": wl.band, "alloc": wl.alloc,
                    "head_alloc": [int(a) for a in alloc], "pi": None if pi is None else [round(float(p), 4) for p in pi],
-                   "launch": "separate" if args.separate else "fused"},
+                   "launch": "separate" if args.separate else "fused",
+                   "precision": "bf16 tensors in and out, fp16 MFMA operands and intermediates, fp32 accumulation"},
         "roofline": roofline, "stages": stage_report,
     }
     if args.dense:

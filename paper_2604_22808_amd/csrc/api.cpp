@@ -479,103 +479,6 @@ static hipError_t inverse_transform_mfma(Ctx& c, void* out, const void* v_in, hi
 }
 
 // Forward transform of one [slices, N, d] tensor into a band-major spectral buffer (sections 3.2, 3.3).
-// The three axis passes of the MFMA path are chained over units small enough for the intermediates to stay in the
-// 256 MB last-level cache: as many whole slices as fit the budget, or, when one slice is larger, groups of t-planes
-// for the W and H passes (the T pass then runs once per slice).  The scratch regions are reused by every unit.
-struct ChainPlan { int ns; int G; };  // slices per unit; planes per W/H launch (T when ns >= 1 whole slices)
-static ChainPlan chain_plan(const Ctx& c) {
-  static int64_t budget = -1;
-  if (budget < 0) {
-    const char* e = getenv("FREQATTN_CHAIN_MB");
-    budget = (e && atoi(e) > 0 ? (int64_t)atoi(e) : ((int64_t)1 << 40)) << 20;
-  }
-  const int64_t slice_bytes = c.N * c.d * (int64_t)sizeof(half_t);
-  ChainPlan p;
-  if (slice_bytes <= budget) {
-    p.ns = (int)std::min<int64_t>(c.slices, std::max<int64_t>(1, budget / slice_bytes));
-    p.G = c.shape.T;
-  } else {
-    const int64_t plane_bytes = slice_bytes / c.shape.T;
-    int64_t g = std::max<int64_t>(1, budget / plane_bytes);
-    if (g > c.shape.T) g = c.shape.T;
-    while (c.shape.T % g) --g;
-    p.ns = 1;
-    p.G = (int)g;
-  }
-  return p;
-}
-
-// MFMA path, forward: W axis (tmp0), H axis (tmp1, left in [h][t] order so that the rows of the T pass are W*d
-// elements apart), T axis, which scatters into the band-major spectral buffer and, when asked to, adds up the
-// router statistics.
-static hipError_t forward_transform_mfma(Ctx& c, const void* x, void* spec, hipStream_t st, int energy_slot) {
-  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
-  const int64_t plane = (int64_t)H * W * d, Nd = c.N * d;
-  const ChainPlan cp = chain_plan(c);
-  hipError_t e;
-  for (int s0 = 0; s0 < c.slices; s0 += cp.ns) {
-    const int ns = std::min(cp.ns, c.slices - s0);
-    const uint16_t* xs = (const uint16_t*)x + (int64_t)s0 * Nd;
-    for (int t0 = 0; t0 < T; t0 += cp.G) {
-      DctPassArgs a{};
-      a.d = d; a.Ntok = c.N;
-      a.in = xs + (int64_t)t0 * plane; a.out = c.tmp0; a.M = c.d_F16[2]; a.n = W; a.inner = d;
-      a.nslab = (int64_t)ns * cp.G * H; a.outer = a.nslab; a.in_bf16 = 1;
-      if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
-      a.in = c.tmp0; a.out = c.tmp1; a.M = c.d_F16[1]; a.n = H; a.inner = (int64_t)W * d;
-      a.nslab = (int64_t)ns * cp.G; a.outer = a.nslab; a.in_bf16 = 0;
-      a.out_swap = 1; a.sw = cp.G; a.sw_total = T; a.sw_off = t0;
-      if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
-    }
-    DctPassArgs a{};
-    a.d = d; a.Ntok = c.N;
-    a.in = c.tmp1; a.out = (uint16_t*)spec + (int64_t)s0 * Nd; a.M = c.d_F16[0]; a.n = T; a.inner = (int64_t)W * d;
-    a.nslab = (int64_t)ns * H; a.outer = H; a.perm_out = c.d_perm; a.perm_k = (int64_t)H * W; a.perm_o = W;
-    if (energy_slot >= 0) {
-      a.energy_part = c.d_energy_part + (size_t)energy_slot * DCT_MAX_WAVES * 3 * 64;
-      a.en_omul = W; a.en_div = W;  // the tile's other coordinates are (kh, kw)
-      a.low_u = c.low_box[1]; a.low_v = c.low_box[2]; a.low_a = c.low_box[0];
-      a.mid_u = c.mid_box[1]; a.mid_v = c.mid_box[2]; a.mid_a = c.mid_box[0];
-    }
-    if ((e = launch_mfma_dct_pass(a, c.num_cu, st, &c.energy_waves)) != hipSuccess) return e;
-  }
-  return hipSuccess;
-}
-
-// MFMA path, inverse (section 3.7): the T axis pass gathers band-major rows (from Y where the band is active for
-// the slice, else from V~) into tmp1 in [h][t] order, then H axis (tmp1 -> tmp0) and W axis (tmp0 -> out).
-static hipError_t inverse_transform_mfma(Ctx& c, void* out, hipStream_t st) {
-  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
-  const int64_t plane = (int64_t)H * W * d, Nd = c.N * d;
-  const ChainPlan cp = chain_plan(c);
-  const int32_t* masks = c.d_lists + c.off_masks;
-  hipError_t e;
-  for (int s0 = 0; s0 < c.slices; s0 += cp.ns) {
-    const int ns = std::min(cp.ns, c.slices - s0);
-    DctPassArgs a{};
-    a.d = d; a.Ntok = c.N;
-    a.in = (const uint16_t*)c.Y + (int64_t)s0 * Nd; a.in_alt = (const uint16_t*)c.specV + (int64_t)s0 * Nd;
-    a.masks = masks + s0; a.band_off1 = (int32_t)c.band_off[1]; a.band_off2 = (int32_t)c.band_off[2];
-    a.perm_in = c.d_perm; a.perm_k = (int64_t)H * W; a.perm_o = W;
-    a.out = c.tmp1; a.M = c.d_Ft16[0]; a.n = T; a.inner = (int64_t)W * d; a.nslab = (int64_t)ns * H; a.outer = H;
-    if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;
-    for (int t0 = 0; t0 < T; t0 += cp.G) {
-      DctPassArgs b{};
-      b.d = d; b.Ntok = c.N;
-      b.in = c.tmp1; b.out = c.tmp0; b.M = c.d_Ft16[1]; b.n = H; b.inner = (int64_t)W * d;
-      b.nslab = (int64_t)ns * cp.G; b.outer = b.nslab;
-      b.in_swap = 1; b.sw = cp.G; b.sw_total = T; b.sw_off = t0;
-      if ((e = launch_mfma_dct_pass(b, c.num_cu, st)) != hipSuccess) return e;
-      b.in_swap = 0;
-      b.in = c.tmp0; b.out = (uint16_t*)out + (int64_t)s0 * Nd + (int64_t)t0 * plane; b.M = c.d_Ft16[2]; b.n = W;
-      b.inner = d; b.nslab = (int64_t)ns * cp.G * H; b.outer = b.nslab; b.out_bf16 = 1;
-      if ((e = launch_mfma_dct_pass(b, c.num_cu, st)) != hipSuccess) return e;
-    }
-  }
-  return hipSuccess;
-}
-
-// Forward transform of one [slices, N, d] tensor into a band-major spectral buffer (sections 3.2, 3.3).
 static hipError_t forward_transform(Ctx& c, const void* x, void* spec, hipStream_t st, int energy_slot = -1) {
   const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
   hipError_t e;
