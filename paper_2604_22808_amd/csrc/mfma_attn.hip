@@ -340,14 +340,23 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       for (int qt = 0; qt < QT; ++qt) {
         const int row = r0 + 32 * qt + nn;
         if (need_mask) {
+          // valid keys of this lane's row form one interval [lo, hi]; relative to the lane's first key of the tile the
+          // register r holds key offset c_r (a compile-time constant), valid iff min(c_r - lo', hi' - c_r) >= 0.
+          // Small integers are exact in fp32, and the float form keeps the test branch-free (5 VALU per score).
+          int lo = 0, hi = nk - 1;
+          if (kind == 2) { lo = row - w > 0 ? row - w : 0; hi = row + w < nk - 1 ? row + w : nk - 1; }
+          const int base = key0 + 4 * g;
+          int dlo = lo - base, dhi = hi - base;
+          dlo = dlo < -1 ? -1 : (dlo > 65 ? 65 : dlo);    // clamped: only the range of c_r matters
+          dhi = dhi < -1 ? -1 : (dhi > 65 ? 65 : dhi);
+          const float flo = (float)dlo, fhi = (float)dhi;
 #pragma unroll
           for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-              const int key = key0 + t2 * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-              bool ok = key < nk;
-              if (kind == 2) ok = ok && (key >= row - w) && (key <= row + w);
-              if (!ok) S[qt][t2][r] = -INFINITY;
+              const float cr = (float)(t2 * 32 + 8 * (r >> 2) + (r & 3));
+              const float tmin = fminf(cr - flo, fhi - cr);
+              S[qt][t2][r] = tmin < 0.f ? -INFINITY : S[qt][t2][r];
             }
         }
         float m0 = -INFINITY;
