@@ -248,3 +248,47 @@ def test_16k_mask_classes_bf16():
     assert np.array_equal(got[0, 0], v[0, 0])          # nothing active: the library returns V itself
     for s in range(len(heads)):
         _check(got[0, s], want[0, s], "bf16", f"16k mask {alloc[s]}")
+
+
+@pytest.mark.parametrize("grid,band_kw", [
+    ((16, 32, 32), dict(mid_block=128, mid_diag=1, mid_stride=4, high_window=96, n_summary=8)),
+    ((16, 16, 48), dict(mid_block=64, mid_diag=2, mid_stride=3, high_window=40, n_summary=5)),
+])
+def test_mfma_head_dim_64_bf16(grid, band_kw):
+    """head_dim 64 instantiations of the matrix-core kernels (transform passes with one 64-column chunk per token,
+    attention with four channel steps), one head per band plus one head that runs all bands."""
+    d = 64
+    rng = np.random.default_rng(11)
+    N = int(np.prod(grid))
+    q, k, v = (WL.round_to_io(0.3 * rng.standard_normal((1, 4, N, d)), "bf16") for _ in range(3))
+    band = dict(WL.WORKLOADS["16k"].band)
+    band.update(low_compress=4, **band_kw)
+    ctx = B.Context(1, 4, d, grid, B.BF16, B.make_cfg(**band))
+    assert ctx.get_path() == B.PATH_MFMA
+    alloc = (1, 2, 4, 7)
+    got = U.run_forward(ctx, q, k, v, "bf16", alloc)
+    want = O.forward(q, k, v, grid, O.BandConfig(**band), alloc)
+    for s in range(4):
+        _check(got[0, s], want[0, s], "bf16", f"d=64 grid {grid} mask {alloc[s]}")
+
+
+@pytest.mark.parametrize("d,grid", [(128, (16, 16, 32)), (64, (16, 16, 16))])
+def test_dense_baseline_matches_dense_reference(d, grid):
+    """The dense comparison kernel (same attention kernel over the untransformed sequence, bf16 in and out) against
+    the oracle's plain softmax attention."""
+    import torch
+    rng = np.random.default_rng(13)
+    N = int(np.prod(grid))
+    q, k, v = (WL.round_to_io(0.5 * rng.standard_normal((1, 2, N, d)), "bf16") for _ in range(3))
+    band = dict(WL.WORKLOADS["16k"].band)
+    band.update(mid_block=128)
+    ctx = B.Context(1, 2, d, grid, B.BF16, B.make_cfg(**band))
+    assert ctx.get_path() == B.PATH_MFMA
+    dq, dk, dv = (U.to_device(x, "bf16") for x in (q, k, v))
+    out = torch.empty_like(dq)
+    ctx.dense_forward(dq, dk, dv, out)
+    torch.cuda.synchronize()
+    got = U.to_host64(out)
+    for s in range(2):
+        want = O.dense_reference(q[0, s], k[0, s], v[0, s])
+        _check(got[0, s], want, "bf16", f"dense d={d} slice {s}")
