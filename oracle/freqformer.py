@@ -25,6 +25,8 @@ docstrings below.  Readings that the paper itself cannot confirm are marked
 Pins per function (tests that run without a GPU):
   dct_matrix / spectral_forward / spectral_inverse : orthonormality, Parseval,
       round trip <= 1e-10, scipy.fft.dctn(type=2, norm="ortho"), closed forms.
+  haar_matrix (transform = 1) : orthonormality, the averaging/differencing pyramid written out as loops,
+      closed forms (constant -> scaling coefficient only, a step at n/2 -> two coefficients), Parseval, round trip.
   band_partition : disjoint cover, closed-form counts, brute-force triple loop,
       energy split sum_l ||P_l F x||^2 = ||x||^2.
   low_band_attention : c = 1 equals dense softmax attention; one compressed token
@@ -72,6 +74,7 @@ class BandConfig:
     high_window: int = 256     # half width w_h: keys i - w_h .. i + w_h
     n_summary: int = 16        # m summary tokens per band (0 switches the exchange off)
     softmax_scale: float = 0.0  # 0 -> 1/sqrt(d_k)
+    transform: int = 0         # per-axis transform: 0 orthonormal DCT-II (reference design), 1 orthonormal Haar wavelet
 
 
 # --------------------------------------------------------------------------- section 3.2
@@ -88,23 +91,55 @@ def dct_matrix(n: int) -> np.ndarray:
     return F
 
 
-def spectral_forward(x: np.ndarray) -> np.ndarray:
+def haar_matrix(n: int) -> np.ndarray:
+    """Orthonormal Haar wavelet matrix of order n = 2^p (section 3.2 allows wavelets in place of the DCT).
+
+    Row 0 is the scaling function, 1/sqrt(n) everywhere.  Row 2^j + i (0 <= i < 2^j, j = 0 .. p-1) is the wavelet of
+    level j at position i: with s = n / 2^j its support is [i s, (i+1) s), value +sqrt(2^j / n) on the first half of
+    the support and -sqrt(2^j / n) on the second.  Rows run from coarse to fine, so the row index plays the role the
+    frequency index plays for the DCT (band edges of section 3.3 cut it the same way).  W W^T = I.
+    """
+    if n < 1 or n & (n - 1):
+        raise ValueError("the Haar transform needs a power-of-two length")
+    Wm = np.zeros((n, n), dtype=np.float64)
+    Wm[0, :] = 1.0 / math.sqrt(n)
+    j = 0
+    while (1 << j) < n:
+        s = n >> j
+        a = math.sqrt((1 << j) / n)
+        for i in range(1 << j):
+            Wm[(1 << j) + i, i * s:i * s + s // 2] = a
+            Wm[(1 << j) + i, i * s + s // 2:(i + 1) * s] = -a
+        j += 1
+    return Wm
+
+
+def axis_matrix(n: int, transform: int = 0) -> np.ndarray:
+    """The 1-D transform of one grid axis (section 3.2): 0 = DCT-II (reference design), 1 = Haar wavelet."""
+    if transform == 0:
+        return dct_matrix(n)
+    if transform == 1:
+        return haar_matrix(n)
+    raise ValueError("unknown transform")
+
+
+def spectral_forward(x: np.ndarray, transform: int = 0) -> np.ndarray:
     """x~ = F(x) with F = F_t (x) F_h (x) F_w (section 3.2); x is [T, H, W, d_k], channels untouched."""
     T, H, W, _ = x.shape
     x = np.asarray(x, dtype=np.float64)
-    y = np.einsum("at,thwc->ahwc", dct_matrix(T), x, optimize=True)
-    y = np.einsum("bh,ahwc->abwc", dct_matrix(H), y, optimize=True)
-    y = np.einsum("gw,abwc->abgc", dct_matrix(W), y, optimize=True)
+    y = np.einsum("at,thwc->ahwc", axis_matrix(T, transform), x, optimize=True)
+    y = np.einsum("bh,ahwc->abwc", axis_matrix(H, transform), y, optimize=True)
+    y = np.einsum("gw,abwc->abgc", axis_matrix(W, transform), y, optimize=True)
     return y
 
 
-def spectral_inverse(c: np.ndarray) -> np.ndarray:
+def spectral_inverse(c: np.ndarray, transform: int = 0) -> np.ndarray:
     """F^{-1} = F^T per axis (section 3.7; orthonormality, section 5)."""
     T, H, W, _ = c.shape
     c = np.asarray(c, dtype=np.float64)
-    y = np.einsum("at,ahwc->thwc", dct_matrix(T), c, optimize=True)
-    y = np.einsum("bh,tbwc->thwc", dct_matrix(H), y, optimize=True)
-    y = np.einsum("gw,thgc->thwc", dct_matrix(W), y, optimize=True)
+    y = np.einsum("at,ahwc->thwc", axis_matrix(T, transform), c, optimize=True)
+    y = np.einsum("bh,tbwc->thwc", axis_matrix(H, transform), y, optimize=True)
+    y = np.einsum("gw,thgc->thwc", axis_matrix(W, transform), y, optimize=True)
     return y
 
 
@@ -257,9 +292,9 @@ def head_forward(q, k, v, cfg: BandConfig, mask: int, return_parts: bool = False
     T, H, W, d = q.shape
     N = T * H * W
     scale = resolve_scale(cfg, d)
-    qs = spectral_forward(q).reshape(N, d)
-    ks = spectral_forward(k).reshape(N, d)
-    vs = spectral_forward(v).reshape(N, d)
+    qs = spectral_forward(q, cfg.transform).reshape(N, d)
+    ks = spectral_forward(k, cfg.transform).reshape(N, d)
+    vs = spectral_forward(v, cfg.transform).reshape(N, d)
     bands = band_partition(T, H, W, cfg)
 
     Y = []
@@ -286,7 +321,7 @@ def head_forward(q, k, v, cfg: BandConfig, mask: int, return_parts: bool = False
     spec = np.empty((N, d), dtype=np.float64)
     for idx, y in zip(bands, Yhat):
         spec[idx] = y
-    out = spectral_inverse(spec.reshape(T, H, W, d))
+    out = spectral_inverse(spec.reshape(T, H, W, d), cfg.transform)
     if return_parts:
         return out, {"qs": qs, "ks": ks, "vs": vs, "bands": bands, "Y": Y, "Yhat": Yhat}
     return out
@@ -367,7 +402,7 @@ def band_statistics(q, k, v, grid, cfg: BandConfig) -> np.ndarray:
     for x in (q, k, v):
         for b in range(Bsz):
             for h in range(nh):
-                xs = spectral_forward(np.asarray(x[b, h], dtype=np.float64).reshape(T, H, W, d)).reshape(N, d)
+                xs = spectral_forward(np.asarray(x[b, h], dtype=np.float64).reshape(T, H, W, d), cfg.transform).reshape(N, d)
                 for l, idx in enumerate(bands):
                     acc[l] += (xs[idx] ** 2).sum(axis=0)
     g = np.empty((3, ROUTER_DR), dtype=np.float64)

@@ -68,3 +68,77 @@ def test_constant_field_is_pure_dc_and_basis_vector_is_one_hot():
     cy = O.spectral_forward(y)
     for ch in range(3):
         assert np.abs(cy[..., ch:ch + 1] - O.spectral_forward(y[..., ch:ch + 1])).max() < 1e-12
+
+
+# --------------------------------------------------------------------------- Haar variant (section 3.2: "wavelets are also possible")
+def _haar_pyramid(x):
+    """Textbook Haar analysis of a length-2^p vector: repeated pairwise (a+b)/sqrt2 averages and (a-b)/sqrt2 details,
+    details of the finest level last; written as plain loops, independently of the matrix."""
+    x = [float(t) for t in x]
+    n = len(x)
+    out = [0.0] * n
+    while n > 1:
+        half = n // 2
+        avg = [(x[2 * i] + x[2 * i + 1]) / np.sqrt(2.0) for i in range(half)]
+        det = [(x[2 * i] - x[2 * i + 1]) / np.sqrt(2.0) for i in range(half)]
+        out[half:n] = det
+        x = avg
+        n = half
+    out[0] = x[0]
+    return np.array(out)
+
+
+@pytest.mark.parametrize("n", [1, 2, 4, 16, 64, 128])
+def test_haar_matrix_is_orthonormal(n):
+    Wm = O.haar_matrix(n)
+    assert np.abs(Wm @ Wm.T - np.eye(n)).max() < 1e-13
+    assert np.abs(Wm.T @ Wm - np.eye(n)).max() < 1e-13
+
+
+@pytest.mark.parametrize("n", [2, 8, 32, 128])
+def test_haar_matrix_matches_pyramid_algorithm(n):
+    rng = np.random.default_rng(n)
+    for _ in range(3):
+        x = rng.standard_normal(n)
+        assert np.abs(O.haar_matrix(n) @ x - _haar_pyramid(x)).max() < 1e-12
+
+
+def test_haar_closed_forms():
+    n = 16
+    Wm = O.haar_matrix(n)
+    c = Wm @ np.full(n, 3.0)                    # constant -> scaling coefficient only
+    assert abs(c[0] - 3.0 * np.sqrt(n)) < 1e-13 and np.abs(c[1:]).max() < 1e-13
+    step = np.r_[np.ones(n // 2), -np.ones(n // 2)]   # a step at n/2 is the coarsest wavelet itself
+    c = Wm @ step
+    assert abs(c[1] - np.sqrt(n)) < 1e-13 and np.abs(np.delete(c, 1)).max() < 1e-13
+    assert np.allclose(O.haar_matrix(2), np.array([[1, 1], [1, -1]]) / np.sqrt(2), atol=1e-15)
+    with pytest.raises(ValueError):
+        O.haar_matrix(12)
+
+
+def test_haar_spectral_round_trip_and_parseval():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((4, 8, 16, 5))
+    c = O.spectral_forward(x, transform=1)
+    assert abs(np.sum(c ** 2) - np.sum(x ** 2)) < 1e-10 * np.sum(x ** 2)
+    assert np.abs(O.spectral_inverse(c, transform=1) - x).max() < 1e-12
+    # separable: one coefficient equals the triple product of matrix rows with the field
+    Wt, Wh, Ww = O.haar_matrix(4), O.haar_matrix(8), O.haar_matrix(16)
+    want = np.einsum("t,h,w,thwc->c", Wt[3], Wh[5], Ww[9], x)
+    assert np.abs(c[3, 5, 9] - want).max() < 1e-12
+    # and differs from the DCT
+    assert np.abs(c - O.spectral_forward(x, transform=0)).max() > 1e-3
+
+
+def test_haar_pipeline_identities():
+    """With the Haar transform the pipeline keeps its invariants: no active band returns V, a one-hot mask changes
+    only that band's coefficients."""
+    rng = np.random.default_rng(8)
+    grid, d = (4, 8, 8), 8
+    cfg = O.BandConfig(mid_block=16, mid_diag=1, mid_stride=4, high_window=16, n_summary=4, transform=1)
+    q, k, v = (rng.standard_normal(grid + (d,)) for _ in range(3))
+    assert np.abs(O.head_forward(q, k, v, cfg, 0) - v).max() < 1e-12
+    out = O.head_forward(q, k, v, cfg, 2)
+    diff = O.spectral_forward(out - v, transform=1).reshape(-1, d)
+    low, mid, high = O.band_partition(*grid, cfg)
+    assert np.abs(diff[low]).max() < 1e-10 and np.abs(diff[high]).max() < 1e-10 and np.abs(diff[mid]).max() > 1e-4
