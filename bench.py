@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--dense", action="store_true", help="also time the dense flash-style baseline (one iteration)")
     ap.add_argument("--separate", action="store_true", help="one launch per branch instead of the fused launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--transform", choices=("dct", "haar"), default="dct",
+                    help="per-axis transform: the reference design's DCT-II or the Haar wavelet variant")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of q (known bytes) so that a counter run can be scaled by it")
     args = ap.parse_args()
@@ -120,6 +122,9 @@ def main():
     torch.cuda.set_device(0)
     q, k, v = WL.qkv_torch(wl, "cuda")
     out = torch.empty_like(q)
+    if args.transform == "haar":
+        import dataclasses
+        wl = dataclasses.replace(wl, band=dict(wl.band, transform=B.TRANSFORM_HAAR))
     cfg = B.make_cfg(**wl.band)
     ctx = B.Context(wl.batch, wl.heads, wl.head_dim, wl.grid, B.BF16, cfg)
     if args.separate:

@@ -56,7 +56,13 @@ typedef struct {
   int32_t high_window;  /* w_h: query i sees keys i-w_h .. i+w_h of the high band (clipped, two-sided)              */
   int32_t n_summary;    /* m summary tokens per band; 0 switches the cross-band exchange off                        */
   float softmax_scale;  /* <= 0 selects 1/sqrt(head_dim)                                                            */
+  int32_t transform;    /* freqattn_transform: the 1-D transform applied along each grid axis (section 3.2)         */
 } freqattn_band_cfg;
+
+/* Per-axis transform of section 3.2: the reference design's orthonormal DCT-II, or the orthonormal Haar wavelet (the
+ * alternative the section names; needs T, H, W to be powers of two).  Haar rows run from coarse to fine - row 0 the
+ * mean, row 2^j + i the level-j wavelet at position i - and the band edges cut the row index like a frequency. */
+typedef enum { FREQATTN_TRANSFORM_DCT = 0, FREQATTN_TRANSFORM_HAAR = 1 } freqattn_transform;
 
 /* How the three band branches are launched (paper section 6.2: one launch for all branches vs one per branch). */
 typedef enum { FREQATTN_LAUNCH_FUSED = 0, FREQATTN_LAUNCH_SEPARATE = 1 } freqattn_launch_mode;
@@ -112,7 +118,7 @@ freqattn_status freqattn_band_index(const freqattn_ctx* ctx, int32_t band, int32
  * [nb+1], nb = ceil(n_mid / mid_block)) and col_idx (HOST [nnz]) are filled when not NULL. */
 freqattn_status freqattn_mid_blocks(const freqattn_ctx* ctx, int32_t* row_ptr, int32_t* col_idx, int64_t* nnz);
 /* Per-axis transform matrix as used on the device, widened to double: axis 0/1/2 = T/H/W, HOST out [n*n] row-major
- * (row = frequency). */
+ * (row = frequency for the DCT, scale for the Haar transform; the entry point keeps its name for both). */
 freqattn_status freqattn_dct_matrix(const freqattn_ctx* ctx, int32_t axis, double* host_out);
 
 /* ---- intermediate results of the last forward, for stage-wise checks ------------------------------------------

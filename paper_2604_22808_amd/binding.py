@@ -17,6 +17,7 @@ OK, EINVAL, ENOMEM, EHIP, EUNSUPPORTED = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 LAUNCH_FUSED, LAUNCH_SEPARATE = 0, 1
 PATH_AUTO, PATH_GENERIC, PATH_MFMA, PATH_TABLES_ONLY = 0, 1, 2, 3
+TRANSFORM_DCT, TRANSFORM_HAAR = 0, 1
 
 
 class Shape(C.Structure):
@@ -26,7 +27,7 @@ class Shape(C.Structure):
 class BandCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("low_num", "low_den", "mid_num", "mid_den", "low_compress", "mid_block",
                                          "mid_diag", "mid_stride", "mid_block0", "high_window", "n_summary")] + \
-               [("softmax_scale", C.c_float)]
+               [("softmax_scale", C.c_float), ("transform", C.c_int32)]
 
 
 EXPORTS = {
@@ -97,7 +98,7 @@ def _stream():
 
 def make_cfg(**kw) -> BandCfg:
     base = dict(low_num=1, low_den=4, mid_num=1, mid_den=2, low_compress=4, mid_block=64, mid_diag=1, mid_stride=8,
-                mid_block0=1, high_window=256, n_summary=16, softmax_scale=0.0)
+                mid_block0=1, high_window=256, n_summary=16, softmax_scale=0.0, transform=0)
     base.update(kw)
     return BandCfg(**base)
 

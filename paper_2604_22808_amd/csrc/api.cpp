@@ -90,6 +90,11 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
   if (g.low_compress < 1 || g.mid_block < 1 || g.mid_stride < 1 || g.mid_diag < 0 || g.high_window < 0 ||
       g.n_summary < 0)
     return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: band operator parameter out of range");
+  if (g.transform != FREQATTN_TRANSFORM_DCT && g.transform != FREQATTN_TRANSFORM_HAAR)
+    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: unknown transform");
+  auto pow2 = [](int n) { return (n & (n - 1)) == 0; };
+  if (g.transform == FREQATTN_TRANSFORM_HAAR && !(pow2(s.T) && pow2(s.H) && pow2(s.W)))
+    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: the Haar transform needs T, H and W to be powers of two");
   if (path != FREQATTN_PATH_AUTO && path != FREQATTN_PATH_GENERIC && path != FREQATTN_PATH_MFMA &&
       path != FREQATTN_PATH_TABLES_ONLY)
     return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: unknown path");
@@ -113,7 +118,10 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
     build_bands(*c);
     build_mid_blocks(*c);
     const int dims[3] = {s.T, s.H, s.W};
-    for (int a = 0; a < 3; ++a) build_dct_matrix(dims[a], c->h_F[a]);
+    for (int a = 0; a < 3; ++a) {
+      if (g.transform == FREQATTN_TRANSFORM_HAAR) build_haar_matrix(dims[a], c->h_F[a]);
+      else build_dct_matrix(dims[a], c->h_F[a]);
+    }
   } catch (const std::bad_alloc&) {
     delete c;
     return fail(nullptr, FREQATTN_ENOMEM, "freqattn_create: host allocation failed");
@@ -319,7 +327,7 @@ static bool same_cfg(const freqattn_band_cfg& a, const freqattn_band_cfg& b) {
   return a.low_num == b.low_num && a.low_den == b.low_den && a.mid_num == b.mid_num && a.mid_den == b.mid_den &&
          a.low_compress == b.low_compress && a.mid_block == b.mid_block && a.mid_diag == b.mid_diag &&
          a.mid_stride == b.mid_stride && (a.mid_block0 != 0) == (b.mid_block0 != 0) &&
-         a.high_window == b.high_window && a.n_summary == b.n_summary;
+         a.high_window == b.high_window && a.n_summary == b.n_summary && a.transform == b.transform;
 }
 
 static void build_lists(Ctx& c, const int32_t* head_alloc) {

@@ -122,6 +122,7 @@ struct Ctx {
 
 // ---- host tables (tables.cpp) --------------------------------------------------------------------------------
 void build_dct_matrix(int n, std::vector<double>& F);  // [n][n], row = frequency
+void build_haar_matrix(int n, std::vector<double>& F); // [n][n], row = scale (coarse to fine), n a power of two
 void build_bands(Ctx& c);
 void build_mid_blocks(Ctx& c);
 

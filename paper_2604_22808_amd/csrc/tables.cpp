@@ -20,6 +20,19 @@ void build_dct_matrix(int n, std::vector<double>& F) {
   }
 }
 
+// Orthonormal Haar wavelet matrix of order n = 2^p (section 3.2 names wavelets as the alternative): row 0 is
+// 1/sqrt(n); row 2^j + i is +-sqrt(2^j / n) on the two halves of [i n/2^j, (i+1) n/2^j) and zero elsewhere.
+void build_haar_matrix(int n, std::vector<double>& F) {
+  F.assign((size_t)n * n, 0.0);
+  for (int j = 0; j < n; ++j) F[j] = 1.0 / std::sqrt((double)n);
+  for (int lev = 0; (1 << lev) < n; ++lev) {
+    const int s = n >> lev;
+    const double a = std::sqrt((double)(1 << lev) / n);
+    for (int i = 0; i < (1 << lev); ++i)
+      for (int j = 0; j < s; ++j) F[(size_t)((1 << lev) + i) * n + i * s + j] = (j < s / 2) ? a : -a;
+  }
+}
+
 // Band membership of section 3.3 with rational edges, decided in 64-bit integers; band-major order is the order of
 // the ascending flat index (kt*H + kh)*W + kw inside each band.  perm maps a flat index to its band-major row, where
 // the low band occupies rows [0, n_low), the mid band the next n_mid rows and the high band the rest.

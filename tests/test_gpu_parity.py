@@ -292,3 +292,57 @@ def test_dense_baseline_matches_dense_reference(d, grid):
     for s in range(2):
         want = O.dense_reference(q[0, s], k[0, s], v[0, s])
         _check(got[0, s], want, "bf16", f"dense d={d} slice {s}")
+
+
+# ------------------------------------------------------------------ Haar wavelet as the per-axis transform (section 3.2)
+def test_haar_tiny_f32_matches_oracle():
+    wl = WL.WORKLOADS["tiny_f32"]
+    q, k, v = _inputs(wl)
+    ctx, band = U.make_ctx(wl, transform=B.TRANSFORM_HAAR)
+    alloc = (2, 7)
+    got = U.run_forward(ctx, q, k, v, wl.dtype, alloc)
+    want = O.forward(q, k, v, wl.grid, U.oracle_cfg(band), alloc)
+    _check(got, want, "f32", "haar tiny f32")
+    dct = O.forward(q, k, v, wl.grid, U.oracle_cfg(dict(band, transform=0)), alloc)
+    assert np.abs(want - dct).max() > 1e-3       # the variant really computes something else
+
+
+def test_haar_16k_bf16_matches_oracle_on_the_matrix_cores():
+    """Same kernels, other matrix: pruned transforms, delta-form inverse and the Parseval statistics only rely on the
+    transform being orthonormal and on bands being index boxes, which the Haar ordering (coarse to fine) keeps."""
+    wl = WL.WORKLOADS["16k"]
+    heads = [0, 2, 5, 7]
+    q, k, v = _inputs(wl, heads=heads)
+    ctx, band = U.make_ctx(wl, path=B.PATH_MFMA, heads=len(heads), transform=B.TRANSFORM_HAAR)
+    alloc = (1, 2, 4, 7)
+    got = U.run_forward(ctx, q, k, v, wl.dtype, alloc)
+    want = O.forward(q, k, v, wl.grid, U.oracle_cfg(band), alloc)
+    for s in range(len(heads)):
+        _check(got[0, s], want[0, s], "bf16", f"haar 16k mask {alloc[s]}")
+    for which, x in ((0, q), (2, v)):            # spectral coefficients of head 3 (all bands computed)
+        xs = O.spectral_forward(x[0, 3].reshape(wl.grid + (wl.head_dim,)), transform=1).reshape(-1, wl.head_dim)
+        for l, idx in enumerate(O.band_partition(*wl.grid, U.oracle_cfg(band))):
+            mx, rl = U.errors(ctx.read_spectral(which, 3, l), xs[idx])
+            assert rl < 2e-3, (which, l, rl)
+
+
+def test_haar_64k_router_statistics_and_routed_forward():
+    import torch
+    wl = WL.WORKLOADS["64k"]
+    heads = [0, 1, 2, 3]
+    q, k, v = _inputs(wl, heads=heads)
+    ctx, band = U.make_ctx(wl, heads=len(heads), transform=B.TRANSFORM_HAAR)
+    cfg = U.oracle_cfg(band)
+    w = WL.router_weights(wl.alloc["hidden"], wl.alloc["seed"])
+    dq, dk, dv = (U.to_device(x, wl.dtype) for x in (q, k, v))
+    got_alloc, got_pi, got_stats = ctx.route_mlp(dq, dk, dv, 0.5, *w)
+    want_alloc, want_pi = O.route_mlp(q, k, v, wl.grid, cfg, 0.5, *w)
+    assert np.abs(got_stats - O.band_statistics(q, k, v, wl.grid, cfg)).max() < 5e-3
+    assert np.abs(got_pi - want_pi).max() < 2e-3
+    assert np.array_equal(got_alloc, want_alloc)
+    out = torch.empty_like(dq)
+    alloc2, _ = ctx.forward_routed(dq, dk, dv, 0.5, *w, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(alloc2, want_alloc)
+    want = O.forward(q, k, v, wl.grid, cfg, want_alloc)
+    _check(U.to_host64(out), want, "bf16", f"haar 64k routed alloc={list(alloc2)}")

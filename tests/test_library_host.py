@@ -69,6 +69,20 @@ def test_dct_matrix_matches_oracle(n):
     assert np.abs(ctx.dct_matrix(0) - O.dct_matrix(n)).max() < 1e-14
 
 
+@pytest.mark.parametrize("n", [1, 2, 8, 64, 128])
+def test_haar_matrix_matches_oracle(n):
+    ctx = tables_ctx((n, 4, 8), transform=B.TRANSFORM_HAAR)
+    assert np.abs(ctx.dct_matrix(0) - O.haar_matrix(n)).max() < 1e-15
+    assert np.abs(ctx.dct_matrix(2) - O.haar_matrix(8)).max() < 1e-15
+
+
+def test_haar_needs_power_of_two_axes_and_known_transform():
+    with pytest.raises(B.FreqAttnError):
+        tables_ctx((12, 4, 4), transform=B.TRANSFORM_HAAR)
+    with pytest.raises(B.FreqAttnError):
+        tables_ctx((8, 4, 4), transform=2)
+
+
 def test_route_fixed():
     assert list(B.route_fixed(8, 2, 3, 3)) == list(O.route_fixed(8, 2, 3, 3))
     with pytest.raises(B.FreqAttnError):
