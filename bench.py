@@ -202,10 +202,14 @@ def main():
         achieved, peak, unit = amount / launches / per_launch_s / 1e9, HBM_PEAK_GBS, "GB/s"
     else:
         achieved, peak, unit = amount / launches / per_launch_s / 1e12, MFMA_PEAK_TFLOPS, "TFLOP/s"
-    traffic = MEASURED_TRAFFIC.get(wl.name, {}).get(dom[0])
+    traffic = MEASURED_TRAFFIC.get(wl.name, {}).get(dom[0]) if args.transform == "dct" else None
+    # what this machine sustains for a plain streaming copy and for a loop of the MFMA instruction the kernels use
+    copy_bps, mfma_fps = ctx.measure_peaks()
+    measured = copy_bps / 1e9 if bound == "hbm" else mfma_fps / 1e12
     roofline = {"bound": bound, "kernel": dom[0], "launches_per_step": launches,
                 "avg_launch_ms": round(per_launch_s * 1e3, 4), "achieved": round(achieved, 2), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": traffic}
+                "frac": round(achieved / peak, 4), "traffic": traffic,
+                "measured_peak": round(measured, 1), "frac_of_measured": round(achieved / measured, 4)}
 
     result = {
         "metric": "tokens/s per forward", "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
@@ -218,6 +222,7 @@ def main():
                    "launch": "separate" if args.separate else "fused",
                    "precision": "bf16 tensors in and out, fp16 MFMA operands and intermediates, fp32 accumulation"},
         "roofline": roofline, "stages": stage_report,
+        "measured_peaks": {"copy_GBs": round(copy_bps / 1e9, 1), "mfma_f16_TFLOPs": round(mfma_fps / 1e12, 1)},
     }
     if args.dense:
         dout = torch.empty_like(q)

@@ -168,6 +168,13 @@ freqattn_status freqattn_set_stage_timing(freqattn_ctx* ctx, int32_t enabled);
 freqattn_status freqattn_stage_times(freqattn_ctx* ctx, int32_t max_stages, const char** names_out, float* ms_out,
                                      int32_t* n_stages);
 
+/* Machine rates for the rooflines (section 6 discusses both bounds), measured with the context's own scratch on
+ * `stream`; the call synchronises.  *copy_bytes_per_s HOST: bytes read plus bytes written per second by a plain
+ * streaming copy of one scratch tensor into another (up to 4 GiB; meaningful when the scratch is much larger than the
+ * 256 MB last-level cache).  *mfma_flops_per_s HOST: flops per second of a loop of independent
+ * v_mfma_f32_32x32x16_f16 on every SIMD.  Either pointer may be NULL.  MFMA path only (FREQATTN_EUNSUPPORTED else). */
+freqattn_status freqattn_measure_peaks(freqattn_ctx* ctx, double* copy_bytes_per_s, double* mfma_flops_per_s, void* stream);
+
 /* Device bytes owned by the context (tables + scratch). */
 int64_t freqattn_workspace_bytes(const freqattn_ctx* ctx);
 

@@ -57,6 +57,7 @@ EXPORTS = {
     "freqattn_stage_times": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
                                        C.POINTER(C.c_int32)]),
     "freqattn_workspace_bytes": (C.c_int64, [C.c_void_p]),
+    "freqattn_measure_peaks": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
 }
 
 _lib = None
@@ -176,6 +177,12 @@ class Context:
 
     def workspace_bytes(self):
         return lib().freqattn_workspace_bytes(self._h)
+
+    def measure_peaks(self):
+        """(bytes/s of a plain streaming copy, flop/s of an MFMA loop) on this machine; synchronises."""
+        cp, mf = C.c_double(0.0), C.c_double(0.0)
+        self._check(lib().freqattn_measure_peaks(self._h, C.byref(cp), C.byref(mf), _stream()))
+        return cp.value, mf.value
 
     def band_sizes(self):
         n = (C.c_int64 * 3)()

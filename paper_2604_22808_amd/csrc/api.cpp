@@ -286,6 +286,44 @@ extern "C" freqattn_status freqattn_set_launch_mode(freqattn_ctx* c, int32_t mod
   return FREQATTN_OK;
 }
 extern "C" int32_t freqattn_get_path(const freqattn_ctx* c) { return c ? c->path : -1; }
+extern "C" freqattn_status freqattn_measure_peaks(freqattn_ctx* c, double* copy_bytes_per_s, double* mfma_flops_per_s,
+                                                  void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  if (c->path != FREQATTN_PATH_MFMA) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_measure_peaks: MFMA path only");
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t e0, e1;
+  HIP_TRY(c, hipEventCreate(&e0));
+  HIP_TRY(c, hipEventCreate(&e1));
+  auto timed = [&](auto&& launch, int reps, float* ms) -> hipError_t {
+    hipError_t e;
+    if ((e = launch()) != hipSuccess) return e;                      // warm-up
+    if ((e = hipEventRecord(e0, st)) != hipSuccess) return e;
+    for (int i = 0; i < reps; ++i)
+      if ((e = launch()) != hipSuccess) return e;
+    if ((e = hipEventRecord(e1, st)) != hipSuccess) return e;
+    if ((e = hipEventSynchronize(e1)) != hipSuccess) return e;
+    return hipEventElapsedTime(ms, e0, e1);
+  };
+  hipError_t err = hipSuccess;
+  if (copy_bytes_per_s) {
+    const int64_t bytes = std::min<int64_t>((int64_t)c->slices * c->N * c->d * (int64_t)sizeof(half_t), (int64_t)4 << 30) / 16 * 16;
+    float ms = 0.f;
+    err = timed([&] { return launch_probe_copy(c->tmp0, c->tmp1, bytes, c->num_cu, st); }, 3, &ms);
+    if (err == hipSuccess) *copy_bytes_per_s = 2.0 * (double)bytes * 3 / (ms * 1e-3);
+  }
+  if (err == hipSuccess && mfma_flops_per_s) {
+    const int blocks = c->num_cu * 2, iters = 20000;   // needs blocks*256 floats of scratch: tmp0 is far larger
+    if ((int64_t)blocks * 256 * 4 > (int64_t)c->slices * c->N * c->d * (int64_t)sizeof(half_t)) err = hipErrorInvalidValue;
+    float ms = 0.f;
+    if (err == hipSuccess) err = timed([&] { return launch_probe_mfma((float*)c->tmp0, blocks, iters, st); }, 2, &ms);
+    if (err == hipSuccess) *mfma_flops_per_s = (double)blocks * 4 * iters * 4 * 32768.0 * 2 / (ms * 1e-3);
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (err != hipSuccess) return fail(c, FREQATTN_EHIP, std::string("freqattn_measure_peaks: ") + hipGetErrorString(err));
+  return FREQATTN_OK;
+}
+
 extern "C" int64_t freqattn_workspace_bytes(const freqattn_ctx* c) { return c ? c->dev_bytes : 0; }
 
 extern "C" freqattn_status freqattn_band_sizes(const freqattn_ctx* c, int64_t n[3]) {

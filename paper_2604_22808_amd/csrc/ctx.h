@@ -171,6 +171,8 @@ hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, fl
                               int is_half, hipStream_t st);
 // Adds up the per-wave partial sums of the three fused W-axis passes in a fixed order: stats[band][channel].
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
+hipError_t launch_probe_copy(const void* in, void* out, int64_t bytes, int num_cu, hipStream_t st);
+hipError_t launch_probe_mfma(float* out, int blocks, int iters, hipStream_t st);
 // out[slice] = in[slice] for the listed slices (slice_bytes each, a multiple of 16).
 hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_list, int n_slices, int64_t slice_bytes,
                               hipStream_t st);

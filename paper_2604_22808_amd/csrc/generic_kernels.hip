@@ -410,6 +410,17 @@ hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Plain streaming copy, 16 bytes per thread and step: the machine's achievable HBM read+write rate, measured next
+// to the transform passes (which are read-once / write-once kernels of the same kind).
+__global__ void __launch_bounds__(256) k_probe_copy(const uint4* __restrict__ in, uint4* __restrict__ out, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) out[i] = in[i];
+}
+hipError_t launch_probe_copy(const void* in, void* out, int64_t bytes, int num_cu, hipStream_t st) {
+  if (bytes < 16) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)(num_cu * 16)), dim3(256), 0, st, (const uint4*)in, (uint4*)out, bytes / 16);
+  return hipGetLastError();
+}
+
 __global__ void k_copy_slices(const uint4* in, uint4* out, const int32_t* slice_list, int64_t vec_per_slice) {
   const int64_t base = (int64_t)slice_list[blockIdx.y] * vec_per_slice;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < vec_per_slice; i += (int64_t)gridDim.x * blockDim.x)

@@ -470,6 +470,32 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
   }
 }
 
+// Loop of independent v_mfma_f32_32x32x16_f16 (four accumulators per wave, two waves per SIMD): the matrix-core rate
+// the machine sustains for this instruction, measured next to the attention kernel.
+__global__ void __launch_bounds__(256, 2) k_probe_mfma(float* out, int iters) {
+  half8 a, b;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { a[j] = (_Float16)(0.001f * (threadIdx.x & 63) + j); b[j] = (_Float16)(0.5f * j - 0.002f * (threadIdx.x & 63)); }
+  float16v c0, c1, c2, c3;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) c0[r] = c1[r] = c2[r] = c3[r] = 0.f;
+  for (int i = 0; i < iters; ++i) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c3, 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s += c0[r] + c1[r] + c2[r] + c3[r];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+// flops of one launch: blocks * 4 waves * iters * 4 MFMAs * 32*32*16*2; out needs blocks*256 floats
+hipError_t launch_probe_mfma(float* out, int blocks, int iters, hipStream_t st) {
+  hipLaunchKernelGGL(k_probe_mfma, dim3((unsigned)blocks), dim3(256), 0, st, out, iters);
+  return hipGetLastError();
+}
+
 template <int D, int NW, int QT, bool BF16IN>
 static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_items, int num_cu, hipStream_t st) {
   // resident workgroups per CU: register-limited waves per SIMD (accumulators of QT query tiles), 4 SIMDs per CU

@@ -346,3 +346,11 @@ def test_haar_64k_router_statistics_and_routed_forward():
     assert np.array_equal(alloc2, want_alloc)
     want = O.forward(q, k, v, wl.grid, cfg, want_alloc)
     _check(U.to_host64(out), want, "bf16", f"haar 64k routed alloc={list(alloc2)}")
+
+
+def test_measure_peaks_reports_machine_rates():
+    wl = WL.WORKLOADS["64k"]
+    ctx, _ = U.make_ctx(wl)
+    copy_bps, mfma_fps = ctx.measure_peaks()
+    print(f"copy {copy_bps / 1e9:.0f} GB/s, mfma loop {mfma_fps / 1e12:.0f} TFLOP/s", flush=True)
+    assert 1e11 < copy_bps < 3e13 and 1e14 < mfma_fps < 5.1e15
