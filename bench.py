@@ -220,6 +220,7 @@ def main():
                    "grid": list(wl.grid), "tokens": wl.n_tokens, "band": wl.band, "alloc": wl.alloc,
                    "head_alloc": [int(a) for a in alloc], "pi": None if pi is None else [round(float(p), 4) for p in pi],
                    "launch": "separate" if args.separate else "fused",
+                   "alloc_prediction": "previous forward's high heads (exact in this constant-t loop)" if router is not None else None,
                    "precision": "bf16 tensors in and out, fp16 MFMA operands and intermediates, fp32 accumulation"},
         "roofline": roofline, "stages": stage_report,
         "measured_peaks": {"copy_GBs": round(copy_bps / 1e9, 1), "mfma_f16_TFLOPs": round(mfma_fps / 1e12, 1)},

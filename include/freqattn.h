@@ -168,6 +168,13 @@ freqattn_status freqattn_set_stage_timing(freqattn_ctx* ctx, int32_t enabled);
 freqattn_status freqattn_stage_times(freqattn_ctx* ctx, int32_t max_stages, const char** names_out, float* ms_out,
                                      int32_t* n_stages);
 
+/* freqattn_forward_routed has to transform Q and K before it knows which heads run the high band (the only ones that
+ * need Q~ and K~ on the whole grid).  With prediction on (the default) it assumes the heads that ran the high band in
+ * the context's last forward will do so again - allocations move slowly along a sampling trajectory (section 3.5) - and
+ * transforms them in full at once; heads that are newly high after routing are completed then, as all of them are
+ * without prediction.  Outputs do not depend on the setting (statistics agree to fp32 rounding). */
+freqattn_status freqattn_set_alloc_prediction(freqattn_ctx* ctx, int32_t enabled);
+
 /* Machine rates for the rooflines (section 6 discusses both bounds), measured with the context's own scratch on
  * `stream`; the call synchronises.  *copy_bytes_per_s HOST: bytes read plus bytes written per second by a plain
  * streaming copy of one scratch tensor into another (up to 4 GiB; meaningful when the scratch is much larger than the

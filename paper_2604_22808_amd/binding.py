@@ -38,6 +38,7 @@ EXPORTS = {
     "freqattn_last_error": (C.c_char_p, [C.c_void_p]),
     "freqattn_set_launch_mode": (C.c_int, [C.c_void_p, C.c_int32]),
     "freqattn_get_path": (C.c_int32, [C.c_void_p]),
+    "freqattn_set_alloc_prediction": (C.c_int, [C.c_void_p, C.c_int32]),
     "freqattn_band_sizes": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "freqattn_band_index": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
     "freqattn_mid_blocks": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
@@ -171,6 +172,9 @@ class Context:
     # ---- options and introspection
     def set_launch_mode(self, mode):
         self._check(lib().freqattn_set_launch_mode(self._h, mode))
+
+    def set_alloc_prediction(self, enabled):
+        self._check(lib().freqattn_set_alloc_prediction(self._h, 1 if enabled else 0))
 
     def get_path(self):
         return lib().freqattn_get_path(self._h)

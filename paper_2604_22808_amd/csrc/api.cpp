@@ -215,7 +215,7 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
   A(dev_alloc_bytes(*c, &c->Cbuf, (size_t)c->slices * 3 * 2 * (size_t)std::max(g.n_summary, 1) * c->d * es));
   const size_t stats_floats = (size_t)3 * c->d * (1 + 64);
   A(dev_alloc(*c, &c->d_stats, stats_floats));
-  if (mf) A(dev_alloc(*c, &c->d_energy_part, (size_t)3 * DCT_MAX_WAVES * 3 * 64));
+  if (mf) A(dev_alloc(*c, &c->d_energy_part, (size_t)5 * DCT_MAX_WAVES * 3 * 64));
   if (mf) A(dev_alloc(*c, &c->d_tot_part, (size_t)2 * DCT_MAX_WAVES * 64));
   {
     auto box = [](int64_t num, int64_t den, int n) { return (int)((num * n + den - 1) / den); };  // #k with k*den < num*n
@@ -236,6 +236,8 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
     c->off_masks = ints; ints += (size_t)c->slices;
     for (int l = 0; l < 3; ++l) { c->off_list[l] = ints; ints += (size_t)c->slices; }
     for (int k = 0; k < 4; ++k) { c->off_cls[k] = ints; ints += (size_t)c->slices; }
+    c->off_nonhigh = ints; ints += (size_t)c->slices;
+    c->off_fix = ints; ints += (size_t)c->slices;
     ints = (ints + 3) & ~(size_t)3;
     c->off_items = ints; ints += 4 * per_slice * c->slices;
     for (int l = 0; l < 3; ++l) { c->off_items_kind[l] = ints; ints += 4 * per_slice * c->slices; }
@@ -283,6 +285,11 @@ extern "C" freqattn_status freqattn_set_launch_mode(freqattn_ctx* c, int32_t mod
   if (mode != FREQATTN_LAUNCH_FUSED && mode != FREQATTN_LAUNCH_SEPARATE)
     return fail(c, FREQATTN_EINVAL, "freqattn_set_launch_mode: unknown mode");
   c->launch_mode = mode;
+  return FREQATTN_OK;
+}
+extern "C" freqattn_status freqattn_set_alloc_prediction(freqattn_ctx* c, int32_t enabled) {
+  if (!c) return FREQATTN_EINVAL;
+  c->predict_alloc = enabled ? 1 : 0;
   return FREQATTN_OK;
 }
 extern "C" int32_t freqattn_get_path(const freqattn_ctx* c) { return c ? c->path : -1; }
@@ -373,6 +380,7 @@ static void build_lists(Ctx& c, const int32_t* head_alloc) {
   const int heads = c.shape.heads;
   for (int l = 0; l < 3; ++l) c.n_list[l] = 0;
   for (int k = 0; k < 4; ++k) c.n_cls[k] = 0;
+  c.n_nonhigh = 0;
   for (int s = 0; s < c.slices; ++s) {
     const int mask = head_alloc[s % heads];
     L[c.off_masks + s] = mask;
@@ -381,6 +389,7 @@ static void build_lists(Ctx& c, const int32_t* head_alloc) {
       if (((mask >> l) & 1) && c.band_n[l] > 0) eff |= 1 << l;
     const int cls = (eff & 4) ? 2 : (eff & 2) ? 1 : (eff & 1) ? 0 : 3;
     L[c.off_cls[cls] + c.n_cls[cls]++] = s;
+    if (cls != 2) L[c.off_nonhigh + c.n_nonhigh++] = s;
     for (int l = 0; l < 3; ++l)
       if (((mask >> l) & 1) && c.band_n[l] > 0) L[c.off_list[l] + c.n_list[l]++] = s;
   }
@@ -615,21 +624,35 @@ struct StageTimer {
 // sections 3.2 / 3.3: spectral transform of Q, K, V into band-major buffers; with_stats also leaves the router's
 // band statistics (section 3.5) in d_stats.
 static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const void* k, const void* v, hipStream_t st,
-                                        bool with_stats) {
+                                        bool with_stats, bool predict = false) {
   const bool fused_stats = with_stats && c->path == FREQATTN_PATH_MFMA;
   if (fused_stats) {
     // Router in the loop: the allocation is not known yet.  V~ is needed everywhere; Q~ and K~ are computed on the
     // low+mid box only, which gives their low and mid statistics exactly and their high-band energy by Parseval;
     // slices that turn out to run the high band get their Q~ and K~ completed afterwards (complete_qk_for_high).
+    // With `predict`, the slices that ran the high band under the context's last allocation (allocations move
+    // slowly along a sampling trajectory) get the whole-grid transform straight away, with all three statistics
+    // taken directly; whatever the router then decides, only slices that are newly high need the completion.
     const int full[3] = {c->shape.T, c->shape.H, c->shape.W};
     int mid[3];
     bool pruned = false;
     for (int a = 0; a < 3; ++a) { mid[a] = keep_rows(c->mid_box[a], full[a]); pruned = pruned || mid[a] < full[a]; }
     c->energy_waves = 0; c->tot_waves = 0; c->qk_on_mid_box = pruned;
-    HIP_TRY(c, launch_fill_zero(c->d_energy_part, (int64_t)3 * DCT_MAX_WAVES * 3 * 64, st));
+    c->qk_full.assign((size_t)c->slices, pruned ? 0 : 1);
+    HIP_TRY(c, launch_fill_zero(c->d_energy_part, (int64_t)5 * DCT_MAX_WAVES * 3 * 64, st));
     if (pruned) HIP_TRY(c, launch_fill_zero(c->d_tot_part, (int64_t)2 * DCT_MAX_WAVES * 64, st));
-    HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, nullptr, c->slices, pruned ? mid : full, 0, pruned ? 0 : -1));
-    HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, nullptr, c->slices, pruned ? mid : full, 1, pruned ? 1 : -1));
+    if (pruned && predict && c->alloc_valid && c->n_cls[2] > 0) {
+      const int32_t* L = c->d_lists;
+      const int32_t* hl = c->h_lists + c->off_cls[2];
+      for (int i = 0; i < c->n_cls[2]; ++i) c->qk_full[(size_t)hl[i]] = 1;
+      HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, L + c->off_nonhigh, c->n_nonhigh, mid, 0, 0));
+      HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, L + c->off_nonhigh, c->n_nonhigh, mid, 1, 1));
+      HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, L + c->off_cls[2], c->n_cls[2], full, 3, -1));
+      HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, L + c->off_cls[2], c->n_cls[2], full, 4, -1));
+    } else {
+      HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, nullptr, c->slices, pruned ? mid : full, 0, pruned ? 0 : -1));
+      HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, nullptr, c->slices, pruned ? mid : full, 1, pruned ? 1 : -1));
+    }
     HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, full, 2, -1));
     HIP_TRY(c, launch_energy_reduce(c->d_energy_part, pruned ? c->d_tot_part : nullptr, c->d_stats, c->d, c->energy_waves,
                                     c->tot_waves, st));
@@ -661,12 +684,21 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
 }
 
 // After routing with Q~ and K~ on the low+mid box only: the slices that run the high band get the full transforms.
+// (The caller has synchronised the stream since the first phase was queued - the router reads the statistics back -
+// so the fix list's region of the pinned host buffer is not the source of a copy still in flight.)
 static freqattn_status complete_qk_for_high(freqattn_ctx* c, const void* q, const void* k, hipStream_t st) {
   if (c->path != FREQATTN_PATH_MFMA || !c->qk_on_mid_box || c->n_cls[2] == 0) return FREQATTN_OK;
   const int full[3] = {c->shape.T, c->shape.H, c->shape.W};
-  const int32_t* list = c->d_lists + c->off_cls[2];
-  HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, list, c->n_cls[2], full, -1, -1));
-  HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, list, c->n_cls[2], full, -1, -1));
+  int32_t* fix = c->h_lists + c->off_fix;
+  const int32_t* high = c->h_lists + c->off_cls[2];
+  int n_fix = 0;
+  for (int i = 0; i < c->n_cls[2]; ++i)
+    if (!c->qk_full[(size_t)high[i]]) fix[n_fix++] = high[i];
+  if (n_fix == 0) return FREQATTN_OK;
+  HIP_TRY(c, hipMemcpyAsync(c->d_lists + c->off_fix, fix, (size_t)n_fix * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  const int32_t* list = c->d_lists + c->off_fix;
+  HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, list, n_fix, full, -1, -1));
+  HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, list, n_fix, full, -1, -1));
   return FREQATTN_OK;
 }
 
@@ -807,7 +839,7 @@ extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* 
   hipStream_t st = (hipStream_t)stream;
   const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
   StageTimer tm(*c, st);
-  fs = transforms_phase(c, q, k, v, st, true);
+  fs = transforms_phase(c, q, k, v, st, true, c->predict_alloc != 0);
   if (fs != FREQATTN_OK) return fs;
   tm.done("forward_transform");
   fs = router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc_out, pi_out, nullptr, st);

@@ -98,6 +98,11 @@ struct Ctx {
   int n_list[3] = {0, 0, 0};
   size_t off_cls[4] = {0, 0, 0, 0};   // [slices] slices by class: 0 low only, 1 mid (no high), 2 high, 3 nothing active
   int n_cls[4] = {0, 0, 0, 0};
+  size_t off_nonhigh = 0;             // [slices] classes 0, 1 and 3 together (every slice that does not run the high band)
+  int n_nonhigh = 0;
+  size_t off_fix = 0;                 // [slices] routed forward: slices whose Q~/K~ have to be completed after routing
+  int predict_alloc = 1;              // routed forward: transform Q/K of the last allocation's high slices in full at once
+  std::vector<char> qk_full;          // routed forward: slices whose Q~/K~ the first phase computed on the whole grid
   size_t off_items = 0;               // AttnItem array (fused order: all branches), then exchange items
   int n_items_branch = 0;             // low+mid+high items in cost order
   int n_items_kind[3] = {0, 0, 0};    // per-branch sub-lists follow at off_items_kind
@@ -176,7 +181,7 @@ hipError_t launch_probe_mfma(float* out, int blocks, int iters, hipStream_t st);
 // out[slice] = in[slice] for the listed slices (slice_bytes each, a multiple of 16).
 hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_list, int n_slices, int64_t slice_bytes,
                               hipStream_t st);
-hipError_t launch_energy_reduce(const float* energy_part /*[3][DCT_MAX_WAVES][3][64]*/,
+hipError_t launch_energy_reduce(const float* energy_part /*[5][DCT_MAX_WAVES][3][64]: Q, K (box), V, Q, K (whole grid)*/,
                                 const float* tot_part /*[2][DCT_MAX_WAVES][64] or NULL*/, float* stats, int d,
                                 int n_waves, int n_waves_tot, hipStream_t st);
 

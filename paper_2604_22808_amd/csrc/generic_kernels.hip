@@ -451,7 +451,7 @@ __global__ void __launch_bounds__(256) k_energy_reduce(const float* part, const 
   const int per = (n_waves - chunk + chunks - 1) / chunks;   // waves of this chunk
   const bool parseval = tot_part != nullptr && band == 2;
   float t = 0.f;
-  for (int i = tid; i < 3 * per; i += 256) {
+  for (int i = tid; i < 5 * per; i += 256) {   // slots: Q, K on the box (Parseval for the high band), V, Q, K on the whole grid
     const int tensor = i / per, w = chunk + (i % per) * chunks;
     const float* p3 = part + (((size_t)tensor * DCT_MAX_WAVES + w) * 3) * 64 + col;
     if (parseval && tensor < 2) t -= p3[0] + p3[64];

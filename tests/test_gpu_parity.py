@@ -354,3 +354,34 @@ def test_measure_peaks_reports_machine_rates():
     copy_bps, mfma_fps = ctx.measure_peaks()
     print(f"copy {copy_bps / 1e9:.0f} GB/s, mfma loop {mfma_fps / 1e12:.0f} TFLOP/s", flush=True)
     assert 1e11 < copy_bps < 3e13 and 1e14 < mfma_fps < 5.1e15
+
+
+def test_routed_forward_with_allocation_prediction():
+    """The routed forward transforms Q/K of the heads that were high in the previous call in full at once and completes
+    only newly high heads after routing: whatever was predicted, allocation and output bits are those of the plain
+    forward with the routed allocation (and of the routed forward with prediction switched off)."""
+    import torch
+    wl = WL.WORKLOADS["64k"]
+    heads = [0, 1, 2, 3, 4, 5]
+    q, k, v = _inputs(wl, heads=heads)
+    ctx, band = U.make_ctx(wl, heads=len(heads))
+    ref, _ = U.make_ctx(wl, heads=len(heads))
+    ref.set_alloc_prediction(False)
+    cfg = U.oracle_cfg(band)
+    w = WL.router_weights(wl.alloc["hidden"], wl.alloc["seed"])
+    dq, dk, dv = (U.to_device(x, "bf16") for x in (q, k, v))
+    out, out_ref, out_plain = (torch.empty_like(dq) for _ in range(3))
+    seen = set()
+    for t in (0.9, 0.9, 0.1, 0.1, 0.5, 0.9):          # first call: nothing to predict from; then right and wrong guesses
+        alloc, pi = ctx.forward_routed(dq, dk, dv, t, *w, out)
+        alloc_ref, _ = ref.forward_routed(dq, dk, dv, t, *w, out_ref)
+        want_alloc, _ = O.route_mlp(q, k, v, wl.grid, cfg, t, *w)
+        torch.cuda.synchronize()
+        assert np.array_equal(alloc, want_alloc) and np.array_equal(alloc_ref, want_alloc), (t, alloc, alloc_ref, want_alloc)
+        ref.forward(dq, dk, dv, alloc, out_plain)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out_plain) and torch.equal(out_ref, out_plain), t
+        seen.add(tuple(int(a) for a in alloc))
+    assert len(seen) >= 2                                # the sequence really changes the allocation
+    want = O.forward(q, k, v, wl.grid, cfg, alloc)
+    _check(U.to_host64(out), want, "bf16", f"64k routed with prediction, alloc={list(alloc)}")
