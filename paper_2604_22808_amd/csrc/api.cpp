@@ -444,7 +444,17 @@ static freqattn_status ensure_lists(freqattn_ctx* c, const int32_t* head_alloc, 
   if (c->alloc_valid && std::memcmp(c->h_alloc.data(), head_alloc, heads * sizeof(int32_t)) == 0) return FREQATTN_OK;
   HIP_TRY(c, hipStreamSynchronize(st));  // earlier forwards may still read the lists
   build_lists(*c, head_alloc);
-  HIP_TRY(c, hipMemcpyAsync(c->d_lists, c->h_lists, c->lists_bytes, hipMemcpyHostToDevice, st));
+  // upload what the new allocation uses: the slice lists, the used part of each item list, and the dense comparison's
+  // list (independent of the allocation) the first time only
+  auto up = [&](size_t off_ints, size_t n_ints) -> hipError_t {
+    if (n_ints == 0) return hipSuccess;
+    return hipMemcpyAsync(c->d_lists + off_ints, c->h_lists + off_ints, n_ints * sizeof(int32_t), hipMemcpyHostToDevice, st);
+  };
+  HIP_TRY(c, up(0, c->off_items));
+  HIP_TRY(c, up(c->off_items, (size_t)4 * c->n_items_branch));
+  for (int kd = 0; kd < 3; ++kd) HIP_TRY(c, up(c->off_items_kind[kd], (size_t)4 * c->n_items_kind[kd]));
+  HIP_TRY(c, up(c->off_items_xchg, (size_t)4 * c->n_items_xchg));
+  if (!c->alloc_valid) HIP_TRY(c, up(c->off_items_dense, (size_t)4 * c->n_items_dense));
   c->h_alloc.assign(head_alloc, head_alloc + heads);
   c->alloc_valid = true;
   return FREQATTN_OK;
