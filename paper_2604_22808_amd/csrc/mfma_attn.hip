@@ -77,6 +77,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
   // so that those tiles are fetched into one L2 once instead of into all eight.
   int it_first = blockIdx.x;
   if ((gridDim.x & 7) == 0) it_first = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  int lds_holds = -1;   // (slice, band) whose summary tiles the LDS copies hold, -1: something else
   for (int it = it_first; it < n_items; it += gridDim.x) {
     const AttnItem item = items[it];
     const int kind = item.kind_band & 0xff, band = item.kind_band >> 8;
@@ -249,7 +250,12 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
     // Pipeline: at the top of iteration i the registers hold tile i+1 (requested one iteration ago); it goes into the
     // LDS copy that tile i-1 used - free since the barrier that ended iteration i-1 - and the loads of tile i+2 are
     // issued, a whole iteration ahead of their use.  The barrier at the end of the iteration publishes tile i+1.
-    if (n_tt > 0) {   // (the barrier that ended the previous item's last tile already freed both copies)
+    // Exchange items of one (slice, band) all see the same <= 2 tiles of summary tokens: a workgroup that has them in
+    // its two LDS copies from its previous item keeps them (no loads, no stores for this item).
+    const int lds_key = (kind == 3 && n_tt <= 2) ? (int)(slice * 4 + band) : -1;
+    const bool reuse = lds_key >= 0 && lds_key == lds_holds;
+    lds_holds = lds_key;
+    if (n_tt > 0 && !reuse) {   // (the barrier that ended the previous item's last tile already freed both copies)
       load_tile(key0_of(0));
       store_tile(0);
       if (n_tt > 1) load_tile(key0_of(1));
@@ -262,7 +268,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       // Staging of the next tiles.  Half of the waves do it before the score MFMAs and half after them, so that the
       // workgroup's LDS stores and global loads do not all queue up behind one barrier.
       auto stage = [&]() {
-        if (idx + 1 < n_tt) {
+        if (idx + 1 < n_tt && !reuse) {
           store_tile((idx + 1) & 1);
           if (idx + 2 < n_tt) load_tile(key0_of(idx + 2));
         }
