@@ -178,6 +178,17 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
     const bool has_next = tile + tile_step < n_tiles32;
     if (has_next) nxt = tile_addr(tile + tile_step);
 
+    // band-major rows of this lane's output rows, requested now so that the stores of the epilogue do not wait for them
+    int32_t prow[MT][4];
+    if (PERM_OUT) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int k = mt * 32 + it * 8 + lrow;
+          prow[mt][it] = k < NO ? a.perm_out[(int64_t)k * a.perm_k + cur.pidx] : 0;
+        }
+    }
     float16v acc[MT][2];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -281,7 +292,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
         if (k < NO) {
           uint4v v = *(const uint4v*)(Xo + (it * 8 + lrow) * DCT_XS_STRIDE + lcol);
           int64_t off;
-          if (PERM_OUT) off = (cur.bm_off + a.perm_out[(int64_t)k * a.perm_k + cur.pidx]) * a.d + cur.dcol;
+          if (PERM_OUT) off = (cur.bm_off + prow[mt][it]) * a.d + cur.dcol;
           else off = cur.out_off + (int64_t)k * cur.out_stride;
           if (!PERM_OUT && a.resid) {   // out = resid + result, both bf16 in memory, the sum formed in fp32
             const uint4v rs = *(const uint4v*)((const uint16_t*)a.resid + off + lcol);
