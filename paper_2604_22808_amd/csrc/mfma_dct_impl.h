@@ -138,9 +138,9 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
     return t;
   };
   // this lane's 16-byte piece of input row j
-  auto load_piece = [&](const TileAddr& t, int j) -> uint4v {
+  // (gather: `row` is the band-major row of input row j, looked up one tile ahead by perm_rows)
+  auto load_piece = [&](const TileAddr& t, int j, int32_t row) -> uint4v {
     if (PERM_IN) {
-      const int32_t row = a.perm_in[(int64_t)j * a.perm_k + t.pidx];
       const int band = row < a.band_off1 ? 0 : (row < a.band_off2 ? 1 : 2);
       const bool active = (t.mask >> band) & 1;
       const int64_t off = (t.bm_off + row) * a.d + t.dcol + lcol;
@@ -166,17 +166,28 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
   constexpr int PD = (NCH % 2 == 0) ? 2 : 1;
   uint4v R[PD][LPC];
   TileAddr cur, nxt;
+  // gather: band-major rows of this lane's NCH*LPC input rows, of the current tile and (requested at the start of the
+  // current tile, so that the data loads at its end do not wait for them) of the next one
+  constexpr int NPR = PERM_IN ? NCH * LPC : 1;
+  int32_t pcur[NPR], pnxt[NPR];
+  auto perm_rows = [&](const TileAddr& t, int32_t (&pr)[NPR]) {
+    if (PERM_IN) {
+#pragma unroll
+      for (int i = 0; i < NPR; ++i) pr[i] = a.perm_in[(int64_t)((i / LPC) * RC + (i % LPC) * 8 + lrow) * a.perm_k + t.pidx];
+    }
+  };
   if (tile < n_tiles32) {
     cur = tile_addr(tile);
+    perm_rows(cur, pcur);
 #pragma unroll
     for (int ch = 0; ch < PD; ++ch)
 #pragma unroll
-      for (int it = 0; it < LPC; ++it) R[ch][it] = load_piece(cur, ch * RC + it * 8 + lrow);
+      for (int it = 0; it < LPC; ++it) R[ch][it] = load_piece(cur, ch * RC + it * 8 + lrow, pcur[PERM_IN ? ch * LPC + it : 0]);
   }
 
   for (; tile < n_tiles32; tile += tile_step) {
     const bool has_next = tile + tile_step < n_tiles32;
-    if (has_next) nxt = tile_addr(tile + tile_step);
+    if (has_next) { nxt = tile_addr(tile + tile_step); perm_rows(nxt, pnxt); }
 
     // band-major rows of this lane's output rows, requested now so that the stores of the epilogue do not wait for them
     int32_t prow[MT][4];
@@ -213,10 +224,12 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
       }
       if (ch + PD < NCH) {
 #pragma unroll
-        for (int it = 0; it < LPC; ++it) R[ch % PD][it] = load_piece(cur, (ch + PD) * RC + it * 8 + lrow);
+        for (int it = 0; it < LPC; ++it)
+          R[ch % PD][it] = load_piece(cur, (ch + PD) * RC + it * 8 + lrow, pcur[PERM_IN ? (ch + PD) * LPC + it : 0]);
       } else if (has_next) {
 #pragma unroll
-        for (int it = 0; it < LPC; ++it) R[ch % PD][it] = load_piece(nxt, (ch + PD - NCH) * RC + it * 8 + lrow);
+        for (int it = 0; it < LPC; ++it)
+          R[ch % PD][it] = load_piece(nxt, (ch + PD - NCH) * RC + it * 8 + lrow, pnxt[PERM_IN ? (ch + PD - NCH) * LPC + it : 0]);
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -310,6 +323,8 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     }
     cur = nxt;
+#pragma unroll
+    for (int i = 0; i < NPR; ++i) pcur[i] = pnxt[i];
   }
   if (ENERGY || TOT) {
     const int gwave = blockIdx.x * DCT_WAVES + wave;
