@@ -365,16 +365,49 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
               S[qt][t2][r] = tmin < 0.f ? -INFINITY : S[qt][t2][r];
             }
         }
-        float m0 = -INFINITY;
+        // row maximum: four independent chains (short dependency depth), then the other lane half through a register
+        // swap (v_permlane32_swap leaves [lo, lo] / [hi, hi] in the two registers; no trip through the LDS pipe)
+        float mc[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-          for (int r = 0; r < 16; r += 2) m0 = __builtin_fmaxf(__builtin_fmaxf(m0, S[qt][t2][r]), S[qt][t2][r + 1]);
-        m0 = fmaxf(m0, __shfl_xor(m0, 32));
+          for (int r = 0; r < 16; r += 2)
+            mc[(r >> 1) & 3] = __builtin_fmaxf(__builtin_fmaxf(mc[(r >> 1) & 3], S[qt][t2][r]), S[qt][t2][r + 1]);
+        float m0 = fmaxf(fmaxf(mc[0], mc[1]), fmaxf(mc[2], mc[3]));
+        {
+          const uint32_t mb = __float_as_uint(m0);
+          const auto sw = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+          m0 = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        }
         mx[qt] = m0;
         bump[qt] = (m_run[qt] == -INFINITY) ? (m0 > -INFINITY) : (m0 > kBump);
         any_bump = any_bump || bump[qt];
       }
+      // Probabilities, two per register, rounded toward zero; the row sum is taken over the rounded values (the ones
+      // the matrix core multiplies), so the rounding direction cancels in P / sum(P).  They are formed before the
+      // (rare) reference bump is known, so that the exponentials overlap the maximum's dependency chain.
+      auto probabilities = [&](int qt) -> float {
+        float ps[4] = {0.f, 0.f, 0.f, 0.f};
+        const half2v ones = {(_Float16)1.f, (_Float16)1.f};
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            uint4v pk;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const half2v h2 = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(
+                  __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + 2 * j]), __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + 2 * j + 1])));
+              ps[j] = __builtin_amdgcn_fdot2(h2, ones, ps[j], false);
+              pk[j] = __builtin_bit_cast(uint32_t, h2);
+            }
+            P[qt][t2][s2] = __builtin_bit_cast(half8, pk);
+          }
+        return (ps[0] + ps[1]) + (ps[2] + ps[3]);
+      };
+      float psum[QT];
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) psum[qt] = probabilities(qt);
       if (__builtin_amdgcn_ballot_w64(any_bump) != 0) {
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
@@ -391,30 +424,11 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
           for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) O[qt][dt][r] *= alpha;
+          psum[qt] = probabilities(qt);   // again, against the moved reference
         }
       }
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
-        float psum = 0.f;
-        const half2v ones = {(_Float16)1.f, (_Float16)1.f};
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            uint4v pk;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              // two probabilities per register, rounded toward zero; the row sum is taken over the rounded values (the
-              // ones the matrix core multiplies), so the rounding direction cancels in P / sum(P)
-              const half2v h2 = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(
-                  __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + 2 * j]), __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + 2 * j + 1])));
-              psum = __builtin_amdgcn_fdot2(h2, ones, psum, false);
-              pk[j] = __builtin_bit_cast(uint32_t, h2);
-            }
-            P[qt][t2][s2] = __builtin_bit_cast(half8, pk);
-          }
-        l_run[qt] += psum;
-      }
+      for (int qt = 0; qt < QT; ++qt) l_run[qt] += psum[qt];
       // ---- O^T += V^T P^T; a V operand feeds all query tiles of the wave
       {
         constexpr int NS = 4 * DT;   // (t2, s2, dt) flattened, dt fastest
