@@ -385,3 +385,31 @@ def test_routed_forward_with_allocation_prediction():
     assert len(seen) >= 2                                # the sequence really changes the allocation
     want = O.forward(q, k, v, wl.grid, cfg, alloc)
     _check(U.to_host64(out), want, "bf16", f"64k routed with prediction, alloc={list(alloc)}")
+
+
+def test_batch_of_two_on_a_side_stream():
+    """batch 2 x 3 heads (slice = batch index * heads + head, the allocation repeats per batch entry), both paths, with
+    the forward queued on a non-default stream."""
+    import torch
+    grid, d = (16, 16, 32), 128
+    rng = np.random.default_rng(21)
+    N = int(np.prod(grid))
+    q, k, v = (WL.round_to_io(0.4 * rng.standard_normal((2, 3, N, d)), "bf16") for _ in range(3))
+    band = dict(WL.WORKLOADS["16k"].band)
+    band.update(mid_block=64, mid_diag=1, mid_stride=4, high_window=100, n_summary=6)
+    alloc = (4, 1, 2)
+    want = O.forward(q, k, v, grid, O.BandConfig(**band), alloc)
+    assert np.abs(want[0] - want[1]).max() > 1e-3      # the two batch entries really differ
+    for path in (B.PATH_MFMA, B.PATH_GENERIC):
+        ctx = B.Context(2, 3, d, grid, B.BF16, B.make_cfg(**band), path=path)
+        dq, dk, dv = (U.to_device(x, "bf16") for x in (q, k, v))
+        out = torch.empty_like(dq)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            ctx.forward(dq, dk, dv, alloc, out)
+        side.synchronize()
+        got = U.to_host64(out)
+        for b in range(2):
+            for h in range(3):
+                _check(got[b, h], want[b, h], "bf16", f"path {path} batch {b} head {h} mask {alloc[h]}")
