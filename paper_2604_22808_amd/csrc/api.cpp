@@ -53,7 +53,7 @@ static hipError_t dev_alloc_bytes(Ctx& c, void** p, size_t bytes) {
 
 static void free_all(Ctx* c) {
   auto F = [](void* p) { if (p) (void)hipFree(p); };
-  F(c->d_perm); F(c->d_row_ptr); F(c->d_col_idx);
+  F(c->d_perm); F(c->d_perm_t); F(c->d_row_ptr); F(c->d_col_idx);
   for (int a = 0; a < 3; ++a) { F(c->d_F32[a]); F(c->d_Ft32[a]); F(c->d_F16[a]); F(c->d_Ft16[a]); }
   F(c->specQ); F(c->specK); F(c->specV); F(c->Y); F(c->tmp0); F(c->tmp1);
   F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_lists); F(c->d_energy_part);
@@ -160,6 +160,14 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
   auto A = [&](hipError_t r) { if (e == hipSuccess) e = r; };
   A(dev_alloc(*c, &c->d_perm, (size_t)c->N));
   up(c->d_perm, c->h_perm.data(), (size_t)c->N * 4);
+  if (mf) {   // [kh*W + kw][kt] copy for the T-axis passes of the MFMA path
+    std::vector<int32_t> pt((size_t)c->N);
+    const int64_t hw = (int64_t)s.H * s.W;
+    for (int64_t kt = 0; kt < s.T; ++kt)
+      for (int64_t r = 0; r < hw; ++r) pt[(size_t)(r * s.T + kt)] = c->h_perm[(size_t)(kt * hw + r)];
+    A(dev_alloc(*c, &c->d_perm_t, (size_t)c->N));
+    up(c->d_perm_t, pt.data(), (size_t)c->N * 4);
+  }
   A(dev_alloc(*c, &c->d_row_ptr, c->h_row_ptr.size()));
   up(c->d_row_ptr, c->h_row_ptr.data(), c->h_row_ptr.size() * 4);
   A(dev_alloc(*c, &c->d_col_idx, c->h_col_idx.size()));
@@ -498,7 +506,7 @@ static hipError_t forward_transform_mfma(Ctx& c, const void* x, void* spec, hipS
   t.d = d; t.Ntok = c.N;
   t.in = c.tmp1; t.out = spec; t.M = c.d_F16[0]; t.ldm = T; t.n = T; t.n_out = kt; t.inner = (int64_t)kw * d;
   t.nslab = (int64_t)ns * kh; t.outer = kh; t.slice_list = slice_list;
-  t.perm_out = c.d_perm; t.perm_k = (int64_t)H * W; t.perm_o = W;
+  t.perm_out = c.d_perm_t; t.perm_k = 1; t.perm_o = W; t.perm_scale = T;
   if (energy_slot >= 0) {
     t.energy_part = c.d_energy_part + (size_t)energy_slot * DCT_MAX_WAVES * 3 * 64;
     t.en_omul = W; t.en_div = W;  // the tile's other coordinates are (kh, kw)
@@ -524,7 +532,7 @@ static hipError_t inverse_transform_mfma(Ctx& c, void* out, const void* v_in, hi
   a.d = d; a.Ntok = c.N;
   a.in = c.Y; a.in_alt = c.specV; a.masks = c.d_lists + c.off_masks; a.slice_list = slice_list; a.delta = delta ? 1 : 0;
   a.band_off1 = (int32_t)c.band_off[1]; a.band_off2 = (int32_t)c.band_off[2];
-  a.perm_in = c.d_perm; a.perm_k = (int64_t)H * W; a.perm_o = W;
+  a.perm_in = c.d_perm_t; a.perm_k = 1; a.perm_o = W; a.perm_scale = T;
   a.out = c.tmp1; a.M = c.d_Ft16[0]; a.ldm = T; a.n = kt; a.n_out = T; a.inner = (int64_t)kw * d;
   a.nslab = (int64_t)ns * kh; a.outer = kh;
   if ((e = launch_mfma_dct_pass(a, c.num_cu, st)) != hipSuccess) return e;

@@ -69,6 +69,7 @@ struct Ctx {
 
   // device tables
   int32_t* d_perm = nullptr;
+  int32_t* d_perm_t = nullptr;   // the same map stored [kh*W + kw][kt]: the 64..128 rows a T-axis tile looks up are adjacent (MFMA path)
   int32_t* d_row_ptr = nullptr;
   int32_t* d_col_idx = nullptr;
   float* d_F32[3] = {nullptr, nullptr, nullptr};    // F  [n][n] fp32 (generic path)
@@ -201,6 +202,7 @@ struct DctPassArgs {
   // Band-major side (section 3.3): with perm_in / perm_out set, row j (k) of the tile at slab s = slice*outer + o and
   // first column col0 is the band-major row perm[j*perm_k + o*perm_o + col0/d] of slice `slice`.
   const int32_t* perm_in; const int32_t* perm_out; int64_t Ntok, perm_k, perm_o;
+  int32_t perm_scale;       // 0/1: index = k*perm_k + tile index; otherwise k*perm_k + tile index*perm_scale (transposed table)
   const void* in_alt; const int32_t* masks; int32_t band_off1, band_off2;
   int in_bf16, out_bf16;    // element type of in / out: bf16 when set, else fp16
   int d;

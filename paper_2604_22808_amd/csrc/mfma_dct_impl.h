@@ -74,6 +74,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
   constexpr bool PERM_IN = MODE == DCT_GATHER, PERM_OUT = MODE == DCT_SCATTER || MODE == DCT_SCATTER_EN;
   constexpr bool ENERGY = MODE == DCT_SCATTER_EN, TOT = MODE == DCT_PLAIN_TOT;
   const int NO = a.n_out;
+  const int pscale = a.perm_scale > 1 ? a.perm_scale : 1;
   // transform matrix -> LDS, rows beyond n_out zero
   for (int e = tid; e < 32 * MT * (NI / 8); e += 64 * DCT_WAVES) {
     const int row = e / (NI / 8), c8 = e % (NI / 8);
@@ -173,7 +174,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
   auto perm_rows = [&](const TileAddr& t, int32_t (&pr)[NPR]) {
     if (PERM_IN) {
 #pragma unroll
-      for (int i = 0; i < NPR; ++i) pr[i] = a.perm_in[(int64_t)((i / LPC) * RC + (i % LPC) * 8 + lrow) * a.perm_k + t.pidx];
+      for (int i = 0; i < NPR; ++i) pr[i] = a.perm_in[(int64_t)((i / LPC) * RC + (i % LPC) * 8 + lrow) * a.perm_k + (int64_t)t.pidx * pscale];
     }
   };
   if (tile < n_tiles32) {
@@ -197,7 +198,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
           const int k = mt * 32 + it * 8 + lrow;
-          prow[mt][it] = k < NO ? a.perm_out[(int64_t)k * a.perm_k + cur.pidx] : 0;
+          prow[mt][it] = k < NO ? a.perm_out[(int64_t)k * a.perm_k + (int64_t)cur.pidx * pscale] : 0;
         }
     }
     float16v acc[MT][2];
