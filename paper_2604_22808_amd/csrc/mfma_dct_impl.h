@@ -285,6 +285,15 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       if (mt * 32 >= NO) break;
+      // the residual rows of this group of 32 are requested before the trip through the staging buffer
+      uint4v rsd[4];
+      if (!PERM_OUT && a.resid) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int k = mt * 32 + it * 8 + lrow;
+          if (k < NO) rsd[it] = *(const uint4v*)((const uint16_t*)a.resid + cur.out_off + (int64_t)k * cur.out_stride + lcol);
+        }
+      }
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt)
@@ -309,7 +318,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
           if (PERM_OUT) off = (cur.bm_off + prow[mt][it]) * a.d + cur.dcol;
           else off = cur.out_off + (int64_t)k * cur.out_stride;
           if (!PERM_OUT && a.resid) {   // out = resid + result, both bf16 in memory, the sum formed in fp32
-            const uint4v rs = *(const uint4v*)((const uint16_t*)a.resid + off + lcol);
+            const uint4v rs = rsd[it];
             const half8 h = __builtin_bit_cast(half8, v);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
