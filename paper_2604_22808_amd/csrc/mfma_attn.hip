@@ -453,39 +453,44 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       }
     }
 
-    // ---- epilogue: normalise, optional residual, store 4 consecutive channels per register group
+    // ---- epilogue: normalise, optional residual, store.  A lane holds, per 16 channels, two groups of four that
+    // interleave with its partner lane's (lane ^ 32, same query): swapping one group each (v_permlane32_swap) leaves
+    // every lane with 8 consecutive channels, i.e. 16-byte stores (and 16-byte residual loads) of whole 32-byte sectors.
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
       const int row = r0 + 32 * qt + nn;
       const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32);
       const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-      if (row < nq) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+      for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int a4 = 0; a4 < 4; ++a4) {
-            const int dd = dt * 32 + a4 * 8 + g * 4;
-            float o[4];
+        for (int j = 0; j < 2; ++j) {
+          float o[8];   // after the swap: channels dt*32 + j*16 + g*8 + 0..7
 #pragma unroll
-            for (int b = 0; b < 4; ++b) o[b] = O[qt][dt][a4 * 4 + b] * inv;
+          for (int b = 0; b < 4; ++b) {
+            const uint32_t lo = __float_as_uint(O[qt][dt][(2 * j) * 4 + b] * inv);       // channels 16j + 4g + b
+            const uint32_t hi = __float_as_uint(O[qt][dt][(2 * j + 1) * 4 + b] * inv);   // channels 16j + 8 + 4g + b
+            const auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
+            o[b] = __uint_as_float(sw[0]);
+            o[4 + b] = __uint_as_float(sw[1]);
+          }
+          if (row < nq) {
+            const int dd = dt * 32 + j * 16 + g * 8;
             uint16_t* dst = Op + (int64_t)row * D + dd;
             if (kind == 3) {
-              const uint2v y = *(const uint2v*)(Qp + (int64_t)row * D + dd);
-              const half4 yh = __builtin_bit_cast(half4, y);
+              const uint4v y = *(const uint4v*)(Qp + (int64_t)row * D + dd);
+              const half8 yh = __builtin_bit_cast(half8, y);
 #pragma unroll
-              for (int b = 0; b < 4; ++b) o[b] += (float)yh[b];
+              for (int b = 0; b < 8; ++b) o[b] += (float)yh[b];
             }
-            uint2v st2;
-            if (in_bf16) {
-              st2[0] = (uint32_t)at_f32_to_bf16(o[0]) | ((uint32_t)at_f32_to_bf16(o[1]) << 16);
-              st2[1] = (uint32_t)at_f32_to_bf16(o[2]) | ((uint32_t)at_f32_to_bf16(o[3]) << 16);
-            } else {
-              st2[0] = pack_h2(o[0], o[1]);
-              st2[1] = pack_h2(o[2], o[3]);
-            }
-            *(uint2v*)dst = st2;
+            uint4v st4;
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+              st4[b] = in_bf16 ? ((uint32_t)at_f32_to_bf16(o[2 * b]) | ((uint32_t)at_f32_to_bf16(o[2 * b + 1]) << 16))
+                               : pack_h2(o[2 * b], o[2 * b + 1]);
+            *(uint4v*)dst = st4;
           }
-      }
+        }
     }
   }
 }
