@@ -78,8 +78,11 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
   int it_first = blockIdx.x;
   if ((gridDim.x & 7) == 0) it_first = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   int lds_holds = -1;   // (slice, band) whose summary tiles the LDS copies hold, -1: something else
+  // the next item's descriptor is fetched while the current item runs (its fields start a chain of dependent loads)
+  AttnItem item_nx = items[it_first < n_items ? it_first : 0];
   for (int it = it_first; it < n_items; it += gridDim.x) {
-    const AttnItem item = items[it];
+    const AttnItem item = item_nx;
+    if (it + (int)gridDim.x < n_items) item_nx = items[it + gridDim.x];
     const int kind = item.kind_band & 0xff, band = item.kind_band >> 8;
     const int64_t slice = item.slice;
     const int q0 = item.q0;
