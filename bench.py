@@ -102,6 +102,7 @@ def main():
     ap.add_argument("--dense", action="store_true", help="also time the dense flash-style baseline (one iteration)")
     ap.add_argument("--separate", action="store_true", help="one launch per branch instead of the fused launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--t", type=float, default=None, help="timestep for the MLP head allocator (default: the workload's)")
     ap.add_argument("--transform", choices=("dct", "haar"), default="dct",
                     help="per-axis transform: the reference design's DCT-II or the Haar wavelet variant")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -122,9 +123,11 @@ def main():
     torch.cuda.set_device(0)
     q, k, v = WL.qkv_torch(wl, "cuda")
     out = torch.empty_like(q)
+    import dataclasses
     if args.transform == "haar":
-        import dataclasses
         wl = dataclasses.replace(wl, band=dict(wl.band, transform=B.TRANSFORM_HAAR))
+    if args.t is not None and wl.alloc["kind"] == "mlp":
+        wl = dataclasses.replace(wl, alloc=dict(wl.alloc, t=args.t))
     cfg = B.make_cfg(**wl.band)
     ctx = B.Context(wl.batch, wl.heads, wl.head_dim, wl.grid, B.BF16, cfg)
     if args.separate:
