@@ -7,7 +7,7 @@
 //   high  the tiles overlapping [q - w, q + w]            (sliding window, element mask on the edge tiles)
 //   exchange  the <= 2m summary tokens of the other bands, result added to the query row (residual)
 //   dense all tiles of the untransformed sequence         (comparison baseline)
-// The launch is persistent: workgroups stride over the item list, which the host orders by decreasing cost, so the
+// The launch is persistent: workgroups stride over the item list (branch by branch, long items first), so the
 // three branches are co-scheduled in one launch.
 //
 // Per 64-key tile, with S^T = K Q^T kept transposed so that a lane owns one query column:
