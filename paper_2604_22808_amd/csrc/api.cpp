@@ -410,12 +410,21 @@ static void build_lists(Ctx& c, const int32_t* head_alloc) {
     if ((mask & 1) && c.band_n[LOW] > 0)
       for (int64_t q0 = 0; q0 < c.nbar; q0 += rows)
         kind[0].push_back({0 | (LOW << 8), s, (int32_t)q0, (int32_t)cd(c.nbar, KT)});
-    if ((mask & 2) && c.band_n[MID] > 0)
-      for (int64_t q0 = 0; q0 < c.band_n[MID]; q0 += rows) {
-        const int64_t I = q0 / c.cfg.mid_block;
-        const int nblk = c.h_row_ptr[I + 1] - c.h_row_ptr[I];
-        kind[1].push_back({1 | (MID << 8), s, (int32_t)q0, (int32_t)(nblk * cd(c.cfg.mid_block, KT))});
-      }
+    if ((mask & 2) && c.band_n[MID] > 0) {
+      // Query blocks I with the same I mod stride share all their strided key blocks (J = I mod stride): they are listed
+      // together, so that workgroups running at the same time fetch those K/V tiles into their L2 once.
+      const int64_t tiles_per_block = std::max<int64_t>(1, c.cfg.mid_block / rows);   // items per query block
+      const int64_t nblocks = (c.band_n[MID] + c.cfg.mid_block - 1) / c.cfg.mid_block;
+      const int64_t stride = std::min<int64_t>(c.cfg.mid_stride, nblocks);
+      for (int64_t r = 0; r < stride; ++r)
+        for (int64_t I = r; I < nblocks; I += stride)
+          for (int64_t u = 0; u < tiles_per_block; ++u) {
+            const int64_t q0 = I * c.cfg.mid_block + u * rows;
+            if (q0 >= c.band_n[MID]) break;
+            const int nblk = c.h_row_ptr[I + 1] - c.h_row_ptr[I];
+            kind[1].push_back({1 | (MID << 8), s, (int32_t)q0, (int32_t)(nblk * cd(c.cfg.mid_block, KT))});
+          }
+    }
     if ((mask & 4) && c.band_n[HIGH] > 0)
       for (int64_t q0 = 0; q0 < c.band_n[HIGH]; q0 += rows) {
         const int64_t k0 = std::max<int64_t>(0, q0 - c.cfg.high_window);
