@@ -25,6 +25,7 @@ namespace fa {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef __fp16 fp16x4 __attribute__((__vector_size__(4 * sizeof(__fp16))));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
@@ -52,7 +53,7 @@ __device__ __forceinline__ uint32_t pack_h2(float a, float b) {
   return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
 }
 
-template <int D, int NW, int QT, bool BF16IN>
+template <int D, int NW, int QT, bool BF16IN, bool DMA>
 __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2 : 1) k_attn(AttnParams p, const AttnItem* __restrict__ items, int n_items) {
   constexpr int KS = D + 8;     // row stride of the K tile in LDS (halfs): rows shift by 16 bytes against the banks
   constexpr int VS = KT + 8;    // row stride of the transposed V tile (halfs)
@@ -67,8 +68,18 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
   __shared__ __attribute__((aligned(16))) half_t Vt2[2][D * VS];
   __shared__ __attribute__((aligned(16))) half_t Qs[QLDS ? ROWS * KS : 8];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  static_assert(!(DMA && BF16IN), "direct-to-LDS staging cannot convert the element type");
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nn = lane & 31, g = lane >> 5;
+  // Direct-to-LDS staging (DMA): K and V tiles are row-major in LDS, rows of D halfs without padding, loaded by
+  // global_load_lds_dwordx4 (lane l of a wave instruction fills bytes 16 l .. 16 l + 15 behind a wave-uniform LDS base,
+  // whatever global address the lane names).  Bank conflicts are avoided by permuting the 16-byte chunks inside a row
+  // through the global address: chunk c of row r sits at position c ^ fK(r) (K, read as 16-byte A operands by 16
+  // consecutive rows) or c ^ fV(r) (V, read through ds_read_b64_tr_b16, which hands lane i of a 16-lane group, for
+  // k = 0..3, element i % 4 of the 8-byte piece named by lane 4 k + i / 4: four rows of 32 bytes per group).
+  constexpr int CPR = D / 8;                       // 16-byte chunks per row
+  auto fK = [](int r) -> int { return D == 128 ? (r & 15) : ((r >> 1) & 7); };
+  auto fV = [](int r) -> int { return D == 128 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); };
   const float c2 = p.scale * 1.4426950408889634f;  // folded into Q: scores come out of the MFMA in units of log2
 
   // Workgroups are dealt to the 8 XCDs round-robin by blockIdx, and each XCD has its own L2.  Consecutive items are
@@ -258,25 +269,49 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
     const int lds_key = (kind == 3 && n_tt <= 2) ? (int)(slice * 4 + band) : -1;
     const bool reuse = lds_key >= 0 && lds_key == lds_holds;
     lds_holds = lds_key;
-    if (n_tt > 0 && !reuse) {   // (the barrier that ended the previous item's last tile already freed both copies)
+    // DMA staging: this wave's share of a tile is RPI rows per instruction, NIW instructions per tensor; rows past the
+    // end of the band are clamped to its last row (their scores are masked, and V rows of real data times zero are zero)
+    constexpr int RPI = 64 / CPR, NIW = KT / (RPI * NW);
+    auto dma_tile = [&](int key0, int buf) {
+      const int lr = lane / CPR, c = lane % CPR;
+#pragma unroll
+      for (int j = 0; j < NIW; ++j) {
+        const int rowbase = (wave * NIW + j) * RPI;      // wave-uniform
+        const int r = rowbase + lr;
+        int key = key0 + r;
+        if (key > nk - 1) key = nk - 1;
+        const uint16_t* ksrc = Kp + (int64_t)key * D + ((c ^ fK(r)) << 3);
+        const uint16_t* vsrc = Vp + (int64_t)key * D + ((c ^ fV(r)) << 3);
+        __builtin_amdgcn_global_load_lds(ksrc, (__attribute__((address_space(3))) half_t*)(Ks2[buf] + rowbase * D), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(vsrc, (__attribute__((address_space(3))) half_t*)(Vt2[buf] + rowbase * D), 16, 0, 0);
+      }
+    };
+    if (DMA) {
+      if (n_tt > 0 && !reuse) dma_tile(key0_of(0), 0);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else if (n_tt > 0 && !reuse) {   // (the barrier that ended the previous item's last tile already freed both copies)
       load_tile(key0_of(0));
       store_tile(0);
       if (n_tt > 1) load_tile(key0_of(1));
     }
     __syncthreads();
-    for (int idx = 0; idx < n_tt; ++idx, __syncthreads()) {
+    for (int idx = 0; idx < n_tt; ++idx, (DMA ? (void)__builtin_amdgcn_s_waitcnt(0x0070) : (void)0), __syncthreads()) {
       const int key0 = key0_of(idx);
       const half_t* Ks = Ks2[idx & 1];
       const half_t* Vt = Vt2[idx & 1];
-      // Staging of the next tiles.  Half of the waves do it before the score MFMAs and half after them, so that the
-      // workgroup's LDS stores and global loads do not all queue up behind one barrier.
+      // Staging of the next tiles.  Register path: half of the waves do it before the score MFMAs and half after them,
+      // so that the workgroup's LDS stores and global loads do not all queue up behind one barrier.  DMA path: the next
+      // tile goes straight into the other LDS copy (free since the barrier that ended the previous iteration); the
+      // wait for it sits in front of the barrier that ends this iteration.
       auto stage = [&]() {
-        if (idx + 1 < n_tt && !reuse) {
+        if (DMA) {
+          if (idx + 1 < n_tt && !reuse) dma_tile(key0_of(idx + 1), (idx + 1) & 1);
+        } else if (idx + 1 < n_tt && !reuse) {
           store_tile((idx + 1) & 1);
           if (idx + 2 < n_tt) load_tile(key0_of(idx + 2));
         }
       };
-      const bool stage_early = (wave & 1) == 0;
+      const bool stage_early = DMA || (wave & 1) == 0;
       if (stage_early) stage();
       if (key0 >= nk) {  // block tail beyond the band (uniform over the workgroup)
         if (!stage_early) stage();
@@ -312,15 +347,20 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       constexpr int PF = 4;
       {
         constexpr int NS = 2 * DK;
+        auto kptr = [&](int i) -> const half8* {
+          const int row = (i / DK) * 32 + nn, chunk = (i % DK) * 2 + g;
+          if (DMA) return (const half8*)(Ks + row * D + ((chunk ^ fK(row)) << 3));
+          return (const half8*)(Ks + row * KS + chunk * 8);
+        };
         half8 Abuf[PF];
 #pragma unroll
-        for (int i = 0; i < PF; ++i) Abuf[i] = *(const half8*)(Ks + ((i / DK) * 32 + nn) * KS + (i % DK) * 16 + g * 8);
+        for (int i = 0; i < PF; ++i) Abuf[i] = *kptr(i);
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
           const int t2 = i / DK, ks = i % DK;
           const half8 A = Abuf[i % PF];
           if (i + PF < NS)
-            Abuf[i % PF] = *(const half8*)(Ks + (((i + PF) / DK) * 32 + nn) * KS + ((i + PF) % DK) * 16 + g * 8);
+            Abuf[i % PF] = *kptr(i + PF);
 #pragma unroll
           for (int qt = 0; qt < QT; ++qt) {
             const half8 Bq = QLDS ? *(const half8*)(Qw + (32 * qt + nn) * KS + ks * 16 + g * 8) : Qr[QLDS ? 0 : qt][QLDS ? 0 : ks];
@@ -441,14 +481,32 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
           const int x = ts * 2 + g;
           return (const half8*)(Vt + vrow * VS + ((x ^ ((vrow >> 4) & 7)) << 3));
         };
+        // DMA path: V is row-major in LDS; the operand (lane = channel, 8 keys in the order of P's registers) comes from
+        // two transposing reads, each delivering 4 consecutive keys: keys 16 ts + 8 h + 4 g + 0..3 for read h
+        auto vread = [&](int i) -> half8 {
+          if (!DMA) return *vptr(i);
+          const int dt = i % DT, ts = i / DT;
+          const int sl = lane & 15, g1 = (lane >> 4) & 1;
+          uint4v r4;
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int row = ts * 16 + 8 * h + 4 * g + (sl >> 2);
+            const int chunk = dt * 4 + 2 * g1 + ((sl & 3) >> 1);
+            const half_t* ptr = Vt + row * D + ((chunk ^ fV(row)) << 3) + (sl & 1) * 4;
+            const fp16x4 t4 = __builtin_amdgcn_ds_read_tr16_b64_v4f16((fp16x4 __attribute__((address_space(3)))*)ptr);
+            const uint2v u2 = __builtin_bit_cast(uint2v, t4);
+            r4[2 * h] = u2[0]; r4[2 * h + 1] = u2[1];
+          }
+          return __builtin_bit_cast(half8, r4);
+        };
         half8 Abuf[PF];
 #pragma unroll
-        for (int i = 0; i < PF; ++i) Abuf[i] = *vptr(i);
+        for (int i = 0; i < PF; ++i) Abuf[i] = vread(i);
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
           const int dt = i % DT, ts = i / DT;
           const half8 A = Abuf[i % PF];
-          if (i + PF < NS) Abuf[i % PF] = *vptr(i + PF);
+          if (i + PF < NS) Abuf[i % PF] = vread(i + PF);
 #pragma unroll
           for (int qt = 0; qt < QT; ++qt)
             O[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[qt][ts >> 1][ts & 1], O[qt][dt], 0, 0, 0);
@@ -524,7 +582,7 @@ hipError_t launch_probe_mfma(float* out, int blocks, int iters, hipStream_t st) 
   return hipGetLastError();
 }
 
-template <int D, int NW, int QT, bool BF16IN>
+template <int D, int NW, int QT, bool BF16IN, bool DMA>
 static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_items, int num_cu, hipStream_t st) {
   // resident workgroups per CU: register-limited waves per SIMD (accumulators of QT query tiles), 4 SIMDs per CU
   const int waves_per_simd = (QT == 1 && (D == 64 || NW == 4 || NW == 8)) ? 2 : 1;   // matches the kernel's launch bounds
@@ -533,7 +591,7 @@ static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_it
   int64_t blocks = (int64_t)num_cu * occ;
   if (blocks > n_items) blocks = n_items;
   if (blocks > 8) blocks -= blocks % 8;   // whole runs per XCD (see the kernel's item mapping)
-  hipLaunchKernelGGL((k_attn<D, NW, QT, BF16IN>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
+  hipLaunchKernelGGL((k_attn<D, NW, QT, BF16IN, DMA>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
   return hipGetLastError();
 }
 
@@ -541,9 +599,13 @@ hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_it
                             hipStream_t st) {
   if (n_items <= 0) return hipSuccess;
   const bool bf = p.denseQ != nullptr && p.dense_bf16;   // the dense comparison reads the caller's bf16 tensors
+  static int dma_env = -1;
+  if (dma_env < 0) { const char* e = getenv("FREQATTN_ATTN_DMA"); dma_env = e ? atoi(e) : 1; }
+  const bool dma = dma_env != 0;
 #define FA_ATTN_CASE(D_, R_, NW_) \
   if (p.d == D_ && rows_per_item == R_) \
-    return bf ? launch_dn<D_, NW_, 1, true>(p, items, n_items, num_cu, st) : launch_dn<D_, NW_, 1, false>(p, items, n_items, num_cu, st);
+    return bf ? launch_dn<D_, NW_, 1, true, false>(p, items, n_items, num_cu, st) \
+              : (dma ? launch_dn<D_, NW_, 1, false, true>(p, items, n_items, num_cu, st) : launch_dn<D_, NW_, 1, false, false>(p, items, n_items, num_cu, st));
   FA_ATTN_CASE(64, 64, 2) FA_ATTN_CASE(64, 128, 4) FA_ATTN_CASE(128, 64, 2) FA_ATTN_CASE(128, 128, 4) FA_ATTN_CASE(128, 256, 8)
 #undef FA_ATTN_CASE
   return hipErrorInvalidValue;
