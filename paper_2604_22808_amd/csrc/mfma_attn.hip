@@ -344,7 +344,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
 #pragma unroll
           for (int r = 0; r < 16; ++r) S[qt][t2][r] = s_init[qt];
       // K operands are requested PF steps ahead of the MFMA that consumes them, so LDS latency overlaps the matrix core
-      constexpr int PF = 4;
+      constexpr int PF = DMA ? 8 : 4;   // the DMA path has the registers for a deeper operand pipeline
       {
         constexpr int NS = 2 * DK;
         auto kptr = [&](int i) -> const half8* {
