@@ -80,6 +80,20 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
   constexpr int CPR = D / 8;                       // 16-byte chunks per row
   auto fK = [](int r) -> int { return D == 128 ? (r & 15) : ((r >> 1) & 7); };
   auto fV = [](int r) -> int { return D == 128 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); };
+  // per-lane parts of the operand addresses of the DMA layout (halfs), fixed for the whole kernel:
+  //   K operand (t2, ks):  Ks + t2*32*D + koff_row + kx[ks]         row nn, chunk (2 ks + g) ^ fK(nn)
+  //   V operand (dt, ts, h): Vt + (16 ts + 8 h)*D + voff_row + vx[dt]  row 4 g + sl/4 (+ 16 ts + 8 h), chunk (4 dt + 2 g1 + (sl & 3)/2) ^ fV(row)
+  int kx[DMA ? D / 16 : 1], vx[DMA ? D / 32 : 1];
+  int koff_row = 0, voff_row = 0;
+  if (DMA) {
+    const int sl = lane & 15, g1 = (lane >> 4) & 1;
+    koff_row = nn * D;
+    voff_row = (4 * g + (sl >> 2)) * D + (sl & 1) * 4;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) kx[ks] = ((2 * ks + g) ^ fK(nn)) << 3;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) vx[dt] = ((4 * dt + 2 * g1 + ((sl & 3) >> 1)) ^ fV(sl >> 2)) << 3;
+  }
   const float c2 = p.scale * 1.4426950408889634f;  // folded into Q: scores come out of the MFMA in units of log2
 
   // Workgroups are dealt to the 8 XCDs round-robin by blockIdx, and each XCD has its own L2.  Consecutive items are
@@ -349,7 +363,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
         constexpr int NS = 2 * DK;
         auto kptr = [&](int i) -> const half8* {
           const int row = (i / DK) * 32 + nn, chunk = (i % DK) * 2 + g;
-          if (DMA) return (const half8*)(Ks + row * D + ((chunk ^ fK(row)) << 3));
+          if (DMA) return (const half8*)(Ks + (i / DK) * 32 * D + koff_row + kx[DMA ? i % DK : 0]);   // fK(t2*32 + nn) = fK(nn)
           return (const half8*)(Ks + row * KS + chunk * 8);
         };
         half8 Abuf[PF];
@@ -486,13 +500,10 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
         auto vread = [&](int i) -> half8 {
           if (!DMA) return *vptr(i);
           const int dt = i % DT, ts = i / DT;
-          const int sl = lane & 15, g1 = (lane >> 4) & 1;
           uint4v r4;
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
-            const int row = ts * 16 + 8 * h + 4 * g + (sl >> 2);
-            const int chunk = dt * 4 + 2 * g1 + ((sl & 3) >> 1);
-            const half_t* ptr = Vt + row * D + ((chunk ^ fV(row)) << 3) + (sl & 1) * 4;
+            const half_t* ptr = Vt + (ts * 16 + 8 * h) * D + voff_row + vx[DMA ? dt : 0];   // fV only sees row & 3 = sl / 4
             const fp16x4 t4 = __builtin_amdgcn_ds_read_tr16_b64_v4f16((fp16x4 __attribute__((address_space(3)))*)ptr);
             const uint2v u2 = __builtin_bit_cast(uint2v, t4);
             r4[2 * h] = u2[0]; r4[2 * h + 1] = u2[1];
