@@ -53,6 +53,16 @@ __device__ __forceinline__ uint32_t pack_h2(float a, float b) {
   return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
 }
 
+// One wave-wide 16-byte-per-lane copy from global memory straight into LDS: lane l's 16 bytes land at dst + 16 l,
+// dst wave-uniform.  Issued as assembly on purpose: the compiler orders every LDS read behind a pending copy of this
+// kind that it knows of (it cannot tell the two LDS tile copies apart), which would put the whole latency of the next
+// tile's fetch in front of the current tile's arithmetic.  The kernel waits for these copies itself (vmcnt(0) in front
+// of the barrier that publishes the tile); the compiler's own waits for its global loads only become stricter.
+__device__ __forceinline__ void lds_dma16(const void* src, const half_t* dst) {
+  const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(const __attribute__((address_space(3))) half_t*)dst);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory", "m0");
+}
+
 template <int D, int NW, int QT, bool BF16IN, bool DMA>
 __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2 : 1) k_attn(AttnParams p, const AttnItem* __restrict__ items, int n_items) {
   constexpr int KS = D + 8;     // row stride of the K tile in LDS (halfs): rows shift by 16 bytes against the banks
@@ -286,19 +296,19 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
     // DMA staging: this wave's share of a tile is RPI rows per instruction, NIW instructions per tensor; rows past the
     // end of the band are clamped to its last row (their scores are masked, and V rows of real data times zero are zero)
     constexpr int RPI = 64 / CPR, NIW = KT / (RPI * NW);
-    auto dma_tile = [&](int key0, int buf) {
+    // piece pi of a tile: K rows (pi even) or V rows (pi odd) of instruction pi / 2 of this wave's share
+    auto dma_piece = [&](int key0, int buf, int pi) {
       const int lr = lane / CPR, c = lane % CPR;
+      const int rowbase = (wave * NIW + pi / 2) * RPI;      // wave-uniform
+      const int r = rowbase + lr;
+      int key = key0 + r;
+      if (key > nk - 1) key = nk - 1;
+      if ((pi & 1) == 0) lds_dma16(Kp + (int64_t)key * D + ((c ^ fK(r)) << 3), Ks2[buf] + rowbase * D);
+      else lds_dma16(Vp + (int64_t)key * D + ((c ^ fV(r)) << 3), Vt2[buf] + rowbase * D);
+    };
+    auto dma_tile = [&](int key0, int buf) {
 #pragma unroll
-      for (int j = 0; j < NIW; ++j) {
-        const int rowbase = (wave * NIW + j) * RPI;      // wave-uniform
-        const int r = rowbase + lr;
-        int key = key0 + r;
-        if (key > nk - 1) key = nk - 1;
-        const uint16_t* ksrc = Kp + (int64_t)key * D + ((c ^ fK(r)) << 3);
-        const uint16_t* vsrc = Vp + (int64_t)key * D + ((c ^ fV(r)) << 3);
-        __builtin_amdgcn_global_load_lds(ksrc, (__attribute__((address_space(3))) half_t*)(Ks2[buf] + rowbase * D), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(vsrc, (__attribute__((address_space(3))) half_t*)(Vt2[buf] + rowbase * D), 16, 0, 0);
-      }
+      for (int pi = 0; pi < 2 * NIW; ++pi) dma_piece(key0, buf, pi);
     };
     if (DMA) {
       if (n_tt > 0 && !reuse) dma_tile(key0_of(0), 0);
@@ -325,8 +335,12 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
           if (idx + 2 < n_tt) load_tile(key0_of(idx + 2));
         }
       };
-      const bool stage_early = DMA || (wave & 1) == 0;
+      const bool stage_early = !DMA && (wave & 1) == 0;
       if (stage_early) stage();
+      // DMA path: the copy instructions of the next tile are spread over the score MFMAs below (a wave issues in
+      // order, and a burst of them right behind the barrier holds every wave of the CU in the memory pipeline's queue)
+      const bool dma_next = DMA && idx + 1 < n_tt && !reuse;
+      const int key0_next = dma_next ? key0_of(idx + 1) : 0;
       if (key0 >= nk) {  // block tail beyond the band (uniform over the workgroup)
         if (!stage_early) stage();
         continue;
@@ -380,6 +394,10 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
             const half8 Bq = QLDS ? *(const half8*)(Qw + (32 * qt + nn) * KS + ks * 16 + g * 8) : Qr[QLDS ? 0 : qt][QLDS ? 0 : ks];
             S[qt][t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Bq, S[qt][t2], 0, 0, 0);
           }
+          if (DMA && dma_next) {
+#pragma unroll
+            for (int pi = i * (2 * NIW) / NS; pi < (i + 1) * (2 * NIW) / NS; ++pi) dma_piece(key0_next, (idx + 1) & 1, pi);
+          }
         }
         if (!QLDS) {   // pin the order: PF reads up front, then one read per MFMA
           __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
@@ -391,7 +409,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
           __builtin_amdgcn_sched_group_barrier(0x008, PF * QT, 0);
         }
       }
-      if (!stage_early) stage();
+      if (!DMA && !stage_early) stage();
       // ---- mask, running softmax (lane = query row; registers = keys).  m_run is a reference maximum, not the exact
       // one: it moves only when a score exceeds it by more than 2^kBump (or when the row sees its first valid key), so
       // probabilities stay within [0, 2^kBump] - exact in the ratio P / sum(P) - and the rescale is rare.
@@ -401,25 +419,25 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       float mx[QT];
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) {
-        const int row = r0 + 32 * qt + nn;
         if (need_mask) {
-          // valid keys of this lane's row form one interval [lo, hi]; relative to the lane's first key of the tile the
-          // register r holds key offset c_r (a compile-time constant), valid iff min(c_r - lo', hi' - c_r) >= 0.
-          // Small integers are exact in fp32, and the float form keeps the test branch-free (5 VALU per score).
+          // valid keys of this lane's row form one interval [lo, hi]; relative to the lane's first key of the tile,
+          // register r holds key offset c_r (a compile-time constant), valid iff (unsigned)(c_r - lo') <= (unsigned)(hi' - lo')
+          const int row = r0 + 32 * qt + nn;
           int lo = 0, hi = nk - 1;
           if (kind == 2) { lo = row - w > 0 ? row - w : 0; hi = row + w < nk - 1 ? row + w : nk - 1; }
           const int base = key0 + 4 * g;
           int dlo = lo - base, dhi = hi - base;
           dlo = dlo < -1 ? -1 : (dlo > 65 ? 65 : dlo);    // clamped: only the range of c_r matters
           dhi = dhi < -1 ? -1 : (dhi > 65 ? 65 : dhi);
-          const float flo = (float)dlo, fhi = (float)dhi;
+          unsigned range = (unsigned)(dhi - dlo);
+          if (dhi < dlo) { dlo = 1000; range = 0u; }      // empty interval: no c_r passes
+          const unsigned ndlo = (unsigned)(-dlo);
 #pragma unroll
           for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-              const float cr = (float)(t2 * 32 + 8 * (r >> 2) + (r & 3));
-              const float tmin = fminf(cr - flo, fhi - cr);
-              S[qt][t2][r] = tmin < 0.f ? -INFINITY : S[qt][t2][r];
+              const unsigned cr = (unsigned)(t2 * 32 + 8 * (r >> 2) + (r & 3));
+              S[qt][t2][r] = (cr + ndlo <= range) ? S[qt][t2][r] : -INFINITY;
             }
         }
         // row maximum: four independent chains (short dependency depth), then the other lane half through a register
