@@ -57,7 +57,7 @@ static void free_all(Ctx* c) {
   for (int a = 0; a < 3; ++a) { F(c->d_F32[a]); F(c->d_Ft32[a]); F(c->d_F16[a]); F(c->d_Ft16[a]); }
   F(c->specQ); F(c->specK); F(c->specV); F(c->Y); F(c->tmp0); F(c->tmp1);
   F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_lists); F(c->d_energy_part);
-  F(c->d_tot_part);
+  F(c->d_tot_part); F(c->d_wsum); F(c->d_vsum_part);
   if (c->h_lists) (void)hipHostFree(c->h_lists);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
   if (c->ev_created)
@@ -69,6 +69,8 @@ static int items_per_slice_max(const Ctx& c, int rows) {
   auto cd = [](int64_t a, int64_t b) { return (int)((a + b - 1) / b); };
   return cd(c.nbar, rows) + cd(c.band_n[MID], rows) + cd(c.band_n[HIGH], rows) + 3;
 }
+
+static int keep_rows(int box, int n);
 
 extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const freqattn_band_cfg* cfg, int32_t path,
                                            freqattn_ctx** out_ctx) {
@@ -223,8 +225,8 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
   A(dev_alloc_bytes(*c, &c->Cbuf, (size_t)c->slices * 3 * 2 * (size_t)std::max(g.n_summary, 1) * c->d * es));
   const size_t stats_floats = (size_t)3 * c->d * (1 + 64);
   A(dev_alloc(*c, &c->d_stats, stats_floats));
-  if (mf) A(dev_alloc(*c, &c->d_energy_part, (size_t)5 * DCT_MAX_WAVES * 3 * 64));
-  if (mf) A(dev_alloc(*c, &c->d_tot_part, (size_t)2 * DCT_MAX_WAVES * 64));
+  if (mf) A(dev_alloc(*c, &c->d_energy_part, (size_t)6 * DCT_MAX_WAVES * 3 * 64));
+  if (mf) A(dev_alloc(*c, &c->d_tot_part, (size_t)3 * DCT_MAX_WAVES * 64));
   {
     auto box = [](int64_t num, int64_t den, int n) { return (int)((num * n + den - 1) / den); };  // #k with k*den < num*n
     const int dims[3] = {s.T, s.H, s.W};
@@ -232,6 +234,30 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
       c->low_box[a] = std::min(dims[a], box(g.low_num, g.low_den, dims[a]));
       c->mid_box[a] = std::min(dims[a], box(g.mid_num, g.mid_den, dims[a]));
     }
+  }
+  // Slices that do not run the high band get V~ on the low+mid box only (see mfma_vsum.hip) when that box is smaller
+  // than the grid and the high band's summary tokens (at most 64) can come from the untransformed V instead.
+  {
+    const int dims[3] = {s.T, s.H, s.W};
+    bool smaller = false;
+    for (int a = 0; a < 3; ++a) smaller = smaller || keep_rows(c->mid_box[a], dims[a]) < dims[a];
+    const char* env = getenv("FREQATTN_V_BOX");
+    c->v_box_ok = mf && smaller && c->N % 64 == 0 && c->slices <= 256 && c->band_n[HIGH] > 0 &&
+                  (g.n_summary == 0 || c->m_eff[HIGH] <= 64) && !(env && atoi(env) == 0);
+    if (c->v_box_ok && g.n_summary > 0 && e == hipSuccess) {
+      try {
+        std::vector<uint16_t> w;
+        build_vsum_weights(*c, w);
+        A(dev_alloc_bytes(*c, (void**)&c->d_wsum, w.size() * sizeof(uint16_t)));
+        up(c->d_wsum, w.data(), w.size() * sizeof(uint16_t));
+      } catch (const std::bad_alloc&) {
+        e = hipErrorOutOfMemory;
+      }
+      // token ranges per slice: about two workgroups per CU in one launch (the kernel's LDS footprint allows two)
+      c->vsum_nsplit = 2 * c->num_cu;
+      A(dev_alloc(*c, &c->d_vsum_part, (size_t)(2 * c->num_cu + c->slices) * 2 * c->d * 64));
+    }
+    c->v_full.assign((size_t)c->slices, 1);
   }
   if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_stats, 3 * c->d * sizeof(float), hipHostMallocDefault);
 
@@ -669,21 +695,27 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
     for (int a = 0; a < 3; ++a) { mid[a] = keep_rows(c->mid_box[a], full[a]); pruned = pruned || mid[a] < full[a]; }
     c->energy_waves = 0; c->tot_waves = 0; c->qk_on_mid_box = pruned;
     c->qk_full.assign((size_t)c->slices, pruned ? 0 : 1);
-    HIP_TRY(c, launch_fill_zero(c->d_energy_part, (int64_t)5 * DCT_MAX_WAVES * 3 * 64, st));
-    if (pruned) HIP_TRY(c, launch_fill_zero(c->d_tot_part, (int64_t)2 * DCT_MAX_WAVES * 64, st));
+    // statistics slots: 0..2 = Q, K, V on the box (high band by Parseval when pruned), 3..5 = the same on the whole grid
+    const bool vbox = pruned && c->v_box_ok;
+    HIP_TRY(c, launch_fill_zero(c->d_energy_part, (int64_t)6 * DCT_MAX_WAVES * 3 * 64, st));
+    if (pruned) HIP_TRY(c, launch_fill_zero(c->d_tot_part, (int64_t)3 * DCT_MAX_WAVES * 64, st));
+    c->v_full.assign((size_t)c->slices, vbox ? 0 : 1);
     if (pruned && predict && c->alloc_valid && c->n_cls[2] > 0) {
       const int32_t* L = c->d_lists;
       const int32_t* hl = c->h_lists + c->off_cls[2];
-      for (int i = 0; i < c->n_cls[2]; ++i) c->qk_full[(size_t)hl[i]] = 1;
+      for (int i = 0; i < c->n_cls[2]; ++i) c->qk_full[(size_t)hl[i]] = c->v_full[(size_t)hl[i]] = 1;
       HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, L + c->off_nonhigh, c->n_nonhigh, mid, 0, 0));
       HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, L + c->off_nonhigh, c->n_nonhigh, mid, 1, 1));
+      if (vbox) HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, L + c->off_nonhigh, c->n_nonhigh, mid, 2, 2));
       HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, L + c->off_cls[2], c->n_cls[2], full, 3, -1));
       HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, L + c->off_cls[2], c->n_cls[2], full, 4, -1));
+      if (vbox) HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, L + c->off_cls[2], c->n_cls[2], full, 5, -1));
     } else {
       HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, nullptr, c->slices, pruned ? mid : full, 0, pruned ? 0 : -1));
       HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, nullptr, c->slices, pruned ? mid : full, 1, pruned ? 1 : -1));
+      if (vbox) HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, mid, 2, 2));
     }
-    HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, full, 2, -1));
+    if (!vbox) HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, full, pruned ? 5 : 2, -1));
     HIP_TRY(c, launch_energy_reduce(c->d_energy_part, pruned ? c->d_tot_part : nullptr, c->d_stats, c->d, c->energy_waves,
                                     c->tot_waves, st));
     return FREQATTN_OK;
@@ -701,9 +733,19 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
       HIP_TRY(c, forward_transform_mfma(*c, xs[i], sp[i], st, L + c->off_cls[1], c->n_cls[1], mid, -1, -1));
       HIP_TRY(c, forward_transform_mfma(*c, xs[i], sp[i], st, L + c->off_cls[2], c->n_cls[2], full, -1, -1));
     }
-    HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, full, -1, -1));
+    if (c->v_box_ok) {   // V~ of a slice without the high band: the low+mid box (its high summaries come from V itself)
+      c->v_full.assign((size_t)c->slices, 0);
+      const int32_t* hl = c->h_lists + c->off_cls[2];
+      for (int i = 0; i < c->n_cls[2]; ++i) c->v_full[(size_t)hl[i]] = 1;
+      HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, L + c->off_nonhigh, c->n_nonhigh, mid, -1, -1));
+      HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, L + c->off_cls[2], c->n_cls[2], full, -1, -1));
+    } else {
+      c->v_full.assign((size_t)c->slices, 1);
+      HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, full, -1, -1));
+    }
     return FREQATTN_OK;
   }
+  c->v_full.assign((size_t)c->slices, 1);
   HIP_TRY(c, forward_transform(*c, q, c->specQ, st));
   HIP_TRY(c, forward_transform(*c, k, c->specK, st));
   HIP_TRY(c, forward_transform(*c, v, c->specV, st));
@@ -713,10 +755,10 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
   return FREQATTN_OK;
 }
 
-// After routing with Q~ and K~ on the low+mid box only: the slices that run the high band get the full transforms.
+// After routing with Q~ and K~ (and V~) on the low+mid box only: the slices that run the high band get the full transforms.
 // (The caller has synchronised the stream since the first phase was queued - the router reads the statistics back -
 // so the fix list's region of the pinned host buffer is not the source of a copy still in flight.)
-static freqattn_status complete_qk_for_high(freqattn_ctx* c, const void* q, const void* k, hipStream_t st) {
+static freqattn_status complete_qk_for_high(freqattn_ctx* c, const void* q, const void* k, const void* v, hipStream_t st) {
   if (c->path != FREQATTN_PATH_MFMA || !c->qk_on_mid_box || c->n_cls[2] == 0) return FREQATTN_OK;
   const int full[3] = {c->shape.T, c->shape.H, c->shape.W};
   int32_t* fix = c->h_lists + c->off_fix;
@@ -729,6 +771,12 @@ static freqattn_status complete_qk_for_high(freqattn_ctx* c, const void* q, cons
   const int32_t* list = c->d_lists + c->off_fix;
   HIP_TRY(c, forward_transform_mfma(*c, q, c->specQ, st, list, n_fix, full, -1, -1));
   HIP_TRY(c, forward_transform_mfma(*c, k, c->specK, st, list, n_fix, full, -1, -1));
+  bool v_too = false;
+  for (int i = 0; i < n_fix; ++i) {
+    v_too = v_too || !c->v_full[(size_t)fix[i]];
+    c->v_full[(size_t)fix[i]] = 1;
+  }
+  if (v_too) HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, list, n_fix, full, -1, -1));
   return FREQATTN_OK;
 }
 
@@ -796,7 +844,25 @@ static freqattn_status bands_phase(freqattn_ctx* c, float scale, const void* v_i
 
   // section 3.6: summary tokens of all bands, then the exchange on the active bands
   if (c->cfg.n_summary > 0) {
-    HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, st));
+    // slices that do not run the high band (their V~ may stop at the low+mid box): the pooling skips their high band,
+    // which is summed from V instead
+    uint64_t skip[4] = {0, 0, 0, 0}, sel[4] = {0, 0, 0, 0};
+    int nsel = 0;
+    if (mf && c->v_box_ok) {
+      for (int s = 0; s < c->slices; ++s) {   // by the allocation alone, also where V~ happens to exist on the whole
+        const int mask = c->h_alloc[(size_t)(s % c->shape.heads)];   // grid: the result must not depend on a prediction
+        if (mask & 4) continue;
+        skip[s >> 6] |= 1ull << (s & 63);
+        if (mask != 0) { sel[s >> 6] |= 1ull << (s & 63); ++nsel; }   // idle slices use no summaries
+      }
+    }
+    HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, skip, st));
+    if (nsel > 0)
+      {
+        int nsplit = std::max(1, c->vsum_nsplit / nsel);   // nsel * nsplit <= 2 CUs' worth + nsel, what the scratch holds
+        nsplit = (int)std::min<int64_t>(nsplit, c->N / 64);
+        HIP_TRY(c, launch_vsum(v_in, c->d_wsum, c->d_vsum_part, c->Cbuf, sel, nsel, c->N, c->d, nsplit, c->band_n[HIGH], c->m_eff, ap.m2, st));
+      }
     tm.done("summaries");
     if (mf) {
       HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(L + c->off_items_xchg), c->n_items_xchg, c->attn_rows, c->num_cu, st));
@@ -877,7 +943,7 @@ extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* 
   fs = ensure_lists(c, head_alloc_out, st);
   if (fs != FREQATTN_OK) return fs;
   tm.done("router");
-  fs = complete_qk_for_high(c, q, k, st);
+  fs = complete_qk_for_high(c, q, k, v, st);
   if (fs != FREQATTN_OK) return fs;
   tm.done("forward_transform_high_qk");
   return bands_phase(c, scale, v, out, st, tm);
@@ -912,6 +978,9 @@ extern "C" freqattn_status freqattn_read_spectral(freqattn_ctx* c, int32_t which
   if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_read_spectral: tables-only context");
   HIP_TRY(c, hipStreamSynchronize((hipStream_t)stream));
   const void* src = which == 0 ? c->specQ : which == 1 ? c->specK : which == 2 ? c->specV : c->Y;
+  if (band == 2 && (which == 2 || (which == 3 && c->alloc_valid && !((c->h_alloc[slice % c->shape.heads] >> band) & 1))) &&
+      (size_t)slice < c->v_full.size() && !c->v_full[(size_t)slice])
+    return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_read_spectral: V~ of this slice was only computed on the low+mid box");
   if (which == 3) {
     if (!c->alloc_valid) return fail(c, FREQATTN_EINVAL, "freqattn_read_spectral: no forward has run");
     if (!((c->h_alloc[slice % c->shape.heads] >> band) & 1)) src = c->specV;

@@ -103,7 +103,14 @@ struct Ctx {
   int n_nonhigh = 0;
   size_t off_fix = 0;                 // [slices] routed forward: slices whose Q~/K~ have to be completed after routing
   int predict_alloc = 1;              // routed forward: transform Q/K of the last allocation's high slices in full at once
-  std::vector<char> qk_full;          // routed forward: slices whose Q~/K~ the first phase computed on the whole grid
+  std::vector<char> qk_full;          // routed forward: slices whose Q~/K~ (and V~) the first phase computed on the whole grid
+  // V~ on the low+mid box only for slices that do not run the high band (MFMA path): their high-band summary tokens
+  // come from the untransformed V through the weights d_wsum (mfma_vsum.hip)
+  bool v_box_ok = false;              // the context can do it: summary weights built, or no summaries configured
+  uint16_t* d_wsum = nullptr;         // bf16 [N/64][64][64]
+  float* d_vsum_part = nullptr;       // [slices][vsum_parts][d][64] partial sums
+  int vsum_nsplit = 0;
+  std::vector<char> v_full;           // per slice: the current forward computed V~ on the whole grid
   size_t off_items = 0;               // AttnItem array (fused order: all branches), then exchange items
   int n_items_branch = 0;             // low+mid+high items in cost order
   int n_items_kind[3] = {0, 0, 0};    // per-branch sub-lists follow at off_items_kind
@@ -131,6 +138,7 @@ void build_dct_matrix(int n, std::vector<double>& F);  // [n][n], row = frequenc
 void build_haar_matrix(int n, std::vector<double>& F); // [n][n], row = scale (coarse to fine), n a power of two
 void build_bands(Ctx& c);
 void build_mid_blocks(Ctx& c);
+void build_vsum_weights(const Ctx& c, std::vector<uint16_t>& out);  // bf16 [N/64][64][64], see mfma_vsum.hip
 
 // ---- generic fp32 kernels (generic_kernels.hip) -----------------------------------------------------------------
 struct AxisPassArgs {
@@ -168,9 +176,13 @@ hipError_t launch_pool_low(const void* spec, void* low, const int32_t* slice_lis
 hipError_t launch_expand_low(const void* lowY, void* Y, const int32_t* slice_list, int n_slices, int64_t N, int d,
                              int64_t n_low, int64_t nbar, int c, int is_half, hipStream_t st);
 // Summary tokens of all bands of all slices, written into the C slots of the two other bands.
+// skip_high: bit s set = the high band of slice s is not pooled here (its V~ rows do not exist; see launch_vsum).
 hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
                             const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2, int is_half,
-                            hipStream_t st);
+                            const uint64_t skip_high[4], hipStream_t st);
+// High-band summary tokens of the slices in `sel` (bit set, nsel of them) from the untransformed bf16 V.
+hipError_t launch_vsum(const void* V, const void* Wsum, float* part, void* C, const uint64_t sel[4], int nsel, int64_t N,
+                       int d, int nsplit, int64_t n_high, const int m_eff[3], int m2rows, hipStream_t st);
 // Router statistics: per band and channel, sum of squares over slices and the three spectral buffers.
 hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, float* stats /*[3][d], zeroed inside*/,
                               int slices, int64_t N, int d, const int64_t band_off[3], const int64_t band_n[3],
@@ -182,8 +194,8 @@ hipError_t launch_probe_mfma(float* out, int blocks, int iters, hipStream_t st);
 // out[slice] = in[slice] for the listed slices (slice_bytes each, a multiple of 16).
 hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_list, int n_slices, int64_t slice_bytes,
                               hipStream_t st);
-hipError_t launch_energy_reduce(const float* energy_part /*[5][DCT_MAX_WAVES][3][64]: Q, K (box), V, Q, K (whole grid)*/,
-                                const float* tot_part /*[2][DCT_MAX_WAVES][64] or NULL*/, float* stats, int d,
+hipError_t launch_energy_reduce(const float* energy_part /*[6][DCT_MAX_WAVES][3][64]: Q, K, V (box), Q, K, V (whole grid)*/,
+                                const float* tot_part /*[3][DCT_MAX_WAVES][64] or NULL*/, float* stats, int d,
                                 int n_waves, int n_waves_tot, hipStream_t st);
 
 // ---- MFMA kernels (mfma_dct.hip, mfma_attn.hip) -------------------------------------------------------------------

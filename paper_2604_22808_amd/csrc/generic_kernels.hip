@@ -224,12 +224,15 @@ hipError_t launch_expand_low(const void* lowY, void* Y, const int32_t* slice_lis
 // One workgroup per (slice, band, chunk); threads split the chunk's rows 256/d ways and the partial sums are added in
 // a fixed order, so the result does not depend on scheduling.  The mean is written to the C rows of the two other
 // bands (band l sees the summaries of the other bands, ascending band order).
+struct SkipBits { uint64_t w[4]; };   // slices whose high band is pooled elsewhere (from the untransformed V)
+
 template <typename T>
 __global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C, const int32_t* masks, int64_t N, int d,
                                                    int64_t off0, int64_t off1, int64_t off2, int64_t n0, int64_t n1,
-                                                   int64_t n2, int m0, int m1, int m2e, int mmax, int m2rows) {
+                                                   int64_t n2, int m0, int m1, int m2e, int mmax, int m2rows, SkipBits skip) {
   __shared__ float part[256];
   const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x;
+  if (band == 2 && slice < 256 && ((skip.w[slice >> 6] >> (slice & 63)) & 1)) return;
   const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
   const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
   const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
@@ -265,10 +268,11 @@ __global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C,
 __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const half_t* V, half_t* C, const int32_t* masks,
                                                       int64_t N, int d, int64_t off0, int64_t off1, int64_t off2,
                                                       int64_t n0, int64_t n1, int64_t n2, int m0, int m1, int m2e,
-                                                      int m2rows) {
+                                                      int m2rows, SkipBits skip) {
   typedef _Float16 h8 __attribute__((ext_vector_type(8)));
   __shared__ float part[256 * 8];
   const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x;
+  if (band == 2 && slice < 256 && ((skip.w[slice >> 6] >> (slice & 63)) & 1)) return;
   const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
   const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
   const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
@@ -321,7 +325,9 @@ __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const hal
 
 hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
                             const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2rows,
-                            int is_half, hipStream_t st) {
+                            int is_half, const uint64_t skip_high[4], hipStream_t st) {
+  SkipBits skip;
+  for (int i = 0; i < 4; ++i) skip.w[i] = skip_high ? skip_high[i] : 0;
   int mmax = m_eff[0] > m_eff[1] ? m_eff[0] : m_eff[1];
   if (m_eff[2] > mmax) mmax = m_eff[2];
   if (mmax == 0 || slices == 0) return hipSuccess;
@@ -329,15 +335,15 @@ hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t
   if (is_half && d % 8 == 0 && 256 % (d / 8) == 0)
     hipLaunchKernelGGL(k_summaries_h8, grid, dim3(256), 0, st, (const half_t*)Y, (const half_t*)V, (half_t*)C, masks, N,
                        d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0], m_eff[1],
-                       m_eff[2], m2rows);
+                       m_eff[2], m2rows, skip);
   else if (is_half)
     hipLaunchKernelGGL(k_summaries<half_t>, grid, dim3(256), 0, st, (const half_t*)Y, (const half_t*)V, (half_t*)C,
                        masks, N, d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0],
-                       m_eff[1], m_eff[2], mmax, m2rows);
+                       m_eff[1], m_eff[2], mmax, m2rows, skip);
   else
     hipLaunchKernelGGL(k_summaries<float>, grid, dim3(256), 0, st, (const float*)Y, (const float*)V, (float*)C, masks, N,
                        d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0], m_eff[1],
-                       m_eff[2], mmax, m2rows);
+                       m_eff[2], mmax, m2rows, skip);
   return hipGetLastError();
 }
 
@@ -440,7 +446,7 @@ hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_li
 // Fixed-order sum of the per-wave partial statistics written by the fused forward passes of Q, K and V.
 // Wave w of a launch worked on column chunk w % (d/64) only.  One workgroup per (band, channel): 256 threads take
 // the (tensor, wave) terms round-robin and a fixed tree adds their partial sums.
-// With tot_part set, Q~ and K~ (tensors 0 and 1) were only computed on the low+mid box: their high-band energy is the
+// With tot_part set, the tensors in slots 0..2 were only computed on the low+mid box: their high-band energy is the
 // energy of the input (Parseval, the transform is orthonormal) minus their low and mid energies.
 __global__ void __launch_bounds__(256) k_energy_reduce(const float* part, const float* tot_part, float* stats, int d,
                                                        int n_waves, int n_waves_tot) {
@@ -451,15 +457,15 @@ __global__ void __launch_bounds__(256) k_energy_reduce(const float* part, const 
   const int per = (n_waves - chunk + chunks - 1) / chunks;   // waves of this chunk
   const bool parseval = tot_part != nullptr && band == 2;
   float t = 0.f;
-  for (int i = tid; i < 5 * per; i += 256) {   // slots: Q, K on the box (Parseval for the high band), V, Q, K on the whole grid
+  for (int i = tid; i < 6 * per; i += 256) {   // slots: Q, K, V on the box (Parseval for the high band), Q, K, V on the whole grid
     const int tensor = i / per, w = chunk + (i % per) * chunks;
     const float* p3 = part + (((size_t)tensor * DCT_MAX_WAVES + w) * 3) * 64 + col;
-    if (parseval && tensor < 2) t -= p3[0] + p3[64];
+    if (parseval && tensor < 3) t -= p3[0] + p3[64];
     else t += p3[band * 64];
   }
   if (parseval) {
     const int per_t = (n_waves_tot - chunk + chunks - 1) / chunks;
-    for (int i = tid; i < 2 * per_t; i += 256) {
+    for (int i = tid; i < 3 * per_t; i += 256) {
       const int tensor = i / per_t, w = chunk + (i % per_t) * chunks;
       t += tot_part[((size_t)tensor * DCT_MAX_WAVES + w) * 64 + col];
     }

@@ -1,4 +1,5 @@
 // Host-side integer tables and transform matrices of libfreqattn.
+#include <cstring>
 #include <cmath>
 
 #include "ctx.h"
@@ -81,6 +82,64 @@ void build_mid_blocks(Ctx& c) {
       if (ad <= g.mid_diag || mod == 0 || (g.mid_block0 && J == 0)) c.h_col_idx.push_back((int32_t)J);
     }
     c.h_row_ptr[(size_t)I + 1] = (int32_t)c.h_col_idx.size();
+  }
+}
+
+// Weights of the high band's summary tokens as functionals of the untransformed input (section 3.6, U = I):
+//   Wsum[u][(t,h,w)] = sum over the rows (kt,kh,kw) of chunk u of F_T[kt][t] F_H[kh][h] F_W[kw][w],
+// chunk u = band rows [floor(u n / m), floor((u+1) n / m)), rows in ascending flat order.  Separable per row, so a
+// chunk is summed kw-run by kw-run into a per-kt plane G[h][w], and each plane goes into the volume with F_T's row.
+// Output: bf16, [N/64][64][64] (tile of 64 tokens, chunk, token; chunks >= m are zero); inside every group of 16 tokens the order is the one in which the
+// transposing LDS reads of the kernel deliver them (stored position 8 g + 4 h + e holds token 8 h + 4 g + e).
+void build_vsum_weights(const Ctx& c, std::vector<uint16_t>& out) {
+  const int T = c.shape.T, H = c.shape.H, W = c.shape.W;
+  const int64_t N = c.N, HW = (int64_t)H * W;
+  const std::vector<int32_t>& idx = c.h_band_index[HIGH];
+  const int64_t nb = (int64_t)idx.size();
+  const int m = c.m_eff[HIGH];
+  const double* Ft = c.h_F[0].data();
+  const double* Fh = c.h_F[1].data();
+  const double* Fw = c.h_F[2].data();
+  out.assign((size_t)64 * N, 0);
+  std::vector<double> acc((size_t)N), G((size_t)HW), srow((size_t)W);
+  for (int u = 0; u < m; ++u) {
+    const int64_t r0 = ((int64_t)u * nb) / m, r1 = ((int64_t)(u + 1) * nb) / m;
+    std::fill(acc.begin(), acc.end(), 0.0);
+    int64_t r = r0;
+    while (r < r1) {
+      const int kt = (int)(idx[(size_t)r] / HW);
+      std::fill(G.begin(), G.end(), 0.0);
+      while (r < r1 && idx[(size_t)r] / HW == kt) {
+        const int64_t rowid = idx[(size_t)r] / W;   // kt*H + kh
+        const int kh = (int)(rowid % H);
+        std::fill(srow.begin(), srow.end(), 0.0);
+        while (r < r1 && idx[(size_t)r] / W == rowid) {
+          const double* fw = Fw + (size_t)(idx[(size_t)r] % W) * W;
+          for (int w = 0; w < W; ++w) srow[(size_t)w] += fw[w];
+          ++r;
+        }
+        const double* fh = Fh + (size_t)kh * H;
+        for (int h = 0; h < H; ++h) {
+          const double a = fh[h];
+          double* g = G.data() + (size_t)h * W;
+          for (int w = 0; w < W; ++w) g[w] += a * srow[(size_t)w];
+        }
+      }
+      const double* ft = Ft + (size_t)kt * T;
+      for (int t = 0; t < T; ++t) {
+        const double a = ft[t];
+        double* dst = acc.data() + (size_t)t * HW;
+        for (int64_t i = 0; i < HW; ++i) dst[i] += a * G[(size_t)i];
+      }
+    }
+    for (int64_t n = 0; n < N; ++n) {
+      const float f = (float)acc[(size_t)n];
+      uint32_t b;
+      std::memcpy(&b, &f, 4);
+      b += 0x7fffu + ((b >> 16) & 1u);   // round to nearest even (the weights are finite)
+      const int o = (int)(n & 15), hh = (o >> 3) & 1, gg = (o >> 2) & 1, e = o & 3;
+      out[(size_t)((n >> 6) * 4096 + (int64_t)u * 64 + ((n & 48) + 8 * gg + 4 * hh + e))] = (uint16_t)(b >> 16);
+    }
   }
 }
 

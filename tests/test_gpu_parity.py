@@ -114,10 +114,13 @@ def _stagewise(ctx, wl, band, q, k, v, alloc, out_gpu):
                 for which, name in ((0, "qs"), (1, "ks")):
                     mx, rl = U.errors(ctx.read_spectral(which, s, l), parts[name][idx])
                     print(f"  slice {s} band {l} {name}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
-            mx, rl = U.errors(ctx.read_spectral(2, s, l), parts["vs"][idx])
-            print(f"  slice {s} band {l} vs: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
-            mx, rl = U.errors(ctx.read_spectral(3, s, l), parts["Yhat"][l])
-            print(f"  slice {s} band {l} Yhat: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+            try:   # a slice that does not run the high band has no V~ rows there (its V~ stops at the low+mid box)
+                mx, rl = U.errors(ctx.read_spectral(2, s, l), parts["vs"][idx])
+                print(f"  slice {s} band {l} vs: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+                mx, rl = U.errors(ctx.read_spectral(3, s, l), parts["Yhat"][l])
+                print(f"  slice {s} band {l} Yhat: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+            except B.FreqAttnError as e:
+                assert e.status == B.EUNSUPPORTED and l == 2 and not (alloc[s] >> 2) & 1
         mx, rl = U.errors(out_gpu[0, s], want.reshape(-1, want.shape[-1]))
         print(f"  slice {s} mask {alloc[s]} out: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
 
