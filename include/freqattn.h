@@ -117,6 +117,12 @@ freqattn_status freqattn_band_index(const freqattn_ctx* ctx, int32_t band, int32
 /* Block list of the mid band in CSR form, columns ascending in a row.  *nnz is always written; row_ptr (HOST
  * [nb+1], nb = ceil(n_mid / mid_block)) and col_idx (HOST [nnz]) are filled when not NULL. */
 freqattn_status freqattn_mid_blocks(const freqattn_ctx* ctx, int32_t* row_ptr, int32_t* col_idx, int64_t* nnz);
+/* Section 3.6 with U = I, read through the transform's linearity: summary token u of band `band` of a tensor whose
+ * coefficients pass through unchanged is (1 / |chunk u|) * sum_n w[u][n] x[n], with w[u][n] the sum of the transform's
+ * rows of chunk u (band rows [floor(u n_l / m), floor((u+1) n_l / m)), m = min(n_summary, n_l)).  host_out HOST
+ * [m][T*H*W], token order (t*H + h)*W + w.  The MFMA path sums the high band's summaries of slices that do not run the
+ * high band with these weights, from the untransformed V.  Host only; works on tables-only contexts. */
+freqattn_status freqattn_summary_weights(const freqattn_ctx* ctx, int32_t band, float* host_out);
 /* Per-axis transform matrix as used on the device, widened to double: axis 0/1/2 = T/H/W, HOST out [n*n] row-major
  * (row = frequency for the DCT, scale for the Haar transform; the entry point keeps its name for both). */
 freqattn_status freqattn_dct_matrix(const freqattn_ctx* ctx, int32_t axis, double* host_out);

@@ -43,6 +43,7 @@ EXPORTS = {
     "freqattn_band_index": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
     "freqattn_mid_blocks": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
     "freqattn_dct_matrix": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
+    "freqattn_summary_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]),
     "freqattn_read_spectral": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.c_void_p]),
     "freqattn_route_fixed": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
     "freqattn_route_mlp": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_int32,
@@ -207,6 +208,13 @@ class Context:
         self._check(lib().freqattn_mid_blocks(self._h, rp.ctypes.data_as(C.POINTER(C.c_int32)),
                                               ci.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nnz)))
         return rp, ci
+
+    def summary_weights(self, band):
+        m = min(self.cfg.n_summary, int(self.band_sizes()[band]))
+        n = self.shape.T * self.shape.H * self.shape.W
+        out = np.zeros((m, n), np.float32)
+        self._check(lib().freqattn_summary_weights(self._h, band, out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
 
     def dct_matrix(self, axis):
         n = (self.shape.T, self.shape.H, self.shape.W)[axis]

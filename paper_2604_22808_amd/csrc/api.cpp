@@ -241,13 +241,20 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
     const int dims[3] = {s.T, s.H, s.W};
     bool smaller = false;
     for (int a = 0; a < 3; ++a) smaller = smaller || keep_rows(c->mid_box[a], dims[a]) < dims[a];
+    // (FREQATTN_V_BOX = 0 / 1 switches it off / on whatever the size; by default grids below 64K tokens keep the
+    // whole-grid V~: the extra launches cost more there than the smaller passes save)
     const char* env = getenv("FREQATTN_V_BOX");
+    const bool wanted = env ? atoi(env) != 0 : c->N >= 65536;
     c->v_box_ok = mf && smaller && c->N % 64 == 0 && c->slices <= 256 && c->band_n[HIGH] > 0 &&
-                  (g.n_summary == 0 || c->m_eff[HIGH] <= 64) && !(env && atoi(env) == 0);
+                  (g.n_summary == 0 || c->m_eff[HIGH] <= 64) && wanted;
     if (c->v_box_ok && g.n_summary > 0 && e == hipSuccess) {
       try {
         std::vector<uint16_t> w;
-        build_vsum_weights(*c, w);
+        {
+          std::vector<float> wf;
+          build_summary_weights(*c, HIGH, wf);
+          pack_vsum_weights(wf, c->m_eff[HIGH], c->N, w);
+        }
         A(dev_alloc_bytes(*c, (void**)&c->d_wsum, w.size() * sizeof(uint16_t)));
         up(c->d_wsum, w.data(), w.size() * sizeof(uint16_t));
       } catch (const std::bad_alloc&) {
@@ -377,6 +384,18 @@ extern "C" freqattn_status freqattn_band_index(const freqattn_ctx* c, int32_t ba
   std::memcpy(host_out, c->h_band_index[band].data(), c->h_band_index[band].size() * sizeof(int32_t));
   return FREQATTN_OK;
 }
+extern "C" freqattn_status freqattn_summary_weights(const freqattn_ctx* c, int32_t band, float* host_out) {
+  if (!c || !host_out || band < 0 || band > 2) return FREQATTN_EINVAL;
+  try {
+    std::vector<float> w;
+    build_summary_weights(*c, band, w);
+    if (!w.empty()) std::memcpy(host_out, w.data(), w.size() * sizeof(float));
+  } catch (const std::bad_alloc&) {
+    return FREQATTN_ENOMEM;
+  }
+  return FREQATTN_OK;
+}
+
 extern "C" freqattn_status freqattn_mid_blocks(const freqattn_ctx* c, int32_t* row_ptr, int32_t* col_idx, int64_t* nnz) {
   if (!c || !nnz) return FREQATTN_EINVAL;
   *nnz = (int64_t)c->h_col_idx.size();
@@ -860,7 +879,7 @@ static freqattn_status bands_phase(freqattn_ctx* c, float scale, const void* v_i
     if (nsel > 0)
       {
         int nsplit = std::max(1, c->vsum_nsplit / nsel);   // nsel * nsplit <= 2 CUs' worth + nsel, what the scratch holds
-        nsplit = (int)std::min<int64_t>(nsplit, c->N / 64);
+        nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(nsplit, c->N / 64 / 8));   // at least eight tiles per range
         HIP_TRY(c, launch_vsum(v_in, c->d_wsum, c->d_vsum_part, c->Cbuf, sel, nsel, c->N, c->d, nsplit, c->band_n[HIGH], c->m_eff, ap.m2, st));
       }
     tm.done("summaries");

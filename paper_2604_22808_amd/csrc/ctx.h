@@ -138,7 +138,8 @@ void build_dct_matrix(int n, std::vector<double>& F);  // [n][n], row = frequenc
 void build_haar_matrix(int n, std::vector<double>& F); // [n][n], row = scale (coarse to fine), n a power of two
 void build_bands(Ctx& c);
 void build_mid_blocks(Ctx& c);
-void build_vsum_weights(const Ctx& c, std::vector<uint16_t>& out);  // bf16 [N/64][64][64], see mfma_vsum.hip
+void build_summary_weights(const Ctx& c, int band, std::vector<float>& out);   // [m_eff[band]][N]
+void pack_vsum_weights(const std::vector<float>& w, int m, int64_t N, std::vector<uint16_t>& out);  // bf16 [N/64][64][64], see mfma_vsum.hip
 
 // ---- generic fp32 kernels (generic_kernels.hip) -----------------------------------------------------------------
 struct AxisPassArgs {

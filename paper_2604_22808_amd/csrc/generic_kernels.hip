@@ -263,8 +263,8 @@ __global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C,
   (void)mmax;
 }
 
-// fp16 variant with 16-byte loads: a thread owns 8 adjacent channels, 256 / (d/8) row groups per workgroup, four rows
-// in flight per thread.  Same chunk rule, same fixed summation order per (row group, then groups ascending).
+// fp16 variant with 16-byte loads: a thread owns 8 adjacent channels, 256 / (d/8) row groups per workgroup, sixteen
+// rows in flight per thread.  Same chunk rule, same fixed summation order per (row group, then groups ascending).
 __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const half_t* V, half_t* C, const int32_t* masks,
                                                       int64_t N, int d, int64_t off0, int64_t off1, int64_t off2,
                                                       int64_t n0, int64_t n1, int64_t n2, int m0, int m1, int m2e,
@@ -286,12 +286,13 @@ __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const hal
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (grp < groups) {
     int64_t r = r0 + grp;
-    for (; r + 3 * (int64_t)groups < r1; r += 4 * (int64_t)groups) {
-      h8 x[4];
+    constexpr int INF = 16;   // rows in flight per thread: few workgroups may be left with all the work (see skip)
+    for (; r + (INF - 1) * (int64_t)groups < r1; r += INF * (int64_t)groups) {
+      h8 x[INF];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) x[k] = *(const h8*)(src + (r + (int64_t)k * groups) * d + c8 * 8);
+      for (int k = 0; k < INF; ++k) x[k] = *(const h8*)(src + (r + (int64_t)k * groups) * d + c8 * 8);
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+      for (int k = 0; k < INF; ++k)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] += (float)x[k][j];
     }

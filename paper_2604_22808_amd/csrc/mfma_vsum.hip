@@ -156,18 +156,25 @@ __global__ void __launch_bounds__(256, 2) k_vsum(const uint16_t* __restrict__ V,
 __global__ void __launch_bounds__(256) k_vsum_reduce(const float* __restrict__ part, half_t* __restrict__ C, VsumBits sel,
                                                      int nparts, int d, int64_t n_high, int m_high, int m0, int m1,
                                                      int m2rows) {
-  const int jsel = blockIdx.x;
+  const int jsel = blockIdx.y;
   const int slice = nth_set_bit(sel.w, jsel);
-  for (int idx = threadIdx.x; idx < d * 64; idx += 256) {
-    const int ch = idx >> 6, u = idx & 63;
-    if (u >= m_high) continue;
-    float t = 0.f;
-    for (int p = 0; p < nparts; ++p) t += part[((int64_t)(jsel * nparts + p) * d) * 64 + idx];
-    const int64_t r0 = ((int64_t)u * n_high) / m_high, r1 = ((int64_t)(u + 1) * n_high) / m_high;
-    const half_t mean = (half_t)(t / (float)(r1 - r0));
-    C[(((int64_t)slice * 3 + 0) * m2rows + m1 + u) * d + ch] = mean;
-    C[(((int64_t)slice * 3 + 1) * m2rows + m0 + u) * d + ch] = mean;
+  const int idx = blockIdx.x * 256 + threadIdx.x;   // (channel, chunk) pair, d * 64 of them
+  const int ch = idx >> 6, u = idx & 63;
+  if (ch >= d || u >= m_high) return;
+  const float* src = part + ((int64_t)jsel * nparts * d) * 64 + idx;
+  const int64_t stride = (int64_t)d * 64;
+  float t4[4] = {0.f, 0.f, 0.f, 0.f};   // four interleaved running sums: loads of independent terms overlap, order fixed
+  int p = 0;
+  for (; p + 3 < nparts; p += 4) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) t4[k] += src[(p + k) * stride];
   }
+  for (; p < nparts; ++p) t4[0] += src[p * stride];
+  const float t = (t4[0] + t4[1]) + (t4[2] + t4[3]);
+  const int64_t r0 = ((int64_t)u * n_high) / m_high, r1 = ((int64_t)(u + 1) * n_high) / m_high;
+  const half_t mean = (half_t)(t / (float)(r1 - r0));
+  C[(((int64_t)slice * 3 + 0) * m2rows + m1 + u) * d + ch] = mean;
+  C[(((int64_t)slice * 3 + 1) * m2rows + m0 + u) * d + ch] = mean;
 }
 
 hipError_t launch_vsum(const void* V, const void* Wsum, float* part, void* C, const uint64_t sel[4], int nsel, int64_t N,
@@ -186,7 +193,7 @@ hipError_t launch_vsum(const void* V, const void* Wsum, float* part, void* C, co
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int nparts = nsplit * (d == 128 ? 1 : 2);
-  hipLaunchKernelGGL(k_vsum_reduce, dim3((unsigned)nsel), dim3(256), 0, st, part, (half_t*)C, b, nparts, d, n_high, m_eff[2],
+  hipLaunchKernelGGL(k_vsum_reduce, dim3((unsigned)(d * 64 / 256), (unsigned)nsel), dim3(256), 0, st, part, (half_t*)C, b, nparts, d, n_high, m_eff[2],
                      m_eff[0], m_eff[1], m2rows);
   return hipGetLastError();
 }

@@ -85,22 +85,21 @@ void build_mid_blocks(Ctx& c) {
   }
 }
 
-// Weights of the high band's summary tokens as functionals of the untransformed input (section 3.6, U = I):
-//   Wsum[u][(t,h,w)] = sum over the rows (kt,kh,kw) of chunk u of F_T[kt][t] F_H[kh][h] F_W[kw][w],
+// Weights of a band's summary tokens as functionals of the untransformed input (section 3.6, U = I):
+//   w[u][(t,h,w)] = sum over the rows (kt,kh,kw) of chunk u of F_T[kt][t] F_H[kh][h] F_W[kw][w],
 // chunk u = band rows [floor(u n / m), floor((u+1) n / m)), rows in ascending flat order.  Separable per row, so a
 // chunk is summed kw-run by kw-run into a per-kt plane G[h][w], and each plane goes into the volume with F_T's row.
-// Output: bf16, [N/64][64][64] (tile of 64 tokens, chunk, token; chunks >= m are zero); inside every group of 16 tokens the order is the one in which the
-// transposing LDS reads of the kernel deliver them (stored position 8 g + 4 h + e holds token 8 h + 4 g + e).
-void build_vsum_weights(const Ctx& c, std::vector<uint16_t>& out) {
+// Output: [m][N] in token order.
+void build_summary_weights(const Ctx& c, int band, std::vector<float>& out) {
   const int T = c.shape.T, H = c.shape.H, W = c.shape.W;
   const int64_t N = c.N, HW = (int64_t)H * W;
-  const std::vector<int32_t>& idx = c.h_band_index[HIGH];
+  const std::vector<int32_t>& idx = c.h_band_index[band];
   const int64_t nb = (int64_t)idx.size();
-  const int m = c.m_eff[HIGH];
+  const int m = c.m_eff[band];
   const double* Ft = c.h_F[0].data();
   const double* Fh = c.h_F[1].data();
   const double* Fw = c.h_F[2].data();
-  out.assign((size_t)64 * N, 0);
+  out.assign((size_t)m * N, 0.f);
   std::vector<double> acc((size_t)N), G((size_t)HW), srow((size_t)W);
   for (int u = 0; u < m; ++u) {
     const int64_t r0 = ((int64_t)u * nb) / m, r1 = ((int64_t)(u + 1) * nb) / m;
@@ -132,15 +131,25 @@ void build_vsum_weights(const Ctx& c, std::vector<uint16_t>& out) {
         for (int64_t i = 0; i < HW; ++i) dst[i] += a * G[(size_t)i];
       }
     }
+    float* row = out.data() + (size_t)u * N;
+    for (int64_t n = 0; n < N; ++n) row[n] = (float)acc[(size_t)n];
+  }
+}
+
+// The layout the summing kernel reads: bf16, [N/64][64][64] (tile of 64 tokens, chunk, token; chunks >= m are zero);
+// inside every group of 16 tokens the order is the one in which the kernel's transposing LDS reads deliver them
+// (stored position 8 g + 4 h + e holds token 8 h + 4 g + e).
+void pack_vsum_weights(const std::vector<float>& w, int m, int64_t N, std::vector<uint16_t>& out) {
+  out.assign((size_t)64 * N, 0);
+  for (int u = 0; u < m; ++u)
     for (int64_t n = 0; n < N; ++n) {
-      const float f = (float)acc[(size_t)n];
+      const float f = w[(size_t)u * N + n];
       uint32_t b;
       std::memcpy(&b, &f, 4);
       b += 0x7fffu + ((b >> 16) & 1u);   // round to nearest even (the weights are finite)
       const int o = (int)(n & 15), hh = (o >> 3) & 1, gg = (o >> 2) & 1, e = o & 3;
       out[(size_t)((n >> 6) * 4096 + (int64_t)u * 64 + ((n & 48) + 8 * gg + 4 * hh + e))] = (uint16_t)(b >> 16);
     }
-  }
 }
 
 }  // namespace fa

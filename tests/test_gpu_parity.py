@@ -253,6 +253,44 @@ def test_16k_mask_classes_bf16():
         _check(got[0, s], want[0, s], "bf16", f"16k mask {alloc[s]}")
 
 
+@pytest.mark.parametrize("name,heads,alloc,routed", [
+    ("16k", [0, 1, 2, 3, 4, 5, 6], (0, 5, 3, 6, 1, 2, 4), False),   # head_dim 64, every class of mask
+    ("16k", [0, 1, 2, 3], None, True),                               # router in the loop
+    ("256k", [0, 5, 11], (1, 2, 3), False),                          # head_dim 128, no head runs the high band
+])
+def test_v_on_the_low_mid_box_matches_oracle_and_whole_grid_path(name, heads, alloc, routed, monkeypatch):
+    """Slices without the high band: V~ on the low+mid box and their high-band summary tokens summed from the
+    untransformed V (forced on here, whatever the size), against the oracle and against the same library with the
+    whole-grid V~ (the two differ by rounding only)."""
+    import torch
+    wl = WL.WORKLOADS[name]
+    q, k, v = _inputs(wl, heads=heads)
+    outs = []
+    for flag in ("1", "0"):
+        monkeypatch.setenv("FREQATTN_V_BOX", flag)
+        ctx, band = U.make_ctx(wl, path=B.PATH_MFMA, heads=len(heads))
+        if routed:
+            w = WL.router_weights(64, 1)
+            dq, dk, dv = (U.to_device(x, "bf16") for x in (q, k, v))
+            out = torch.empty_like(dq)
+            for t in (0.9, 0.1, 0.5):   # from the second call on, the previous allocation serves as the prediction
+                al, pi = ctx.forward_routed(dq, dk, dv, t, *w, out)
+            torch.cuda.synchronize()
+            outs.append((out.to(torch.float64).cpu().numpy(), tuple(int(a) for a in al)))
+        else:
+            outs.append((U.run_forward(ctx, q, k, v, wl.dtype, alloc), alloc))
+        ctx.destroy()
+    (got, al), (ref, al_ref) = outs
+    assert tuple(al) == tuple(al_ref)
+    if name == "16k":
+        want = O.forward(q, k, v, wl.grid, U.oracle_cfg(band), al)
+        for s in range(len(heads)):
+            _check(got[0, s], want[0, s], "bf16", f"{name} V on the box, mask {al[s]}")
+    mx, rl = U.errors(got, ref)
+    print(f"{name}: box vs whole grid max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+    assert mx <= 1e-2 and rl <= 2e-3, (mx, rl)
+
+
 @pytest.mark.parametrize("grid,band_kw", [
     ((16, 32, 32), dict(mid_block=128, mid_diag=1, mid_stride=4, high_window=96, n_summary=8)),
     ((16, 16, 48), dict(mid_block=64, mid_diag=2, mid_stride=3, high_window=40, n_summary=5)),

@@ -117,3 +117,27 @@ def test_tables_only_context_refuses_compute():
     dummy = C.c_void_p(16)
     st = B.lib().freqattn_forward(ctx._h, dummy, dummy, dummy, C.byref(cfg), ha, C.c_void_p(32), None)
     assert st == B.EUNSUPPORTED and b"tables-only" in B.lib().freqattn_last_error(ctx._h)
+
+
+@pytest.mark.parametrize("grid,m,transform", [((4, 8, 8), 4, 0), ((16, 32, 32), 16, 0), ((3, 5, 7), 7, 0),
+                                              ((2, 6, 10), 200, 0), ((8, 16, 16), 5, 1)])
+def test_summary_weights_pool_the_spectrum_of_the_input(grid, m, transform):
+    """Section 3.6 (U = I) through linearity: the weights applied to x in token space give the mean-pooled summary
+    tokens of x's coefficients, band by band (the oracle transforms first and pools afterwards)."""
+    T, H, W = grid
+    ctx = tables_ctx(grid, n_summary=m, transform=transform)
+    cfg = O.BandConfig(n_summary=m, transform=transform)
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((T, H, W, 3))
+    xs = O.spectral_forward(x, transform=transform).reshape(-1, 3)
+    for l, idx in enumerate(O.band_partition(T, H, W, cfg)):
+        w = ctx.summary_weights(l)
+        if len(idx) == 0:
+            assert w.shape[0] == 0
+            continue
+        want = O.summary_tokens(xs[idx], m)
+        n, me = len(idx), min(m, len(idx))
+        assert w.shape == (me, T * H * W)
+        sizes = np.array([((u + 1) * n) // me - (u * n) // me for u in range(me)], np.float64)
+        got = (w.astype(np.float64) @ x.reshape(-1, 3)) / sizes[:, None]
+        assert np.abs(got - want).max() < 2e-6, (l, np.abs(got - want).max())
