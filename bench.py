@@ -181,8 +181,12 @@ def main():
     masks = [int(a) for a in alloc]
     cls_present = [any((m & 4) == 0 and (m & 2) == 0 and (m & 1) for m in masks), any((m & 4) == 0 and (m & 2) for m in masks),
                    any(m & 4 for m in masks)]
-    if router is not None:
-        fwd_launches = 9 + (6 if cls_present[2] else 0)
+    vbox = ctx.get_v_box()   # V~ of a slice without the high band on the low+mid box: V follows Q and K class by class
+    nonhigh_present = cls_present[0] or cls_present[1] or any(m == 0 for m in masks)
+    if router is not None:   # routed: slices split into "ran the high band last time" and the rest
+        fwd_launches = (9 if nonhigh_present else 0) + ((9 if vbox else 6) if cls_present[2] else 0) + (0 if vbox else 3)
+    elif vbox:
+        fwd_launches = 6 * sum(cls_present) + (3 if nonhigh_present else 0) + (3 if cls_present[2] else 0)
     else:
         fwd_launches = 3 + 6 * sum(cls_present)
     inv_launches = 3 * sum(cls_present) + (1 if any(m == 0 for m in masks) else 0)
@@ -224,6 +228,7 @@ def main():
                    "head_alloc": [int(a) for a in alloc], "pi": None if pi is None else [round(float(p), 4) for p in pi],
                    "launch": "separate" if args.separate else "fused",
                    "alloc_prediction": "previous forward's high heads (exact in this constant-t loop)" if router is not None else None,
+                   "v_on_low_mid_box": bool(vbox),
                    "precision": "bf16 tensors in and out, fp16 MFMA operands and intermediates, fp32 accumulation"},
         "roofline": roofline, "stages": stage_report,
         "measured_peaks": {"copy_GBs": round(copy_bps / 1e9, 1), "mfma_f16_TFLOPs": round(mfma_fps / 1e12, 1)},

@@ -108,6 +108,9 @@ const char* freqattn_last_error(const freqattn_ctx* ctx);
 freqattn_status freqattn_set_launch_mode(freqattn_ctx* ctx, int32_t mode);
 /* Returns the path the context resolved to (FREQATTN_PATH_GENERIC or FREQATTN_PATH_MFMA). */
 int32_t freqattn_get_path(const freqattn_ctx* ctx);
+/* 1 when the context computes V~ of a slice that does not run the high band on the low+mid box only (MFMA path, grids
+ * of 64K tokens and more unless FREQATTN_V_BOX says otherwise; see freqattn_summary_weights), else 0. */
+int32_t freqattn_get_v_box(const freqattn_ctx* ctx);
 
 /* ---- introspection of the integer tables (section 3.3 band lists, section 3.4.2 block pattern) ---------------- */
 /* n[l] = number of coefficients in band l (0 low, 1 mid, 2 high); HOST out. */

@@ -43,6 +43,7 @@ EXPORTS = {
     "freqattn_band_index": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
     "freqattn_mid_blocks": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
     "freqattn_dct_matrix": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
+    "freqattn_get_v_box": (C.c_int32, [C.c_void_p]),
     "freqattn_summary_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]),
     "freqattn_read_spectral": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.c_void_p]),
     "freqattn_route_fixed": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
@@ -208,6 +209,9 @@ class Context:
         self._check(lib().freqattn_mid_blocks(self._h, rp.ctypes.data_as(C.POINTER(C.c_int32)),
                                               ci.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nnz)))
         return rp, ci
+
+    def get_v_box(self):
+        return int(lib().freqattn_get_v_box(self._h))
 
     def summary_weights(self, band):
         m = min(self.cfg.n_summary, int(self.band_sizes()[band]))

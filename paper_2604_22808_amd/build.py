@@ -27,22 +27,27 @@ def build(verbose: bool = False, jobs: int = 6) -> str:
     os.makedirs(objdir, exist_ok=True)
     flags = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wno-unused-value"]
+             "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wno-unused-value", "-Wno-inline-asm"]   # (m0 named as clobbered by the LDS-copy assembly)
     procs = []
     objs = []
     for src in SOURCES:
         obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
         objs.append(obj)
         cmd = [hipcc()] + flags + ["-c", os.path.join(CSRC, src), "-o", obj]
-        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
-        while sum(p.poll() is None for _, p in procs) >= jobs:
-            for _, p in procs:
+        # compiler output goes to a file: a pipe nobody reads while the build waits would block a chatty compile
+        log = open(obj + ".log", "w+")
+        procs.append((src, subprocess.Popen(cmd, stdout=log, stderr=subprocess.STDOUT), log))
+        while sum(p.poll() is None for _, p, _ in procs) >= jobs:
+            for _, p, _ in procs:
                 if p.poll() is None:
                     p.wait()
                     break
     failed = False
-    for src, p in procs:
-        out, _ = p.communicate()
+    for src, p, log in procs:
+        p.wait()
+        log.seek(0)
+        out = log.read()
+        log.close()
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
         if p.returncode != 0:
             failed = True

@@ -384,6 +384,8 @@ extern "C" freqattn_status freqattn_band_index(const freqattn_ctx* c, int32_t ba
   std::memcpy(host_out, c->h_band_index[band].data(), c->h_band_index[band].size() * sizeof(int32_t));
   return FREQATTN_OK;
 }
+extern "C" int32_t freqattn_get_v_box(const freqattn_ctx* c) { return (c && c->v_box_ok) ? 1 : 0; }
+
 extern "C" freqattn_status freqattn_summary_weights(const freqattn_ctx* c, int32_t band, float* host_out) {
   if (!c || !host_out || band < 0 || band > 2) return FREQATTN_EINVAL;
   try {
