@@ -14,8 +14,13 @@
 //   K tile   -> LDS row-major, A operand of v_mfma_f32_32x32x16_f16 (lane = key, 8 consecutive channels)
 //   Q        -> registers, B operand (lane = query, 8 consecutive channels), loaded once per item
 //   softmax  -> running max / sum per lane (one query per lane; the two lane halves hold different keys)
-//   V tile   -> LDS transposed [channel][key] with the key order of the S^T accumulator, so that the
-//               accumulator registers, converted to fp16, are the B operand of O^T += V^T P^T directly.
+//   V tile   -> V^T operand (A) in the key order of the S^T accumulator, so that the accumulator registers,
+//               converted to fp16, are the B operand of O^T += V^T P^T directly.
+// Two ways of staging the tiles (template flag DMA):
+//   DMA      K and V rows copied straight from global memory into LDS, row-major; V^T comes out of transposing
+//            LDS reads.  Every fp16 tensor of the path takes this road.
+//   register loads a tile ahead into registers, conversion, V transposed by byte permutes on its way into LDS.
+//            The bf16 dense comparison, whose operands need converting, takes this one.
 #include <hip/hip_runtime.h>
 
 #include "ctx.h"
@@ -193,7 +198,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       n_outer = (nk + KT - 1) / KT;
     }
 
-    // Tiles are staged through registers: the global loads of tile i+1 are issued before the arithmetic of tile i, so
+    // Register path: tiles are staged through registers: the global loads of tile i+1 are issued before the arithmetic of tile i, so
     // their latency hides behind it; the registers are written to LDS after the barrier that ends tile i.
     constexpr int KPT = (KT * (D / 8) + NT - 1) / NT;          // 16-byte K pieces per thread
     constexpr int VPT = ((KT / 4) * (D / 8) + NT - 1) / NT;    // (4 keys x 8 channels) V units per thread
@@ -285,7 +290,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       }
     };
 
-    // Pipeline: at the top of iteration i the registers hold tile i+1 (requested one iteration ago); it goes into the
+    // Pipeline of the register path: at the top of iteration i the registers hold tile i+1 (requested one iteration ago); it goes into the
     // LDS copy that tile i-1 used - free since the barrier that ended iteration i-1 - and the loads of tile i+2 are
     // issued, a whole iteration ahead of their use.  The barrier at the end of the iteration publishes tile i+1.
     // Exchange items of one (slice, band) all see the same <= 2 tiles of summary tokens: a workgroup that has them in
