@@ -64,3 +64,38 @@ def test_1m_launch_modes_agree_and_idle_head_returns_v():
     rel = float(diff.norm() / v[0, 3].float().norm())
     print(f"1m idle head: max-abs {float(diff.abs().max()):.3e} rel-L2 {rel:.3e}", flush=True)
     assert float(diff.abs().max()) <= 2e-2 and rel <= 5e-3
+
+
+def test_1m_benchmark_configuration_routed_with_prediction():
+    """The configuration bench.py times: 16 heads, router in the loop at t = 0.5, second call with the first call's
+    allocation as the prediction (V~ of heads without the high band on the low+mid box, their high-band summaries from
+    the untransformed V).  The routed output must equal the plain forward with the same allocation bit for bit, and
+    one head per band is compared with the oracle on every element."""
+    import torch
+    wl = WL.WORKLOADS["1m"]
+    q, k, v = WL.qkv_torch(wl, "cuda")
+    cfg = B.make_cfg(**wl.band)
+    ctx = B.Context(wl.batch, wl.heads, wl.head_dim, wl.grid, B.BF16, cfg)
+    assert ctx.get_path() == B.PATH_MFMA and ctx.get_v_box() == 1
+    w = WL.router_weights(wl.alloc["hidden"], wl.alloc["seed"])
+    out = torch.empty_like(q); plain = torch.empty_like(q)
+    for _ in range(2):
+        alloc, pi = ctx.forward_routed(q, k, v, wl.alloc["t"], *w, out)
+    torch.cuda.synchronize()
+    alloc = [int(a) for a in alloc]
+    print(f"1m routed allocation {alloc} pi {pi}", flush=True)
+    ctx.forward(q, k, v, alloc, plain)
+    torch.cuda.synchronize()
+    assert torch.equal(out, plain)
+    T, H, W = wl.grid
+    seen = set()
+    for h, mask in enumerate(alloc):
+        if mask in seen or mask == 0:
+            continue
+        seen.add(mask)
+        host = [U.to_host64(x[:, h:h + 1])[0, 0].reshape(T, H, W, wl.head_dim) for x in (q, k, v)]
+        want = O.head_forward(host[0], host[1], host[2], O.BandConfig(**wl.band), mask).reshape(-1, wl.head_dim)
+        got = U.to_host64(out[:, h:h + 1])[0, 0]
+        mx, rl = U.errors(got, want)
+        print(f"1m routed head {h} mask {mask}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+        assert mx <= 2e-2 and rl <= 5e-3, (h, mask, mx, rl)
