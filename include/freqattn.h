@@ -14,6 +14,12 @@
  * caller except freqattn_create (tables and scratch, owned by the context, released by freqattn_destroy).
  * Errors are returned as codes; freqattn_last_error gives the text of the last failure on a context.
  * A context must be used from one host thread at a time and with one stream at a time.
+ *
+ * Environment switches (diagnostics and A/B runs; results agree within rounding either way):
+ *   FREQATTN_V_BOX=0|1     read at freqattn_create: never / always compute V~ of slices without the high band on the
+ *                          low+mid box only (default: from 64K tokens on; see freqattn_get_v_box)
+ *   FREQATTN_ATTN_DMA=0    read at the first attention launch of the process: stage attention tiles through
+ *                          registers instead of copying them straight into LDS
  */
 #ifndef FREQATTN_H
 #define FREQATTN_H
