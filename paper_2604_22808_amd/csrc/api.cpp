@@ -57,7 +57,7 @@ static void free_all(Ctx* c) {
   for (int a = 0; a < 3; ++a) { F(c->d_F32[a]); F(c->d_Ft32[a]); F(c->d_F16[a]); F(c->d_Ft16[a]); }
   F(c->specQ); F(c->specK); F(c->specV); F(c->Y); F(c->tmp0); F(c->tmp1);
   F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_lists); F(c->d_energy_part);
-  F(c->d_tot_part); F(c->d_wsum); F(c->d_vsum_part);
+  F(c->d_tot_part); F(c->d_wsum); F(c->d_vsum_part); F(c->d_pool_part);
   if (c->h_lists) (void)hipHostFree(c->h_lists);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
   if (c->ev_created)
@@ -225,6 +225,7 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
   A(dev_alloc_bytes(*c, &c->Cbuf, (size_t)c->slices * 3 * 2 * (size_t)std::max(g.n_summary, 1) * c->d * es));
   const size_t stats_floats = (size_t)3 * c->d * (1 + 64);
   A(dev_alloc(*c, &c->d_stats, stats_floats));
+  if (mf && g.n_summary > 0 && g.n_summary < 64) A(dev_alloc(*c, &c->d_pool_part, (size_t)c->slices * 3 * 128 * c->d));
   if (mf) A(dev_alloc(*c, &c->d_energy_part, (size_t)6 * DCT_MAX_WAVES * 3 * 64));
   if (mf) A(dev_alloc(*c, &c->d_tot_part, (size_t)3 * DCT_MAX_WAVES * 64));
   {
@@ -877,7 +878,7 @@ static freqattn_status bands_phase(freqattn_ctx* c, float scale, const void* v_i
         if (mask != 0) { sel[s >> 6] |= 1ull << (s & 63); ++nsel; }   // idle slices use no summaries
       }
     }
-    HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, skip, st));
+    HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, skip, c->d_pool_part, st));
     if (nsel > 0)
       {
         int nsplit = std::max(1, c->vsum_nsplit / nsel);   // nsel * nsplit <= 2 CUs' worth + nsel, what the scratch holds

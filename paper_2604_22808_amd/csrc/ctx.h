@@ -109,6 +109,7 @@ struct Ctx {
   bool v_box_ok = false;              // the context can do it: summary weights built, or no summaries configured
   uint16_t* d_wsum = nullptr;         // bf16 [N/64][64][64]
   float* d_vsum_part = nullptr;       // [slices][vsum_parts][d][64] partial sums
+  float* d_pool_part = nullptr;       // [slices][3][128][d]: partial sums of the pooling when chunks are cut into row ranges (m < 64)
   int vsum_nsplit = 0;
   std::vector<char> v_full;           // per slice: the current forward computed V~ on the whole grid
   size_t off_items = 0;               // AttnItem array (fused order: all branches), then exchange items
@@ -180,7 +181,7 @@ hipError_t launch_expand_low(const void* lowY, void* Y, const int32_t* slice_lis
 // skip_high: bit s set = the high band of slice s is not pooled here (its V~ rows do not exist; see launch_vsum).
 hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
                             const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2, int is_half,
-                            const uint64_t skip_high[4], hipStream_t st);
+                            const uint64_t skip_high[4], float* split_part /*[slices][3][128][d] or NULL*/, hipStream_t st);
 // High-band summary tokens of the slices in `sel` (bit set, nsel of them) from the untransformed bf16 V.
 hipError_t launch_vsum(const void* V, const void* Wsum, float* part, void* C, const uint64_t sel[4], int nsel, int64_t N,
                        int d, int nsplit, int64_t n_high, const int m_eff[3], int m2rows, hipStream_t st);

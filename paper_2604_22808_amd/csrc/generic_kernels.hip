@@ -268,17 +268,20 @@ __global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C,
 __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const half_t* V, half_t* C, const int32_t* masks,
                                                       int64_t N, int d, int64_t off0, int64_t off1, int64_t off2,
                                                       int64_t n0, int64_t n1, int64_t n2, int m0, int m1, int m2e,
-                                                      int m2rows, SkipBits skip) {
+                                                      int m2rows, SkipBits skip, int nsplit, float* split_part) {
   typedef _Float16 h8 __attribute__((ext_vector_type(8)));
   __shared__ float part[256 * 8];
-  const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x;
+  const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x / nsplit, sp = blockIdx.x % nsplit;
   if (band == 2 && slice < 256 && ((skip.w[slice >> 6] >> (slice & 63)) & 1)) return;
   const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
   const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
   const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
   if (u >= me) return;
   const half_t* src = (((masks[slice] >> band) & 1) ? Y : V) + ((int64_t)slice * N + off) * d;
-  const int64_t r0 = ((int64_t)u * n) / me, r1 = ((int64_t)(u + 1) * n) / me;
+  const int64_t c0 = ((int64_t)u * n) / me, c1 = ((int64_t)(u + 1) * n) / me;   // the chunk
+  // with few chunks (small m) a chunk is cut into nsplit row ranges, one workgroup each; their sums meet in
+  // k_summaries_finish in a fixed order
+  const int64_t r0 = c0 + ((c1 - c0) * sp) / nsplit, r1 = c0 + ((c1 - c0) * (sp + 1)) / nsplit;
   const int tpr = d / 8;               // threads per row
   const int groups = 256 / tpr;        // rows per workgroup step
   const int tid = threadIdx.x;
@@ -306,13 +309,21 @@ __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const hal
   for (int j = 0; j < 8; ++j) part[tid * 8 + j] = acc[j];
   __syncthreads();
   if (grp == 0) {
-    const float inv = 1.f / (float)(r1 - r0);
+    const float inv = 1.f / (float)(c1 - c0);
     h8 mean;
+    float sum[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       float t = 0.f;
       for (int g2 = 0; g2 < groups; ++g2) t += part[(g2 * tpr + c8) * 8 + j];
+      sum[j] = t;
       mean[j] = (_Float16)(t * inv);
+    }
+    if (nsplit > 1) {   // [slice][band][u][split][d]
+      float* dst = split_part + ((((int64_t)slice * 3 + band) * gridDim.x + blockIdx.x) * d) + c8 * 8;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dst[j] = sum[j];
+      return;
     }
     for (int b = 0; b < 3; ++b) {
       if (b == band) continue;
@@ -324,20 +335,48 @@ __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const hal
   }
 }
 
+// Second stage of the split pooling: adds the nsplit partial sums of a chunk in order and writes the mean rows.
+__global__ void __launch_bounds__(256) k_summaries_finish(const float* split_part, half_t* C, int d, int64_t n0, int64_t n1,
+                                                          int64_t n2, int m0, int m1, int m2e, int m2rows, SkipBits skip,
+                                                          int nsplit, int mmax) {
+  const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x, ch = threadIdx.x;
+  if (band == 2 && slice < 256 && ((skip.w[slice >> 6] >> (slice & 63)) & 1)) return;
+  const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
+  const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
+  if (u >= me || ch >= d) return;
+  const int64_t c0 = ((int64_t)u * n) / me, c1 = ((int64_t)(u + 1) * n) / me;
+  const float* src = split_part + ((((int64_t)slice * 3 + band) * (mmax * nsplit) + (int64_t)u * nsplit) * d) + ch;
+  float t = 0.f;
+  for (int sp = 0; sp < nsplit; ++sp) t += src[(int64_t)sp * d];
+  const half_t mean = (half_t)(t / (float)(c1 - c0));
+  for (int b = 0; b < 3; ++b) {
+    if (b == band) continue;
+    int pos = u;
+    for (int o = 0; o < band; ++o)
+      if (o != b) pos += (o == 0 ? m0 : o == 1 ? m1 : m2e);
+    C[(((int64_t)slice * 3 + b) * m2rows + pos) * d + ch] = mean;
+  }
+}
+
 hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
                             const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2rows,
-                            int is_half, const uint64_t skip_high[4], hipStream_t st) {
+                            int is_half, const uint64_t skip_high[4], float* split_part, hipStream_t st) {
   SkipBits skip;
   for (int i = 0; i < 4; ++i) skip.w[i] = skip_high ? skip_high[i] : 0;
   int mmax = m_eff[0] > m_eff[1] ? m_eff[0] : m_eff[1];
   if (m_eff[2] > mmax) mmax = m_eff[2];
   if (mmax == 0 || slices == 0) return hipSuccess;
   dim3 grid((unsigned)mmax, 3, (unsigned)slices);
-  if (is_half && d % 8 == 0 && 256 % (d / 8) == 0)
-    hipLaunchKernelGGL(k_summaries_h8, grid, dim3(256), 0, st, (const half_t*)Y, (const half_t*)V, (half_t*)C, masks, N,
-                       d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0], m_eff[1],
-                       m_eff[2], m2rows, skip);
-  else if (is_half)
+  if (is_half && d % 8 == 0 && 256 % (d / 8) == 0) {
+    // at least 64 workgroups per (slice, band): with few chunks each is cut into row ranges (scratch: 128 rows per pair)
+    const int nsplit = (split_part && mmax < 64) ? (64 + mmax - 1) / mmax : 1;
+    hipLaunchKernelGGL(k_summaries_h8, dim3((unsigned)(mmax * nsplit), 3, (unsigned)slices), dim3(256), 0, st, (const half_t*)Y,
+                       (const half_t*)V, (half_t*)C, masks, N, d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1],
+                       band_n[2], m_eff[0], m_eff[1], m_eff[2], m2rows, skip, nsplit, split_part);
+    if (nsplit > 1)
+      hipLaunchKernelGGL(k_summaries_finish, grid, dim3(256), 0, st, split_part, (half_t*)C, d, band_n[0], band_n[1], band_n[2],
+                         m_eff[0], m_eff[1], m_eff[2], m2rows, skip, nsplit, mmax);
+  } else if (is_half)
     hipLaunchKernelGGL(k_summaries<half_t>, grid, dim3(256), 0, st, (const half_t*)Y, (const half_t*)V, (half_t*)C,
                        masks, N, d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0],
                        m_eff[1], m_eff[2], mmax, m2rows, skip);
