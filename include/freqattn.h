@@ -183,8 +183,8 @@ freqattn_status freqattn_set_stage_timing(freqattn_ctx* ctx, int32_t enabled);
 freqattn_status freqattn_stage_times(freqattn_ctx* ctx, int32_t max_stages, const char** names_out, float* ms_out,
                                      int32_t* n_stages);
 
-/* freqattn_forward_routed has to transform Q and K before it knows which heads run the high band (the only ones that
- * need Q~ and K~ on the whole grid).  With prediction on (the default) it assumes the heads that ran the high band in
+/* freqattn_forward_routed has to transform Q and K (and V, see freqattn_get_v_box) before it knows which heads run the
+ * high band (the only ones that need them on the whole grid).  With prediction on (the default) it assumes the heads that ran the high band in
  * the context's last forward will do so again - allocations move slowly along a sampling trajectory (section 3.5) - and
  * transforms them in full at once; heads that are newly high after routing are completed then, as all of them are
  * without prediction.  Outputs do not depend on the setting (statistics agree to fp32 rounding). */
