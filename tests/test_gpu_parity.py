@@ -295,9 +295,13 @@ def test_v_on_the_low_mid_box_matches_oracle_and_whole_grid_path(name, heads, al
     ((16, 32, 32), dict(mid_block=128, mid_diag=1, mid_stride=4, high_window=96, n_summary=8)),
     ((16, 16, 48), dict(mid_block=64, mid_diag=2, mid_stride=3, high_window=40, n_summary=5)),
 ])
-def test_mfma_head_dim_64_bf16(grid, band_kw):
+@pytest.mark.parametrize("v_box", ["0", "1"])
+def test_mfma_head_dim_64_bf16(grid, band_kw, v_box, monkeypatch):
     """head_dim 64 instantiations of the matrix-core kernels (transform passes with one 64-column chunk per token,
-    attention with four channel steps), one head per band plus one head that runs all bands."""
+    attention with four channel steps), one head per band plus one head that runs all bands; with V~ on the whole grid
+    and with V~ of the heads without the high band on the low+mid box (summary weights over ragged chunks, white-noise
+    inputs: nothing is small in the high band)."""
+    monkeypatch.setenv("FREQATTN_V_BOX", v_box)
     d = 64
     rng = np.random.default_rng(11)
     N = int(np.prod(grid))
@@ -306,6 +310,8 @@ def test_mfma_head_dim_64_bf16(grid, band_kw):
     band.update(low_compress=4, **band_kw)
     ctx = B.Context(1, 4, d, grid, B.BF16, B.make_cfg(**band))
     assert ctx.get_path() == B.PATH_MFMA
+    if grid == (16, 32, 32):       # (the 16x16x48 grid has no smaller low+mid box in the kernels' granularity)
+        assert ctx.get_v_box() == int(v_box)
     alloc = (1, 2, 4, 7)
     got = U.run_forward(ctx, q, k, v, "bf16", alloc)
     want = O.forward(q, k, v, grid, O.BandConfig(**band), alloc)
