@@ -20,6 +20,8 @@
  *                          low+mid box only (default: from 64K tokens on; see freqattn_get_v_box)
  *   FREQATTN_ATTN_DMA=0    read at the first attention launch of the process: stage attention tiles through
  *                          registers instead of copying them straight into LDS
+ *   FREQATTN_DENSE_BF16_DIRECT=1  freqattn_dense_forward reads the bf16 tensors in the kernel (register staging)
+ *                          instead of converting them to fp16 scratch first
  */
 #ifndef FREQATTN_H
 #define FREQATTN_H
@@ -170,7 +172,9 @@ freqattn_status freqattn_forward_routed(freqattn_ctx* ctx, const void* q, const 
 
 /* ---- dense comparison (section 4: N^2 pairs per head) ----------------------------------------------------------
  * Plain softmax(scale * Q K^T) V over all N tokens of every head with the library's own flash-style MFMA kernel;
- * BF16 contexts on the MFMA path only.  Same pointer conventions as freqattn_forward.  Asynchronous. */
+ * BF16 contexts on the MFMA path only.  Same pointer conventions as freqattn_forward.  Asynchronous.  Uses the
+ * context's scratch (fp16 copies of q, k, v and of the result): freqattn_read_spectral is meaningless afterwards until
+ * the next forward. */
 freqattn_status freqattn_dense_forward(freqattn_ctx* ctx, const void* q, const void* k, const void* v, void* out,
                                        void* stream);
 

@@ -986,9 +986,24 @@ extern "C" freqattn_status freqattn_dense_forward(freqattn_ctx* c, const void* q
   AttnParams ap;
   const float scale = c->cfg.softmax_scale > 0.f ? c->cfg.softmax_scale : 1.0f / std::sqrt((float)c->d);
   fill_attn_params(*c, ap, scale);
-  ap.denseQ = q; ap.denseK = k; ap.denseV = v; ap.denseO = out; ap.dense_bf16 = 1;
   StageTimer tm(*c, st);
-  HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(c->d_lists + c->off_items_dense), c->n_items_dense, c->attn_rows, c->num_cu, st));
+  // The attention kernel is fastest on fp16 tensors (tiles copied straight into LDS): the bf16 inputs are converted
+  // into the context's spectral scratch first, and the fp16 result back into the caller's bf16 tensor - two
+  // element-wise passes beside an N^2 kernel.  (FREQATTN_DENSE_BF16_DIRECT=1: the kernel converts on the fly.)
+  static int direct = -1;
+  if (direct < 0) { const char* e = getenv("FREQATTN_DENSE_BF16_DIRECT"); direct = e ? atoi(e) : 0; }
+  const int64_t n_el = (int64_t)c->slices * c->N * c->d;
+  if (!direct && n_el % 8 == 0) {
+    HIP_TRY(c, launch_convert_16(q, c->specQ, n_el, 0, st));
+    HIP_TRY(c, launch_convert_16(k, c->specK, n_el, 0, st));
+    HIP_TRY(c, launch_convert_16(v, c->specV, n_el, 0, st));
+    ap.denseQ = c->specQ; ap.denseK = c->specK; ap.denseV = c->specV; ap.denseO = c->Y; ap.dense_bf16 = 0;
+    HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(c->d_lists + c->off_items_dense), c->n_items_dense, c->attn_rows, c->num_cu, st));
+    HIP_TRY(c, launch_convert_16(c->Y, out, n_el, 1, st));
+  } else {
+    ap.denseQ = q; ap.denseK = k; ap.denseV = v; ap.denseO = out; ap.dense_bf16 = 1;
+    HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(c->d_lists + c->off_items_dense), c->n_items_dense, c->attn_rows, c->num_cu, st));
+  }
   tm.done("dense_attention");
   return FREQATTN_OK;
 }

@@ -194,6 +194,8 @@ hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 hipError_t launch_probe_copy(const void* in, void* out, int64_t bytes, int num_cu, hipStream_t st);
 hipError_t launch_probe_mfma(float* out, int blocks, int iters, hipStream_t st);
 // out[slice] = in[slice] for the listed slices (slice_bytes each, a multiple of 16).
+// out[i] = in[i] converted bf16 -> fp16 (to_bf16 = 0) or fp16 -> bf16 (round to nearest even), n elements, n % 8 == 0.
+hipError_t launch_convert_16(const void* in, void* out, int64_t n, int to_bf16, hipStream_t st);
 hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_list, int n_slices, int64_t slice_bytes,
                               hipStream_t st);
 hipError_t launch_energy_reduce(const float* energy_part /*[6][DCT_MAX_WAVES][3][64]: Q, K, V (box), Q, K, V (whole grid)*/,

@@ -483,6 +483,51 @@ hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_li
   return hipGetLastError();
 }
 
+// Element-wise conversions between the caller's bf16 tensors and fp16 scratch (n a multiple of 8): the dense comparison
+// runs the attention kernel's direct-to-LDS path, which needs its operands in fp16 in memory.
+__global__ void k_bf16_to_f16(const uint4* in, uint4* out, int64_t nvec) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * blockDim.x) {
+    const uint4 v = in[i];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const half_t lo = (half_t)__uint_as_float(w[j] << 16), hi = (half_t)__uint_as_float(w[j] & 0xffff0000u);
+      o[j] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+    }
+    out[i] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+__global__ void k_f16_to_bf16(const uint4* in, uint4* out, int64_t nvec) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * blockDim.x) {
+    const uint4 v = in[i];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t r[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const float f = (float)__builtin_bit_cast(half_t, (uint16_t)(h ? (w[j] >> 16) : (w[j] & 0xffffu)));
+        uint32_t u = __float_as_uint(f);
+        u = (u & 0x7f800000u) == 0x7f800000u ? u : u + 0x7fffu + ((u >> 16) & 1u);   // round to nearest even
+        r[h] = u >> 16;
+      }
+      o[j] = r[0] | (r[1] << 16);
+    }
+    out[i] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+hipError_t launch_convert_16(const void* in, void* out, int64_t n, int to_bf16, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  if (n % 8) return hipErrorInvalidValue;
+  const int64_t nvec = n / 8;
+  const unsigned gx = (unsigned)std::min<int64_t>((nvec + 255) / 256, 8192);
+  if (to_bf16) hipLaunchKernelGGL(k_f16_to_bf16, dim3(gx), dim3(256), 0, st, (const uint4*)in, (uint4*)out, nvec);
+  else hipLaunchKernelGGL(k_bf16_to_f16, dim3(gx), dim3(256), 0, st, (const uint4*)in, (uint4*)out, nvec);
+  return hipGetLastError();
+}
+
 // Fixed-order sum of the per-wave partial statistics written by the fused forward passes of Q, K and V.
 // Wave w of a launch worked on column chunk w % (d/64) only.  One workgroup per (band, channel): 256 threads take
 // the (tensor, wave) terms round-robin and a fixed tree adds their partial sums.
