@@ -866,19 +866,24 @@ static freqattn_status bands_phase(freqattn_ctx* c, float scale, const void* v_i
 
   // section 3.6: summary tokens of all bands, then the exchange on the active bands
   if (c->cfg.n_summary > 0) {
-    // slices that do not run the high band (their V~ may stop at the low+mid box): the pooling skips their high band,
-    // which is summed from V instead
-    uint64_t skip[4] = {0, 0, 0, 0}, sel[4] = {0, 0, 0, 0};
+    // Band l of a slice is summarised only if another band of the slice is active (the exchange of that band is the only
+    // reader).  For slices that do not run the high band (their V~ may stop at the low+mid box) the high band's summaries
+    // are summed from V instead of pooled - by the allocation alone, also where V~ happens to exist on the whole grid:
+    // the result must not depend on a prediction.
+    uint64_t skip[3][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}}, sel[4] = {0, 0, 0, 0};
     int nsel = 0;
-    if (mf && c->v_box_ok) {
-      for (int s = 0; s < c->slices; ++s) {   // by the allocation alone, also where V~ happens to exist on the whole
-        const int mask = c->h_alloc[(size_t)(s % c->shape.heads)];   // grid: the result must not depend on a prediction
-        if (mask & 4) continue;
-        skip[s >> 6] |= 1ull << (s & 63);
-        if (mask != 0) { sel[s >> 6] |= 1ull << (s & 63); ++nsel; }   // idle slices use no summaries
+    if (c->slices <= 256) {
+      for (int s = 0; s < c->slices; ++s) {
+        const int mask = c->h_alloc[(size_t)(s % c->shape.heads)];
+        for (int l = 0; l < 3; ++l)
+          if ((mask & ~(1 << l) & 7) == 0) skip[l][s >> 6] |= 1ull << (s & 63);
+        if (mf && c->v_box_ok && !(mask & 4)) {
+          skip[2][s >> 6] |= 1ull << (s & 63);
+          if (mask != 0) { sel[s >> 6] |= 1ull << (s & 63); ++nsel; }
+        }
       }
     }
-    HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, skip, c->d_pool_part, st));
+    HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, &skip[0][0], c->d_pool_part, st));
     if (nsel > 0)
       {
         int nsplit = std::max(1, c->vsum_nsplit / nsel);   // nsel * nsplit <= 2 CUs' worth + nsel, what the scratch holds

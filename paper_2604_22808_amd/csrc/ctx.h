@@ -178,10 +178,11 @@ hipError_t launch_pool_low(const void* spec, void* low, const int32_t* slice_lis
 hipError_t launch_expand_low(const void* lowY, void* Y, const int32_t* slice_list, int n_slices, int64_t N, int d,
                              int64_t n_low, int64_t nbar, int c, int is_half, hipStream_t st);
 // Summary tokens of all bands of all slices, written into the C slots of the two other bands.
-// skip_high: bit s set = the high band of slice s is not pooled here (its V~ rows do not exist; see launch_vsum).
+// skip_bits[l][..]: bit s set = band l of slice s is not pooled here (no active band of the slice looks at it, or - high
+// band only - its V~ rows do not exist and launch_vsum supplies it).
 hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
                             const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2, int is_half,
-                            const uint64_t skip_high[4], float* split_part /*[slices][3][128][d] or NULL*/, hipStream_t st);
+                            const uint64_t* skip_bits /*[3][4] or NULL*/, float* split_part /*[slices][3][128][d] or NULL*/, hipStream_t st);
 // High-band summary tokens of the slices in `sel` (bit set, nsel of them) from the untransformed bf16 V.
 hipError_t launch_vsum(const void* V, const void* Wsum, float* part, void* C, const uint64_t sel[4], int nsel, int64_t N,
                        int d, int nsplit, int64_t n_high, const int m_eff[3], int m2rows, hipStream_t st);

@@ -224,7 +224,7 @@ hipError_t launch_expand_low(const void* lowY, void* Y, const int32_t* slice_lis
 // One workgroup per (slice, band, chunk); threads split the chunk's rows 256/d ways and the partial sums are added in
 // a fixed order, so the result does not depend on scheduling.  The mean is written to the C rows of the two other
 // bands (band l sees the summaries of the other bands, ascending band order).
-struct SkipBits { uint64_t w[4]; };   // slices whose high band is pooled elsewhere (from the untransformed V)
+struct SkipBits { uint64_t w[3][4]; };   // per band: slices whose summaries of that band are not pooled here (unused, or summed from the untransformed V)
 
 template <typename T>
 __global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C, const int32_t* masks, int64_t N, int d,
@@ -232,7 +232,7 @@ __global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C,
                                                    int64_t n2, int m0, int m1, int m2e, int mmax, int m2rows, SkipBits skip) {
   __shared__ float part[256];
   const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x;
-  if (band == 2 && slice < 256 && ((skip.w[slice >> 6] >> (slice & 63)) & 1)) return;
+  if (slice < 256 && ((skip.w[band][slice >> 6] >> (slice & 63)) & 1)) return;
   const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
   const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
   const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
@@ -272,7 +272,7 @@ __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const hal
   typedef _Float16 h8 __attribute__((ext_vector_type(8)));
   __shared__ float part[256 * 8];
   const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x / nsplit, sp = blockIdx.x % nsplit;
-  if (band == 2 && slice < 256 && ((skip.w[slice >> 6] >> (slice & 63)) & 1)) return;
+  if (slice < 256 && ((skip.w[band][slice >> 6] >> (slice & 63)) & 1)) return;
   const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
   const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
   const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
@@ -340,7 +340,7 @@ __global__ void __launch_bounds__(256) k_summaries_finish(const float* split_par
                                                           int64_t n2, int m0, int m1, int m2e, int m2rows, SkipBits skip,
                                                           int nsplit, int mmax) {
   const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x, ch = threadIdx.x;
-  if (band == 2 && slice < 256 && ((skip.w[slice >> 6] >> (slice & 63)) & 1)) return;
+  if (slice < 256 && ((skip.w[band][slice >> 6] >> (slice & 63)) & 1)) return;
   const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
   const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
   if (u >= me || ch >= d) return;
@@ -360,9 +360,10 @@ __global__ void __launch_bounds__(256) k_summaries_finish(const float* split_par
 
 hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
                             const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2rows,
-                            int is_half, const uint64_t skip_high[4], float* split_part, hipStream_t st) {
+                            int is_half, const uint64_t* skip_bits /*[3][4] or NULL*/, float* split_part, hipStream_t st) {
   SkipBits skip;
-  for (int i = 0; i < 4; ++i) skip.w[i] = skip_high ? skip_high[i] : 0;
+  for (int l = 0; l < 3; ++l)
+    for (int i = 0; i < 4; ++i) skip.w[l][i] = skip_bits ? skip_bits[l * 4 + i] : 0;
   int mmax = m_eff[0] > m_eff[1] ? m_eff[0] : m_eff[1];
   if (m_eff[2] > mmax) mmax = m_eff[2];
   if (mmax == 0 || slices == 0) return hipSuccess;
