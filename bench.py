@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 matrix-core peak
 # HBM bytes per launch of a stage's kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the plain-copy
 # calibration (profiles/hbm_traffic_bench_1m.md); None where no counter run exists for the workload.
-MEASURED_TRAFFIC = {"1m": {"forward_transform": 2.49e9, "inverse_transform": 1.86e9, "band_attention_fused": 12.4e9}}
+MEASURED_TRAFFIC = {"1m": {"forward_transform": 2.49e9, "inverse_transform": 1.86e9, "band_attention_fused": 13.2e9}}
 
 
 def algorithmic_work(wl, ctx, alloc):
