@@ -460,3 +460,22 @@ def test_batch_of_two_on_a_side_stream():
         for b in range(2):
             for h in range(3):
                 _check(got[b, h], want[b, h], "bf16", f"path {path} batch {b} head {h} mask {alloc[h]}")
+
+
+def test_contexts_release_their_device_memory():
+    """freqattn_destroy gives back everything freqattn_create took (tables, scratch, summary weights, partial-sum
+    buffers): free device memory after twenty create/forward/destroy rounds equals what it was after the first."""
+    import torch
+    wl = WL.WORKLOADS["64k"]
+    heads = [0, 1, 2]
+    q, k, v = _inputs(wl, heads=heads)
+    dq, dk, dv = (U.to_device(x, "bf16") for x in (q, k, v))
+    out = torch.empty_like(dq)
+    free = []
+    for it in range(20):
+        ctx, _ = U.make_ctx(wl, path=B.PATH_MFMA, heads=len(heads))
+        ctx.forward(dq, dk, dv, (1, 2, 4), out)
+        torch.cuda.synchronize()
+        ctx.destroy()
+        free.append(torch.cuda.mem_get_info()[0])
+    assert free[-1] == free[0], (free[0], free[-1])
