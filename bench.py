@@ -109,8 +109,8 @@ def main():
                     help="also run one plain device copy of q (known bytes) so that a counter run can be scaled by it")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (every (batch, head) is independent; see DESIGN.md for how "
-                 "the path would shard); run with --gpus 1")
+        sys.exit("bench.py: this build runs on one GPU only (every (batch, head) is independent, so the path would shard "
+                 "by heads without any exchange); run with --gpus 1")
 
     import numpy as np
     import torch
