@@ -705,9 +705,10 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
                                         bool with_stats, bool predict = false) {
   const bool fused_stats = with_stats && c->path == FREQATTN_PATH_MFMA;
   if (fused_stats) {
-    // Router in the loop: the allocation is not known yet.  V~ is needed everywhere; Q~ and K~ are computed on the
-    // low+mid box only, which gives their low and mid statistics exactly and their high-band energy by Parseval;
-    // slices that turn out to run the high band get their Q~ and K~ completed afterwards (complete_qk_for_high).
+    // Router in the loop: the allocation is not known yet.  Q~ and K~ - and V~ where the context keeps it on the box
+    // for slices without the high band (v_box_ok; otherwise V~ is computed everywhere) - are computed on the low+mid
+    // box only, which gives their low and mid statistics exactly and their high-band energy by Parseval; slices that
+    // turn out to run the high band get them completed afterwards (complete_qk_for_high).
     // With `predict`, the slices that ran the high band under the context's last allocation (allocations move
     // slowly along a sampling trajectory) get the whole-grid transform straight away, with all three statistics
     // taken directly; whatever the router then decides, only slices that are newly high need the completion.
