@@ -176,11 +176,17 @@ def test_16k_fused_and_separate_launches_agree():
     dict(mid_block=128, mid_diag=0, mid_stride=3, mid_block0=0, high_window=100, n_summary=5, low_compress=3),
     dict(mid_block=192, mid_diag=1, mid_stride=2, high_window=0, n_summary=300),
 ])
-def test_16k_bf16_parameter_edges(band):
+@pytest.mark.parametrize("v_box", ["0", "1"])
+def test_16k_bf16_parameter_edges(band, v_box, monkeypatch):
+    """Degenerate and odd band parameters, with V~ on the whole grid and with V~ of slices without the high band on the
+    low+mid box (no summaries at all; more summary tokens than the summing kernel takes, where the library keeps the
+    whole-grid V~ by itself)."""
+    monkeypatch.setenv("FREQATTN_V_BOX", v_box)
     wl = WL.WORKLOADS["16k"]
     q, k, v = _inputs(wl, heads=[1, 4])
     ctx, bandd = U.make_ctx(wl, heads=2, **band)
     assert ctx.get_path() == B.PATH_MFMA
+    assert ctx.get_v_box() == (int(v_box) if band["n_summary"] <= 64 else 0)
     alloc = (3, 6)
     got = U.run_forward(ctx, q, k, v, wl.dtype, alloc)
     want = O.forward(q, k, v, wl.grid, U.oracle_cfg(bandd), alloc)
