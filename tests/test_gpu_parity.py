@@ -193,17 +193,20 @@ def test_16k_bf16_parameter_edges(band, v_box, monkeypatch):
     _check(got, want, "bf16", f"16k edges {band}")
 
 
-def test_mfma_ragged_grid_bf16():
-    """Grid 16x48x80 (axis lengths that are not powers of two), head_dim 128, ragged tails in every band."""
+@pytest.mark.parametrize("v_box,alloc", [("0", (7, 4)), ("1", (7, 4)), ("1", (1, 2, 3))])
+def test_mfma_ragged_grid_bf16(v_box, alloc, monkeypatch):
+    """Grid 16x48x80 (axis lengths that are not powers of two), head_dim 128, ragged tails in every band; also with V~ of
+    the heads without the high band on the low+mid box, wherever the kernels' granularity gives a smaller box."""
+    monkeypatch.setenv("FREQATTN_V_BOX", v_box)
     grid, d = (16, 48, 80), 128
     rng = np.random.default_rng(5)
     N = int(np.prod(grid))
-    q, k, v = (WL.round_to_io(0.3 * rng.standard_normal((1, 2, N, d)), "bf16") for _ in range(3))
+    q, k, v = (WL.round_to_io(0.3 * rng.standard_normal((1, len(alloc), N, d)), "bf16") for _ in range(3))
     band = dict(WL.WORKLOADS["16k"].band)
     band.update(mid_block=128, mid_diag=1, mid_stride=5, high_window=200, n_summary=7, low_compress=4)
-    ctx = B.Context(1, 2, d, grid, B.BF16, B.make_cfg(**band))
+    ctx = B.Context(1, len(alloc), d, grid, B.BF16, B.make_cfg(**band))
     assert ctx.get_path() == B.PATH_MFMA
-    alloc = (7, 4)
+    print(f"ragged grid: V on the box = {ctx.get_v_box()}", flush=True)
     got = U.run_forward(ctx, q, k, v, "bf16", alloc)
     want = O.forward(q, k, v, grid, O.BandConfig(**band), alloc)
     _check(got, want, "bf16", "ragged 16x48x80")
