@@ -393,7 +393,8 @@ def band_statistics(q, k, v, grid, cfg: BandConfig) -> np.ndarray:
     Reading: for band l and channel group r (d_k / d_r adjacent channels), the mean over batch,
     heads, the band's coefficients and the three tensors Q~, K~, V~ of the squared coefficient,
     then log(eps + .), centred by the mean of the 3 d_r values so that only the relative spectral shape
-    reaches the router (a common gain on Q, K, V changes nothing).  parity unpinned (reading)."""
+    reaches the router (a common gain on Q, K, V changes nothing).  The arithmetic is pinned by a per-coefficient
+    loop over a library transform; the reading itself is one no printed value confirms."""
     T, H, W = grid
     Bsz, nh, N, d = q.shape
     assert d % ROUTER_DR == 0
@@ -431,6 +432,15 @@ def router_probabilities(g, t: float, w1, b1, w2, b2) -> np.ndarray:
     z = z - z.max()
     e = np.exp(z)
     return e / e.sum()
+
+
+def load_balance_loss(pi_heads, lam: float) -> float:
+    """Load-balancing term of section 3.5: lambda * sum over bands of (mean over heads of pi[h, l] - 1/3)^2.
+    pi_heads is [n_h, 3]; a router with one distribution for all heads passes it n_h times, a hard allocation its
+    one-hot rows."""
+    p = np.asarray(pi_heads, dtype=np.float64)
+    assert p.ndim == 2 and p.shape[1] == 3
+    return float(lam * ((p.mean(axis=0) - 1.0 / 3.0) ** 2).sum())
 
 
 def apportion_heads(pi, n_heads: int) -> np.ndarray:
