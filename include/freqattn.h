@@ -18,10 +18,8 @@
  * Environment switches (diagnostics and A/B runs; results agree within rounding either way):
  *   FREQATTN_V_BOX=0|1     read at freqattn_create: never / always compute V~ of slices without the high band on the
  *                          low+mid box only (default: from 64K tokens on; see freqattn_get_v_box)
- *   FREQATTN_ATTN_DMA=0    read at the first attention launch of the process: stage attention tiles through
- *                          registers instead of copying them straight into LDS
- *   FREQATTN_DENSE_BF16_DIRECT=1  freqattn_dense_forward reads the bf16 tensors in the kernel (register staging)
- *                          instead of converting them to fp16 scratch first
+ *   FREQATTN_DCT_OCC=n     read at the first transform launch of each pass shape: resident workgroups per compute unit
+ *                          of the transform passes (default: what 160 KB of LDS allow, at most 4)
  */
 #ifndef FREQATTN_H
 #define FREQATTN_H
@@ -39,7 +37,8 @@ typedef enum {
   FREQATTN_EINVAL = 1,       /* bad argument; nothing was launched */
   FREQATTN_ENOMEM = 2,       /* host or device allocation failed in freqattn_create */
   FREQATTN_EHIP = 3,         /* a HIP runtime call failed */
-  FREQATTN_EUNSUPPORTED = 4  /* valid request that this build has no kernel for */
+  FREQATTN_EUNSUPPORTED = 4, /* valid request that this build has no kernel for */
+  FREQATTN_ERANGE = 5        /* non-finite values met: inputs outside the range contract of freqattn_forward */
 } freqattn_status;
 
 typedef enum { FREQATTN_F32 = 0, FREQATTN_BF16 = 1 } freqattn_dtype;

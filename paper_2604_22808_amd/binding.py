@@ -13,7 +13,7 @@ import numpy as np
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libfreqattn.so")
 
-OK, EINVAL, ENOMEM, EHIP, EUNSUPPORTED = 0, 1, 2, 3, 4
+OK, EINVAL, ENOMEM, EHIP, EUNSUPPORTED, ERANGE = 0, 1, 2, 3, 4, 5
 F32, BF16 = 0, 1
 LAUNCH_FUSED, LAUNCH_SEPARATE = 0, 1
 PATH_AUTO, PATH_GENERIC, PATH_MFMA, PATH_TABLES_ONLY = 0, 1, 2, 3
@@ -133,18 +133,48 @@ class Context:
         except Exception:
             pass
 
+    def _check_tensors(self, who, **tensors):
+        """The library sees raw addresses only: a tensor on the host, of another type, shape or layout would make its
+        kernels read or write out of bounds, so every device tensor is checked here before its pointer is taken."""
+        import torch
+        s = self.shape
+        want_shape = (s.batch, s.heads, s.T * s.H * s.W, s.head_dim)
+        want_dtype = torch.bfloat16 if s.dtype == BF16 else torch.float32
+        for name, t in tensors.items():
+            if not isinstance(t, torch.Tensor):
+                raise TypeError(f"{who}: {name} must be a torch tensor")
+            if not t.is_cuda:
+                raise ValueError(f"{who}: {name} must be a device tensor")
+            if t.dtype != want_dtype:
+                raise ValueError(f"{who}: {name} has dtype {t.dtype}, the context was created for {want_dtype}")
+            if tuple(t.shape) != want_shape:
+                raise ValueError(f"{who}: {name} has shape {tuple(t.shape)}, expected {want_shape}")
+            if not t.is_contiguous():
+                raise ValueError(f"{who}: {name} must be contiguous")
+
     # ---- hot path
     def forward(self, q, k, v, head_alloc, out, cfg=None):
+        self._check_tensors("forward", q=q, k=k, v=v, out=out)
         ha = np.ascontiguousarray(head_alloc, dtype=np.int32)
+        if ha.shape != (self.shape.heads,):
+            raise ValueError(f"forward: head_alloc must hold {self.shape.heads} entries, got shape {ha.shape}")
         cfg = cfg or self.cfg
         self._check(lib().freqattn_forward(self._h, _ptr(q), _ptr(k), _ptr(v), C.byref(cfg),
                                            ha.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(out), _stream()))
         return out
 
-    def forward_routed(self, q, k, v, t, w1, b1, w2, b2, out, cfg=None):
-        hidden = int(w1.shape[1])
+    @staticmethod
+    def _router_weights(who, w1, b1, w2, b2):
         f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
         w1, b1, w2, b2 = f(w1), f(b1), f(w2), f(b2)
+        hidden = int(w1.shape[1]) if w1.ndim == 2 else -1
+        if w1.shape != (256, hidden) or b1.shape != (hidden,) or w2.shape != (hidden, 3) or b2.shape != (3,) or hidden < 1:
+            raise ValueError(f"{who}: router weights must be w1 [256, hidden], b1 [hidden], w2 [hidden, 3], b2 [3]")
+        return hidden, w1, b1, w2, b2
+
+    def forward_routed(self, q, k, v, t, w1, b1, w2, b2, out, cfg=None):
+        self._check_tensors("forward_routed", q=q, k=k, v=v, out=out)
+        hidden, w1, b1, w2, b2 = self._router_weights("forward_routed", w1, b1, w2, b2)
         alloc = np.zeros(self.shape.heads, np.int32)
         pi = np.zeros(3, np.float32)
         P = lambda a: a.ctypes.data_as(C.POINTER(C.c_float))
@@ -155,13 +185,13 @@ class Context:
         return alloc, pi
 
     def dense_forward(self, q, k, v, out):
+        self._check_tensors("dense_forward", q=q, k=k, v=v, out=out)
         self._check(lib().freqattn_dense_forward(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _stream()))
         return out
 
     def route_mlp(self, q, k, v, t, w1, b1, w2, b2):
-        hidden = int(w1.shape[1])
-        f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
-        w1, b1, w2, b2 = f(w1), f(b1), f(w2), f(b2)
+        self._check_tensors("route_mlp", q=q, k=k, v=v)
+        hidden, w1, b1, w2, b2 = self._router_weights("route_mlp", w1, b1, w2, b2)
         alloc = np.zeros(self.shape.heads, np.int32)
         pi = np.zeros(3, np.float32)
         stats = np.zeros(192, np.float32)

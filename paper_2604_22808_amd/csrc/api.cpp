@@ -26,6 +26,18 @@ static freqattn_status fail(freqattn_ctx* c, freqattn_status s, const std::strin
       return fail(ctx, FREQATTN_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__));        \
   } while (0)
 
+// No exception may cross the C boundary: entry points whose bodies can allocate on the host run inside this.
+template <class F>
+static freqattn_status guarded(freqattn_ctx* c, const char* who, F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return fail(c, FREQATTN_ENOMEM, std::string(who) + ": host allocation failed");
+  } catch (...) {
+    return fail(c, FREQATTN_EHIP, std::string(who) + ": unexpected exception");
+  }
+}
+
 static size_t esize(const Ctx& c) { return c.path == FREQATTN_PATH_MFMA ? sizeof(half_t) : sizeof(float); }
 static int io_kind(const Ctx& c) { return c.shape.dtype == FREQATTN_BF16 ? 1 : 0; }
 
@@ -281,10 +293,12 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
     c->off_nonhigh = ints; ints += (size_t)c->slices;
     c->off_fix = ints; ints += (size_t)c->slices;
     ints = (ints + 3) & ~(size_t)3;
-    c->off_items = ints; ints += 4 * per_slice * c->slices;
-    for (int l = 0; l < 3; ++l) { c->off_items_kind[l] = ints; ints += 4 * per_slice * c->slices; }
-    c->off_items_xchg = ints; ints += 4 * xchg_per_slice * c->slices;
-    c->off_items_dense = ints; ints += 4 * xchg_per_slice * c->slices;
+    c->cap_items_kind = mf ? per_slice * c->slices : 0;      // the generic kernels read no item lists
+    c->cap_items_xchg = mf ? xchg_per_slice * c->slices : 0;
+    c->off_items = ints; ints += 4 * c->cap_items_kind;
+    for (int l = 0; l < 3; ++l) { c->off_items_kind[l] = ints; ints += 4 * c->cap_items_kind; }
+    c->off_items_xchg = ints; ints += 4 * c->cap_items_xchg;
+    c->off_items_dense = ints; ints += 4 * c->cap_items_xchg;
     c->lists_bytes = ints * 4;
     A(dev_alloc_bytes(*c, (void**)&c->d_lists, c->lists_bytes));
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_lists, c->lists_bytes, hipHostMallocDefault);
@@ -431,7 +445,10 @@ static bool same_cfg(const freqattn_band_cfg& a, const freqattn_band_cfg& b) {
          a.high_window == b.high_window && a.n_summary == b.n_summary && a.transform == b.transform;
 }
 
-static void build_lists(Ctx& c, const int32_t* head_alloc) {
+// Fills the pinned host mirror of the per-forward lists.  The item lists are only read by the MFMA attention kernel;
+// the generic path gets the slice lists alone.  Nothing here allocates; every item region is written through a
+// capacity check, and the function returns false (lists unusable) if a region would overflow.
+static bool build_lists(Ctx& c, const int32_t* head_alloc) {
   int32_t* L = c.h_lists;
   const int heads = c.shape.heads;
   for (int l = 0; l < 3; ++l) c.n_list[l] = 0;
@@ -449,15 +466,27 @@ static void build_lists(Ctx& c, const int32_t* head_alloc) {
     for (int l = 0; l < 3; ++l)
       if (((mask >> l) & 1) && c.band_n[l] > 0) L[c.off_list[l] + c.n_list[l]++] = s;
   }
+  c.n_items_branch = 0;
+  for (int k = 0; k < 3; ++k) c.n_items_kind[k] = 0;
+  c.n_items_xchg = 0;
+  c.n_items_dense = 0;
+  if (c.path != FREQATTN_PATH_MFMA) return true;
+
   const int rows = c.attn_rows;
   const int KT = 64;  // key tile of the MFMA attention kernel
-  std::vector<AttnItem> kind[3], xchg;
+  bool ok = true;
+  auto push = [&](size_t off, int& n, size_t cap, AttnItem it) {
+    if ((size_t)n >= cap) { ok = false; return; }
+    std::memcpy(L + off + (size_t)4 * n, &it, sizeof(AttnItem));
+    ++n;
+  };
   auto cd = [](int64_t a, int64_t b) { return (a + b - 1) / b; };
+  const size_t cap_kind = c.cap_items_kind, cap_x = c.cap_items_xchg;
   for (int s = 0; s < c.slices; ++s) {
     const int mask = L[c.off_masks + s];
     if ((mask & 1) && c.band_n[LOW] > 0)
       for (int64_t q0 = 0; q0 < c.nbar; q0 += rows)
-        kind[0].push_back({0 | (LOW << 8), s, (int32_t)q0, (int32_t)cd(c.nbar, KT)});
+        push(c.off_items_kind[0], c.n_items_kind[0], cap_kind, {0 | (LOW << 8), s, (int32_t)q0, (int32_t)cd(c.nbar, KT)});
     if ((mask & 2) && c.band_n[MID] > 0) {
       // Query blocks I with the same I mod stride share all their strided key blocks (J = I mod stride): they are listed
       // together, so that workgroups running at the same time fetch those K/V tiles into their L2 once.
@@ -470,48 +499,45 @@ static void build_lists(Ctx& c, const int32_t* head_alloc) {
             const int64_t q0 = I * c.cfg.mid_block + u * rows;
             if (q0 >= c.band_n[MID]) break;
             const int nblk = c.h_row_ptr[I + 1] - c.h_row_ptr[I];
-            kind[1].push_back({1 | (MID << 8), s, (int32_t)q0, (int32_t)(nblk * cd(c.cfg.mid_block, KT))});
+            push(c.off_items_kind[1], c.n_items_kind[1], cap_kind, {1 | (MID << 8), s, (int32_t)q0, (int32_t)(nblk * cd(c.cfg.mid_block, KT))});
           }
     }
     if ((mask & 4) && c.band_n[HIGH] > 0)
       for (int64_t q0 = 0; q0 < c.band_n[HIGH]; q0 += rows) {
         const int64_t k0 = std::max<int64_t>(0, q0 - c.cfg.high_window);
         const int64_t k1 = std::min<int64_t>(c.band_n[HIGH] - 1, q0 + rows - 1 + (int64_t)c.cfg.high_window);
-        kind[2].push_back({2 | (HIGH << 8), s, (int32_t)q0, (int32_t)(k1 / KT - k0 / KT + 1)});
+        push(c.off_items_kind[2], c.n_items_kind[2], cap_kind, {2 | (HIGH << 8), s, (int32_t)q0, (int32_t)(k1 / KT - k0 / KT + 1)});
       }
     if (c.cfg.n_summary > 0)
       for (int l = 0; l < 3; ++l)
         if (((mask >> l) & 1) && c.band_n[l] > 0 && c.n_c[l] > 0)
           for (int64_t q0 = 0; q0 < c.band_n[l]; q0 += rows)
-            xchg.push_back({3 | (l << 8), s, (int32_t)q0, (int32_t)cd(c.n_c[l], KT)});
+            push(c.off_items_xchg, c.n_items_xchg, cap_x, {3 | (l << 8), s, (int32_t)q0, (int32_t)cd(c.n_c[l], KT)});
   }
   // One list for the fused launch: the branches one after the other (long low and mid items first, the many short
   // window items last, which keeps the tail of the launch short), inside a branch by slice and query tile, so that
   // workgroups running at the same time work on neighbouring query tiles and share their K/V tiles in the L2.  (Sorting
   // the whole list by cost scatters the mid band's query tiles and measured 3 % slower.)
-  std::vector<AttnItem> fused;
-  for (int k = 0; k < 3; ++k) fused.insert(fused.end(), kind[k].begin(), kind[k].end());
-  c.n_items_branch = (int)fused.size();
-  if (!fused.empty()) std::memcpy(L + c.off_items, fused.data(), fused.size() * sizeof(AttnItem));
   for (int k = 0; k < 3; ++k) {
-    c.n_items_kind[k] = (int)kind[k].size();
-    if (!kind[k].empty()) std::memcpy(L + c.off_items_kind[k], kind[k].data(), kind[k].size() * sizeof(AttnItem));
+    if ((size_t)(c.n_items_branch + c.n_items_kind[k]) > cap_kind) { ok = false; break; }
+    if (c.n_items_kind[k] > 0)
+      std::memcpy(L + c.off_items + (size_t)4 * c.n_items_branch, L + c.off_items_kind[k], (size_t)c.n_items_kind[k] * sizeof(AttnItem));
+    c.n_items_branch += c.n_items_kind[k];
   }
-  c.n_items_xchg = (int)xchg.size();
-  if (!xchg.empty()) std::memcpy(L + c.off_items_xchg, xchg.data(), xchg.size() * sizeof(AttnItem));
   // dense baseline items (do not depend on the allocation)
-  std::vector<AttnItem> dense;
   for (int s = 0; s < c.slices; ++s)
-    for (int64_t q0 = 0; q0 < c.N; q0 += rows) dense.push_back({4, s, (int32_t)q0, (int32_t)cd(c.N, KT)});
-  c.n_items_dense = (int)dense.size();
-  if (!dense.empty()) std::memcpy(L + c.off_items_dense, dense.data(), dense.size() * sizeof(AttnItem));
+    for (int64_t q0 = 0; q0 < c.N; q0 += rows) push(c.off_items_dense, c.n_items_dense, cap_x, {4, s, (int32_t)q0, (int32_t)cd(c.N, KT)});
+  return ok;
 }
 
 static freqattn_status ensure_lists(freqattn_ctx* c, const int32_t* head_alloc, hipStream_t st) {
   const int heads = c->shape.heads;
   if (c->alloc_valid && std::memcmp(c->h_alloc.data(), head_alloc, heads * sizeof(int32_t)) == 0) return FREQATTN_OK;
   HIP_TRY(c, hipStreamSynchronize(st));  // earlier forwards may still read the lists
-  build_lists(*c, head_alloc);
+  if (!build_lists(*c, head_alloc)) {
+    c->alloc_valid = false;
+    return fail(c, FREQATTN_EINVAL, "work lists: item count exceeds the capacity sized at freqattn_create");
+  }
   // upload what the new allocation uses: the slice lists, the used part of each item list, and the dense comparison's
   // list (independent of the allocation) the first time only
   auto up = [&](size_t off_ints, size_t n_ints) -> hipError_t {
@@ -702,7 +728,7 @@ struct StageTimer {
 // sections 3.2 / 3.3: spectral transform of Q, K, V into band-major buffers; with_stats also leaves the router's
 // band statistics (section 3.5) in d_stats.
 static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const void* k, const void* v, hipStream_t st,
-                                        bool with_stats, bool predict = false) {
+                                        bool with_stats, bool predict = false, bool whole_grid = false) {
   const bool fused_stats = with_stats && c->path == FREQATTN_PATH_MFMA;
   if (fused_stats) {
     // Router in the loop: the allocation is not known yet.  Q~ and K~ - and V~ where the context keeps it on the box
@@ -716,6 +742,7 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
     int mid[3];
     bool pruned = false;
     for (int a = 0; a < 3; ++a) { mid[a] = keep_rows(c->mid_box[a], full[a]); pruned = pruned || mid[a] < full[a]; }
+    if (whole_grid) pruned = false;   // every statistic taken directly from whole-grid transforms
     c->energy_waves = 0; c->tot_waves = 0; c->qk_on_mid_box = pruned;
     c->qk_full.assign((size_t)c->slices, pruned ? 0 : 1);
     // statistics slots: 0..2 = Q, K, V on the box (high band by Parseval when pruned), 3..5 = the same on the whole grid
@@ -929,6 +956,7 @@ static freqattn_status check_forward_args(freqattn_ctx* c, const void* q, const 
 extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, const void* k, const void* v,
                                             const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,
                                             void* stream) {
+  return guarded(c, "freqattn_forward", [&]() -> freqattn_status {
   if (!c) return FREQATTN_EINVAL;
   if (!head_alloc) return fail(c, FREQATTN_EINVAL, "freqattn_forward: NULL argument");
   freqattn_status fs = check_forward_args(c, q, k, v, band_cfg, out, "freqattn_forward");
@@ -944,16 +972,18 @@ extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, cons
   if (fs != FREQATTN_OK) return fs;
   tm.done("forward_transform");
   return bands_phase(c, scale, v, out, st, tm);
+  });
 }
 
 static freqattn_status router_from_spectral(freqattn_ctx* c, float t, int32_t hidden, const float* w1, const float* b1,
                                             const float* w2, const float* b2, int32_t* head_alloc, float pi[3],
-                                            float* stats_out, hipStream_t st);
+                                            float* stats_out, hipStream_t st, bool* high_unreliable = nullptr);
 
 extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* q, const void* k, const void* v,
                                                    const freqattn_band_cfg* band_cfg, float t, int32_t hidden,
                                                    const float* w1, const float* b1, const float* w2, const float* b2,
                                                    void* out, int32_t* head_alloc_out, float pi_out[3], void* stream) {
+  return guarded(c, "freqattn_forward_routed", [&]() -> freqattn_status {
   if (!c) return FREQATTN_EINVAL;
   if (!w1 || !b1 || !w2 || !b2 || !head_alloc_out || !pi_out || hidden < 1)
     return fail(c, FREQATTN_EINVAL, "freqattn_forward_routed: NULL argument or hidden < 1");
@@ -966,8 +996,16 @@ extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* 
   fs = transforms_phase(c, q, k, v, st, true, c->predict_alloc != 0);
   if (fs != FREQATTN_OK) return fs;
   tm.done("forward_transform");
-  fs = router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc_out, pi_out, nullptr, st);
+  bool redo = false;
+  fs = router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc_out, pi_out, nullptr, st, &redo);
   if (fs != FREQATTN_OK) return fs;
+  if (redo) {
+    // the high band holds too little energy for the difference form: whole-grid transforms with direct statistics
+    fs = transforms_phase(c, q, k, v, st, true, false, true);
+    if (fs != FREQATTN_OK) return fs;
+    fs = router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc_out, pi_out, nullptr, st);
+    if (fs != FREQATTN_OK) return fs;
+  }
   fs = ensure_lists(c, head_alloc_out, st);
   if (fs != FREQATTN_OK) return fs;
   tm.done("router");
@@ -975,17 +1013,19 @@ extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* 
   if (fs != FREQATTN_OK) return fs;
   tm.done("forward_transform_high_qk");
   return bands_phase(c, scale, v, out, st, tm);
+  });
 }
 
 
 extern "C" freqattn_status freqattn_dense_forward(freqattn_ctx* c, const void* q, const void* k, const void* v, void* out,
                                                   void* stream) {
+  return guarded(c, "freqattn_dense_forward", [&]() -> freqattn_status {
   if (!c) return FREQATTN_EINVAL;
   if (!q || !k || !v || !out) return fail(c, FREQATTN_EINVAL, "freqattn_dense_forward: NULL argument");
   if (c->path != FREQATTN_PATH_MFMA) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_dense_forward: MFMA path only");
   hipStream_t st = (hipStream_t)stream;
-  if (!c->alloc_valid) {
-    std::vector<int32_t> zero(c->shape.heads, 0);
+  if (!c->alloc_valid) {   // the dense item list is uploaded with the first allocation's lists
+    std::vector<int32_t> zero((size_t)c->shape.heads, 0);
     freqattn_status fs = ensure_lists(c, zero.data(), st);
     if (fs != FREQATTN_OK) return fs;
   }
@@ -993,29 +1033,24 @@ extern "C" freqattn_status freqattn_dense_forward(freqattn_ctx* c, const void* q
   const float scale = c->cfg.softmax_scale > 0.f ? c->cfg.softmax_scale : 1.0f / std::sqrt((float)c->d);
   fill_attn_params(*c, ap, scale);
   StageTimer tm(*c, st);
-  // The attention kernel is fastest on fp16 tensors (tiles copied straight into LDS): the bf16 inputs are converted
-  // into the context's spectral scratch first, and the fp16 result back into the caller's bf16 tensor - two
-  // element-wise passes beside an N^2 kernel.  (FREQATTN_DENSE_BF16_DIRECT=1: the kernel converts on the fly.)
-  static int direct = -1;
-  if (direct < 0) { const char* e = getenv("FREQATTN_DENSE_BF16_DIRECT"); direct = e ? atoi(e) : 0; }
-  const int64_t n_el = (int64_t)c->slices * c->N * c->d;
-  if (!direct && n_el % 8 == 0) {
-    HIP_TRY(c, launch_convert_16(q, c->specQ, n_el, 0, st));
-    HIP_TRY(c, launch_convert_16(k, c->specK, n_el, 0, st));
-    HIP_TRY(c, launch_convert_16(v, c->specV, n_el, 0, st));
-    ap.denseQ = c->specQ; ap.denseK = c->specK; ap.denseV = c->specV; ap.denseO = c->Y; ap.dense_bf16 = 0;
-    HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(c->d_lists + c->off_items_dense), c->n_items_dense, c->attn_rows, c->num_cu, st));
-    HIP_TRY(c, launch_convert_16(c->Y, out, n_el, 1, st));
-  } else {
-    ap.denseQ = q; ap.denseK = k; ap.denseV = v; ap.denseO = out; ap.dense_bf16 = 1;
-    HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(c->d_lists + c->off_items_dense), c->n_items_dense, c->attn_rows, c->num_cu, st));
-  }
+  // The attention kernel reads fp16 tensors (tiles copied straight into LDS): the bf16 inputs are converted into the
+  // context's spectral scratch first, and the fp16 result back into the caller's bf16 tensor - two element-wise
+  // passes beside an N^2 kernel.
+  const int64_t n_el = (int64_t)c->slices * c->N * c->d;   // a multiple of 64 on this path
+  HIP_TRY(c, launch_convert_16(q, c->specQ, n_el, 0, st));
+  HIP_TRY(c, launch_convert_16(k, c->specK, n_el, 0, st));
+  HIP_TRY(c, launch_convert_16(v, c->specV, n_el, 0, st));
+  ap.denseQ = c->specQ; ap.denseK = c->specK; ap.denseV = c->specV; ap.denseO = c->Y;
+  HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(c->d_lists + c->off_items_dense), c->n_items_dense, c->attn_rows, c->num_cu, st));
+  HIP_TRY(c, launch_convert_16(c->Y, out, n_el, 1, st));
   tm.done("dense_attention");
   return FREQATTN_OK;
+  });
 }
 
 extern "C" freqattn_status freqattn_read_spectral(freqattn_ctx* c, int32_t which, int32_t slice, int32_t band,
                                                   float* host_out, void* stream) {
+  return guarded(c, "freqattn_read_spectral", [&]() -> freqattn_status {
   if (!c || !host_out || which < 0 || which > 3 || slice < 0 || slice >= c->slices || band < 0 || band > 2)
     return FREQATTN_EINVAL;
   if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_read_spectral: tables-only context");
@@ -1039,15 +1074,30 @@ extern "C" freqattn_status freqattn_read_spectral(freqattn_ctx* c, int32_t which
     HIP_TRY(c, hipMemcpy(host_out, (const float*)src + off, cnt * sizeof(float), hipMemcpyDeviceToHost));
   }
   return FREQATTN_OK;
+  });
 }
 
 // ------------------------------------------------------------------------------------------------ router
 static freqattn_status router_from_spectral(freqattn_ctx* c, float t, int32_t hidden, const float* w1, const float* b1,
                                             const float* w2, const float* b2, int32_t* head_alloc, float pi[3],
-                                            float* stats_out, hipStream_t st) {
+                                            float* stats_out, hipStream_t st, bool* high_unreliable) {
   const int d = c->d, DR = 64, DT = 64;
   HIP_TRY(c, hipMemcpyAsync(c->h_stats, c->d_stats, 3 * d * sizeof(float), hipMemcpyDeviceToHost, st));
   HIP_TRY(c, hipStreamSynchronize(st));
+  for (int i = 0; i < 3 * d; ++i)
+    if (!std::isfinite(c->h_stats[i]))
+      return fail(c, FREQATTN_ERANGE, "router statistics are not finite: the inputs leave the fp16 range of the spectral "
+                                      "buffers (sqrt(N) * max|x| must stay below 65504) or are not finite themselves");
+  if (high_unreliable) {
+    // High-band energy taken as total minus low minus mid (section 5: the transform is orthonormal) inherits the
+    // rounding of the fp16 transform, about 1e-4 of the total; below 1 % of a channel's total it is not trusted.
+    *high_unreliable = false;
+    if (c->path == FREQATTN_PATH_MFMA && c->qk_on_mid_box)
+      for (int ch = 0; ch < d; ++ch) {
+        const double tot = (double)c->h_stats[ch] + c->h_stats[d + ch] + c->h_stats[2 * d + ch];
+        if ((double)c->h_stats[2 * d + ch] < 0.01 * tot) *high_unreliable = true;
+      }
+  }
   // g: log(eps + mean energy) per band and channel group, centred (section 3.5 "pooled statistics")
   double x[3 * 64 + 64];
   const int per = d / DR;
@@ -1089,6 +1139,8 @@ static freqattn_status router_from_spectral(freqattn_ctx* c, float t, int32_t hi
   double p[3], ps = 0;
   for (int o = 0; o < 3; ++o) { p[o] = std::exp(z[o] - zm); ps += p[o]; }
   for (int o = 0; o < 3; ++o) { p[o] /= ps; pi[o] = (float)p[o]; }
+  if (!(std::isfinite(p[0]) && std::isfinite(p[1]) && std::isfinite(p[2])))
+    return fail(c, FREQATTN_ERANGE, "router: allocation probabilities are not finite (non-finite router weights?)");
   // apportionment: one head per band when heads >= 3, the rest by largest remainder, ties to the lower band
   const int heads = c->shape.heads;
   const int base = heads >= 3 ? 1 : 0;
@@ -1115,6 +1167,7 @@ extern "C" freqattn_status freqattn_route_mlp(freqattn_ctx* c, const void* q, co
                                               int32_t hidden, const float* w1, const float* b1, const float* w2,
                                               const float* b2, int32_t* head_alloc, float pi[3], float* stats_out,
                                               void* stream) {
+  return guarded(c, "freqattn_route_mlp", [&]() -> freqattn_status {
   if (!c) return FREQATTN_EINVAL;
   if (!q || !k || !v || !w1 || !b1 || !w2 || !b2 || !head_alloc || !pi || hidden < 1)
     return fail(c, FREQATTN_EINVAL, "freqattn_route_mlp: NULL argument or hidden < 1");
@@ -1123,7 +1176,13 @@ extern "C" freqattn_status freqattn_route_mlp(freqattn_ctx* c, const void* q, co
   hipStream_t st = (hipStream_t)stream;
   freqattn_status fs = transforms_phase(c, q, k, v, st, true);
   if (fs != FREQATTN_OK) return fs;
+  bool redo = false;
+  fs = router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc, pi, stats_out, st, &redo);
+  if (fs != FREQATTN_OK || !redo) return fs;
+  fs = transforms_phase(c, q, k, v, st, true, false, true);
+  if (fs != FREQATTN_OK) return fs;
   return router_from_spectral(c, t, hidden, w1, b1, w2, b2, head_alloc, pi, stats_out, st);
+  });
 }
 
 // ------------------------------------------------------------------------------------------------ stage timing

@@ -42,8 +42,7 @@ struct AttnParams {
   int32_t mid_block, high_window;
   float scale;
   // dense baseline
-  const void* denseQ; const void* denseK; const void* denseV; void* denseO;
-  int32_t dense_bf16;
+  const void* denseQ; const void* denseK; const void* denseV; void* denseO;   // fp16
 };
 
 struct Ctx {
@@ -118,6 +117,7 @@ struct Ctx {
   size_t off_items_kind[3] = {0, 0, 0};
   size_t off_items_xchg = 0; int n_items_xchg = 0;
   size_t off_items_dense = 0; int n_items_dense = 0;
+  size_t cap_items_kind = 0, cap_items_xchg = 0;   // AttnItem capacity of each branch / fused region and of the exchange / dense regions
   int attn_rows = 0;                  // query rows per attention item on the MFMA path
   int num_cu = 256;
 

@@ -562,7 +562,9 @@ __global__ void __launch_bounds__(256) k_energy_reduce(const float* part, const 
     if (tid < sft) red[tid] += red[tid + sft];
     __syncthreads();
   }
-  if (tid == 0) stats[idx] = red[0];
+  // The Parseval difference of a band that holds (almost) no energy can come out slightly negative (the low and mid
+  // sums carry the rounding of the fp16 transform): an energy is never below zero.
+  if (tid == 0) stats[idx] = (parseval && red[0] < 0.f) ? 0.f : red[0];   // (a NaN stays a NaN: the host reports it)
 }
 
 hipError_t launch_energy_reduce(const float* energy_part, const float* tot_part, float* stats, int d, int n_waves,

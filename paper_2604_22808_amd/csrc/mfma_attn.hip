@@ -16,11 +16,8 @@
 //   softmax  -> running max / sum per lane (one query per lane; the two lane halves hold different keys)
 //   V tile   -> V^T operand (A) in the key order of the S^T accumulator, so that the accumulator registers,
 //               converted to fp16, are the B operand of O^T += V^T P^T directly.
-// Two ways of staging the tiles (template flag DMA):
-//   DMA      K and V rows copied straight from global memory into LDS, row-major; V^T comes out of transposing
-//            LDS reads.  Every fp16 tensor of the path takes this road.
-//   register loads a tile ahead into registers, conversion, V transposed by byte permutes on its way into LDS.
-//            The bf16 dense comparison, whose operands need converting, takes this one.
+// Staging: K and V rows are copied straight from global memory into LDS, row-major; V^T comes out of transposing LDS
+// reads.  All tensors are fp16 (the dense comparison converts its bf16 tensors into fp16 scratch first).
 #include <hip/hip_runtime.h>
 
 #include "ctx.h"
@@ -37,22 +34,6 @@ typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
 
 #define KT 64  // keys per tile
 
-__device__ __forceinline__ uint16_t at_f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ uint4v at_bf16x8_to_f16x8(uint4v v) {
-  uint4v r;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const _Float16 hl = (_Float16)__uint_as_float(v[i] << 16);
-    const _Float16 hh = (_Float16)__uint_as_float(v[i] & 0xffff0000u);
-    r[i] = (uint32_t)__builtin_bit_cast(uint16_t, hl) | ((uint32_t)__builtin_bit_cast(uint16_t, hh) << 16);
-  }
-  return r;
-}
 __device__ __forceinline__ uint32_t pack_h2(float a, float b) {
   const _Float16 ha = (_Float16)a, hb = (_Float16)b;
   return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
@@ -68,25 +49,20 @@ __device__ __forceinline__ void lds_dma16(const void* src, const half_t* dst) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory", "m0");
 }
 
-template <int D, int NW, int QT, bool BF16IN, bool DMA>
-__global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2 : 1) k_attn(AttnParams p, const AttnItem* __restrict__ items, int n_items) {
-  constexpr int KS = D + 8;     // row stride of the K tile in LDS (halfs): rows shift by 16 bytes against the banks
-  constexpr int VS = KT + 8;    // row stride of the transposed V tile (halfs)
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(AttnParams p, const AttnItem* __restrict__ items, int n_items) {
   constexpr int DT = D / 32;    // 32-channel tiles of the output
   constexpr int DK = D / 16;    // MFMA steps over the channels for S
   constexpr int NT = 64 * NW;
-  constexpr int ROWS = 32 * QT * NW;  // query rows per item
-  constexpr int WROWS = 32 * QT;      // query rows per wave
-  constexpr bool QLDS = QT > 1;  // with two query tiles per wave the Q operands live in (wave-private) LDS, not registers
-  // two copies of the K / V^T tiles: tile i+1 is written while tile i is still being read, one barrier per tile
-  __shared__ __attribute__((aligned(16))) half_t Ks2[2][KT * KS];
-  __shared__ __attribute__((aligned(16))) half_t Vt2[2][D * VS];
-  __shared__ __attribute__((aligned(16))) half_t Qs[QLDS ? ROWS * KS : 8];
+  constexpr int ROWS = 32 * NW;  // query rows per item
+  constexpr int WROWS = 32;      // query rows per wave
+  // two copies of the K / V tiles: tile i+1 is written while tile i is still being read, one barrier per tile
+  __shared__ __attribute__((aligned(16))) half_t Ks2[2][KT * D];
+  __shared__ __attribute__((aligned(16))) half_t Vt2[2][KT * D];
 
-  static_assert(!(DMA && BF16IN), "direct-to-LDS staging cannot convert the element type");
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nn = lane & 31, g = lane >> 5;
-  // Direct-to-LDS staging (DMA): K and V tiles are row-major in LDS, rows of D halfs without padding, loaded by
+  // K and V tiles are row-major in LDS, rows of D halfs without padding, loaded by
   // global_load_lds_dwordx4 (lane l of a wave instruction fills bytes 16 l .. 16 l + 15 behind a wave-uniform LDS base,
   // whatever global address the lane names).  Bank conflicts are avoided by permuting the 16-byte chunks inside a row
   // through the global address: chunk c of row r sits at position c ^ fK(r) (K, read as 16-byte A operands by 16
@@ -98,9 +74,9 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
   // per-lane parts of the operand addresses of the DMA layout (halfs), fixed for the whole kernel:
   //   K operand (t2, ks):  Ks + t2*32*D + koff_row + kx[ks]         row nn, chunk (2 ks + g) ^ fK(nn)
   //   V operand (dt, ts, h): Vt + (16 ts + 8 h)*D + voff_row + vx[dt]  row 4 g + sl/4 (+ 16 ts + 8 h), chunk (4 dt + 2 g1 + (sl & 3)/2) ^ fV(row)
-  int kx[DMA ? D / 16 : 1], vx[DMA ? D / 32 : 1];
-  int koff_row = 0, voff_row = 0;
-  if (DMA) {
+  int kx[D / 16], vx[D / 32];
+  int koff_row, voff_row;
+  {
     const int sl = lane & 15, g1 = (lane >> 4) & 1;
     koff_row = nn * D;
     voff_row = (4 * g + (sl >> 2)) * D + (sl & 1) * 4;
@@ -129,7 +105,6 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
     const uint16_t *Qp, *Kp, *Vp;
     uint16_t* Op;
     int nq, nk;
-    constexpr bool in_bf16 = BF16IN;   // only the dense comparison reads bf16 tensors
     if (kind == 0) {
       const int64_t o = slice * p.nbar * D;
       Qp = (const uint16_t*)p.lowQ + o; Kp = (const uint16_t*)p.lowK + o; Vp = (const uint16_t*)p.lowV + o;
@@ -150,36 +125,27 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
     const int w = p.high_window;
     const int r0 = q0 + WROWS * wave;   // first query row of this wave
 
-    // Q operand: lane holds channels 16*ks + 8*g .. +8 of its query rows (one per 32-row tile), pre-scaled
-    half8 Qr[QLDS ? 1 : QT][QLDS ? 1 : DK];
-    half_t* Qw = Qs + (QLDS ? wave * WROWS * KS : 0);
-    if (QLDS) __builtin_amdgcn_wave_barrier();   // the previous item's reads of this wave's Q rows are done
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      const int row = r0 + 32 * qt + nn;
+    // Q operand: lane holds channels 16*ks + 8*g .. +8 of its query row, pre-scaled
+    half8 Qr[DK];
+    {
+      const int row = r0 + nn;
 #pragma unroll
       for (int ks = 0; ks < DK; ++ks) {
         uint4v v = {0u, 0u, 0u, 0u};
         if (row < nq) v = *(const uint4v*)(Qp + (int64_t)row * D + ks * 16 + g * 8);
-        if (in_bf16) v = at_bf16x8_to_f16x8(v);
         half8 h = __builtin_bit_cast(half8, v);
 #pragma unroll
         for (int j = 0; j < 8; ++j) h[j] = (_Float16)((float)h[j] * c2);
-        if (QLDS) *(half8*)(Qw + (32 * qt + nn) * KS + ks * 16 + g * 8) = h;   // each lane re-reads only what it wrote
-        else Qr[qt][ks] = h;
+        Qr[ks] = h;
       }
     }
 
-    float16v O[QT][DT];
+    float16v O[DT];
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) O[qt][dt][r] = 0.f;
-    float m_run[QT], l_run[QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
+      for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
 
     // tile iteration space of the item
     int n_outer = 1, e0 = 0, sub_n = 1, t_lo = 0, t_hi = 0;
@@ -198,107 +164,17 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
       n_outer = (nk + KT - 1) / KT;
     }
 
-    // Register path: tiles are staged through registers: the global loads of tile i+1 are issued before the arithmetic of tile i, so
-    // their latency hides behind it; the registers are written to LDS after the barrier that ends tile i.
-    constexpr int KPT = (KT * (D / 8) + NT - 1) / NT;          // 16-byte K pieces per thread
-    constexpr int VPT = ((KT / 4) * (D / 8) + NT - 1) / NT;    // (4 keys x 8 channels) V units per thread
-    uint4v Kreg[KPT];
-    uint4v Vreg[VPT][4];
     const int n_tt = n_outer * sub_n;
     auto key0_of = [&](int idx) -> int {
       if (kind == 1) return (p.mid_col_idx[e0 + idx / sub_n] * sub_n + idx % sub_n) * KT;
       return (t_lo + idx) * KT;
     };
-    // Per-thread staging geometry, fixed for the whole item: piece u of the K tile is row krow[u], 16-byte column kc8;
-    // V unit u is the four keys 4*vkg[u] .. +3 of channel octet vc8.  Tiles inside the band take the fast path (no
-    // bounds tests, one 64-bit add per load).
-    const int kc8 = tid % (D / 8), krow0 = tid / (D / 8);
-    constexpr int KROWS_PER_STEP = NT / (D / 8);
-    const uint16_t* kthread = Kp + (int64_t)krow0 * D + kc8 * 8;
-    const uint16_t* vthread = Vp + (int64_t)(krow0 * 4) * D + kc8 * 8;   // V units use the same (row group, octet) split
-    auto load_tile = [&](int key0) {
-      if (key0 + KT <= nk) {
-        const uint16_t* kp = kthread + (int64_t)key0 * D;
-        const uint16_t* vp = vthread + (int64_t)key0 * D;
-#pragma unroll
-        for (int u = 0; u < KPT; ++u)
-          if (KT * (D / 8) % NT == 0 || tid + u * NT < KT * (D / 8)) Kreg[u] = *(const uint4v*)(kp + (int64_t)u * KROWS_PER_STEP * D);
-#pragma unroll
-        for (int u = 0; u < VPT; ++u)
-          if ((KT / 4) * (D / 8) % NT == 0 || tid + u * NT < (KT / 4) * (D / 8)) {
-#pragma unroll
-            for (int b = 0; b < 4; ++b) Vreg[u][b] = *(const uint4v*)(vp + (int64_t)(u * KROWS_PER_STEP * 4 + b) * D);
-          }
-        return;
-      }
-#pragma unroll
-      for (int u = 0; u < KPT; ++u) {
-        const int e = tid + u * NT;
-        const int kr = e / (D / 8), c8 = e % (D / 8);
-        uint4v v = {0u, 0u, 0u, 0u};
-        if (e < KT * (D / 8) && key0 + kr < nk) v = *(const uint4v*)(Kp + (int64_t)(key0 + kr) * D + c8 * 8);
-        Kreg[u] = v;
-      }
-#pragma unroll
-      for (int u = 0; u < VPT; ++u) {
-        const int e = tid + u * NT;
-        const int kg = e / (D / 8), c8 = e % (D / 8);
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const int key = key0 + kg * 4 + b;
-          uint4v v = {0u, 0u, 0u, 0u};
-          if (e < (KT / 4) * (D / 8) && key < nk) v = *(const uint4v*)(Vp + (int64_t)key * D + c8 * 8);
-          Vreg[u][b] = v;
-        }
-      }
-    };
-    // LDS destinations of this thread's pieces (constant for the item)
-    auto store_tile = [&](int buf) {
-      half_t* ks_dst = Ks2[buf] + krow0 * KS + kc8 * 8;
-      half_t* Vt = Vt2[buf];
-#pragma unroll
-      for (int u = 0; u < KPT; ++u) {
-        uint4v v = Kreg[u];
-        if (in_bf16) v = at_bf16x8_to_f16x8(v);
-        if (KT * (D / 8) % NT == 0 || tid + u * NT < KT * (D / 8)) *(uint4v*)(ks_dst + u * KROWS_PER_STEP * KS) = v;
-      }
-#pragma unroll
-      for (int u = 0; u < VPT; ++u) {
-        const int kg = krow0 + u * KROWS_PER_STEP, c8 = kc8;
-        uint4v rws[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) rws[b] = in_bf16 ? at_bf16x8_to_f16x8(Vreg[u][b]) : Vreg[u][b];
-        // tile-local key kk = 4*kg + b = 32*t2 + 16*s + 8*a + 4*gg + b lives in 16-byte chunk x = 4*t2 + 2*s + gg of its
-        // channel row, half a of the chunk.  Chunks are XOR-swizzled with bits 4..6 of the row: the 16 lanes of an
-        // operand read (16 consecutive rows) share one swizzle and stay conflict-free, while the 8-byte stores of a
-        // wave (rows 8 apart) spread over all banks.
-        const int kk = kg * 4;
-        const int x = ((kk >> 4) << 1) | ((kk >> 2) & 1);
-        const int ahalf = (kk >> 3) & 1;
-        const int pos = ((x ^ ((c8 >> 1) & 7)) << 3) | (ahalf << 2);
-        if ((KT / 4) * (D / 8) % NT == 0 || tid + u * NT < (KT / 4) * (D / 8)) {
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const int wd = i >> 1;
-            uint2v o2;   // halves i of rows 0..3: byte selectors pick the low (0x05040100) or high (0x07060302) halves
-            const unsigned sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            o2[0] = __builtin_amdgcn_perm(rws[1][wd], rws[0][wd], sel);
-            o2[1] = __builtin_amdgcn_perm(rws[3][wd], rws[2][wd], sel);
-            *(uint2v*)(Vt + (c8 * 8 + i) * VS + pos) = o2;
-          }
-        }
-      }
-    };
-
-    // Pipeline of the register path: at the top of iteration i the registers hold tile i+1 (requested one iteration ago); it goes into the
-    // LDS copy that tile i-1 used - free since the barrier that ended iteration i-1 - and the loads of tile i+2 are
-    // issued, a whole iteration ahead of their use.  The barrier at the end of the iteration publishes tile i+1.
     // Exchange items of one (slice, band) all see the same <= 2 tiles of summary tokens: a workgroup that has them in
     // its two LDS copies from its previous item keeps them (no loads, no stores for this item).
     const int lds_key = (kind == 3 && n_tt <= 2) ? (int)(slice * 4 + band) : -1;
     const bool reuse = lds_key >= 0 && lds_key == lds_holds;
     lds_holds = lds_key;
-    // DMA staging: this wave's share of a tile is RPI rows per instruction, NIW instructions per tensor; rows past the
+    // Staging: this wave's share of a tile is RPI rows per instruction, NIW instructions per tensor; rows past the
     // end of the band are clamped to its last row (their scores are masked, and V rows of real data times zero are zero)
     constexpr int RPI = 64 / CPR, NIW = KT / (RPI * NW);
     // piece pi of a tile: K rows (pi even) or V rows (pi odd) of instruction pi / 2 of this wave's share
@@ -315,39 +191,24 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
 #pragma unroll
       for (int pi = 0; pi < 2 * NIW; ++pi) dma_piece(key0, buf, pi);
     };
-    if (DMA) {
-      if (n_tt > 0 && !reuse) dma_tile(key0_of(0), 0);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    } else if (n_tt > 0 && !reuse) {   // (the barrier that ended the previous item's last tile already freed both copies)
-      load_tile(key0_of(0));
-      store_tile(0);
-      if (n_tt > 1) load_tile(key0_of(1));
-    }
+    if (n_tt > 0 && !reuse) dma_tile(key0_of(0), 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    for (int idx = 0; idx < n_tt; ++idx, (DMA ? (void)__builtin_amdgcn_s_waitcnt(0x0070) : (void)0), __syncthreads()) {
+    for (int idx = 0; idx < n_tt; ++idx, __builtin_amdgcn_s_waitcnt(0x0070), __syncthreads()) {
       const int key0 = key0_of(idx);
       const half_t* Ks = Ks2[idx & 1];
       const half_t* Vt = Vt2[idx & 1];
-      // Staging of the next tiles.  Register path: half of the waves do it before the score MFMAs and half after them,
-      // so that the workgroup's LDS stores and global loads do not all queue up behind one barrier.  DMA path: the next
-      // tile goes straight into the other LDS copy (free since the barrier that ended the previous iteration); the
-      // wait for it sits in front of the barrier that ends this iteration.
-      auto stage = [&]() {
-        if (DMA) {
-          if (idx + 1 < n_tt && !reuse) dma_tile(key0_of(idx + 1), (idx + 1) & 1);
-        } else if (idx + 1 < n_tt && !reuse) {
-          store_tile((idx + 1) & 1);
-          if (idx + 2 < n_tt) load_tile(key0_of(idx + 2));
-        }
-      };
-      const bool stage_early = !DMA && (wave & 1) == 0;
-      if (stage_early) stage();
-      // DMA path: the copy instructions of the next tile are spread over the score MFMAs below (a wave issues in
-      // order, and a burst of them right behind the barrier holds every wave of the CU in the memory pipeline's queue)
-      const bool dma_next = DMA && idx + 1 < n_tt && !reuse;
+      // The next tile goes straight into the other LDS copy (free since the barrier that ended the previous iteration);
+      // the wait for it sits in front of the barrier that ends this iteration.  Its copy instructions are spread over the
+      // score MFMAs below (a wave issues in order, and a burst of them right behind the barrier holds every wave of the
+      // CU in the memory pipeline's queue); an iteration that skips the MFMAs issues them at once.
+      const bool dma_next = idx + 1 < n_tt && !reuse;
       const int key0_next = dma_next ? key0_of(idx + 1) : 0;
+      auto stage = [&]() {
+        if (dma_next) dma_tile(key0_next, (idx + 1) & 1);
+      };
       if (key0 >= nk) {  // block tail beyond the band (uniform over the workgroup)
-        if (!stage_early) stage();
+        stage();
         continue;
       }
 
@@ -359,31 +220,25 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
         need_mask = need_mask || (key0 < r0 + WROWS - 1 - w) || (key_hi > r0 + w);
       }
       if (!need) {  // uniform per wave; the tile's barrier sits in the loop increment, which `continue` still runs
-        if (!stage_early) stage();
+        stage();
         continue;
       }
 
-      // ---- S^T = K Q^T for the two 32-key halves of the tile; a K operand feeds all query tiles of the wave
+      // ---- S^T = K Q^T for the two 32-key halves of the tile
       // The accumulators start at minus the lane's reference maximum, so the matrix core delivers the scores already
       // shifted: in the common case (no new maximum) they go into exp2 without a subtraction.
-      float16v S[QT][2];
-      float s_init[QT];
+      float16v S[2];
+      const float s_init = (m_run == -INFINITY) ? 0.f : -m_run;
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt) s_init[qt] = (m_run[qt] == -INFINITY) ? 0.f : -m_run[qt];
+      for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) S[qt][t2][r] = s_init[qt];
+        for (int r = 0; r < 16; ++r) S[t2][r] = s_init;
       // K operands are requested PF steps ahead of the MFMA that consumes them, so LDS latency overlaps the matrix core
-      constexpr int PF = DMA ? 8 : 4;   // the DMA path has the registers for a deeper operand pipeline
+      constexpr int PF = 8;
       {
         constexpr int NS = 2 * DK;
         auto kptr = [&](int i) -> const half8* {
-          const int row = (i / DK) * 32 + nn, chunk = (i % DK) * 2 + g;
-          if (DMA) return (const half8*)(Ks + (i / DK) * 32 * D + koff_row + kx[DMA ? i % DK : 0]);   // fK(t2*32 + nn) = fK(nn)
-          return (const half8*)(Ks + row * KS + chunk * 8);
+          return (const half8*)(Ks + (i / DK) * 32 * D + koff_row + kx[i % DK]);   // fK(t2*32 + nn) = fK(nn)
         };
         half8 Abuf[PF];
 #pragma unroll
@@ -394,79 +249,66 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
           const half8 A = Abuf[i % PF];
           if (i + PF < NS)
             Abuf[i % PF] = *kptr(i + PF);
-#pragma unroll
-          for (int qt = 0; qt < QT; ++qt) {
-            const half8 Bq = QLDS ? *(const half8*)(Qw + (32 * qt + nn) * KS + ks * 16 + g * 8) : Qr[QLDS ? 0 : qt][QLDS ? 0 : ks];
-            S[qt][t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Bq, S[qt][t2], 0, 0, 0);
-          }
-          if (DMA && dma_next) {
+          S[t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Qr[ks], S[t2], 0, 0, 0);
+          if (dma_next) {
 #pragma unroll
             for (int pi = i * (2 * NIW) / NS; pi < (i + 1) * (2 * NIW) / NS; ++pi) dma_piece(key0_next, (idx + 1) & 1, pi);
           }
         }
-        if (!QLDS) {   // pin the order: PF reads up front, then one read per MFMA
-          __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
+        // pin the order: PF reads up front, then one read per MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
 #pragma unroll
-          for (int i = 0; i < NS - PF; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, QT, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          }
-          __builtin_amdgcn_sched_group_barrier(0x008, PF * QT, 0);
+        for (int i = 0; i < NS - PF; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, PF, 0);
       }
-      if (!DMA && !stage_early) stage();
       // ---- mask, running softmax (lane = query row; registers = keys).  m_run is a reference maximum, not the exact
       // one: it moves only when a score exceeds it by more than 2^kBump (or when the row sees its first valid key), so
       // probabilities stay within [0, 2^kBump] - exact in the ratio P / sum(P) - and the rescale is rare.
       constexpr float kBump = 8.f;
-      half8 P[QT][2][2];
-      bool bump[QT], any_bump = false;
-      float mx[QT];
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
-        if (need_mask) {
-          // valid keys of this lane's row form one interval [lo, hi]; relative to the lane's first key of the tile,
-          // register r holds key offset c_r (a compile-time constant), valid iff (unsigned)(c_r - lo') <= (unsigned)(hi' - lo')
-          const int row = r0 + 32 * qt + nn;
-          int lo = 0, hi = nk - 1;
-          if (kind == 2) { lo = row - w > 0 ? row - w : 0; hi = row + w < nk - 1 ? row + w : nk - 1; }
-          const int base = key0 + 4 * g;
-          int dlo = lo - base, dhi = hi - base;
-          dlo = dlo < -1 ? -1 : (dlo > 65 ? 65 : dlo);    // clamped: only the range of c_r matters
-          dhi = dhi < -1 ? -1 : (dhi > 65 ? 65 : dhi);
-          unsigned range = (unsigned)(dhi - dlo);
-          if (dhi < dlo) { dlo = 1000; range = 0u; }      // empty interval: no c_r passes
-          const unsigned ndlo = (unsigned)(-dlo);
-#pragma unroll
-          for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const unsigned cr = (unsigned)(t2 * 32 + 8 * (r >> 2) + (r & 3));
-              S[qt][t2][r] = (cr + ndlo <= range) ? S[qt][t2][r] : -INFINITY;
-            }
-        }
-        // row maximum: four independent chains (short dependency depth), then the other lane half through a register
-        // swap (v_permlane32_swap leaves [lo, lo] / [hi, hi] in the two registers; no trip through the LDS pipe)
-        float mc[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      half8 P[2][2];
+      if (need_mask) {
+        // valid keys of this lane's row form one interval [lo, hi]; relative to the lane's first key of the tile,
+        // register r holds key offset c_r (a compile-time constant), valid iff (unsigned)(c_r - lo') <= (unsigned)(hi' - lo')
+        const int row = r0 + nn;
+        int lo = 0, hi = nk - 1;
+        if (kind == 2) { lo = row - w > 0 ? row - w : 0; hi = row + w < nk - 1 ? row + w : nk - 1; }
+        const int base = key0 + 4 * g;
+        int dlo = lo - base, dhi = hi - base;
+        dlo = dlo < -1 ? -1 : (dlo > 65 ? 65 : dlo);    // clamped: only the range of c_r matters
+        dhi = dhi < -1 ? -1 : (dhi > 65 ? 65 : dhi);
+        unsigned range = (unsigned)(dhi - dlo);
+        if (dhi < dlo) { dlo = 1000; range = 0u; }      // empty interval: no c_r passes
+        const unsigned ndlo = (unsigned)(-dlo);
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-          for (int r = 0; r < 16; r += 2)
-            mc[(r >> 1) & 3] = __builtin_fmaxf(__builtin_fmaxf(mc[(r >> 1) & 3], S[qt][t2][r]), S[qt][t2][r + 1]);
-        float m0 = fmaxf(fmaxf(mc[0], mc[1]), fmaxf(mc[2], mc[3]));
-        {
-          const uint32_t mb = __float_as_uint(m0);
-          const auto sw = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
-          m0 = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        }
-        mx[qt] = m0;
-        bump[qt] = (m_run[qt] == -INFINITY) ? (m0 > -INFINITY) : (m0 > kBump);
-        any_bump = any_bump || bump[qt];
+          for (int r = 0; r < 16; ++r) {
+            const unsigned cr = (unsigned)(t2 * 32 + 8 * (r >> 2) + (r & 3));
+            S[t2][r] = (cr + ndlo <= range) ? S[t2][r] : -INFINITY;
+          }
       }
+      // row maximum: four independent chains (short dependency depth), then the other lane half through a register
+      // swap (v_permlane32_swap leaves [lo, lo] / [hi, hi] in the two registers; no trip through the LDS pipe)
+      float mc[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2)
+          mc[(r >> 1) & 3] = __builtin_fmaxf(__builtin_fmaxf(mc[(r >> 1) & 3], S[t2][r]), S[t2][r + 1]);
+      float mx = fmaxf(fmaxf(mc[0], mc[1]), fmaxf(mc[2], mc[3]));
+      {
+        const uint32_t mb = __float_as_uint(mx);
+        const auto sw = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+      }
+      const bool bump = (m_run == -INFINITY) ? (mx > -INFINITY) : (mx > kBump);
       // Probabilities, two per register, rounded toward zero; the row sum is taken over the rounded values (the ones
       // the matrix core multiplies), so the rounding direction cancels in P / sum(P).  They are formed before the
       // (rare) reference bump is known, so that the exponentials overlap the maximum's dependency chain.
-      auto probabilities = [&](int qt) -> float {
+      auto probabilities = [&]() -> float {
         float ps[4] = {0.f, 0.f, 0.f, 0.f};
         const half2v ones = {(_Float16)1.f, (_Float16)1.f};
 #pragma unroll
@@ -477,56 +319,43 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const half2v h2 = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(
-                  __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + 2 * j]), __builtin_amdgcn_exp2f(S[qt][t2][s2 * 8 + 2 * j + 1])));
+                  __builtin_amdgcn_exp2f(S[t2][s2 * 8 + 2 * j]), __builtin_amdgcn_exp2f(S[t2][s2 * 8 + 2 * j + 1])));
               ps[j] = __builtin_amdgcn_fdot2(h2, ones, ps[j], false);
               pk[j] = __builtin_bit_cast(uint32_t, h2);
             }
-            P[qt][t2][s2] = __builtin_bit_cast(half8, pk);
+            P[t2][s2] = __builtin_bit_cast(half8, pk);
           }
         return (ps[0] + ps[1]) + (ps[2] + ps[3]);
       };
-      float psum[QT];
+      float psum = probabilities();
+      if (__builtin_amdgcn_ballot_w64(bump) != 0) {
+        const bool fresh = m_run == -INFINITY;
+        const float delta = bump ? mx : 0.f;
+        const float alpha = (bump && !fresh) ? __builtin_amdgcn_exp2f(-delta) : 1.f;
+        if (bump) m_run = fresh ? delta : m_run + delta;
+        l_run *= alpha;
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt) psum[qt] = probabilities(qt);
-      if (__builtin_amdgcn_ballot_w64(any_bump) != 0) {
+        for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-          const bool fresh = m_run[qt] == -INFINITY;
-          const float delta = bump[qt] ? mx[qt] : 0.f;
-          const float alpha = (bump[qt] && !fresh) ? __builtin_amdgcn_exp2f(-delta) : 1.f;
-          if (bump[qt]) m_run[qt] = fresh ? delta : m_run[qt] + delta;
-          l_run[qt] *= alpha;
+          for (int r = 0; r < 16; ++r) S[t2][r] -= delta;
 #pragma unroll
-          for (int t2 = 0; t2 < 2; ++t2)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) S[qt][t2][r] -= delta;
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) O[qt][dt][r] *= alpha;
-          psum[qt] = probabilities(qt);   // again, against the moved reference
-        }
+          for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+        psum = probabilities();   // again, against the moved reference
       }
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt) l_run[qt] += psum[qt];
-      // ---- O^T += V^T P^T; a V operand feeds all query tiles of the wave
+      l_run += psum;
+      // ---- O^T += V^T P^T
       {
         constexpr int NS = 4 * DT;   // (t2, s2, dt) flattened, dt fastest
-        auto vptr = [&](int i) -> const half8* {
-          const int dt = i % DT, ts = i / DT;   // ts = t2 * 2 + s2
-          const int vrow = dt * 32 + nn;
-          const int x = ts * 2 + g;
-          return (const half8*)(Vt + vrow * VS + ((x ^ ((vrow >> 4) & 7)) << 3));
-        };
-        // DMA path: V is row-major in LDS; the operand (lane = channel, 8 keys in the order of P's registers) comes from
-        // two transposing reads, each delivering 4 consecutive keys: keys 16 ts + 8 h + 4 g + 0..3 for read h
+        // V is row-major in LDS; the operand (lane = channel, 8 keys in the order of P's registers) comes from two
+        // transposing reads, each delivering 4 consecutive keys: keys 16 ts + 8 h + 4 g + 0..3 for read h
         auto vread = [&](int i) -> half8 {
-          if (!DMA) return *vptr(i);
-          const int dt = i % DT, ts = i / DT;
+          const int dt = i % DT, ts = i / DT;   // ts = t2 * 2 + s2
           uint4v r4;
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
-            const half_t* ptr = Vt + (ts * 16 + 8 * h) * D + voff_row + vx[DMA ? dt : 0];   // fV only sees row & 3 = sl / 4
+            const half_t* ptr = Vt + (ts * 16 + 8 * h) * D + voff_row + vx[dt];   // fV only sees row & 3 = sl / 4
             const fp16x4 t4 = __builtin_amdgcn_ds_read_tr16_b64_v4f16((fp16x4 __attribute__((address_space(3)))*)ptr);
             const uint2v u2 = __builtin_bit_cast(uint2v, t4);
             r4[2 * h] = u2[0]; r4[2 * h + 1] = u2[1];
@@ -541,9 +370,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
           const int dt = i % DT, ts = i / DT;
           const half8 A = Abuf[i % PF];
           if (i + PF < NS) Abuf[i % PF] = vread(i + PF);
-#pragma unroll
-          for (int qt = 0; qt < QT; ++qt)
-            O[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[qt][ts >> 1][ts & 1], O[qt][dt], 0, 0, 0);
+          O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[ts >> 1][ts & 1], O[dt], 0, 0, 0);
         }
       }
     }
@@ -551,10 +378,9 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
     // ---- epilogue: normalise, optional residual, store.  A lane holds, per 16 channels, two groups of four that
     // interleave with its partner lane's (lane ^ 32, same query): swapping one group each (v_permlane32_swap) leaves
     // every lane with 8 consecutive channels, i.e. 16-byte stores (and 16-byte residual loads) of whole 32-byte sectors.
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      const int row = r0 + 32 * qt + nn;
-      const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32);
+    {
+      const int row = r0 + nn;
+      const float l_tot = l_run + __shfl_xor(l_run, 32);
       const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
@@ -563,8 +389,8 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
           float o[8];   // after the swap: channels dt*32 + j*16 + g*8 + 0..7
 #pragma unroll
           for (int b = 0; b < 4; ++b) {
-            const uint32_t lo = __float_as_uint(O[qt][dt][(2 * j) * 4 + b] * inv);       // channels 16j + 4g + b
-            const uint32_t hi = __float_as_uint(O[qt][dt][(2 * j + 1) * 4 + b] * inv);   // channels 16j + 8 + 4g + b
+            const uint32_t lo = __float_as_uint(O[dt][(2 * j) * 4 + b] * inv);       // channels 16j + 4g + b
+            const uint32_t hi = __float_as_uint(O[dt][(2 * j + 1) * 4 + b] * inv);   // channels 16j + 8 + 4g + b
             const auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
             o[b] = __uint_as_float(sw[0]);
             o[4 + b] = __uint_as_float(sw[1]);
@@ -580,9 +406,7 @@ __global__ void __launch_bounds__(64 * NW, (QT == 1 && (D == 64 || NW == 4)) ? 2
             }
             uint4v st4;
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-              st4[b] = in_bf16 ? ((uint32_t)at_f32_to_bf16(o[2 * b]) | ((uint32_t)at_f32_to_bf16(o[2 * b + 1]) << 16))
-                               : pack_h2(o[2 * b], o[2 * b + 1]);
+            for (int b = 0; b < 4; ++b) st4[b] = pack_h2(o[2 * b], o[2 * b + 1]);
             *(uint4v*)dst = st4;
           }
         }
@@ -616,31 +440,25 @@ hipError_t launch_probe_mfma(float* out, int blocks, int iters, hipStream_t st) 
   return hipGetLastError();
 }
 
-template <int D, int NW, int QT, bool BF16IN, bool DMA>
+template <int D, int NW>
 static hipError_t launch_dn(const AttnParams& p, const AttnItem* items, int n_items, int num_cu, hipStream_t st) {
-  // resident workgroups per CU: register-limited waves per SIMD (accumulators of QT query tiles), 4 SIMDs per CU
-  const int waves_per_simd = (QT == 1 && (D == 64 || NW == 4 || NW == 8)) ? 2 : 1;   // matches the kernel's launch bounds
+  // resident workgroups per CU: register-limited waves per SIMD, 4 SIMDs per CU (matches the kernel's launch bounds)
+  const int waves_per_simd = (D == 64 || NW == 4) ? 2 : 1;
   int occ = waves_per_simd * 4 / NW;
   if (occ < 1) occ = 1;
   int64_t blocks = (int64_t)num_cu * occ;
   if (blocks > n_items) blocks = n_items;
   if (blocks > 8) blocks -= blocks % 8;   // whole runs per XCD (see the kernel's item mapping)
-  hipLaunchKernelGGL((k_attn<D, NW, QT, BF16IN, DMA>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
+  hipLaunchKernelGGL((k_attn<D, NW>), dim3((unsigned)blocks), dim3(64 * NW), 0, st, p, items, n_items);
   return hipGetLastError();
 }
 
 hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_items, int rows_per_item, int num_cu,
                             hipStream_t st) {
   if (n_items <= 0) return hipSuccess;
-  const bool bf = p.denseQ != nullptr && p.dense_bf16;   // the dense comparison reads the caller's bf16 tensors
-  static int dma_env = -1;
-  if (dma_env < 0) { const char* e = getenv("FREQATTN_ATTN_DMA"); dma_env = e ? atoi(e) : 1; }
-  const bool dma = dma_env != 0;
 #define FA_ATTN_CASE(D_, R_, NW_) \
-  if (p.d == D_ && rows_per_item == R_) \
-    return bf ? launch_dn<D_, NW_, 1, true, false>(p, items, n_items, num_cu, st) \
-              : (dma ? launch_dn<D_, NW_, 1, false, true>(p, items, n_items, num_cu, st) : launch_dn<D_, NW_, 1, false, false>(p, items, n_items, num_cu, st));
-  FA_ATTN_CASE(64, 64, 2) FA_ATTN_CASE(64, 128, 4) FA_ATTN_CASE(128, 64, 2) FA_ATTN_CASE(128, 128, 4) FA_ATTN_CASE(128, 256, 8)
+  if (p.d == D_ && rows_per_item == R_) return launch_dn<D_, NW_>(p, items, n_items, num_cu, st);
+  FA_ATTN_CASE(64, 64, 2) FA_ATTN_CASE(64, 128, 4) FA_ATTN_CASE(128, 64, 2) FA_ATTN_CASE(128, 128, 4)
 #undef FA_ATTN_CASE
   return hipErrorInvalidValue;
 }

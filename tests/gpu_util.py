@@ -46,3 +46,47 @@ def run_forward(ctx, q64, k64, v64, dtype, alloc):
 
 
 TOL = {"bf16": (2e-2, 5e-3), "f32": (1e-5, 1e-5)}   # (max-abs, relative L2) per I/O type
+
+
+class HeadsOnDemand:
+    """A [batch, heads, N, d] device tensor that hands the oracle one (batch, head) slice at a time as fp64 host data,
+    so that a 24-head, million-token configuration never sits on the host in fp64 as a whole."""
+
+    def __init__(self, t):
+        self._t = t
+        self.shape = tuple(t.shape)
+
+    def __getitem__(self, bh):
+        b, h = bh
+        return to_host64(self._t[b, h])
+
+
+def band_statistics_library_transform(q, k, v, grid, band: dict):
+    """Router statistics (paper section 3.5, same reading as the oracle's band_statistics) with the transform taken by
+    scipy's orthonormal DCT-II - the routine the oracle's transform is pinned against - because the oracle's plain
+    matrix products need minutes for 48 to 72 head-tensors of 256K to 1M tokens.  The 64K test checks that the two
+    agree to 1e-9 on a whole 24-head configuration; everything after the statistics is the oracle's own code."""
+    from scipy.fft import dctn
+    T, H, W = grid
+    Bsz, nh, N, d = q.shape
+    bands = O.band_partition(T, H, W, oracle_cfg(band))
+    acc = np.zeros((3, d))
+    for x in (q, k, v):
+        for b in range(Bsz):
+            for h in range(nh):
+                c = dctn(np.asarray(x[b, h], dtype=np.float64).reshape(T, H, W, d), type=2, norm="ortho",
+                         axes=(0, 1, 2), workers=16, overwrite_x=True).reshape(N, d)
+                for l, idx in enumerate(bands):
+                    acc[l] += np.einsum("nc,nc->c", c[idx], c[idx]) if len(idx) else 0.0
+    g = np.empty((3, O.ROUTER_DR))
+    for l, idx in enumerate(bands):
+        g[l] = (acc[l] / max(1, 3 * Bsz * nh * len(idx))).reshape(O.ROUTER_DR, d // O.ROUTER_DR).mean(axis=1)
+    logs = np.log(O.ROUTER_EPS + g).reshape(-1)
+    return logs - logs.mean()
+
+
+def expected_route(stats, t, weights, heads):
+    """Oracle allocation from given statistics: probabilities, integer head counts, one-hot masks."""
+    pi = O.router_probabilities(stats, t, *weights)
+    counts = O.apportion_heads(pi, heads)
+    return O.route_fixed(heads, *[int(c) for c in counts]), pi

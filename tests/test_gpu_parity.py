@@ -101,8 +101,10 @@ def test_forward_rejects_bad_arguments():
 
 
 # ------------------------------------------------------------------ bf16 configurations (MFMA kernels)
-def _stagewise(ctx, wl, band, q, k, v, alloc, out_gpu):
-    """Per-slice, per-stage report against the oracle's intermediate results."""
+def _stagewise(ctx, wl, band, q, k, v, alloc, out_gpu, tol_rel=2e-3):
+    """Per-slice, per-stage comparison with the oracle's intermediate results: spectral Q~, K~ (active bands), V~ and the
+    band outputs after the exchange must each be within tol_rel (relative L2) - an error in one stage cannot hide behind
+    the pass-through of the inactive bands in the final output."""
     cfg = U.oracle_cfg(band)
     T, H, W = wl.grid
     for s in range(q.shape[1]):
@@ -114,11 +116,14 @@ def _stagewise(ctx, wl, band, q, k, v, alloc, out_gpu):
                 for which, name in ((0, "qs"), (1, "ks")):
                     mx, rl = U.errors(ctx.read_spectral(which, s, l), parts[name][idx])
                     print(f"  slice {s} band {l} {name}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+                    assert rl <= tol_rel, (s, l, name, rl)
             try:   # a slice that does not run the high band has no V~ rows there (its V~ stops at the low+mid box)
                 mx, rl = U.errors(ctx.read_spectral(2, s, l), parts["vs"][idx])
                 print(f"  slice {s} band {l} vs: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+                assert rl <= tol_rel, (s, l, "vs", rl)
                 mx, rl = U.errors(ctx.read_spectral(3, s, l), parts["Yhat"][l])
                 print(f"  slice {s} band {l} Yhat: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+                assert rl <= tol_rel, (s, l, "Yhat", rl)
             except B.FreqAttnError as e:
                 assert e.status == B.EUNSUPPORTED and l == 2 and not (alloc[s] >> 2) & 1
         mx, rl = U.errors(out_gpu[0, s], want.reshape(-1, want.shape[-1]))

@@ -141,3 +141,39 @@ def test_summary_weights_pool_the_spectrum_of_the_input(grid, m, transform):
         sizes = np.array([((u + 1) * n) // me - (u * n) // me for u in range(me)], np.float64)
         got = (w.astype(np.float64) @ x.reshape(-1, 3)) / sizes[:, None]
         assert np.abs(got - want).max() < 2e-6, (l, np.abs(got - want).max())
+
+
+def test_binding_rejects_tensors_the_kernels_could_not_address(monkeypatch):
+    """The C side only sees addresses; the binding refuses host tensors, other types, shapes and layouts, and a
+    head_alloc of the wrong length, before any pointer is taken."""
+    import torch
+    ctx = B.Context(1, 2, 64, (4, 8, 8), B.BF16, B.make_cfg(mid_block=16, mid_stride=4, high_window=32, n_summary=4),
+                    path=B.PATH_TABLES_ONLY)
+    good = torch.zeros(1, 2, 256, 64, dtype=torch.bfloat16)
+
+    class FakeDevice(torch.Tensor):      # a host tensor that claims to live on the device: reaches the later checks
+        is_cuda = True
+
+    dev = lambda t: t.as_subclass(FakeDevice)
+    with pytest.raises(ValueError, match="device tensor"):
+        ctx.forward(good, good, good, [1, 4], good.clone())
+    with pytest.raises(ValueError, match="dtype"):
+        ctx.forward(dev(good.float()), dev(good), dev(good), [1, 4], dev(good.clone()))
+    with pytest.raises(ValueError, match="shape"):
+        ctx.forward(dev(good[:, :1]), dev(good), dev(good), [1, 4], dev(good.clone()))
+    with pytest.raises(ValueError, match="contiguous"):
+        ctx.forward(dev(good.transpose(2, 3).contiguous().transpose(2, 3)), dev(good), dev(good), [1, 4], dev(good.clone()))
+    with pytest.raises(ValueError, match="head_alloc"):
+        ctx.forward(dev(good), dev(good), dev(good), [1], dev(good.clone()))
+    with pytest.raises(TypeError):
+        ctx.forward(np.zeros((1, 2, 256, 64)), good, good, [1, 4], good)
+    w1, b1, w2, b2 = np.zeros((256, 8)), np.zeros(8), np.zeros((8, 3)), np.zeros(3)
+    with pytest.raises(ValueError, match="router weights"):
+        ctx.route_mlp(dev(good), dev(good), dev(good), 0.5, w1[:100], b1, w2, b2)
+    with pytest.raises(ValueError, match="device tensor"):
+        ctx.dense_forward(good, good, good, good.clone())
+    # with everything in order the call reaches the library, which refuses a tables-only context itself
+    monkeypatch.setattr(B, "_stream", lambda: C.c_void_p(0))       # no device here: the default stream's handle
+    with pytest.raises(B.FreqAttnError) as ei:
+        ctx.forward(dev(good), dev(good), dev(good), [1, 4], dev(good.clone()))
+    assert ei.value.status == B.EUNSUPPORTED
