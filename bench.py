@@ -21,9 +21,25 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 matrix-core peak
-# HBM bytes per launch of a stage's kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the plain-copy
-# calibration (profiles/hbm_traffic_bench_1m.md); None where no counter run exists for the workload.
-MEASURED_TRAFFIC = {"1m": {"forward_transform": 2.49e9, "inverse_transform": 1.86e9, "band_attention_fused": 13.2e9}}
+
+
+def measured_traffic(workload: str, stage: str):
+    """HBM bytes per launch of a stage's kernels from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by the
+    plain-copy calibration), read from the figures file written next to the counter summary of that workload
+    (profiles/hbm_traffic_bench_<workload>.txt: `key: value` lines, among them `<stage>_bytes_per_step`,
+    `<stage>_launches` and the commit the counters were taken at).  None where no counter run exists."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_bench_{workload}.txt")
+    if not os.path.exists(path):
+        return None, None
+    vals = {}
+    for line in open(path):
+        if ":" in line and not line.startswith("#"):
+            key, val = line.split(":", 1)
+            vals[key.strip()] = val.strip()
+    try:
+        return float(vals[f"{stage}_bytes_per_step"]) / float(vals[f"{stage}_launches"]), vals.get("commit")
+    except (KeyError, ValueError, ZeroDivisionError):
+        return None, vals.get("commit")
 
 
 def algorithmic_work(wl, ctx, alloc):
@@ -53,7 +69,19 @@ def algorithmic_work(wl, ctx, alloc):
                     attn_flops[l] += 4.0 * d * pairs[l]
                     xchg_flops += 4.0 * d * n * n_c[l]
     io = 2  # bytes per bf16 element
-    return {
+    # What the pruned scheme strictly needs for the forward transforms: every input element read once, and only the
+    # coefficients somebody uses written (Q~, K~ on the box of the bands a head runs; V~ on the low+mid box for heads
+    # without the high band when the context sums their high-band summaries from V, else everywhere).
+    box = {0: n_low, 1: n_low + n_mid, 2: N}
+    fwd_min = 0.0
+    for h in range(wl.heads):
+        mk = int(alloc[h])
+        top = 2 if mk & 4 else (1 if mk & 2 else (0 if mk & 1 else -1))
+        qk_rows = box[top] if top >= 0 else 0
+        v_rows = N if (top == 2 or not ctx.get_v_box()) else box[1]
+        fwd_min += wl.batch * d * io * (3 * N + 2 * qk_rows + v_rows)
+    work_min = {"forward_transform": fwd_min}
+    return work_min, {
         "forward_transform": ("hbm", 3 * S * N * d * io * 2.0, 9),     # 3 tensors, one read + one write each; 9 launches
         "inverse_transform": ("hbm", S * N * d * io * 2.0, 3),
         "band_attention_fused": ("mfma", sum(attn_flops), 1),
@@ -66,31 +94,65 @@ def algorithmic_work(wl, ctx, alloc):
     }
 
 
-def cpu_baseline(wl, alloc):
-    """Times the fp64 oracle on the host cores on a bounded sample: one head per distinct band mask, on a reduced
-    token grid with the workload's head_dim and band parameters; scaled to whole-forward tokens/s."""
-    import numpy as np
+def cpu_baseline(wl, alloc, q, k, v):
+    """Times the fp64 oracle on the host cores on a bounded sample of the workload itself: one whole head (the
+    workload's own token grid, head_dim and band parameters, the benchmark's own input tensors) per distinct band mask of
+    the allocation.  The whole-forward figure charges every head of the allocation the seconds measured for its mask."""
     from oracle import freqformer as O
-    from paper_2604_22808_amd import workloads as WL
     T, H, W = wl.grid
-    sample_grid = (min(T, 16), min(H, 32), min(W, 64))
-    ns = sample_grid[0] * sample_grid[1] * sample_grid[2]
     cfg = O.BandConfig(**wl.band)
-    masks = sorted(set(int(a) for a in alloc))
-    per_mask = {}
-    for mk in masks:
-        x = [WL.round_to_io(WL.field_numpy(sample_grid, wl.head_dim, wl.seed, s, mk), wl.dtype).reshape(sample_grid + (wl.head_dim,))
-             for s in range(3)]
+    masks = [int(a) for a in alloc]
+    per_mask, sampled = {}, []
+    for h, mk in enumerate(masks):
+        if mk in per_mask:
+            continue
+        x = [t[0, h].to("cpu").double().numpy().reshape(T, H, W, wl.head_dim) for t in (q, k, v)]
         t0 = time.perf_counter()
         O.head_forward(x[0], x[1], x[2], cfg, mk)
         per_mask[mk] = time.perf_counter() - t0
-    total_s = sum(per_mask[int(a)] for a in alloc) * wl.batch      # all heads at sample size
-    tokens = ns * wl.batch
+        sampled.append(h)
+    total_s = sum(per_mask[mk] for mk in masks) * wl.batch
     cores = len(os.sched_getaffinity(0))
-    return {"value": tokens / total_s, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"fp64 numpy oracle, one head per distinct band mask {masks} on a {sample_grid[0]}x{sample_grid[1]}x"
-                      f"{sample_grid[2]} grid ({ns} of {wl.n_tokens} tokens per head) with the workload's head_dim and band "
-                      f"parameters; seconds summed over the {wl.heads} heads of the allocation ({total_s:.2f} s of CPU work)"}
+    return {"value": wl.batch * wl.n_tokens / total_s, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "measured_s": {str(mk): round(sec, 2) for mk, sec in per_mask.items()},
+            "sample": f"fp64 numpy oracle, heads {sampled} of the benchmark's own tensors (one whole head per distinct band "
+                      f"mask {sorted(per_mask)}, full {T}x{H}x{W} grid, {sum(per_mask.values()):.1f} s of CPU work); the "
+                      f"forward's time is extrapolated over the {wl.heads} heads, each charged its mask's measured seconds "
+                      f"({total_s:.1f} s)"}
+
+
+def dense_comparison_256k(steps=3):
+    """The path against plain dense attention on the same tensors at 256K tokens (the 256k workload, router at its
+    t): both through the library's own kernels, in this run."""
+    import torch
+    from paper_2604_22808_amd import binding as B
+    from paper_2604_22808_amd import workloads as WL
+    wl = WL.WORKLOADS["256k"]
+    q, k, v = WL.qkv_torch(wl, "cuda")
+    out = torch.empty_like(q)
+    ctx = B.Context(wl.batch, wl.heads, wl.head_dim, wl.grid, B.BF16, B.make_cfg(**wl.band))
+    router = WL.router_weights(wl.alloc["hidden"], wl.alloc["seed"])
+    for _ in range(3):
+        alloc, _ = ctx.forward_routed(q, k, v, wl.alloc["t"], *router, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ctx.forward_routed(q, k, v, wl.alloc["t"], *router, out)
+    torch.cuda.synchronize()
+    path_ms = 1e3 * (time.perf_counter() - t0) / steps
+    ctx.dense_forward(q, k, v, out)          # warm-up: clocks under matrix load
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.dense_forward(q, k, v, out)
+    torch.cuda.synchronize()
+    dense_ms = 1e3 * (time.perf_counter() - t0)
+    flops = 4.0 * wl.head_dim * float(wl.n_tokens) ** 2 * wl.batch * wl.heads
+    ctx.destroy()
+    return {"workload": "256k", "tokens": wl.n_tokens, "heads": wl.heads, "head_dim": wl.head_dim,
+            "head_alloc_counts": [int((alloc == m).sum()) for m in (1, 2, 4)],
+            "freqattn_ms": round(path_ms, 3), "dense_ms": round(dense_ms, 2),
+            "dense_achieved_TFLOPs": round(flops / (dense_ms * 1e-3) / 1e12, 1),
+            "speedup_of_freqattn": round(dense_ms / path_ms, 1)}
 
 
 def main():
@@ -102,6 +164,7 @@ def main():
     ap.add_argument("--dense", action="store_true", help="also time the dense flash-style baseline (one iteration)")
     ap.add_argument("--separate", action="store_true", help="one launch per branch instead of the fused launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense-256k", action="store_true", help="skip the dense comparison at 256K tokens")
     ap.add_argument("--t", type=float, default=None, help="timestep for the MLP head allocator (default: the workload's)")
     ap.add_argument("--transform", choices=("dct", "haar"), default="dct",
                     help="per-axis transform: the reference design's DCT-II or the Haar wavelet variant")
@@ -166,7 +229,21 @@ def main():
     tokens = wl.batch * wl.n_tokens
     value = tokens / (elapsed / args.steps)
 
-    work = algorithmic_work(wl, ctx, alloc)
+    # the same loop with the allocation prediction off: every forward transforms on the low+mid box first and completes
+    # the heads routed to the high band afterwards (what a call pays whose previous allocation is no guide)
+    ms_no_prediction = None
+    if router is not None:
+        ctx.set_alloc_prediction(False)
+        step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        ms_no_prediction = 1e3 * (time.perf_counter() - t0) / args.steps
+        ctx.set_alloc_prediction(True)
+
+    work_min, work = algorithmic_work(wl, ctx, alloc)
     # the forward transform may be split in two stages (completion of Q~/K~ for the heads routed to the high band)
     merged, extra = [], 0.0
     for name, ms in stages:
@@ -209,18 +286,26 @@ def main():
         achieved, peak, unit = amount / launches / per_launch_s / 1e9, HBM_PEAK_GBS, "GB/s"
     else:
         achieved, peak, unit = amount / launches / per_launch_s / 1e12, MFMA_PEAK_TFLOPS, "TFLOP/s"
-    traffic = MEASURED_TRAFFIC.get(wl.name, {}).get(dom[0]) if args.transform == "dct" else None
+    traffic, traffic_commit = measured_traffic(wl.name, dom[0]) if args.transform == "dct" and args.t is None else (None, None)
     # what this machine sustains for a plain streaming copy and for a loop of the MFMA instruction the kernels use
     copy_bps, mfma_fps = ctx.measure_peaks()
     measured = copy_bps / 1e9 if bound == "hbm" else mfma_fps / 1e12
     roofline = {"bound": bound, "kernel": dom[0], "launches_per_step": launches,
                 "avg_launch_ms": round(per_launch_s * 1e3, 4), "achieved": round(achieved, 2), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": traffic,
+                "frac": round(achieved / peak, 4), "traffic": traffic, "traffic_measured_at_commit": traffic_commit,
                 "measured_peak": round(measured, 1), "frac_of_measured": round(achieved / measured, 4)}
+    if dom[0] in work_min:   # the same stage against the bytes the pruned scheme strictly needs
+        ach_min = work_min[dom[0]] / (dom[1] * 1e-3) / 1e9
+        roofline["achieved_pruned_minimum"] = round(ach_min, 2)
+        roofline["frac_pruned_minimum"] = round(ach_min / peak, 4)
+        roofline["algorithmic_bytes_per_step"] = amount
+        roofline["pruned_minimum_bytes_per_step"] = work_min[dom[0]]
 
     result = {
         "metric": "tokens/s per forward", "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_no_prediction": None if ms_no_prediction is None else round(ms_no_prediction, 4),
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "heads": wl.heads, "head_dim": wl.head_dim,
@@ -246,8 +331,11 @@ def main():
         result["dense_baseline"] = {"ms": round(dense_s * 1e3, 3), "tokens_per_s": round(tokens / dense_s, 1),
                                     "achieved_TFLOPs": round(dflops / dense_s / 1e12, 2),
                                     "speedup_of_freqattn": round(dense_s * 1e3 / ms_per_step, 2)}
+    ctx.destroy()
+    if not args.no_dense_256k:
+        result["dense_256k"] = dense_comparison_256k()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, alloc)
+        result["cpu_baseline"] = cpu_baseline(wl, alloc, q, k, v)
     print(json.dumps(result))
 
 

@@ -75,7 +75,7 @@ def band_statistics_library_transform(q, k, v, grid, band: dict):
         for b in range(Bsz):
             for h in range(nh):
                 c = dctn(np.asarray(x[b, h], dtype=np.float64).reshape(T, H, W, d), type=2, norm="ortho",
-                         axes=(0, 1, 2), workers=16, overwrite_x=True).reshape(N, d)
+                         axes=(0, 1, 2), workers=16).reshape(N, d)
                 for l, idx in enumerate(bands):
                     acc[l] += np.einsum("nc,nc->c", c[idx], c[idx]) if len(idx) else 0.0
     g = np.empty((3, O.ROUTER_DR))
