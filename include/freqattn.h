@@ -104,6 +104,22 @@ freqattn_status freqattn_create(const freqattn_shape* shape /*HOST*/, const freq
 freqattn_status freqattn_forward(freqattn_ctx* ctx, const void* q, const void* k, const void* v,
                                  const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): freqattn_forward with every device buffer the library needs - transform matrices, band and block
+ * tables, spectral scratch, work lists - laid out inside one static device array of 128 MiB (each GPU the library runs
+ * on holds its copy until the process ends).  Calls no hipMalloc, hipFree, hipHostMalloc or event creation.  `ctx` may be
+ * any context, including a FREQATTN_PATH_TABLES_ONLY one, whose freqattn_create touches no device either; a
+ * tables-only context runs on the path FREQATTN_PATH_AUTO would pick.  Arguments, results and error codes as in
+ * freqattn_forward, plus FREQATTN_ENOMEM when the shape needs more than the array holds (the message names the bytes).
+ * The first call for a context (and the first after a call for another context on the same GPU) waits for `stream`,
+ * copies the tables into the array through `stream` and waits again; later calls for the same context only launch
+ * kernels (and, when head_alloc changes, wait for `stream` and upload the new work lists like freqattn_forward).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU - different streams or host
+ * threads - race, and stage timing and freqattn_read_spectral do not apply to these calls. */
+freqattn_status freqattn_forward_static(freqattn_ctx* ctx, const void* q, const void* k, const void* v,
+                                        const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,
+                                        void* stream);
+
 /* Releases everything the context owns.  freqattn_destroy(NULL) is a no-op.  The caller must have synchronised. */
 void freqattn_destroy(freqattn_ctx* ctx);
 

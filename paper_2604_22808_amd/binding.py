@@ -34,6 +34,8 @@ EXPORTS = {
     "freqattn_create": (C.c_int, [C.POINTER(Shape), C.POINTER(BandCfg), C.c_int32, C.POINTER(C.c_void_p)]),
     "freqattn_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(BandCfg),
                                    C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]),
+    "freqattn_forward_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(BandCfg),
+                                          C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]),
     "freqattn_destroy": (None, [C.c_void_p]),
     "freqattn_last_error": (C.c_char_p, [C.c_void_p]),
     "freqattn_set_launch_mode": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -161,6 +163,16 @@ class Context:
         cfg = cfg or self.cfg
         self._check(lib().freqattn_forward(self._h, _ptr(q), _ptr(k), _ptr(v), C.byref(cfg),
                                            ha.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(out), _stream()))
+        return out
+
+    def forward_static(self, q, k, v, head_alloc, out, cfg=None):
+        self._check_tensors("forward_static", q=q, k=k, v=v, out=out)
+        ha = np.ascontiguousarray(head_alloc, dtype=np.int32)
+        if ha.shape != (self.shape.heads,):
+            raise ValueError(f"forward_static: head_alloc must hold {self.shape.heads} entries, got shape {ha.shape}")
+        cfg = cfg or self.cfg
+        self._check(lib().freqattn_forward_static(self._h, _ptr(q), _ptr(k), _ptr(v), C.byref(cfg),
+                                                  ha.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(out), _stream()))
         return out
 
     @staticmethod

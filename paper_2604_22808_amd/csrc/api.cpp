@@ -1,5 +1,6 @@
 // C-ABI entry points of libfreqattn and the host-side orchestration of the hot path.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -47,23 +48,35 @@ static bool mfma_shape_ok(const freqattn_shape& s, const freqattn_band_cfg& g) {
          g.mid_block % 64 == 0;
 }
 
-template <typename T>
-static hipError_t dev_alloc(Ctx& c, T** p, size_t count) {
-  *p = nullptr;
-  if (count == 0) count = 1;
-  hipError_t e = hipMalloc((void**)p, count * sizeof(T));
-  if (e == hipSuccess) c.dev_bytes += (int64_t)(count * sizeof(T));
-  return e;
-}
+// Device memory of a context: hipMalloc, or - for a context that lives in a caller-provided arena (the static scratch
+// of freqattn_forward_static) - the next 256-byte-aligned piece of that arena.  arena_need keeps counting past the end,
+// so that a failed set-up can say how much it would have taken.
 static hipError_t dev_alloc_bytes(Ctx& c, void** p, size_t bytes) {
   *p = nullptr;
   if (bytes == 0) bytes = 16;
+  if (c.arena_base) {
+    const size_t at = (c.arena_need + 255) & ~(size_t)255;
+    c.arena_need = at + bytes;
+    if (c.arena_need > c.arena_cap) return hipErrorOutOfMemory;
+    *p = c.arena_base + at;
+    c.dev_bytes += (int64_t)bytes;
+    return hipSuccess;
+  }
   hipError_t e = hipMalloc(p, bytes);
   if (e == hipSuccess) c.dev_bytes += (int64_t)bytes;
   return e;
 }
+template <typename T>
+static hipError_t dev_alloc(Ctx& c, T** p, size_t count) {
+  return dev_alloc_bytes(c, (void**)p, (count == 0 ? 1 : count) * sizeof(T));
+}
 
 static void free_all(Ctx* c) {
+  if (c->arena_base) {   // nothing was allocated on the device, and the host mirrors are plain memory
+    delete[] c->h_lists;
+    delete[] c->h_stats;
+    return;
+  }
   auto F = [](void* p) { if (p) (void)hipFree(p); };
   F(c->d_perm); F(c->d_perm_t); F(c->d_row_ptr); F(c->d_col_idx);
   for (int a = 0; a < 3; ++a) { F(c->d_F32[a]); F(c->d_Ft32[a]); F(c->d_F16[a]); F(c->d_Ft16[a]); }
@@ -84,9 +97,11 @@ static int items_per_slice_max(const Ctx& c, int rows) {
 
 static int keep_rows(int box, int n);
 
-extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const freqattn_band_cfg* cfg, int32_t path,
-                                           freqattn_ctx** out_ctx) {
-  if (!shape || !cfg || !out_ctx) return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: NULL argument");
+static std::atomic<uint64_t> g_next_uid{1};
+
+// Host half of freqattn_create: argument checks, path resolution and every host table.  No device is touched.
+static freqattn_status host_setup(const freqattn_shape* shape, const freqattn_band_cfg* cfg, int32_t path,
+                                  freqattn_ctx** out_ctx) {
   *out_ctx = nullptr;
   const freqattn_shape& s = *shape;
   const freqattn_band_cfg& g = *cfg;
@@ -147,29 +162,40 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
     for (int o = 0; o < 3; ++o)
       if (o != l) c->n_c[l] += c->m_eff[o];
   }
-  const bool mf = c->path == FREQATTN_PATH_MFMA;
-  if (mf && 2 * g.n_summary > 1024) {
+  if (c->path == FREQATTN_PATH_MFMA && 2 * g.n_summary > 1024) {
     delete c;
     return fail(nullptr, FREQATTN_EUNSUPPORTED, "freqattn_create: n_summary > 512 on the MFMA path");
   }
   c->attn_rows = (g.mid_block % 128 == 0) ? 128 : 64;
-  if (c->path == FREQATTN_PATH_TABLES_ONLY) {
-    *out_ctx = c;
-    return FREQATTN_OK;
-  }
+  c->uid = g_next_uid.fetch_add(1);
+  *out_ctx = c;
+  return FREQATTN_OK;
+}
 
+// Device half of freqattn_create: uploads the tables and carves out the scratch, with hipMalloc or - when the context
+// has an arena - from that arena, in which case the uploads go through `st` (each one waited for, the sources are
+// temporaries) and nothing is allocated, neither pinned host memory nor events (such a context cannot time its stages).
+// On failure the caller releases the context (free_all + delete).
+static hipError_t device_setup(freqattn_ctx* c, hipStream_t st) {
+  const freqattn_shape& s = c->shape;
+  const freqattn_band_cfg& g = c->cfg;
+  const bool mf = c->path == FREQATTN_PATH_MFMA;
+  const bool arena = c->arena_base != nullptr;
   hipDeviceProp_t prop;
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
-    delete c;
-    return fail(nullptr, FREQATTN_EHIP, "freqattn_create: no usable HIP device");
-  }
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorNoDevice;
   c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
   // ---- device tables
   hipError_t e = hipSuccess;
   auto up = [&](void* dst, const void* src, size_t bytes) {
-    if (e == hipSuccess && bytes) e = hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess || !bytes) return;
+    if (arena) {
+      e = hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st);
+      if (e == hipSuccess) e = hipStreamSynchronize(st);
+    } else {
+      e = hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
+    }
   };
   auto A = [&](hipError_t r) { if (e == hipSuccess) e = r; };
   A(dev_alloc(*c, &c->d_perm, (size_t)c->N));
@@ -279,7 +305,10 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
     }
     c->v_full.assign((size_t)c->slices, 1);
   }
-  if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_stats, 3 * c->d * sizeof(float), hipHostMallocDefault);
+  if (e == hipSuccess) {
+    if (arena) { c->h_stats = new (std::nothrow) float[(size_t)3 * c->d]; if (!c->h_stats) e = hipErrorOutOfMemory; }
+    else e = hipHostMalloc((void**)&c->h_stats, 3 * c->d * sizeof(float), hipHostMallocDefault);
+  }
 
   // ---- per-forward lists
   {
@@ -301,9 +330,12 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
     c->off_items_dense = ints; ints += 4 * c->cap_items_xchg;
     c->lists_bytes = ints * 4;
     A(dev_alloc_bytes(*c, (void**)&c->d_lists, c->lists_bytes));
-    if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_lists, c->lists_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) {
+      if (arena) { c->h_lists = new (std::nothrow) int32_t[ints]; if (!c->h_lists) e = hipErrorOutOfMemory; }
+      else e = hipHostMalloc((void**)&c->h_lists, c->lists_bytes, hipHostMallocDefault);
+    }
   }
-  if (e == hipSuccess) {
+  if (e == hipSuccess && !arena) {
     bool all = true;
     for (int t = 0; t < Ctx::MAX_TIMED; ++t)
       for (int i = 0; i <= Ctx::MAX_STAGES; ++i) {
@@ -316,12 +348,26 @@ extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const fr
       }
     c->ev_created = all;
   }
+  return e;
+}
+
+extern "C" freqattn_status freqattn_create(const freqattn_shape* shape, const freqattn_band_cfg* cfg, int32_t path,
+                                           freqattn_ctx** out_ctx) {
+  if (!shape || !cfg || !out_ctx) return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: NULL argument");
+  freqattn_ctx* c = nullptr;
+  freqattn_status fs = host_setup(shape, cfg, path, &c);
+  if (fs != FREQATTN_OK || c->path == FREQATTN_PATH_TABLES_ONLY) {
+    *out_ctx = c;
+    return fs;
+  }
+  const hipError_t e = device_setup(c, nullptr);
   if (e != hipSuccess) {
     const bool oom = (e == hipErrorOutOfMemory);
     std::string msg = std::string("freqattn_create: ") + hipGetErrorString(e);
     free_all(c);
     delete c;
     (void)hipGetLastError();
+    *out_ctx = nullptr;
     return fail(nullptr, oom ? FREQATTN_ENOMEM : FREQATTN_EHIP, msg);
   }
   *out_ctx = c;
@@ -953,17 +999,14 @@ static freqattn_status check_forward_args(freqattn_ctx* c, const void* q, const 
   return FREQATTN_OK;
 }
 
-extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, const void* k, const void* v,
-                                            const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,
-                                            void* stream) {
-  return guarded(c, "freqattn_forward", [&]() -> freqattn_status {
-  if (!c) return FREQATTN_EINVAL;
-  if (!head_alloc) return fail(c, FREQATTN_EINVAL, "freqattn_forward: NULL argument");
-  freqattn_status fs = check_forward_args(c, q, k, v, band_cfg, out, "freqattn_forward");
+static freqattn_status forward_impl(freqattn_ctx* c, const void* q, const void* k, const void* v,
+                                    const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,
+                                    hipStream_t st, const char* who) {
+  if (!head_alloc) return fail(c, FREQATTN_EINVAL, std::string(who) + ": NULL argument");
+  freqattn_status fs = check_forward_args(c, q, k, v, band_cfg, out, who);
   if (fs != FREQATTN_OK) return fs;
   for (int h = 0; h < c->shape.heads; ++h)
-    if (head_alloc[h] < 0 || head_alloc[h] > 7) return fail(c, FREQATTN_EINVAL, "freqattn_forward: head_alloc entry outside 0..7");
-  hipStream_t st = (hipStream_t)stream;
+    if (head_alloc[h] < 0 || head_alloc[h] > 7) return fail(c, FREQATTN_EINVAL, std::string(who) + ": head_alloc entry outside 0..7");
   const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
   fs = ensure_lists(c, head_alloc, st);
   if (fs != FREQATTN_OK) return fs;
@@ -972,6 +1015,82 @@ extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, cons
   if (fs != FREQATTN_OK) return fs;
   tm.done("forward_transform");
   return bands_phase(c, scale, v, out, st, tm);
+}
+
+extern "C" freqattn_status freqattn_forward(freqattn_ctx* c, const void* q, const void* k, const void* v,
+                                            const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,
+                                            void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  return guarded(c, "freqattn_forward", [&]() -> freqattn_status {
+    return forward_impl(c, q, k, v, band_cfg, head_alloc, out, (hipStream_t)stream, "freqattn_forward");
+  });
+}
+
+// ------------------------------------------------------------------------------------------------ static scratch
+// freqattn_forward_static: the same forward with every device buffer - tables, spectral scratch, work lists - inside
+// one file-scope device array instead of memory from hipMalloc.  Each device has its own copy of the array at its own
+// address; the address is looked up once per device.  A shadow context per device holds the carving of the array for
+// the context it last served.
+#define FREQATTN_STATIC_BYTES ((size_t)128 << 20)
+static __device__ __align__(256) unsigned char scratch[FREQATTN_STATIC_BYTES];
+
+namespace {
+struct StaticSlot {
+  char* ptr = nullptr;              // device address of this device's copy of `scratch`
+  freqattn_ctx* shadow = nullptr;   // context whose device pointers point into it
+  uint64_t owner_uid = 0;           // uid of the caller's context the shadow was built for
+};
+constexpr int kMaxDevices = 64;
+StaticSlot g_static[kMaxDevices];
+}  // namespace
+
+extern "C" freqattn_status freqattn_forward_static(freqattn_ctx* c, const void* q, const void* k, const void* v,
+                                                   const freqattn_band_cfg* band_cfg, const int32_t* head_alloc,
+                                                   void* out, void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  return guarded(c, "freqattn_forward_static", [&]() -> freqattn_status {
+    hipStream_t st = (hipStream_t)stream;
+    if (!q || !k || !v || !band_cfg || !head_alloc || !out)
+      return fail(c, FREQATTN_EINVAL, "freqattn_forward_static: NULL argument");
+    if (!same_cfg(*band_cfg, c->cfg))
+      return fail(c, FREQATTN_EINVAL, "freqattn_forward_static: band_cfg differs from the one given to freqattn_create");
+    int dev = 0;
+    HIP_TRY(c, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_static: device index too large");
+    StaticSlot& slot = g_static[dev];
+    if (!slot.ptr) {
+      void* p = nullptr;
+      HIP_TRY(c, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+      if (!p) return fail(c, FREQATTN_EHIP, "freqattn_forward_static: the scratch array has no address on this device");
+      slot.ptr = (char*)p;
+    }
+    if (!slot.shadow || slot.owner_uid != c->uid) {
+      // Another context (or none) owns the carving: wait for whatever still uses the array on this stream, then lay
+      // the new context out in it.  Steady-state calls for one context skip all of this.
+      HIP_TRY(c, hipStreamSynchronize(st));
+      if (slot.shadow) { free_all(slot.shadow); delete slot.shadow; slot.shadow = nullptr; slot.owner_uid = 0; }
+      freqattn_ctx* sh = nullptr;
+      const int32_t path = c->path == FREQATTN_PATH_TABLES_ONLY ? (int32_t)FREQATTN_PATH_AUTO : c->path;
+      freqattn_status fs = host_setup(&c->shape, &c->cfg, path, &sh);
+      if (fs != FREQATTN_OK) return fail(c, fs, std::string("freqattn_forward_static: ") + g_create_error);
+      sh->arena_base = slot.ptr; sh->arena_cap = FREQATTN_STATIC_BYTES; sh->arena_need = 0;
+      const hipError_t e = device_setup(sh, st);
+      if (e != hipSuccess) {
+        const size_t need = sh->arena_need;
+        free_all(sh);
+        delete sh;
+        (void)hipGetLastError();
+        if (e == hipErrorOutOfMemory)
+          return fail(c, FREQATTN_ENOMEM, "freqattn_forward_static: this shape needs at least " + std::to_string(need) +
+                                          " bytes of scratch, the static array holds " + std::to_string(FREQATTN_STATIC_BYTES));
+        return fail(c, FREQATTN_EHIP, std::string("freqattn_forward_static: ") + hipGetErrorString(e));
+      }
+      slot.shadow = sh;
+      slot.owner_uid = c->uid;
+    }
+    const freqattn_status fs = forward_impl(slot.shadow, q, k, v, band_cfg, head_alloc, out, st, "freqattn_forward_static");
+    if (fs != FREQATTN_OK) c->err = slot.shadow->err;
+    return fs;
   });
 }
 

@@ -132,6 +132,9 @@ struct Ctx {
   bool ev_created = false;
 
   int64_t dev_bytes = 0;
+  uint64_t uid = 0;                 // distinct for every context of the process
+  // A context whose device memory is carved out of a caller-provided arena instead of hipMalloc (static scratch)
+  char* arena_base = nullptr; size_t arena_cap = 0, arena_need = 0;
 };
 
 // ---- host tables (tables.cpp) --------------------------------------------------------------------------------
