@@ -84,7 +84,10 @@ typedef enum {
 
 /* Builds the per-axis DCT matrices, band index lists, block list of the mid band and summary chunk bounds (host,
  * then uploaded) and allocates all device scratch on the current HIP device.  `path` is a freqattn_path.
- * Returns EINVAL for non-positive dimensions, edges not satisfying 0 < low < mid <= 1, low_compress < 1,
+ * Band count (the L of the ablation list in section 8): three bands is the reference design; mid edge == low edge leaves
+ * the mid band empty, i.e. two bands (compressed dense low band, windowed high band); mid edge == 1 leaves the high
+ * band empty (low + block-sparse rest).  Four bands are not built.
+ * Returns EINVAL for non-positive dimensions, edges not satisfying 0 < low <= mid <= 1, low_compress < 1,
  * mid_block < 1, mid_stride < 1, mid_diag < 0, high_window < 0, n_summary < 0, unknown dtype or NULL pointers;
  * EUNSUPPORTED if FREQATTN_PATH_MFMA is forced on a shape it cannot run; ENOMEM / EHIP on allocation failure. */
 freqattn_status freqattn_create(const freqattn_shape* shape /*HOST*/, const freqattn_band_cfg* cfg /*HOST*/,
@@ -174,6 +177,11 @@ freqattn_status freqattn_route_fixed(int32_t heads, int32_t n_low, int32_t n_mid
 freqattn_status freqattn_route_mlp(freqattn_ctx* ctx, const void* q, const void* k, const void* v, float t,
                                    int32_t hidden, const float* w1, const float* b1, const float* w2, const float* b2,
                                    int32_t* head_alloc, float pi[3], float* stats_out, void* stream);
+
+/* Load-balancing term of section 3.5: lambda * sum over the three bands of (mean over heads of pi[h][l] - 1/3)^2.
+ * pi_heads HOST [heads][3] (a router with one distribution for all heads repeats it; a hard allocation passes one-hot
+ * rows); *out HOST.  Host only, needs no context.  EINVAL: NULL pointer or heads < 1. */
+freqattn_status freqattn_load_balance(const float* pi_heads, int32_t heads, float lambda, float* out);
 
 /* Whole hot path with the router in the loop (sections 3.2-3.7 including 3.5): transforms Q, K, V once, reduces the
  * band statistics on the device, waits for them (the single host synchronisation of the call), evaluates the MLP

@@ -49,6 +49,7 @@ EXPORTS = {
     "freqattn_summary_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]),
     "freqattn_read_spectral": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.c_void_p]),
     "freqattn_route_fixed": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
+    "freqattn_load_balance": (C.c_int, [C.POINTER(C.c_float), C.c_int32, C.c_float, C.POINTER(C.c_float)]),
     "freqattn_route_mlp": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_int32,
                                      C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float),
                                      C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_float),
@@ -283,6 +284,17 @@ class Context:
         n = C.c_int32()
         self._check(lib().freqattn_stage_times(self._h, 16, names, ms, C.byref(n)))
         return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
+
+
+def load_balance(pi_heads, lam):
+    p = np.ascontiguousarray(pi_heads, dtype=np.float32)
+    if p.ndim != 2 or p.shape[1] != 3:
+        raise ValueError("load_balance: pi_heads must be [heads, 3]")
+    out = C.c_float(0.0)
+    st = lib().freqattn_load_balance(p.ctypes.data_as(C.POINTER(C.c_float)), p.shape[0], float(lam), C.byref(out))
+    if st != OK:
+        raise FreqAttnError(st, "freqattn_load_balance: bad arguments")
+    return float(out.value)
 
 
 def route_fixed(heads, n_low, n_mid, n_high):

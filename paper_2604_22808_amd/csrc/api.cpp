@@ -114,8 +114,8 @@ static freqattn_status host_setup(const freqattn_shape* shape, const freqattn_ba
       (int64_t)s.batch * s.heads * s.T * s.H * s.W > (int64_t)2000000000)
     return fail(nullptr, FREQATTN_EUNSUPPORTED, "freqattn_create: token count too large for 32-bit row indices");
   if (g.low_num < 1 || g.low_den < 1 || g.mid_num < 1 || g.mid_den < 1 ||
-      !((int64_t)g.low_num * g.mid_den < (int64_t)g.mid_num * g.low_den) || g.mid_num > g.mid_den)
-    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: band edges must satisfy 0 < low < mid <= 1");
+      !((int64_t)g.low_num * g.mid_den <= (int64_t)g.mid_num * g.low_den) || g.mid_num > g.mid_den)
+    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: band edges must satisfy 0 < low <= mid <= 1");
   if (g.low_compress < 1 || g.mid_block < 1 || g.mid_stride < 1 || g.mid_diag < 0 || g.high_window < 0 ||
       g.n_summary < 0)
     return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: band operator parameter out of range");
@@ -480,6 +480,19 @@ extern "C" freqattn_status freqattn_route_fixed(int32_t heads, int32_t n_low, in
   for (int i = 0; i < n_low; ++i) head_alloc[h++] = 1;
   for (int i = 0; i < n_mid; ++i) head_alloc[h++] = 2;
   for (int i = 0; i < n_high; ++i) head_alloc[h++] = 4;
+  return FREQATTN_OK;
+}
+
+extern "C" freqattn_status freqattn_load_balance(const float* pi_heads, int32_t heads, float lambda, float* out) {
+  if (!pi_heads || !out || heads < 1) return FREQATTN_EINVAL;
+  double loss = 0.0;
+  for (int l = 0; l < 3; ++l) {
+    double mean = 0.0;
+    for (int h = 0; h < heads; ++h) mean += (double)pi_heads[(size_t)h * 3 + l];
+    mean /= heads;
+    loss += (mean - 1.0 / 3.0) * (mean - 1.0 / 3.0);
+  }
+  *out = (float)((double)lambda * loss);
   return FREQATTN_OK;
 }
 

@@ -144,3 +144,47 @@ def test_generic_path_small_mid_blocks_at_16k(mid_block):
     mx, rl = U.errors(got, want)
     print(f"generic mid_block={mid_block}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
     assert mx <= 2e-2 and rl <= 5e-3
+
+
+@pytest.mark.parametrize("edges", [dict(mid_num=1, mid_den=4), dict(mid_num=1, mid_den=1)])
+def test_two_band_layouts_on_both_paths(edges):
+    """Band count L = 2: the mid band empty (low + windowed rest) or the high band empty (low + block-sparse rest), on
+    the matrix-core path at 16K tokens and on the generic fp32 path."""
+    wl = WL.WORKLOADS["16k"]
+    q, k, v = (WL.round_to_io(x, "bf16") for x in WL.qkv_numpy(wl, heads=[0, 4, 7]))
+    band = dict(wl.band, **edges)
+    ctx = B.Context(1, 3, wl.head_dim, wl.grid, B.BF16, B.make_cfg(**band))
+    assert ctx.get_path() == B.PATH_MFMA and 0 in ctx.band_sizes()
+    alloc = (1, 6, 7)
+    got = U.run_forward(ctx, q, k, v, "bf16", alloc)
+    want = O.forward(q, k, v, wl.grid, O.BandConfig(**band), alloc)
+    for s in range(3):
+        mx, rl = U.errors(got[0, s], want[0, s])
+        print(f"two bands {edges} mask {alloc[s]}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+        assert mx <= 2e-2 and rl <= 5e-3
+    tiny = WL.WORKLOADS["tiny_f32"]
+    q, k, v = (WL.round_to_io(x, "f32") for x in WL.qkv_numpy(tiny))
+    bandt = dict(tiny.band, **edges)
+    ctx = B.Context(1, 2, tiny.head_dim, tiny.grid, B.F32, B.make_cfg(**bandt))
+    got = U.run_forward(ctx, q, k, v, "f32", (7, 3))
+    want = O.forward(q, k, v, tiny.grid, O.BandConfig(**bandt), (7, 3))
+    mx, rl = U.errors(got, want)
+    assert mx <= 1e-5 and rl <= 1e-5
+
+
+def test_paper_dimension_router_hidden_128():
+    """The router at the paper's dimensions (256 -> 128 -> 3: 33,283 parameters, section 3.5) on the 64K grid."""
+    wl = WL.WORKLOADS["64k"]
+    heads = [0, 5, 11, 17, 23]
+    q, k, v = (WL.round_to_io(x, "bf16") for x in WL.qkv_numpy(wl, heads=heads))
+    w = WL.router_weights(128, 3)
+    assert sum(a.size for a in w) == 33283
+    w = (w[0], (0.1 * np.random.default_rng(5).standard_normal(128)).astype(np.float32), w[2], np.array([0.2, -0.1, 0.05], np.float32))
+    ctx, band = U.make_ctx(wl, heads=len(heads))
+    dq, dk, dv = (U.to_device(x, "bf16") for x in (q, k, v))
+    for t in (0.9, 0.3):
+        got_alloc, got_pi, got_stats = ctx.route_mlp(dq, dk, dv, t, *w)
+        want_alloc, want_pi = O.route_mlp(q, k, v, wl.grid, U.oracle_cfg(band), t, *w)
+        assert np.abs(got_pi - want_pi).max() < 2e-3 and np.array_equal(got_alloc, want_alloc)
+        lb = B.load_balance(np.tile(got_pi, (len(heads), 1)), 0.01)
+        assert abs(lb - O.load_balance_loss(np.tile(want_pi, (len(heads), 1)), 0.01)) < 1e-5

@@ -90,7 +90,7 @@ def test_route_fixed():
 
 
 @pytest.mark.parametrize("bad", [dict(low_compress=0), dict(mid_block=0), dict(mid_stride=0), dict(mid_diag=-1),
-                                 dict(high_window=-1), dict(n_summary=-1), dict(low_num=1, low_den=2, mid_num=1, mid_den=2),
+                                 dict(high_window=-1), dict(n_summary=-1), dict(low_num=3, low_den=4, mid_num=1, mid_den=2),
                                  dict(mid_num=3, mid_den=2), dict(low_num=0)])
 def test_create_rejects_bad_band_cfg(bad):
     with pytest.raises(B.FreqAttnError) as e:
@@ -177,3 +177,21 @@ def test_binding_rejects_tensors_the_kernels_could_not_address(monkeypatch):
     with pytest.raises(B.FreqAttnError) as ei:
         ctx.forward(dev(good), dev(good), dev(good), [1, 4], dev(good.clone()))
     assert ei.value.status == B.EUNSUPPORTED
+
+
+def test_two_band_tables_and_load_balance_term():
+    """L = 2 band layouts (an empty mid or high band) give the oracle's lists; the load-balancing term of section 3.5
+    equals the oracle's."""
+    for kw in (dict(mid_num=1, mid_den=4), dict(mid_num=1, mid_den=1)):
+        ctx = tables_ctx((8, 16, 16), **kw)
+        want = O.band_partition(8, 16, 16, O.BandConfig(**kw))
+        assert ctx.band_sizes() == [len(w) for w in want] and 0 in ctx.band_sizes()
+        for l in range(3):
+            assert np.array_equal(ctx.band_index(l).astype(np.int64), want[l])
+    with pytest.raises(B.FreqAttnError):
+        tables_ctx((8, 16, 16), low_num=1, low_den=2, mid_num=1, mid_den=4)      # low edge above the mid edge
+    rng = np.random.default_rng(4)
+    pi = rng.random((24, 3)); pi /= pi.sum(axis=1, keepdims=True)
+    assert abs(B.load_balance(pi, 0.01) - O.load_balance_loss(pi.astype(np.float32), 0.01)) < 1e-9
+    hard = np.eye(3)[[0] * 16 + [1] * 6 + [2] * 2]
+    assert abs(B.load_balance(hard, 1.0) - O.load_balance_loss(hard, 1.0)) < 1e-7

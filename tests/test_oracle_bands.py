@@ -98,3 +98,23 @@ def test_csr_agrees_with_mask_and_is_sorted():
         cols = ci[rp[I]:rp[I + 1]]
         assert list(cols) == sorted(set(cols)) == list(np.nonzero(m[I])[0])
     assert rp[-1] == 177      # 16K benchmark configuration: 28 blocks, 177 active
+
+
+def test_two_band_layouts_are_the_three_band_rule_with_an_empty_band():
+    """Band count L = 2 (ablation list, section 8): mid edge == low edge empties the mid band, mid edge == 1 empties the
+    high band; the partition still covers the grid, and a head allocated to the empty band changes nothing."""
+    grid = (4, 8, 8)
+    two = O.BandConfig(low_num=1, low_den=4, mid_num=1, mid_den=4, mid_block=16, mid_stride=4, high_window=32, n_summary=4)
+    low, mid, high = O.band_partition(*grid, two)
+    ref = O.band_partition(*grid, O.BandConfig())
+    assert len(mid) == 0 and np.array_equal(low, ref[0])
+    assert np.array_equal(high, np.sort(np.concatenate([ref[1], ref[2]])))
+    no_high = O.BandConfig(low_num=1, low_den=4, mid_num=1, mid_den=1, mid_block=16, mid_stride=4, high_window=32, n_summary=4)
+    low2, mid2, high2 = O.band_partition(*grid, no_high)
+    assert len(high2) == 0 and len(low2) + len(mid2) == 256
+    rng = np.random.default_rng(2)
+    q, k, v = (rng.standard_normal((1, 1, 256, 8)) for _ in range(3))
+    assert np.abs(O.forward(q, k, v, grid, two, [2]) - v).max() < 1e-10          # the empty band's operator is a no-op
+    assert np.abs(O.forward(q, k, v, grid, two, [7]) - O.forward(q, k, v, grid, two, [5])).max() < 1e-12
+    assert np.abs(O.forward(q, k, v, grid, two, [5]) - v).max() > 1e-3
+    assert np.abs(O.forward(q, k, v, grid, no_high, [4]) - v).max() < 1e-10
