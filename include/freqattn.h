@@ -100,6 +100,11 @@ freqattn_status freqattn_create(const freqattn_shape* shape /*HOST*/, const freq
  *             bit is clear passes V~ through unchanged on that band (it still contributes summary tokens).
  *   out       DEVICE, same shape and type as q; must not overlap q, k, v
  *   stream    hipStream_t (NULL = default stream)
+ * Range contract of BF16 contexts on the matrix-core path: spectral coefficients are kept in fp16, and an orthonormal
+ * transform can concentrate sqrt(N) * max|x| in one coefficient (the mean of a channel lands in one place), so the
+ * inputs must satisfy sqrt(N) * max|x| < 65504 (|x| < 64 at 2^20 tokens).  A violation is detected on the device -
+ * freqattn_check_range reports it, freqattn_forward_routed and freqattn_route_mlp return FREQATTN_ERANGE by themselves -
+ * and the output of such a forward is not defined.  FREQATTN_F32 contexts and FREQATTN_PATH_GENERIC have no such limit.
  * Asynchronous: work is enqueued on `stream` and the call returns.  The one exception is a call whose head_alloc
  * differs from the previous call's on this context: it first waits for `stream` so that the work lists of earlier
  * calls are no longer in use.  Allocates nothing.  EINVAL: NULL pointer, head_alloc entry outside 0..7, band_cfg
@@ -223,6 +228,11 @@ freqattn_status freqattn_set_alloc_prediction(freqattn_ctx* ctx, int32_t enabled
  * 256 MB last-level cache).  *mfma_flops_per_s HOST: flops per second of a loop of independent
  * v_mfma_f32_32x32x16_f16 on every SIMD.  Either pointer may be NULL.  MFMA path only (FREQATTN_EUNSUPPORTED else). */
 freqattn_status freqattn_measure_peaks(freqattn_ctx* ctx, double* copy_bytes_per_s, double* mfma_flops_per_s, void* stream);
+
+/* Waits for `stream`, then reports whether a forward on this context since the last call met spectral coefficients
+ * outside the fp16 range (see the range contract at freqattn_forward): *out_of_range HOST is set to 1 and
+ * FREQATTN_ERANGE returned if so (the mark is cleared), else 0 and FREQATTN_OK. */
+freqattn_status freqattn_check_range(freqattn_ctx* ctx, int32_t* out_of_range, void* stream);
 
 /* Device bytes owned by the context (tables + scratch). */
 int64_t freqattn_workspace_bytes(const freqattn_ctx* ctx);

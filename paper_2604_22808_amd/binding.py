@@ -63,6 +63,7 @@ EXPORTS = {
     "freqattn_stage_times": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
                                        C.POINTER(C.c_int32)]),
     "freqattn_workspace_bytes": (C.c_int64, [C.c_void_p]),
+    "freqattn_check_range": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.c_void_p]),
     "freqattn_measure_peaks": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
 }
 
@@ -223,6 +224,12 @@ class Context:
 
     def get_path(self):
         return lib().freqattn_get_path(self._h)
+
+    def check_range(self):
+        """Synchronises; raises FreqAttnError (ERANGE) if a forward since the last check left the fp16 range."""
+        flag = C.c_int32(0)
+        self._check(lib().freqattn_check_range(self._h, C.byref(flag), _stream()))
+        return int(flag.value)
 
     def workspace_bytes(self):
         return lib().freqattn_workspace_bytes(self._h)

@@ -81,7 +81,7 @@ static void free_all(Ctx* c) {
   F(c->d_perm); F(c->d_perm_t); F(c->d_row_ptr); F(c->d_col_idx);
   for (int a = 0; a < 3; ++a) { F(c->d_F32[a]); F(c->d_Ft32[a]); F(c->d_F16[a]); F(c->d_Ft16[a]); }
   F(c->specQ); F(c->specK); F(c->specV); F(c->Y); F(c->tmp0); F(c->tmp1);
-  F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_lists); F(c->d_energy_part);
+  F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_range_flag); F(c->d_lists); F(c->d_energy_part);
   F(c->d_tot_part); F(c->d_wsum); F(c->d_vsum_part); F(c->d_pool_part);
   if (c->h_lists) (void)hipHostFree(c->h_lists);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
@@ -263,6 +263,8 @@ static hipError_t device_setup(freqattn_ctx* c, hipStream_t st) {
   A(dev_alloc_bytes(*c, &c->Cbuf, (size_t)c->slices * 3 * 2 * (size_t)std::max(g.n_summary, 1) * c->d * es));
   const size_t stats_floats = (size_t)3 * c->d * (1 + 64);
   A(dev_alloc(*c, &c->d_stats, stats_floats));
+  A(dev_alloc(*c, &c->d_range_flag, 64));
+  if (e == hipSuccess) e = launch_fill_zero((float*)c->d_range_flag, 64, st);   // (a zero float is a zero int)
   if (mf && g.n_summary > 0 && g.n_summary < 64) A(dev_alloc(*c, &c->d_pool_part, (size_t)c->slices * 3 * 128 * c->d));
   if (mf) A(dev_alloc(*c, &c->d_energy_part, (size_t)6 * DCT_MAX_WAVES * 3 * 64));
   if (mf) A(dev_alloc(*c, &c->d_tot_part, (size_t)3 * DCT_MAX_WAVES * 64));
@@ -306,8 +308,8 @@ static hipError_t device_setup(freqattn_ctx* c, hipStream_t st) {
     c->v_full.assign((size_t)c->slices, 1);
   }
   if (e == hipSuccess) {
-    if (arena) { c->h_stats = new (std::nothrow) float[(size_t)3 * c->d]; if (!c->h_stats) e = hipErrorOutOfMemory; }
-    else e = hipHostMalloc((void**)&c->h_stats, 3 * c->d * sizeof(float), hipHostMallocDefault);
+    if (arena) { c->h_stats = new (std::nothrow) float[(size_t)3 * c->d + 1]; if (!c->h_stats) e = hipErrorOutOfMemory; }
+    else e = hipHostMalloc((void**)&c->h_stats, (3 * c->d + 1) * sizeof(float), hipHostMallocDefault);
   }
 
   // ---- per-forward lists
@@ -431,6 +433,22 @@ extern "C" freqattn_status freqattn_measure_peaks(freqattn_ctx* c, double* copy_
   (void)hipEventDestroy(e1);
   if (err != hipSuccess) return fail(c, FREQATTN_EHIP, std::string("freqattn_measure_peaks: ") + hipGetErrorString(err));
   return FREQATTN_OK;
+}
+
+extern "C" freqattn_status freqattn_check_range(freqattn_ctx* c, int32_t* out_of_range, void* stream) {
+  if (!c || !out_of_range) return FREQATTN_EINVAL;
+  *out_of_range = 0;
+  if (c->path == FREQATTN_PATH_TABLES_ONLY) return FREQATTN_OK;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t flag = 0;
+  HIP_TRY(c, hipStreamSynchronize(st));
+  HIP_TRY(c, hipMemcpy(&flag, c->d_range_flag, sizeof(flag), hipMemcpyDeviceToHost));
+  if (flag == 0) return FREQATTN_OK;
+  *out_of_range = 1;
+  HIP_TRY(c, launch_fill_zero((float*)c->d_range_flag, 1, st));
+  HIP_TRY(c, hipStreamSynchronize(st));
+  return fail(c, FREQATTN_ERANGE, "spectral coefficients left the fp16 range of the matrix-core path in a forward since the "
+                                  "last check: the inputs must satisfy sqrt(N) * max|x| < 65504 (or use the fp32 path)");
 }
 
 extern "C" int64_t freqattn_workspace_bytes(const freqattn_ctx* c) { return c ? c->dev_bytes : 0; }
@@ -652,6 +670,7 @@ static hipError_t forward_transform_mfma(Ctx& c, const void* x, void* spec, hipS
   t.in = c.tmp1; t.out = spec; t.M = c.d_F16[0]; t.ldm = T; t.n = T; t.n_out = kt; t.inner = (int64_t)kw * d;
   t.nslab = (int64_t)ns * kh; t.outer = kh; t.slice_list = slice_list;
   t.perm_out = c.d_perm_t; t.perm_k = 1; t.perm_o = W; t.perm_scale = T;
+  t.range_flag = c.d_range_flag;
   if (energy_slot >= 0) {
     t.energy_part = c.d_energy_part + (size_t)energy_slot * DCT_MAX_WAVES * 3 * 64;
     t.en_omul = W; t.en_div = W;  // the tile's other coordinates are (kh, kw)
@@ -730,8 +749,11 @@ static hipError_t inverse_transform(Ctx& c, void* out, const void* v_in, hipStre
     int low[3], mid[3];
     for (int a = 0; a < 3; ++a) { low[a] = keep_rows(c.low_box[a], full[a]); mid[a] = keep_rows(c.mid_box[a], full[a]); }
     const int32_t* L = c.d_lists;
-    if ((e = inverse_transform_mfma(c, out, v_in, st, L + c.off_cls[0], c.n_cls[0], low, true)) != hipSuccess) return e;
-    if ((e = inverse_transform_mfma(c, out, v_in, st, L + c.off_cls[1], c.n_cls[1], mid, true)) != hipSuccess) return e;
+    // (a box that is the whole grid saves nothing, and out = V + F^-1(Y^ - V~) would then cancel most of V against its own
+    // round trip through the fp16 transform: such a class takes the select form)
+    auto boxed = [&](const int* keep) { return keep[0] < T || keep[1] < H || keep[2] < W; };
+    if ((e = inverse_transform_mfma(c, out, v_in, st, L + c.off_cls[0], c.n_cls[0], low, boxed(low))) != hipSuccess) return e;
+    if ((e = inverse_transform_mfma(c, out, v_in, st, L + c.off_cls[1], c.n_cls[1], mid, boxed(mid))) != hipSuccess) return e;
     if ((e = inverse_transform_mfma(c, out, v_in, st, L + c.off_cls[2], c.n_cls[2], full, false)) != hipSuccess) return e;
     return launch_copy_slices(v_in, out, L + c.off_cls[3], c.n_cls[3], c.N * c.d * 2, st);
   }
@@ -1215,7 +1237,13 @@ static freqattn_status router_from_spectral(freqattn_ctx* c, float t, int32_t hi
                                             float* stats_out, hipStream_t st, bool* high_unreliable) {
   const int d = c->d, DR = 64, DT = 64;
   HIP_TRY(c, hipMemcpyAsync(c->h_stats, c->d_stats, 3 * d * sizeof(float), hipMemcpyDeviceToHost, st));
+  HIP_TRY(c, hipMemcpyAsync(c->h_stats + 3 * d, c->d_range_flag, sizeof(int32_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(c, hipStreamSynchronize(st));
+  if (c->h_stats[3 * d] != 0.f) {   // (any set bit pattern of the flag reads as a non-zero float)
+    (void)launch_fill_zero((float*)c->d_range_flag, 1, st);
+    return fail(c, FREQATTN_ERANGE, "spectral coefficients leave the fp16 range of the matrix-core path: the inputs must "
+                                    "satisfy sqrt(N) * max|x| < 65504 (or use the fp32 path)");
+  }
   for (int i = 0; i < 3 * d; ++i)
     if (!std::isfinite(c->h_stats[i]))
       return fail(c, FREQATTN_ERANGE, "router statistics are not finite: the inputs leave the fp16 range of the spectral "

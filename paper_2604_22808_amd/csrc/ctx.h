@@ -81,6 +81,7 @@ struct Ctx {
   void* tmp0 = nullptr; void* tmp1 = nullptr;     // transform ping-pong, 3*slices*N*d
   void* lowQ = nullptr; void* lowK = nullptr; void* lowV = nullptr; void* lowY = nullptr;
   void* Cbuf = nullptr;
+  int32_t* d_range_flag = nullptr;                // set by the scattering transform passes when a coefficient leaves the fp16 range (sticky)
   float* d_stats = nullptr;                       // router statistics [3][d] (+ partial sums of the generic kernel)
   float* d_energy_part = nullptr;                 // per-wave partial sums of the fused statistics (MFMA path)
   float* d_tot_part = nullptr;                    // per-wave partial sums of the inputs' squares (Q, K), MFMA path
@@ -236,6 +237,8 @@ struct DctPassArgs {
   // coordinates of the tile on the two axes the pass does not transform (flat index = u*en_div + v), rows [0, t1) are
   // low, [t1, t2) mid and the rest high, t1 = low_a if u < low_u and v < low_v else 0, t2 likewise from the mid box.
   float* energy_part;
+  // Scatter passes (perm_out set): a lane whose result leaves the fp16 range (or is not finite) stores 1 here.
+  int32_t* range_flag;
   int en_omul, en_div, low_u, low_v, low_a, mid_u, mid_v, mid_a;  // flat index of the tile = o*en_omul + col0/d
 };
 #define DCT_MAX_WAVES 4096   // upper bound of waves in one launch of the DCT pass (sizes energy_part)

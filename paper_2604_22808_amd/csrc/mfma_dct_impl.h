@@ -88,6 +88,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
   const int lrow = lane >> 3, lcol = (lane & 7) * 8;  // this lane's row (within 8) and first column of a row segment
   float en[3][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};  // band x column tile, this lane's rows only
   float te[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // sum of squares of the input, this lane's 8 columns
+  bool out_of_range = false;   // scatter passes: a spectral coefficient that fp16 cannot hold (or a non-finite one)
 
   // Per-tile addressing, computed once per tile: rows of a tile are `stride` elements apart from `base`, except on the
   // band-major side where every row is looked up through the permutation.
@@ -301,6 +302,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
         for (int r = 0; r < 16; ++r) {
           const int row = 8 * (r >> 2) + 4 * g + (r & 3);
           const float val = acc[mt][nt][r];
+          if (PERM_OUT) out_of_range = out_of_range || !(__builtin_fabsf(val) <= 65504.f);
           uint16_t bits;
           if (stage_bf16) bits = dct_f32_to_bf16(val);
           else { const _Float16 hv = (_Float16)val; bits = __builtin_bit_cast(uint16_t, hv); }
@@ -336,6 +338,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
 #pragma unroll
     for (int i = 0; i < NPR; ++i) pcur[i] = pnxt[i];
   }
+  if (PERM_OUT && a.range_flag && out_of_range) *a.range_flag = 1;   // (every writer stores the same value)
   if (ENERGY || TOT) {
     const int gwave = blockIdx.x * DCT_WAVES + wave;
     if (ENERGY) {

@@ -188,3 +188,45 @@ def test_paper_dimension_router_hidden_128():
         assert np.abs(got_pi - want_pi).max() < 2e-3 and np.array_equal(got_alloc, want_alloc)
         lb = B.load_balance(np.tile(got_pi, (len(heads), 1)), 0.01)
         assert abs(lb - O.load_balance_loss(np.tile(want_pi, (len(heads), 1)), 0.01)) < 1e-5
+
+
+def test_inputs_beyond_the_fp16_range_are_reported():
+    """sqrt(N) * mean = 256 * 300 > 65504 at 64K tokens: the DC coefficient does not fit fp16.  The plain forward marks
+    it on the device (freqattn_check_range), the routed forward refuses by itself; the context stays usable, and the same
+    input is fine on the fp32 kernels."""
+    import torch
+    wl = WL.WORKLOADS["64k"]
+    ctx, band = U.make_ctx(wl, heads=2)
+    g = torch.Generator(device="cuda").manual_seed(3)
+    x = torch.randn((1, 2, wl.n_tokens, wl.head_dim), device="cuda", generator=g)
+    ok = (0.5 * x).to(torch.bfloat16)
+    big = (300.0 + x).to(torch.bfloat16)
+    out = torch.empty_like(ok)
+    ctx.forward(ok, ok, ok.clone(), (2, 4), out)
+    assert ctx.check_range() == 0
+    ctx.forward(big, big, big.clone(), (2, 4), out)
+    with pytest.raises(B.FreqAttnError) as e:
+        ctx.check_range()
+    assert e.value.status == B.ERANGE
+    assert ctx.check_range() == 0                       # the mark is cleared by the check
+    w = WL.router_weights(64, 1)
+    with pytest.raises(B.FreqAttnError) as e:
+        ctx.forward_routed(big, big, big.clone(), 0.5, *w, out)
+    assert e.value.status == B.ERANGE
+    alloc, pi = ctx.forward_routed(ok, ok, ok.clone(), 0.5, *w, out)      # still usable
+    torch.cuda.synchronize()
+    assert np.isfinite(pi).all() and torch.isfinite(out.float()).all()
+
+
+def test_ablation_speed_sweep_helper():
+    """The speed sweep over the paper's ablation dimensions (section 8's list) times real forwards: its helper must run a
+    changed configuration end to end and report the mid band's keys per query from the library's own block list."""
+    import torch
+    from paper_2604_22808_amd import sweep
+    wl = WL.WORKLOADS["16k"]
+    sweep.time_forward.inputs = WL.qkv_torch(wl, "cuda")
+    sweep.time_forward.out = torch.empty_like(sweep.time_forward.inputs[0])
+    ms0, keys0 = sweep.time_forward(wl, dict(wl.band), steps=2, warmup=1)
+    ms1, keys1 = sweep.time_forward(wl, dict(wl.band, mid_stride=4, high_window=64), steps=2, warmup=1)
+    assert ms0 > 0 and ms1 > 0 and keys1 > keys0 > 0
+    assert torch.isfinite(sweep.time_forward.out.float()).all()
