@@ -183,6 +183,22 @@ freqattn_status freqattn_route_mlp(freqattn_ctx* ctx, const void* q, const void*
                                    int32_t hidden, const float* w1, const float* b1, const float* w2, const float* b2,
                                    int32_t* head_alloc, float pi[3], float* stats_out, void* stream);
 
+/* The path with the projections of sections 3.1 and 3.7 folded around it: Q = X W_Q, K = X W_K, V = X W_V per head, the
+ * per-head path, then concat(heads) W_O.  The transform acts on the token axes and the projections on channels, so they
+ * commute: X is transformed once instead of Q, K and V, the projections run on spectral rows (Q~ and K~ only on the
+ * rows of the bands a head runs), W_O is applied to the band outputs and one inverse transform of model width follows.
+ *   x, out   DEVICE, contiguous [batch, N, d_model] bf16; out must not overlap x
+ *   wq, wk, wv  DEVICE bf16 [d_model, heads * head_dim] row-major (head h owns columns h*head_dim ..)
+ *   wo       DEVICE bf16 [heads * head_dim, d_model] row-major
+ *   d_model  multiple of 64, at most heads * head_dim
+ * BF16 contexts on the matrix-core path only (FREQATTN_EUNSUPPORTED otherwise).  The first call for a d_model allocates
+ * the model-width buffers (two of batch * N * d_model fp16, the transposed weights) and synchronises; later calls
+ * allocate nothing.  Asynchronous otherwise, like freqattn_forward; the range contract stated there applies to x. */
+freqattn_status freqattn_forward_projected(freqattn_ctx* ctx, const void* x, int32_t d_model, const void* wq,
+                                           const void* wk, const void* wv, const void* wo,
+                                           const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,
+                                           void* stream);
+
 /* Load-balancing term of section 3.5: lambda * sum over the three bands of (mean over heads of pi[h][l] - 1/3)^2.
  * pi_heads HOST [heads][3] (a router with one distribution for all heads repeats it; a hard allocation passes one-hot
  * rows); *out HOST.  Host only, needs no context.  EINVAL: NULL pointer or heads < 1. */

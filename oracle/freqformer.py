@@ -341,6 +341,26 @@ def forward(q, k, v, grid, cfg: BandConfig, head_alloc) -> np.ndarray:
     return out
 
 
+def forward_projected(x, wq, wk, wv, wo, grid, cfg: BandConfig, head_alloc) -> np.ndarray:
+    """The layer around the path (sections 3.1, 3.7): Q = X W_Q, K = X W_K, V = X W_V, split into heads, each head through
+    the path, heads concatenated and multiplied by W_O.  x is [batch, N, d_model]; wq, wk, wv are [d_model, n_h d_k] with
+    head h owning columns h d_k ..; wo is [n_h d_k, d_model].  Written as the definition: project first, then call
+    forward (the library instead transforms X once and projects spectral rows, which is the same map because the
+    transform acts on tokens and the projections on channels)."""
+    x = np.asarray(x, dtype=np.float64)
+    Bsz, N, _ = x.shape
+    nh = len(head_alloc)
+    hd = np.asarray(wq).shape[1]
+    assert hd % nh == 0
+    d = hd // nh
+
+    def split_heads(w):
+        return (x @ np.asarray(w, dtype=np.float64)).reshape(Bsz, N, nh, d).transpose(0, 2, 1, 3)
+
+    y = forward(split_heads(wq), split_heads(wk), split_heads(wv), grid, cfg, head_alloc)
+    return y.transpose(0, 2, 1, 3).reshape(Bsz, N, hd) @ np.asarray(wo, dtype=np.float64)
+
+
 def dense_reference(q, k, v, scale: float | None = None) -> np.ndarray:
     """Plain dense attention over all N tokens of one head (the comparison of section 4: N^2 pairs)."""
     q = np.asarray(q, dtype=np.float64)

@@ -36,6 +36,8 @@ EXPORTS = {
                                    C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]),
     "freqattn_forward_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(BandCfg),
                                           C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]),
+    "freqattn_forward_projected": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.POINTER(BandCfg), C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]),
     "freqattn_destroy": (None, [C.c_void_p]),
     "freqattn_last_error": (C.c_char_p, [C.c_void_p]),
     "freqattn_set_launch_mode": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -165,6 +167,28 @@ class Context:
         cfg = cfg or self.cfg
         self._check(lib().freqattn_forward(self._h, _ptr(q), _ptr(k), _ptr(v), C.byref(cfg),
                                            ha.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(out), _stream()))
+        return out
+
+    def forward_projected(self, x, wq, wk, wv, wo, head_alloc, out, cfg=None):
+        import torch
+        s = self.shape
+        hd = s.heads * s.head_dim
+        if not isinstance(x, torch.Tensor) or x.dim() != 3:
+            raise ValueError("forward_projected: x must be a [batch, N, d_model] tensor")
+        d_model = int(x.shape[2])
+        want = {"x": (s.batch, s.T * s.H * s.W, d_model), "out": (s.batch, s.T * s.H * s.W, d_model),
+                "wq": (d_model, hd), "wk": (d_model, hd), "wv": (d_model, hd), "wo": (hd, d_model)}
+        for name, t in (("x", x), ("out", out), ("wq", wq), ("wk", wk), ("wv", wv), ("wo", wo)):
+            if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.bfloat16 or not t.is_contiguous() \
+                    or tuple(t.shape) != want[name]:
+                raise ValueError(f"forward_projected: {name} must be a contiguous bf16 device tensor of shape {want[name]}")
+        ha = np.ascontiguousarray(head_alloc, dtype=np.int32)
+        if ha.shape != (s.heads,):
+            raise ValueError(f"forward_projected: head_alloc must hold {s.heads} entries")
+        cfg = cfg or self.cfg
+        self._check(lib().freqattn_forward_projected(self._h, _ptr(x), d_model, _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
+                                                     C.byref(cfg), ha.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(out),
+                                                     _stream()))
         return out
 
     def forward_static(self, q, k, v, head_alloc, out, cfg=None):

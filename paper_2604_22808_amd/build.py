@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfreqattn.so")
 SOURCES = ["mfma_dct_plain.hip", "mfma_dct_plain_tot.hip", "mfma_dct_scatter.hip", "mfma_dct_scatter_en.hip",
-           "mfma_dct_gather.hip", "mfma_attn.hip", "mfma_vsum.hip", "api.cpp", "tables.cpp", "generic_kernels.hip", "mfma_dct.hip"]
+           "mfma_dct_gather.hip", "mfma_attn.hip", "mfma_vsum.hip", "mfma_gemm.hip", "api.cpp", "tables.cpp", "generic_kernels.hip", "mfma_dct.hip"]
 
 
 def hipcc() -> str:

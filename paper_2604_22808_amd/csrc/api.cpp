@@ -83,6 +83,10 @@ static void free_all(Ctx* c) {
   F(c->specQ); F(c->specK); F(c->specV); F(c->Y); F(c->tmp0); F(c->tmp1);
   F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_range_flag); F(c->d_lists); F(c->d_energy_part);
   F(c->d_tot_part); F(c->d_wsum); F(c->d_vsum_part); F(c->d_pool_part);
+  F(c->projX); F(c->projZ); F(c->projWq); F(c->projWk); F(c->projWv); F(c->projWo); F(c->proj_ones);
+  F(c->d_gemm_prob); F(c->d_gemm_seg);
+  if (c->h_gemm_prob) (void)hipHostFree(c->h_gemm_prob);
+  if (c->h_gemm_seg) (void)hipHostFree(c->h_gemm_seg);
   if (c->h_lists) (void)hipHostFree(c->h_lists);
   if (c->h_stats) (void)hipHostFree(c->h_stats);
   if (c->ev_created)
@@ -628,6 +632,7 @@ static freqattn_status ensure_lists(freqattn_ctx* c, const int32_t* head_alloc, 
   if (!c->alloc_valid) HIP_TRY(c, up(c->off_items_dense, (size_t)4 * c->n_items_dense));
   c->h_alloc.assign(head_alloc, head_alloc + heads);
   c->alloc_valid = true;
+  c->gemm_tables_valid = false;
   return FREQATTN_OK;
 }
 
@@ -646,10 +651,12 @@ static int keep_rows(int box, int n) {
 // and mid) band needs Q~ and K~ on that box only, and every pass after the first then moves a fraction of the tensor.
 // energy_slot >= 0 adds up the router's band statistics in the T pass, tot_slot >= 0 the input's sum of squares in
 // the W pass.
+// `width` > 0 transforms a tensor of that many channels per token instead of head_dim (the projected forward transforms X,
+// [batch][N][d_model], as `ns` = batch slices).
 static hipError_t forward_transform_mfma(Ctx& c, const void* x, void* spec, hipStream_t st, const int32_t* slice_list,
-                                         int ns, const int keep[3], int energy_slot, int tot_slot) {
+                                         int ns, const int keep[3], int energy_slot, int tot_slot, int width = 0) {
   if (ns <= 0) return hipSuccess;
-  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
+  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = width > 0 ? width : c.d;
   const int kt = keep[0], kh = keep[1], kw = keep[2];
   hipError_t e;
   DctPassArgs a{};
@@ -686,15 +693,19 @@ static hipError_t forward_transform_mfma(Ctx& c, const void* x, void* spec, hipS
 //   delta  (delta = true):  rows are Y - V~ on the active bands and zero elsewhere, restricted to the box keep[] that
 //                           contains the active bands, and the last pass adds the input V:  out = V + F^-1(Y^ - V~),
 //                           which is the same sum because F^-1(V~) = V.
+// `wide` != nullptr: the same three passes on one band-major tensor of `width` channels per token ([ns][N][width], every
+// band read from it; `wide_masks` device [ns], all 7).
 static hipError_t inverse_transform_mfma(Ctx& c, void* out, const void* v_in, hipStream_t st, const int32_t* slice_list,
-                                         int ns, const int keep[3], bool delta) {
+                                         int ns, const int keep[3], bool delta, const void* wide = nullptr, int width = 0,
+                                         const int32_t* wide_masks = nullptr) {
   if (ns <= 0) return hipSuccess;
-  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = c.d;
+  const int T = c.shape.T, H = c.shape.H, W = c.shape.W, d = wide ? width : c.d;
   const int kt = keep[0], kh = keep[1], kw = keep[2];
   hipError_t e;
   DctPassArgs a{};
   a.d = d; a.Ntok = c.N;
-  a.in = c.Y; a.in_alt = c.specV; a.masks = c.d_lists + c.off_masks; a.slice_list = slice_list; a.delta = delta ? 1 : 0;
+  a.in = wide ? wide : c.Y; a.in_alt = wide ? wide : c.specV; a.masks = wide ? wide_masks : c.d_lists + c.off_masks;
+  a.slice_list = slice_list; a.delta = delta ? 1 : 0;
   a.band_off1 = (int32_t)c.band_off[1]; a.band_off2 = (int32_t)c.band_off[2];
   a.perm_in = c.d_perm_t; a.perm_k = 1; a.perm_o = W; a.perm_scale = T;
   a.out = c.tmp1; a.M = c.d_Ft16[0]; a.ldm = T; a.n = kt; a.n_out = T; a.inner = (int64_t)kw * d;
@@ -911,8 +922,10 @@ static freqattn_status complete_qk_for_high(freqattn_ctx* c, const void* q, cons
   return FREQATTN_OK;
 }
 
-static freqattn_status bands_phase(freqattn_ctx* c, float scale, const void* v_in, void* out, hipStream_t st,
-                                   StageTimer& tm) {
+// Sections 3.3-3.6 on the band-major buffers: compression, band operators, expansion, summaries, exchange.  `v_in` is
+// the untransformed V (for the high-band summaries of slices whose V~ stops at the low+mid box), or NULL when V~ exists
+// on the whole grid for every slice.
+static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in, hipStream_t st, StageTimer& tm) {
   const bool mf = c->path == FREQATTN_PATH_MFMA;
   const int is_half = mf ? 1 : 0;
   const int32_t* L = c->d_lists;
@@ -986,7 +999,7 @@ static freqattn_status bands_phase(freqattn_ctx* c, float scale, const void* v_i
         const int mask = c->h_alloc[(size_t)(s % c->shape.heads)];
         for (int l = 0; l < 3; ++l)
           if ((mask & ~(1 << l) & 7) == 0) skip[l][s >> 6] |= 1ull << (s & 63);
-        if (mf && c->v_box_ok && !(mask & 4)) {
+        if (mf && c->v_box_ok && v_in && !(mask & 4)) {
           skip[2][s >> 6] |= 1ull << (s & 63);
           if (mask != 0) { sel[s >> 6] |= 1ull << (s & 63); ++nsel; }
         }
@@ -1017,7 +1030,13 @@ static freqattn_status bands_phase(freqattn_ctx* c, float scale, const void* v_i
     }
     tm.done("exchange");
   }
+  return FREQATTN_OK;
+}
 
+static freqattn_status bands_phase(freqattn_ctx* c, float scale, const void* v_in, void* out, hipStream_t st,
+                                   StageTimer& tm) {
+  freqattn_status fs = bands_core(c, scale, v_in, st, tm);
+  if (fs != FREQATTN_OK) return fs;
   // section 3.7: scatter + inverse transform
   HIP_TRY(c, inverse_transform(*c, out, v_in, st));
   tm.done("inverse_transform");
@@ -1126,6 +1145,165 @@ extern "C" freqattn_status freqattn_forward_static(freqattn_ctx* c, const void* 
     const freqattn_status fs = forward_impl(slot.shadow, q, k, v, band_cfg, head_alloc, out, st, "freqattn_forward_static");
     if (fs != FREQATTN_OK) c->err = slot.shadow->err;
     return fs;
+  });
+}
+
+
+// ------------------------------------------------------------------------------------------------ projected forward
+// Sections 3.1 and 3.7 folded around the path: Q = X W_Q, K = X W_K, V = X W_V, output = concat(heads) W_O.  The
+// transform acts on the token axes, the projections on channels, so F(X W) = F(X) W: X is transformed once (instead of
+// Q, K and V), the projections run on band-major spectral rows - Q~ and K~ only on the rows of the bands a head runs -
+// and W_O is applied to the band outputs before one inverse transform of model width.
+static freqattn_status ensure_projection_buffers(freqattn_ctx* c, int d_model, hipStream_t st) {
+  if (c->proj_d_model == d_model) return FREQATTN_OK;
+  HIP_TRY(c, hipStreamSynchronize(st));
+  auto F = [&](auto*& p) { if (p) { (void)hipFree((void*)p); p = nullptr; } };
+  F(c->projX); F(c->projZ); F(c->projWq); F(c->projWk); F(c->projWv); F(c->projWo); F(c->proj_ones);
+  F(c->d_gemm_prob); F(c->d_gemm_seg);
+  if (c->h_gemm_prob) { (void)hipHostFree(c->h_gemm_prob); c->h_gemm_prob = nullptr; }
+  if (c->h_gemm_seg) { (void)hipHostFree(c->h_gemm_seg); c->h_gemm_seg = nullptr; }
+  c->proj_d_model = 0;
+  c->gemm_tables_valid = false;
+  const int B = c->shape.batch, heads = c->shape.heads, hd = heads * c->d;
+  const size_t wide = (size_t)B * (size_t)c->N * (size_t)d_model * sizeof(half_t);
+  hipError_t e = hipSuccess;
+  auto A = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  A(dev_alloc_bytes(*c, &c->projX, wide));
+  A(dev_alloc_bytes(*c, &c->projZ, wide));
+  A(dev_alloc(*c, &c->projWq, (size_t)hd * d_model));
+  A(dev_alloc(*c, &c->projWk, (size_t)hd * d_model));
+  A(dev_alloc(*c, &c->projWv, (size_t)hd * d_model));
+  A(dev_alloc(*c, &c->projWo, (size_t)hd * d_model));
+  A(dev_alloc(*c, &c->proj_ones, (size_t)B));
+  c->gemm_cap_prob = 3 * B * heads + 3 * B;
+  c->gemm_cap_seg = 3 * B * heads + 3 * B * heads;
+  A(dev_alloc(*c, &c->d_gemm_prob, (size_t)c->gemm_cap_prob));
+  A(dev_alloc(*c, &c->d_gemm_seg, (size_t)c->gemm_cap_seg));
+  if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_gemm_prob, (size_t)c->gemm_cap_prob * sizeof(GemmProblem), hipHostMallocDefault);
+  if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_gemm_seg, (size_t)c->gemm_cap_seg * sizeof(GemmSeg), hipHostMallocDefault);
+  if (e == hipSuccess) {
+    std::vector<int32_t> ones((size_t)B, 7);
+    e = hipMemcpy(c->proj_ones, ones.data(), (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice);
+  }
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(c, e == hipErrorOutOfMemory ? FREQATTN_ENOMEM : FREQATTN_EHIP,
+                std::string("freqattn_forward_projected: ") + hipGetErrorString(e));
+  }
+  c->proj_d_model = d_model;
+  return FREQATTN_OK;
+}
+
+// Problem tables of the three product launches for the current allocation: [Q~ and K~ per (batch, head) on the hull of
+// the head's active bands] [V~ per (batch, head) on every row] [output projection per (batch, band), K running over
+// the heads: band output where the head runs the band, V~ where it passes through].
+static void build_gemm_tables(Ctx& c) {
+  const int B = c.shape.batch, heads = c.shape.heads, d = c.d, dm = c.proj_d_model, hd = heads * d;
+  half_t* X = (half_t*)c.projX;
+  int np = 0, ns = 0;
+  auto add = [&](int launch, half_t* Cp, int ldc, int m, int n, int seg0, int nseg) {
+    c.h_gemm_prob[np] = GemmProblem{Cp, ldc, m, n, seg0, nseg, 0};
+    c.gemm_tiles_max[launch] = std::max(c.gemm_tiles_max[launch], gemm_tiles(m, n));
+    ++np; ++c.gemm_n[launch];
+  };
+  for (int l = 0; l < 3; ++l) { c.gemm_n[l] = 0; c.gemm_tiles_max[l] = 0; }
+  c.gemm_first[0] = 0;
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < heads; ++h) {
+      const int mask = c.h_alloc[(size_t)h];
+      int lo = -1, hi = -1;
+      for (int l = 0; l < 3; ++l)
+        if (((mask >> l) & 1) && c.band_n[l] > 0) { if (lo < 0) lo = l; hi = l; }
+      if (lo < 0) continue;
+      const int64_t r0 = c.band_off[lo], r1 = c.band_off[hi] + c.band_n[hi];
+      const int64_t slice = (int64_t)b * heads + h;
+      for (int which = 0; which < 2; ++which) {
+        const half_t* Wt = (which == 0 ? c.projWq : c.projWk) + (size_t)h * d * dm;
+        half_t* spec = (half_t*)(which == 0 ? c.specQ : c.specK) + (slice * c.N + r0) * d;
+        c.h_gemm_seg[ns] = GemmSeg{X + ((int64_t)b * c.N + r0) * dm, Wt, dm, dm, dm, 0};
+        add(0, spec, d, (int)(r1 - r0), d, ns, 1);
+        ++ns;
+      }
+    }
+  c.gemm_first[1] = np;
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < heads; ++h) {
+      const int64_t slice = (int64_t)b * heads + h;
+      c.h_gemm_seg[ns] = GemmSeg{X + (int64_t)b * c.N * dm, c.projWv + (size_t)h * d * dm, dm, dm, dm, 0};
+      add(1, (half_t*)c.specV + slice * c.N * d, d, (int)c.N, d, ns, 1);
+      ++ns;
+    }
+  c.gemm_first[2] = np;
+  for (int b = 0; b < B; ++b)
+    for (int l = 0; l < 3; ++l) {
+      if (c.band_n[l] <= 0) continue;
+      const int seg0 = ns;
+      for (int h = 0; h < heads; ++h) {
+        const int64_t slice = (int64_t)b * heads + h;
+        const bool active = (c.h_alloc[(size_t)h] >> l) & 1;
+        const half_t* src = (const half_t*)(active ? c.Y : c.specV) + (slice * c.N + c.band_off[l]) * d;
+        c.h_gemm_seg[ns++] = GemmSeg{src, c.projWo + (size_t)h * d, d, hd, d, 0};
+      }
+      add(2, (half_t*)c.projZ + ((int64_t)b * c.N + c.band_off[l]) * dm, dm, (int)c.band_n[l], dm, seg0, heads);
+    }
+}
+
+extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const void* x, int32_t d_model, const void* wq,
+                                                      const void* wk, const void* wv, const void* wo,
+                                                      const freqattn_band_cfg* band_cfg, const int32_t* head_alloc,
+                                                      void* out, void* stream) {
+  if (!c) return FREQATTN_EINVAL;
+  return guarded(c, "freqattn_forward_projected", [&]() -> freqattn_status {
+    if (!x || !wq || !wk || !wv || !wo || !band_cfg || !head_alloc || !out)
+      return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: NULL argument");
+    if (c->path != FREQATTN_PATH_MFMA)
+      return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_projected: needs a context on the matrix-core path");
+    if (!same_cfg(*band_cfg, c->cfg))
+      return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: band_cfg differs from the one given to freqattn_create");
+    if (out == x) return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: out aliases x");
+    const int heads = c->shape.heads, B = c->shape.batch;
+    if (d_model < 64 || d_model % 64 != 0 || (int64_t)d_model > (int64_t)heads * c->d)
+      return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_projected: d_model must be a multiple of 64 and at most "
+                                            "heads * head_dim (the transform passes share the context's scratch)");
+    for (int h = 0; h < heads; ++h)
+      if (head_alloc[h] < 0 || head_alloc[h] > 7) return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: head_alloc entry outside 0..7");
+    hipStream_t st = (hipStream_t)stream;
+    const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
+    freqattn_status fs = ensure_lists(c, head_alloc, st);
+    if (fs != FREQATTN_OK) return fs;
+    fs = ensure_projection_buffers(c, d_model, st);
+    if (fs != FREQATTN_OK) return fs;
+    if (!c->gemm_tables_valid) {
+      // (ensure_lists or ensure_projection_buffers waited for the stream when they invalidated the tables)
+      build_gemm_tables(*c);
+      const int np = c->gemm_first[2] + c->gemm_n[2];
+      int ns = 0;
+      for (int i = 0; i < np; ++i) ns = std::max(ns, c->h_gemm_prob[i].seg0 + c->h_gemm_prob[i].nseg);
+      if (np > 0) HIP_TRY(c, hipMemcpyAsync(c->d_gemm_prob, c->h_gemm_prob, (size_t)np * sizeof(GemmProblem), hipMemcpyHostToDevice, st));
+      if (ns > 0) HIP_TRY(c, hipMemcpyAsync(c->d_gemm_seg, c->h_gemm_seg, (size_t)ns * sizeof(GemmSeg), hipMemcpyHostToDevice, st));
+      c->gemm_tables_valid = true;
+    }
+    StageTimer tm(*c, st);
+    const int hd = heads * c->d;
+    HIP_TRY(c, launch_transpose_bf16_to_f16(wq, c->projWq, d_model, hd, st));
+    HIP_TRY(c, launch_transpose_bf16_to_f16(wk, c->projWk, d_model, hd, st));
+    HIP_TRY(c, launch_transpose_bf16_to_f16(wv, c->projWv, d_model, hd, st));
+    HIP_TRY(c, launch_transpose_bf16_to_f16(wo, c->projWo, hd, d_model, st));
+    tm.done("weights");
+    const int full[3] = {c->shape.T, c->shape.H, c->shape.W};
+    HIP_TRY(c, forward_transform_mfma(*c, x, c->projX, st, nullptr, B, full, -1, -1, d_model));
+    tm.done("x_transform");
+    for (int l = 0; l < 2; ++l)
+      HIP_TRY(c, launch_gemm_nt(c->d_gemm_prob + c->gemm_first[l], c->d_gemm_seg, c->gemm_n[l], c->gemm_tiles_max[l], st));
+    tm.done("qkv_projection");
+    c->v_full.assign((size_t)c->slices, 1);
+    fs = bands_core(c, scale, nullptr, st, tm);
+    if (fs != FREQATTN_OK) return fs;
+    HIP_TRY(c, launch_gemm_nt(c->d_gemm_prob + c->gemm_first[2], c->d_gemm_seg, c->gemm_n[2], c->gemm_tiles_max[2], st));
+    tm.done("o_projection");
+    HIP_TRY(c, inverse_transform_mfma(*c, out, nullptr, st, nullptr, B, full, false, c->projZ, d_model, c->proj_ones));
+    tm.done("inverse_transform");
+    return FREQATTN_OK;
   });
 }
 

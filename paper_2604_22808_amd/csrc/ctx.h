@@ -45,6 +45,10 @@ struct AttnParams {
   const void* denseQ; const void* denseK; const void* denseV; void* denseO;   // fp16
 };
 
+// Matrix products of the projected forward (mfma_gemm.hip): C[i][j] = sum_s sum_k A_s[i][k] B_s[j][k], fp16, K-contiguous.
+struct GemmSeg { const half_t* A; const half_t* B; int32_t lda, ldb, K, pad; };
+struct GemmProblem { half_t* C; int32_t ldc, m, n, seg0, nseg, pad; };
+
 struct Ctx {
   freqattn_shape shape;
   freqattn_band_cfg cfg;
@@ -131,6 +135,18 @@ struct Ctx {
   int n_stages = 0;                               // stages of the last timed forward
   int64_t timed_steps = 0;                        // timed forwards since timing was switched on
   bool ev_created = false;
+
+  // Projected forward (freqattn_forward_projected): buffers allocated at its first call for a model width
+  int proj_d_model = 0;
+  void* projX = nullptr; void* projZ = nullptr;           // X~ and the projected spectral output, [batch][N][d_model] fp16, band-major rows
+  half_t* projWq = nullptr; half_t* projWk = nullptr; half_t* projWv = nullptr;   // [heads*d][d_model]: W^T, K-contiguous
+  half_t* projWo = nullptr;                               // [d_model][heads*d]: W_O^T
+  int32_t* proj_ones = nullptr;                           // [batch] band masks "every band from the first source" of the wide inverse
+  GemmProblem* d_gemm_prob = nullptr; GemmProblem* h_gemm_prob = nullptr;   // device table + pinned mirror
+  GemmSeg* d_gemm_seg = nullptr; GemmSeg* h_gemm_seg = nullptr;
+  int gemm_cap_prob = 0, gemm_cap_seg = 0;
+  int gemm_n[3] = {0, 0, 0}, gemm_first[3] = {0, 0, 0}, gemm_tiles_max[3] = {0, 0, 0};   // launches: Q/K, V, output projection
+  bool gemm_tables_valid = false;                         // built for the current allocation (h_alloc)
 
   int64_t dev_bytes = 0;
   uint64_t uid = 0;                 // distinct for every context of the process
@@ -244,6 +260,9 @@ struct DctPassArgs {
 #define DCT_MAX_WAVES 4096   // upper bound of waves in one launch of the DCT pass (sizes energy_part)
 hipError_t launch_mfma_dct_pass(const DctPassArgs& a, int num_cu, hipStream_t st, int* waves_out = nullptr);
 bool mfma_dct_supported(int n_in, int n_out);
+hipError_t launch_gemm_nt(const GemmProblem* d_probs, const GemmSeg* d_segs, int n_problems, int max_tiles, hipStream_t st);
+hipError_t launch_transpose_bf16_to_f16(const void* in /*[R][Cc] bf16*/, void* out /*[Cc][R] fp16*/, int R, int Cc, hipStream_t st);
+int gemm_tiles(int m, int n);
 hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_items, int rows_per_item, int num_cu,
                             hipStream_t st);
 

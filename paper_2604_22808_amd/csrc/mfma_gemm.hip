@@ -1,0 +1,176 @@
+// Channel-mixing products around the spectral transform (paper sections 3.1 and 3.7: Q = X W_Q, K = X W_K, V = X W_V,
+// concatenated heads times W_O).  The transform acts on the token axes and the projections on the channel axis, so
+// they commute: F(X W) = F(X) W.  This file holds the matrix-core kernel those products run on once X itself has been
+// transformed:
+//
+//   C[i][j] = sum over segments s, sum over k < K_s:  A_s[i][k] * B_s[j][k]
+//
+// with every operand K-contiguous (A_s [m][K_s], row stride lda; B_s [n][K_s], row stride ldb), fp16 in, fp32
+// accumulation, fp16 out.  Segments let one product take its K range from several tensors (the output projection sums
+// over heads whose rows live in per-head buffers, and picks per head the band output or the passed-through V~).
+//
+// Tile: 128 rows of C x 128 columns per workgroup of four waves, K in steps of 64.  Both operand tiles are copied from
+// global memory straight into LDS (16 bytes per lane, rows of 128 bytes, the 16-byte chunks of a row permuted through
+// the source address so that the 16-byte operand reads of 16 consecutive rows hit 16 different bank groups), double
+// buffered, one barrier per step.  A wave owns 32 rows and all 128 columns: C^T = B A^T, so that a lane owns one row
+// of C and its accumulator registers run over columns - the same register layout as the attention kernel's output.
+#include <hip/hip_runtime.h>
+
+#include "ctx.h"
+
+namespace fa {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+
+namespace {
+
+__device__ __forceinline__ void gemm_dma16(const void* src, const half_t* dst) {
+  // one wave-wide copy of 16 bytes per lane into LDS at dst + 16 * lane (dst wave-uniform); issued as assembly so that the
+  // compiler does not order every later LDS read behind it - the kernel waits for its copies itself
+  const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(const __attribute__((address_space(3))) half_t*)dst);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t gemm_pack_h2(float a, float b) {
+  const _Float16 ha = (_Float16)a, hb = (_Float16)b;
+  return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
+}
+
+constexpr int GM = 128, GN = 128, GK = 64;   // tile of C and K step
+
+__global__ void __launch_bounds__(256, 2) k_gemm_nt(const GemmProblem* __restrict__ probs, const GemmSeg* __restrict__ segs) {
+  __shared__ __attribute__((aligned(16))) half_t As[2][GM * GK];
+  __shared__ __attribute__((aligned(16))) half_t Bs[2][GN * GK];
+  const GemmProblem pr = probs[blockIdx.y];
+  const int tiles_n = (pr.n + GN - 1) / GN;
+  const int tiles_m = (pr.m + GM - 1) / GM;
+  if ((int)blockIdx.x >= tiles_m * tiles_n) return;   // (uniform over the workgroup: problems of a launch differ in size)
+  const int m0 = ((int)blockIdx.x / tiles_n) * GM, n0 = ((int)blockIdx.x % tiles_n) * GN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nn = lane & 31, g = lane >> 5;
+  auto fK = [](int r) -> int { return (r >> 1) & 7; };
+
+  // this lane's rows of the copies: instruction i of this wave moves rows (wave*4 + i)*8 + lane/8, chunk lane%8
+  const int lr = lane >> 3, lc = lane & 7;
+  int a_row[4], b_row[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = (wave * 4 + i) * 8 + lr;
+    a_row[i] = m0 + r < pr.m ? m0 + r : pr.m - 1;   // rows past the end repeat the last row; their results are not stored
+    b_row[i] = n0 + r < pr.n ? n0 + r : pr.n - 1;
+  }
+  auto stage = [&](const GemmSeg& sg, int k0, int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = (wave * 4 + i) * 8 + lr;
+      const int chunk = (lc ^ fK(r)) << 3;
+      gemm_dma16(sg.A + (int64_t)a_row[i] * sg.lda + k0 + chunk, As[buf] + (wave * 4 + i) * 8 * GK);
+      gemm_dma16(sg.B + (int64_t)b_row[i] * sg.ldb + k0 + chunk, Bs[buf] + (wave * 4 + i) * 8 * GK);
+    }
+  };
+
+  float16v acc[4];
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+
+  // flattened (segment, k) iteration; the copy of step i+1 is in flight while step i is multiplied
+  int seg_i = 0, k_i = 0;               // position of the step being staged next
+  GemmSeg sg = segs[pr.seg0];
+  int total_steps = 0;
+  for (int s = 0; s < pr.nseg; ++s) total_steps += segs[pr.seg0 + s].K / GK;
+  auto advance = [&]() {
+    k_i += GK;
+    if (k_i >= sg.K) {
+      k_i = 0;
+      ++seg_i;
+      if (seg_i < pr.nseg) sg = segs[pr.seg0 + seg_i];
+    }
+  };
+  if (total_steps > 0) { stage(sg, k_i, 0); advance(); }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  for (int step = 0; step < total_steps; ++step) {
+    const int buf = step & 1;
+    if (step + 1 < total_steps) { stage(sg, k_i, buf ^ 1); advance(); }
+    const half_t* Ab = As[buf] + (32 * wave + nn) * GK;
+    const half_t* Bb = Bs[buf] + nn * GK;
+#pragma unroll
+    for (int ks = 0; ks < GK / 16; ++ks) {
+      const int pos = ((2 * ks + g) ^ fK(nn)) << 3;        // fK(32 w + nn) = fK(32 t + nn) = fK(nn)
+      const half8 rows = *(const half8*)(Ab + pos);
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        const half8 cols = *(const half8*)(Bb + nt * 32 * GK + pos);
+        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(cols, rows, acc[nt], 0, 0, 0);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+
+  // store: lane = row of C, registers = columns; a register swap with the partner lane (lane ^ 32, same row) leaves
+  // every lane with 8 consecutive columns, i.e. 16-byte stores
+  const int row = m0 + 32 * wave + nn;
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      float o[8];   // columns nt*32 + j*16 + g*8 + 0..7
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const uint32_t lo = __float_as_uint(acc[nt][(2 * j) * 4 + b]);
+        const uint32_t hi = __float_as_uint(acc[nt][(2 * j + 1) * 4 + b]);
+        const auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
+        o[b] = __uint_as_float(sw[0]);
+        o[4 + b] = __uint_as_float(sw[1]);
+      }
+      const int col = n0 + nt * 32 + j * 16 + g * 8;
+      if (row < pr.m && col < pr.n) {   // (n is a multiple of 8)
+        uint4v st4;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) st4[b] = gemm_pack_h2(o[2 * b], o[2 * b + 1]);
+        *(uint4v*)(pr.C + (int64_t)row * pr.ldc + col) = st4;
+      }
+    }
+}
+
+// out[c][r] = (fp16) in[r][c] for a bf16 matrix [R][Cc]: the weights arrive [k][n] (n contiguous) and the product wants
+// them K-contiguous.  32 x 32 tiles through LDS.
+__global__ void __launch_bounds__(256) k_transpose_bf16_to_f16(const uint16_t* __restrict__ in, half_t* __restrict__ out, int R, int Cc) {
+  __shared__ half_t tile[32][33];
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  for (int i = ty; i < 32; i += 8) {
+    const int r = r0 + i, c = c0 + tx;
+    float v = 0.f;
+    if (r < R && c < Cc) v = __uint_as_float((uint32_t)in[(int64_t)r * Cc + c] << 16);
+    tile[i][tx] = (half_t)v;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int c = c0 + i, r = r0 + tx;
+    if (r < R && c < Cc) out[(int64_t)c * R + r] = tile[tx][i];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_gemm_nt(const GemmProblem* d_probs, const GemmSeg* d_segs, int n_problems, int max_tiles, hipStream_t st) {
+  if (n_problems <= 0 || max_tiles <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_gemm_nt, dim3((unsigned)max_tiles, (unsigned)n_problems), dim3(256), 0, st, d_probs, d_segs);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_bf16_to_f16(const void* in, void* out, int R, int Cc, hipStream_t st) {
+  if (R <= 0 || Cc <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_transpose_bf16_to_f16, dim3((unsigned)((Cc + 31) / 32), (unsigned)((R + 31) / 32)), dim3(256), 0, st,
+                     (const uint16_t*)in, (half_t*)out, R, Cc);
+  return hipGetLastError();
+}
+
+int gemm_tiles(int m, int n) { return ((m + GM - 1) / GM) * ((n + GN - 1) / GN); }
+
+}  // namespace fa

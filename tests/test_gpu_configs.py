@@ -230,3 +230,40 @@ def test_ablation_speed_sweep_helper():
     ms1, keys1 = sweep.time_forward(wl, dict(wl.band, mid_stride=4, high_window=64), steps=2, warmup=1)
     assert ms0 > 0 and ms1 > 0 and keys1 > keys0 > 0
     assert torch.isfinite(sweep.time_forward.out.float()).all()
+
+
+@pytest.mark.parametrize("name,heads,alloc", [("16k", 8, (1, 1, 2, 2, 2, 4, 4, 7)), ("64k", 6, (1, 2, 4, 3, 0, 6))])
+def test_projected_forward_matches_oracle(name, heads, alloc):
+    """Projections folded around the path (sections 3.1, 3.7): X transformed once, Q~/K~/V~ projected from spectral rows,
+    W_O applied before one inverse transform of model width - against the oracle's project-then-forward definition."""
+    import torch
+    wl = WL.WORKLOADS[name]
+    d, N = wl.head_dim, wl.n_tokens
+    dm = heads * d
+    rng = np.random.default_rng(23)
+    xs = np.stack([WL.field_numpy(wl.grid, d, 5, 0, h) for h in range(heads)], axis=1).reshape(1, N, dm)   # field per channel group
+    x = WL.round_to_io(xs, "bf16")
+    wq, wk, wv = (WL.round_to_io(rng.standard_normal((dm, dm)) / np.sqrt(dm), "bf16") for _ in range(3))
+    wo = WL.round_to_io(rng.standard_normal((dm, dm)) / np.sqrt(dm), "bf16")
+    band = dict(wl.band)
+    ctx = B.Context(1, heads, d, wl.grid, B.BF16, B.make_cfg(**band))
+    dev = lambda a: U.to_device(a, "bf16")
+    dx, dwq, dwk, dwv, dwo = dev(x), dev(wq), dev(wk), dev(wv), dev(wo)
+    out = torch.empty_like(dx)
+    for _ in range(2):           # second call: buffers and tables exist
+        ctx.forward_projected(dx, dwq, dwk, dwv, dwo, alloc, out)
+    torch.cuda.synchronize()
+    assert ctx.check_range() == 0
+    got = U.to_host64(out)
+    want = O.forward_projected(x, wq, wk, wv, wo, wl.grid, O.BandConfig(**band), alloc)
+    mx, rl = U.errors(got, want)
+    print(f"projected {name}: max-abs {mx:.3e} rel-L2 {rl:.3e} (|want| max {np.abs(want).max():.2f})", flush=True)
+    assert mx <= 2e-2 and rl <= 5e-3
+    # another allocation on the same context: new product tables
+    alloc2 = tuple(reversed(alloc))
+    ctx.forward_projected(dx, dwq, dwk, dwv, dwo, alloc2, out)
+    torch.cuda.synchronize()
+    want2 = O.forward_projected(x, wq, wk, wv, wo, wl.grid, O.BandConfig(**band), alloc2)
+    mx, rl = U.errors(U.to_host64(out), want2)
+    print(f"projected {name} second allocation: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+    assert mx <= 2e-2 and rl <= 5e-3

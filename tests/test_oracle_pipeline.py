@@ -131,3 +131,38 @@ def test_interaction_count_closed_form(grid, kw):
     assert O.interaction_count(*grid, cfg, 2) == mid
     if grid == (16, 32, 32):   # 16K configuration: 64^2 low pairs, 177 full blocks, window average 508.4
         assert nbar == 64 and mid == 177 * 64 * 64 and abs((total - 4096 - mid) / n_high - 508.4) < 0.05
+
+
+def test_projected_forward_pins():
+    """Sections 3.1 / 3.7 around the path: (a) the transform commutes with a channel projection, F(X W) = F(X) W, which
+    is what lets X be transformed once; (b) identity weights reduce the projected forward to the plain one on channel
+    slices; (c) with no active band it is X W_V W_O; (d) per-head loops over explicitly sliced weights give the same."""
+    grid, nh, d = (4, 8, 8), 3, 8
+    N, dm = 256, 24
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((2, N, dm))
+    wq, wk, wv = (rng.standard_normal((dm, nh * d)) / np.sqrt(dm) for _ in range(3))
+    wo = rng.standard_normal((nh * d, dm)) / np.sqrt(nh * d)
+    cfg = O.BandConfig(mid_block=16, mid_stride=4, high_window=32, n_summary=4)
+    # (a)
+    xs = O.spectral_forward(x[0].reshape(*grid, dm))
+    assert np.abs(O.spectral_forward((x[0] @ wq).reshape(*grid, nh * d)) - xs @ wq).max() < 1e-10
+    # (b)
+    eye = np.eye(dm)
+    alloc = (1, 6, 7)
+    got = O.forward_projected(x, eye, eye, eye, eye, grid, cfg, alloc)
+    heads = x.reshape(2, N, nh, d).transpose(0, 2, 1, 3)
+    want = O.forward(heads, heads, heads, grid, cfg, alloc).transpose(0, 2, 1, 3).reshape(2, N, dm)
+    assert np.abs(got - want).max() < 1e-12
+    # (c)
+    assert np.abs(O.forward_projected(x, wq, wk, wv, wo, grid, cfg, (0, 0, 0)) - x @ wv @ wo).max() < 1e-10
+    # (d)
+    got = O.forward_projected(x, wq, wk, wv, wo, grid, cfg, alloc)
+    want = np.zeros((2, N, dm))
+    for b in range(2):
+        for h in range(nh):
+            sl = slice(h * d, (h + 1) * d)
+            f = lambda w: (x[b] @ w[:, sl]).reshape(*grid, d)
+            want[b] += O.head_forward(f(wq), f(wk), f(wv), cfg, alloc[h]).reshape(N, d) @ wo[sl]
+    assert np.abs(got - want).max() < 1e-10
+    assert np.abs(got - x @ wv @ wo).max() > 1e-3
