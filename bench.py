@@ -155,6 +155,75 @@ def dense_comparison_256k(steps=3):
             "speedup_of_freqattn": round(dense_ms / path_ms, 1)}
 
 
+def projected_comparison(wl, alloc, steps=3):
+    """The layer around the path (sections 3.1, 3.7) at the workload's shape, two ways, same tensors, same run:
+    unfolded - Q, K, V projected in token space (torch.matmul, i.e. the vendor GEMM a model would call), the q/k/v path,
+    output projection; folded - freqattn_forward_projected (X transformed once, projections on spectral rows)."""
+    import torch
+    from paper_2604_22808_amd import binding as B
+    from paper_2604_22808_amd import workloads as WL
+    N, heads, d = wl.n_tokens, wl.heads, wl.head_dim
+    dm = heads * d
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    q, _, _ = WL.qkv_torch(wl, "cuda")                         # [1, heads, N, d]: used as X's channel groups
+    x = q.permute(0, 2, 1, 3).reshape(wl.batch, N, dm).contiguous()
+    del q
+    w = [(torch.randn((dm, dm), device="cuda", generator=gen) / dm ** 0.5).to(torch.bfloat16) for _ in range(4)]
+    ctx = B.Context(wl.batch, heads, d, wl.grid, B.BF16, B.make_cfg(**wl.band))
+    out = torch.empty_like(x)
+
+    def folded():
+        ctx.forward_projected(x, w[0], w[1], w[2], w[3], alloc, out)
+
+    def timed(fn):
+        fn(); fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t0) / steps
+
+    folded_ms = timed(folded)
+    ctx.set_stage_timing(True)
+    for _ in range(steps):
+        folded()
+    torch.cuda.synchronize()
+    stages = {name: round(ms, 3) for name, ms in ctx.stage_times()}
+    ctx.set_stage_timing(False)
+    y = torch.empty((wl.batch, heads, N, d), device="cuda", dtype=torch.bfloat16)
+
+    def heads_of(t):
+        return t.reshape(wl.batch, N, heads, d).permute(0, 2, 1, 3).contiguous()
+
+    parts = {}
+
+    def unfolded():
+        t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+        t2 = torch.cuda.Event(enable_timing=True); t3 = torch.cuda.Event(enable_timing=True)
+        t0.record()
+        qh, kh, vh = (heads_of(x @ w[i]) for i in range(3))
+        t1.record()
+        ctx.forward(qh, kh, vh, alloc, y)
+        t2.record()
+        torch.matmul(y.permute(0, 2, 1, 3).reshape(wl.batch, N, dm), w[3], out=out)
+        t3.record()
+        parts["ev"] = (t0, t1, t2, t3)
+
+    unfolded_ms = timed(unfolded)
+    torch.cuda.synchronize()
+    t0, t1, t2, t3 = parts["ev"]
+    res = {"workload": wl.name, "d_model": dm, "head_alloc": [int(a) for a in alloc],
+           "folded_ms": round(folded_ms, 3), "folded_stages_ms": stages,
+           "unfolded_ms": round(unfolded_ms, 3),
+           "unfolded_stages_ms": {"qkv_projection_and_head_split (torch)": round(t0.elapsed_time(t1), 3),
+                                  "freqattn_forward": round(t1.elapsed_time(t2), 3),
+                                  "head_merge_and_o_projection (torch)": round(t2.elapsed_time(t3), 3)},
+           "speedup_of_folding": round(unfolded_ms / folded_ms, 3)}
+    ctx.destroy()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -165,6 +234,7 @@ def main():
     ap.add_argument("--separate", action="store_true", help="one launch per branch instead of the fused launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-256k", action="store_true", help="skip the dense comparison at 256K tokens")
+    ap.add_argument("--no-projected", action="store_true", help="skip the folded-projection comparison")
     ap.add_argument("--t", type=float, default=None, help="timestep for the MLP head allocator (default: the workload's)")
     ap.add_argument("--transform", choices=("dct", "haar"), default="dct",
                     help="per-axis transform: the reference design's DCT-II or the Haar wavelet variant")
@@ -332,6 +402,11 @@ def main():
                                     "achieved_TFLOPs": round(dflops / dense_s / 1e12, 2),
                                     "speedup_of_freqattn": round(dense_s * 1e3 / ms_per_step, 2)}
     ctx.destroy()
+    if not args.no_projected:
+        del out
+        torch.cuda.empty_cache()
+        result["projected"] = projected_comparison(wl, alloc)
+        out = None
     if not args.no_dense_256k:
         result["dense_256k"] = dense_comparison_256k()
     if not args.no_cpu_baseline:

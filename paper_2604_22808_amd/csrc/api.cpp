@@ -1194,46 +1194,52 @@ static freqattn_status ensure_projection_buffers(freqattn_ctx* c, int d_model, h
   return FREQATTN_OK;
 }
 
-// Problem tables of the three product launches for the current allocation: [Q~ and K~ per (batch, head) on the hull of
-// the head's active bands] [V~ per (batch, head) on every row] [output projection per (batch, band), K running over
-// the heads: band output where the head runs the band, V~ where it passes through].
-static void build_gemm_tables(Ctx& c) {
+// Problem tables of the product launches for the current allocation.  A launch takes problems with the same rows of
+// A: [Q~ and K~ of all heads with the same hull of active bands, per batch entry] [V~ of all heads on every row, per
+// batch entry] [output projection per (batch, band), K running over the heads: band output where the head runs the
+// band, V~ where it passes through].
+static int build_gemm_tables(Ctx& c) {
   const int B = c.shape.batch, heads = c.shape.heads, d = c.d, dm = c.proj_d_model, hd = heads * d;
   half_t* X = (half_t*)c.projX;
   int np = 0, ns = 0;
-  auto add = [&](int launch, half_t* Cp, int ldc, int m, int n, int seg0, int nseg) {
-    c.h_gemm_prob[np] = GemmProblem{Cp, ldc, m, n, seg0, nseg, 0};
-    c.gemm_tiles_max[launch] = std::max(c.gemm_tiles_max[launch], gemm_tiles(m, n));
-    ++np; ++c.gemm_n[launch];
+  c.gemm_groups.clear();
+  auto hull = [&](int h, int64_t& r0, int64_t& r1) -> bool {
+    const int mask = c.h_alloc[(size_t)h];
+    int lo = -1, hi = -1;
+    for (int l = 0; l < 3; ++l)
+      if (((mask >> l) & 1) && c.band_n[l] > 0) { if (lo < 0) lo = l; hi = l; }
+    if (lo < 0) return false;
+    r0 = c.band_off[lo]; r1 = c.band_off[hi] + c.band_n[hi];
+    return true;
   };
-  for (int l = 0; l < 3; ++l) { c.gemm_n[l] = 0; c.gemm_tiles_max[l] = 0; }
-  c.gemm_first[0] = 0;
-  for (int b = 0; b < B; ++b)
-    for (int h = 0; h < heads; ++h) {
-      const int mask = c.h_alloc[(size_t)h];
-      int lo = -1, hi = -1;
-      for (int l = 0; l < 3; ++l)
-        if (((mask >> l) & 1) && c.band_n[l] > 0) { if (lo < 0) lo = l; hi = l; }
-      if (lo < 0) continue;
-      const int64_t r0 = c.band_off[lo], r1 = c.band_off[hi] + c.band_n[hi];
-      const int64_t slice = (int64_t)b * heads + h;
-      for (int which = 0; which < 2; ++which) {
-        const half_t* Wt = (which == 0 ? c.projWq : c.projWk) + (size_t)h * d * dm;
-        half_t* spec = (half_t*)(which == 0 ? c.specQ : c.specK) + (slice * c.N + r0) * d;
-        c.h_gemm_seg[ns] = GemmSeg{X + ((int64_t)b * c.N + r0) * dm, Wt, dm, dm, dm, 0};
-        add(0, spec, d, (int)(r1 - r0), d, ns, 1);
-        ++ns;
+  for (int b = 0; b < B; ++b) {
+    std::vector<char> done((size_t)heads, 0);
+    for (int h0 = 0; h0 < heads; ++h0) {
+      int64_t r0, r1;
+      if (done[(size_t)h0] || !hull(h0, r0, r1)) continue;
+      const int first = np;
+      for (int h = h0; h < heads; ++h) {
+        int64_t q0, q1;
+        if (done[(size_t)h] || !hull(h, q0, q1) || q0 != r0 || q1 != r1) continue;
+        done[(size_t)h] = 1;
+        const int64_t slice = (int64_t)b * heads + h;
+        for (int which = 0; which < 2; ++which) {
+          const half_t* Wt = (which == 0 ? c.projWq : c.projWk) + (size_t)h * d * dm;
+          half_t* spec = (half_t*)(which == 0 ? c.specQ : c.specK) + (slice * c.N + r0) * d;
+          c.h_gemm_seg[ns] = GemmSeg{X + ((int64_t)b * c.N + r0) * dm, Wt, dm, dm, dm, 0};
+          c.h_gemm_prob[np++] = GemmProblem{spec, d, (int)(r1 - r0), d, ns++, 1, 0};
+        }
       }
+      c.gemm_groups.push_back({first, np - first, (int)(r1 - r0), d, 0});
     }
-  c.gemm_first[1] = np;
-  for (int b = 0; b < B; ++b)
+    const int first = np;
     for (int h = 0; h < heads; ++h) {
       const int64_t slice = (int64_t)b * heads + h;
       c.h_gemm_seg[ns] = GemmSeg{X + (int64_t)b * c.N * dm, c.projWv + (size_t)h * d * dm, dm, dm, dm, 0};
-      add(1, (half_t*)c.specV + slice * c.N * d, d, (int)c.N, d, ns, 1);
-      ++ns;
+      c.h_gemm_prob[np++] = GemmProblem{(half_t*)c.specV + slice * c.N * d, d, (int)c.N, d, ns++, 1, 0};
     }
-  c.gemm_first[2] = np;
+    c.gemm_groups.push_back({first, heads, (int)c.N, d, 0});
+  }
   for (int b = 0; b < B; ++b)
     for (int l = 0; l < 3; ++l) {
       if (c.band_n[l] <= 0) continue;
@@ -1244,8 +1250,11 @@ static void build_gemm_tables(Ctx& c) {
         const half_t* src = (const half_t*)(active ? c.Y : c.specV) + (slice * c.N + c.band_off[l]) * d;
         c.h_gemm_seg[ns++] = GemmSeg{src, c.projWo + (size_t)h * d, d, hd, d, 0};
       }
-      add(2, (half_t*)c.projZ + ((int64_t)b * c.N + c.band_off[l]) * dm, dm, (int)c.band_n[l], dm, seg0, heads);
+      c.h_gemm_prob[np] = GemmProblem{(half_t*)c.projZ + ((int64_t)b * c.N + c.band_off[l]) * dm, dm, (int)c.band_n[l], dm, seg0, heads, 0};
+      c.gemm_groups.push_back({np, 1, (int)c.band_n[l], dm, 1});
+      ++np;
     }
+  return np;
 }
 
 extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const void* x, int32_t d_model, const void* wq,
@@ -1275,8 +1284,7 @@ extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const voi
     if (fs != FREQATTN_OK) return fs;
     if (!c->gemm_tables_valid) {
       // (ensure_lists or ensure_projection_buffers waited for the stream when they invalidated the tables)
-      build_gemm_tables(*c);
-      const int np = c->gemm_first[2] + c->gemm_n[2];
+      const int np = build_gemm_tables(*c);
       int ns = 0;
       for (int i = 0; i < np; ++i) ns = std::max(ns, c->h_gemm_prob[i].seg0 + c->h_gemm_prob[i].nseg);
       if (np > 0) HIP_TRY(c, hipMemcpyAsync(c->d_gemm_prob, c->h_gemm_prob, (size_t)np * sizeof(GemmProblem), hipMemcpyHostToDevice, st));
@@ -1293,13 +1301,14 @@ extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const voi
     const int full[3] = {c->shape.T, c->shape.H, c->shape.W};
     HIP_TRY(c, forward_transform_mfma(*c, x, c->projX, st, nullptr, B, full, -1, -1, d_model));
     tm.done("x_transform");
-    for (int l = 0; l < 2; ++l)
-      HIP_TRY(c, launch_gemm_nt(c->d_gemm_prob + c->gemm_first[l], c->d_gemm_seg, c->gemm_n[l], c->gemm_tiles_max[l], st));
+    for (const Ctx::GemmGroup& gg : c->gemm_groups)
+      if (gg.stage == 0) HIP_TRY(c, launch_gemm_nt(c->d_gemm_prob + gg.first, c->d_gemm_seg, gg.per, gg.m, gg.n, st));
     tm.done("qkv_projection");
     c->v_full.assign((size_t)c->slices, 1);
     fs = bands_core(c, scale, nullptr, st, tm);
     if (fs != FREQATTN_OK) return fs;
-    HIP_TRY(c, launch_gemm_nt(c->d_gemm_prob + c->gemm_first[2], c->d_gemm_seg, c->gemm_n[2], c->gemm_tiles_max[2], st));
+    for (const Ctx::GemmGroup& gg : c->gemm_groups)
+      if (gg.stage == 1) HIP_TRY(c, launch_gemm_nt(c->d_gemm_prob + gg.first, c->d_gemm_seg, gg.per, gg.m, gg.n, st));
     tm.done("o_projection");
     HIP_TRY(c, inverse_transform_mfma(*c, out, nullptr, st, nullptr, B, full, false, c->projZ, d_model, c->proj_ones));
     tm.done("inverse_transform");

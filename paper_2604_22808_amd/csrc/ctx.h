@@ -145,7 +145,8 @@ struct Ctx {
   GemmProblem* d_gemm_prob = nullptr; GemmProblem* h_gemm_prob = nullptr;   // device table + pinned mirror
   GemmSeg* d_gemm_seg = nullptr; GemmSeg* h_gemm_seg = nullptr;
   int gemm_cap_prob = 0, gemm_cap_seg = 0;
-  int gemm_n[3] = {0, 0, 0}, gemm_first[3] = {0, 0, 0}, gemm_tiles_max[3] = {0, 0, 0};   // launches: Q/K, V, output projection
+  struct GemmGroup { int first, per, m, n, stage; };       // one launch: problems [first, first + per) of equal m, n and A rows
+  std::vector<GemmGroup> gemm_groups;                     // stage 0: Q~/K~ and V~ projections, stage 1: output projection
   bool gemm_tables_valid = false;                         // built for the current allocation (h_alloc)
 
   int64_t dev_bytes = 0;
@@ -260,9 +261,8 @@ struct DctPassArgs {
 #define DCT_MAX_WAVES 4096   // upper bound of waves in one launch of the DCT pass (sizes energy_part)
 hipError_t launch_mfma_dct_pass(const DctPassArgs& a, int num_cu, hipStream_t st, int* waves_out = nullptr);
 bool mfma_dct_supported(int n_in, int n_out);
-hipError_t launch_gemm_nt(const GemmProblem* d_probs, const GemmSeg* d_segs, int n_problems, int max_tiles, hipStream_t st);
+hipError_t launch_gemm_nt(const GemmProblem* d_probs, const GemmSeg* d_segs, int per, int m, int n, hipStream_t st);
 hipError_t launch_transpose_bf16_to_f16(const void* in /*[R][Cc] bf16*/, void* out /*[Cc][R] fp16*/, int R, int Cc, hipStream_t st);
-int gemm_tiles(int m, int n);
 hipError_t launch_mfma_attn(const AttnParams& p, const AttnItem* items, int n_items, int rows_per_item, int num_cu,
                             hipStream_t st);
 

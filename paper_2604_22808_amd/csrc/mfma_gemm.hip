@@ -39,14 +39,20 @@ __device__ __forceinline__ uint32_t gemm_pack_h2(float a, float b) {
 
 constexpr int GM = 128, GN = 128, GK = 64;   // tile of C and K step
 
-__global__ void __launch_bounds__(256, 2) k_gemm_nt(const GemmProblem* __restrict__ probs, const GemmSeg* __restrict__ segs) {
+// A launch runs `per` problems that share m, n and - in the callers here - their A rows (the same spectral rows
+// projected with different heads' weights).  Workgroups are dealt to the 8 XCDs round-robin by blockIdx and each XCD has
+// its own L2: XCD x takes the row tiles x, x + 8, ... and walks, for each of them, all column tiles of all problems
+// back to back, so that a row tile of A is fetched into one L2 once and reused tiles_n * per times.
+__global__ void __launch_bounds__(256, 2) k_gemm_nt(const GemmProblem* __restrict__ probs, const GemmSeg* __restrict__ segs,
+                                                    int per, int tiles_m, int tiles_n) {
   __shared__ __attribute__((aligned(16))) half_t As[2][GM * GK];
   __shared__ __attribute__((aligned(16))) half_t Bs[2][GN * GK];
-  const GemmProblem pr = probs[blockIdx.y];
-  const int tiles_n = (pr.n + GN - 1) / GN;
-  const int tiles_m = (pr.m + GM - 1) / GM;
-  if ((int)blockIdx.x >= tiles_m * tiles_n) return;   // (uniform over the workgroup: problems of a launch differ in size)
-  const int m0 = ((int)blockIdx.x / tiles_n) * GM, n0 = ((int)blockIdx.x % tiles_n) * GN;
+  const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+  const int inner_n = tiles_n * per;
+  const int mt = (seq / inner_n) * 8 + xcd, inner = seq % inner_n;
+  if (mt >= tiles_m) return;   // (uniform over the workgroup: the grid is padded to whole rounds of 8 row tiles)
+  const GemmProblem pr = probs[inner / tiles_n];
+  const int m0 = mt * GM, n0 = (inner % tiles_n) * GN;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nn = lane & 31, g = lane >> 5;
   auto fK = [](int r) -> int { return (r >> 1) & 7; };
@@ -158,9 +164,13 @@ __global__ void __launch_bounds__(256) k_transpose_bf16_to_f16(const uint16_t* _
 
 }  // namespace
 
-hipError_t launch_gemm_nt(const GemmProblem* d_probs, const GemmSeg* d_segs, int n_problems, int max_tiles, hipStream_t st) {
-  if (n_problems <= 0 || max_tiles <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_gemm_nt, dim3((unsigned)max_tiles, (unsigned)n_problems), dim3(256), 0, st, d_probs, d_segs);
+// `per` problems d_probs[0 .. per) of identical m and n (host-checked by the caller).
+hipError_t launch_gemm_nt(const GemmProblem* d_probs, const GemmSeg* d_segs, int per, int m, int n, hipStream_t st) {
+  if (per <= 0 || m <= 0 || n <= 0) return hipSuccess;
+  const int tiles_m = (m + GM - 1) / GM, tiles_n = (n + GN - 1) / GN;
+  const int64_t blocks = (int64_t)((tiles_m + 7) / 8) * 8 * tiles_n * per;
+  if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_gemm_nt, dim3((unsigned)blocks), dim3(256), 0, st, d_probs, d_segs, per, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
@@ -170,7 +180,5 @@ hipError_t launch_transpose_bf16_to_f16(const void* in, void* out, int R, int Cc
                      (const uint16_t*)in, (half_t*)out, R, Cc);
   return hipGetLastError();
 }
-
-int gemm_tiles(int m, int n) { return ((m + GM - 1) / GM) * ((n + GN - 1) / GN); }
 
 }  // namespace fa
