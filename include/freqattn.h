@@ -137,6 +137,12 @@ const char* freqattn_last_error(const freqattn_ctx* ctx);
 /* FREQATTN_LAUNCH_FUSED (default): low, mid and high work items run in one persistent launch (section 6.2).
  * FREQATTN_LAUNCH_SEPARATE: one launch per branch (the unfused comparison of section 6.6). */
 freqattn_status freqattn_set_launch_mode(freqattn_ctx* ctx, int32_t mode);
+/* Cross-band exchange (section 3.6) inside the band items (default, enabled = 1): a slice that runs a single band gets
+ * its summary tokens from the passed-through V~ of the other bands, which exist before the band operators run, so the
+ * item that computes a tile of the band's output goes on to attend to them and adds the residual without the output
+ * leaving the registers; slices that run several bands use the separate exchange launch.  enabled = 0: the separate
+ * launch for every slice.  Results are bit-identical either way.  MFMA path; ignored on the generic path. */
+freqattn_status freqattn_set_exchange_fusion(freqattn_ctx* ctx, int32_t enabled);
 /* Returns the path the context resolved to (FREQATTN_PATH_GENERIC or FREQATTN_PATH_MFMA). */
 int32_t freqattn_get_path(const freqattn_ctx* ctx);
 /* 1 when the context computes V~ of a slice that does not run the high band on the low+mid box only (MFMA path, grids

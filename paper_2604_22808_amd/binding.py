@@ -42,6 +42,7 @@ EXPORTS = {
     "freqattn_last_error": (C.c_char_p, [C.c_void_p]),
     "freqattn_set_launch_mode": (C.c_int, [C.c_void_p, C.c_int32]),
     "freqattn_get_path": (C.c_int32, [C.c_void_p]),
+    "freqattn_set_exchange_fusion": (C.c_int, [C.c_void_p, C.c_int32]),
     "freqattn_set_alloc_prediction": (C.c_int, [C.c_void_p, C.c_int32]),
     "freqattn_band_sizes": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "freqattn_band_index": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
@@ -242,6 +243,9 @@ class Context:
     # ---- options and introspection
     def set_launch_mode(self, mode):
         self._check(lib().freqattn_set_launch_mode(self._h, mode))
+
+    def set_exchange_fusion(self, enabled):
+        self._check(lib().freqattn_set_exchange_fusion(self._h, 1 if enabled else 0))
 
     def set_alloc_prediction(self, enabled):
         self._check(lib().freqattn_set_alloc_prediction(self._h, 1 if enabled else 0))

@@ -395,6 +395,14 @@ extern "C" freqattn_status freqattn_set_launch_mode(freqattn_ctx* c, int32_t mod
   c->launch_mode = mode;
   return FREQATTN_OK;
 }
+extern "C" freqattn_status freqattn_set_exchange_fusion(freqattn_ctx* c, int32_t enabled) {
+  if (!c) return FREQATTN_EINVAL;
+  if (c->exchange_fusion != (enabled ? 1 : 0)) {
+    c->exchange_fusion = enabled ? 1 : 0;
+    c->alloc_valid = false;   // the work lists carry the choice
+  }
+  return FREQATTN_OK;
+}
 extern "C" freqattn_status freqattn_set_alloc_prediction(freqattn_ctx* c, int32_t enabled) {
   if (!c) return FREQATTN_EINVAL;
   c->predict_alloc = enabled ? 1 : 0;
@@ -556,6 +564,16 @@ static bool build_lists(Ctx& c, const int32_t* head_alloc) {
   const int rows = c.attn_rows;
   const int KT = 64;  // key tile of the MFMA attention kernel
   bool ok = true;
+  // A band item also carries the band's exchange (section 3.6) when every other band of the slice passes V~ through:
+  // the summary tokens it attends to are then pooled from V~ before the band operators run (bit 16 of kind_band).
+  const bool fusion = c.exchange_fusion && c.cfg.n_summary > 0 && c.slices <= 256;
+  auto fused_xchg = [&](int mask, int l) -> bool {
+    if (!fusion || c.n_c[l] <= 0) return false;
+    int eff = 0;
+    for (int o = 0; o < 3; ++o)
+      if (((mask >> o) & 1) && c.band_n[o] > 0) eff |= 1 << o;
+    return eff == (1 << l);
+  };
   auto push = [&](size_t off, int& n, size_t cap, AttnItem it) {
     if ((size_t)n >= cap) { ok = false; return; }
     std::memcpy(L + off + (size_t)4 * n, &it, sizeof(AttnItem));
@@ -567,7 +585,7 @@ static bool build_lists(Ctx& c, const int32_t* head_alloc) {
     const int mask = L[c.off_masks + s];
     if ((mask & 1) && c.band_n[LOW] > 0)
       for (int64_t q0 = 0; q0 < c.nbar; q0 += rows)
-        push(c.off_items_kind[0], c.n_items_kind[0], cap_kind, {0 | (LOW << 8), s, (int32_t)q0, (int32_t)cd(c.nbar, KT)});
+        push(c.off_items_kind[0], c.n_items_kind[0], cap_kind, {0 | (LOW << 8) | (fused_xchg(mask, LOW) ? 1 << 16 : 0), s, (int32_t)q0, (int32_t)cd(c.nbar, KT)});
     if ((mask & 2) && c.band_n[MID] > 0) {
       // Query blocks I with the same I mod stride share all their strided key blocks (J = I mod stride): they are listed
       // together, so that workgroups running at the same time fetch those K/V tiles into their L2 once.
@@ -580,18 +598,18 @@ static bool build_lists(Ctx& c, const int32_t* head_alloc) {
             const int64_t q0 = I * c.cfg.mid_block + u * rows;
             if (q0 >= c.band_n[MID]) break;
             const int nblk = c.h_row_ptr[I + 1] - c.h_row_ptr[I];
-            push(c.off_items_kind[1], c.n_items_kind[1], cap_kind, {1 | (MID << 8), s, (int32_t)q0, (int32_t)(nblk * cd(c.cfg.mid_block, KT))});
+            push(c.off_items_kind[1], c.n_items_kind[1], cap_kind, {1 | (MID << 8) | (fused_xchg(mask, MID) ? 1 << 16 : 0), s, (int32_t)q0, (int32_t)(nblk * cd(c.cfg.mid_block, KT))});
           }
     }
     if ((mask & 4) && c.band_n[HIGH] > 0)
       for (int64_t q0 = 0; q0 < c.band_n[HIGH]; q0 += rows) {
         const int64_t k0 = std::max<int64_t>(0, q0 - c.cfg.high_window);
         const int64_t k1 = std::min<int64_t>(c.band_n[HIGH] - 1, q0 + rows - 1 + (int64_t)c.cfg.high_window);
-        push(c.off_items_kind[2], c.n_items_kind[2], cap_kind, {2 | (HIGH << 8), s, (int32_t)q0, (int32_t)(k1 / KT - k0 / KT + 1)});
+        push(c.off_items_kind[2], c.n_items_kind[2], cap_kind, {2 | (HIGH << 8) | (fused_xchg(mask, HIGH) ? 1 << 16 : 0), s, (int32_t)q0, (int32_t)(k1 / KT - k0 / KT + 1)});
       }
     if (c.cfg.n_summary > 0)
       for (int l = 0; l < 3; ++l)
-        if (((mask >> l) & 1) && c.band_n[l] > 0 && c.n_c[l] > 0)
+        if (((mask >> l) & 1) && c.band_n[l] > 0 && c.n_c[l] > 0 && !fused_xchg(mask, l))
           for (int64_t q0 = 0; q0 < c.band_n[l]; q0 += rows)
             push(c.off_items_xchg, c.n_items_xchg, cap_x, {3 | (l << 8), s, (int32_t)q0, (int32_t)cd(c.n_c[l], KT)});
   }
@@ -938,9 +956,53 @@ static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in
   }
   tm.done("low_compress");
 
-  // section 3.4: the three band operators
+  // section 3.6, first half: summary tokens.  Band l of a slice is summarised only if another band of the slice is active
+  // (the exchange of that band is the only reader).  For slices that do not run the high band (their V~ may stop at the
+  // low+mid box) the high band's summaries are summed from V instead of pooled - by the allocation alone, also where V~
+  // happens to exist on the whole grid: the result must not depend on a prediction.
+  // which = 0: every band; 1: only bands the slice passes through (pooled from V~: can run before the band operators);
+  // 2: only bands the slice runs (pooled from the band outputs).
   AttnParams ap;
   fill_attn_params(*c, ap, scale);
+  auto summaries = [&](int which) -> freqattn_status {
+    uint64_t skip[3][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}}, sel[4] = {0, 0, 0, 0};
+    int nsel = 0, npool = 0;
+    if (c->slices <= 256) {
+      for (int s = 0; s < c->slices; ++s) {
+        const int mask = c->h_alloc[(size_t)(s % c->shape.heads)];
+        for (int l = 0; l < 3; ++l) {
+          const bool active = (mask >> l) & 1;
+          bool skp = (mask & ~(1 << l) & 7) == 0 || (which == 1 && active) || (which == 2 && !active);
+          if (l == 2 && mf && c->v_box_ok && v_in && !(mask & 4)) {
+            skp = true;
+            if (mask != 0 && which != 2) { sel[s >> 6] |= 1ull << (s & 63); ++nsel; }
+          }
+          if (skp) skip[l][s >> 6] |= 1ull << (s & 63);
+          else ++npool;
+        }
+      }
+    } else {
+      npool = 1;
+    }
+    if (npool > 0)
+      HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, &skip[0][0], c->d_pool_part, st));
+    if (nsel > 0) {
+      int nsplit = std::max(1, c->vsum_nsplit / nsel);   // nsel * nsplit <= 2 CUs' worth + nsel, what the scratch holds
+      nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(nsplit, c->N / 64 / 8));   // at least eight tiles per range
+      HIP_TRY(c, launch_vsum(v_in, c->d_wsum, c->d_vsum_part, c->Cbuf, sel, nsel, c->N, c->d, nsplit, c->band_n[HIGH], c->m_eff, ap.m2, st));
+    }
+    return FREQATTN_OK;
+  };
+  // Slices that run a single band carry its exchange inside the band items (see build_lists): the summary tokens of
+  // the bands they pass through are needed before the launch.
+  const bool split_summaries = mf && c->exchange_fusion && c->cfg.n_summary > 0 && c->slices <= 256;
+  if (split_summaries) {
+    freqattn_status fs = summaries(1);
+    if (fs != FREQATTN_OK) return fs;
+    tm.done("summaries");
+  }
+
+  // section 3.4: the three band operators
   if (mf) {
     if (c->launch_mode == FREQATTN_LAUNCH_FUSED) {
       HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(L + c->off_items), c->n_items_branch, c->attn_rows, c->num_cu, st));
@@ -986,33 +1048,12 @@ static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in
     HIP_TRY(c, launch_expand_low(c->lowY, c->Y, L + c->off_list[LOW], c->n_list[LOW], c->N, c->d, c->band_n[LOW], c->nbar, c->cfg.low_compress, is_half, st));
   tm.done("low_expand");
 
-  // section 3.6: summary tokens of all bands, then the exchange on the active bands
+  // section 3.6: remaining summary tokens (of the bands a slice runs, from the band outputs), then the exchange of
+  // the slices that run more than one band
   if (c->cfg.n_summary > 0) {
-    // Band l of a slice is summarised only if another band of the slice is active (the exchange of that band is the only
-    // reader).  For slices that do not run the high band (their V~ may stop at the low+mid box) the high band's summaries
-    // are summed from V instead of pooled - by the allocation alone, also where V~ happens to exist on the whole grid:
-    // the result must not depend on a prediction.
-    uint64_t skip[3][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}}, sel[4] = {0, 0, 0, 0};
-    int nsel = 0;
-    if (c->slices <= 256) {
-      for (int s = 0; s < c->slices; ++s) {
-        const int mask = c->h_alloc[(size_t)(s % c->shape.heads)];
-        for (int l = 0; l < 3; ++l)
-          if ((mask & ~(1 << l) & 7) == 0) skip[l][s >> 6] |= 1ull << (s & 63);
-        if (mf && c->v_box_ok && v_in && !(mask & 4)) {
-          skip[2][s >> 6] |= 1ull << (s & 63);
-          if (mask != 0) { sel[s >> 6] |= 1ull << (s & 63); ++nsel; }
-        }
-      }
-    }
-    HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, &skip[0][0], c->d_pool_part, st));
-    if (nsel > 0)
-      {
-        int nsplit = std::max(1, c->vsum_nsplit / nsel);   // nsel * nsplit <= 2 CUs' worth + nsel, what the scratch holds
-        nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(nsplit, c->N / 64 / 8));   // at least eight tiles per range
-        HIP_TRY(c, launch_vsum(v_in, c->d_wsum, c->d_vsum_part, c->Cbuf, sel, nsel, c->N, c->d, nsplit, c->band_n[HIGH], c->m_eff, ap.m2, st));
-      }
-    tm.done("summaries");
+    freqattn_status fs = summaries(split_summaries ? 2 : 0);
+    if (fs != FREQATTN_OK) return fs;
+    tm.done(split_summaries ? "summaries_active" : "summaries");
     if (mf) {
       HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(L + c->off_items_xchg), c->n_items_xchg, c->attn_rows, c->num_cu, st));
     } else {

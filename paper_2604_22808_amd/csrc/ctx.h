@@ -54,6 +54,7 @@ struct Ctx {
   freqattn_band_cfg cfg;
   int path;         // resolved freqattn_path
   int launch_mode;
+  int exchange_fusion = 1;   // band items of single-band slices carry the exchange (section 3.6) themselves
   int slices;       // batch*heads
   int64_t N;
   int d;

@@ -99,7 +99,7 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
   for (int it = it_first; it < n_items; it += gridDim.x) {
     const AttnItem item = item_nx;
     if (it + (int)gridDim.x < n_items) item_nx = items[it + gridDim.x];
-    const int kind = item.kind_band & 0xff, band = item.kind_band >> 8;
+    const int kind = item.kind_band & 0xff, band = (item.kind_band >> 8) & 0xff;   // bit 16: exchange in the item (phase 1)
     const int64_t slice = item.slice;
     const int q0 = item.q0;
     const uint16_t *Qp, *Kp, *Vp;
@@ -147,232 +147,295 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
       for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // tile iteration space of the item
-    int n_outer = 1, e0 = 0, sub_n = 1, t_lo = 0, t_hi = 0;
-    if (kind == 1) {
-      const int I = q0 / p.mid_block;
-      e0 = p.mid_row_ptr[I];
-      n_outer = p.mid_row_ptr[I + 1] - e0;
-      sub_n = p.mid_block / KT;
-    } else if (kind == 2) {
-      const int klo = q0 - w > 0 ? q0 - w : 0;
-      int khi = q0 + ROWS - 1 + w;
-      if (khi > nk - 1) khi = nk - 1;
-      t_lo = klo / KT; t_hi = khi / KT;
-      n_outer = t_hi - t_lo + 1;
-    } else {
-      n_outer = (nk + KT - 1) / KT;
-    }
-
-    const int n_tt = n_outer * sub_n;
-    auto key0_of = [&](int idx) -> int {
-      if (kind == 1) return (p.mid_col_idx[e0 + idx / sub_n] * sub_n + idx % sub_n) * KT;
-      return (t_lo + idx) * KT;
-    };
-    // Exchange items of one (slice, band) all see the same <= 2 tiles of summary tokens: a workgroup that has them in
-    // its two LDS copies from its previous item keeps them (no loads, no stores for this item).
-    const int lds_key = (kind == 3 && n_tt <= 2) ? (int)(slice * 4 + band) : -1;
-    const bool reuse = lds_key >= 0 && lds_key == lds_holds;
-    lds_holds = lds_key;
     // Staging: this wave's share of a tile is RPI rows per instruction, NIW instructions per tensor; rows past the
-    // end of the band are clamped to its last row (their scores are masked, and V rows of real data times zero are zero)
+    // end of the key range are clamped to its last row (their scores are masked, and V rows of real data times zero are zero)
     constexpr int RPI = 64 / CPR, NIW = KT / (RPI * NW);
     // piece pi of a tile: K rows (pi even) or V rows (pi odd) of instruction pi / 2 of this wave's share
-    auto dma_piece = [&](int key0, int buf, int pi) {
+    auto dma_piece = [&](const uint16_t* Ksrc, const uint16_t* Vsrc, int nkeys, int key0, int buf, int pi) {
       const int lr = lane / CPR, c = lane % CPR;
       const int rowbase = (wave * NIW + pi / 2) * RPI;      // wave-uniform
       const int r = rowbase + lr;
       int key = key0 + r;
-      if (key > nk - 1) key = nk - 1;
-      if ((pi & 1) == 0) lds_dma16(Kp + (int64_t)key * D + ((c ^ fK(r)) << 3), Ks2[buf] + rowbase * D);
-      else lds_dma16(Vp + (int64_t)key * D + ((c ^ fV(r)) << 3), Vt2[buf] + rowbase * D);
+      if (key > nkeys - 1) key = nkeys - 1;
+      if ((pi & 1) == 0) lds_dma16(Ksrc + (int64_t)key * D + ((c ^ fK(r)) << 3), Ks2[buf] + rowbase * D);
+      else lds_dma16(Vsrc + (int64_t)key * D + ((c ^ fV(r)) << 3), Vt2[buf] + rowbase * D);
     };
-    auto dma_tile = [&](int key0, int buf) {
-#pragma unroll
-      for (int pi = 0; pi < 2 * NIW; ++pi) dma_piece(key0, buf, pi);
-    };
-    if (n_tt > 0 && !reuse) dma_tile(key0_of(0), 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    for (int idx = 0; idx < n_tt; ++idx, __builtin_amdgcn_s_waitcnt(0x0070), __syncthreads()) {
-      const int key0 = key0_of(idx);
-      const half_t* Ks = Ks2[idx & 1];
-      const half_t* Vt = Vt2[idx & 1];
-      // The next tile goes straight into the other LDS copy (free since the barrier that ended the previous iteration);
-      // the wait for it sits in front of the barrier that ends this iteration.  Its copy instructions are spread over the
-      // score MFMAs below (a wave issues in order, and a burst of them right behind the barrier holds every wave of the
-      // CU in the memory pipeline's queue); an iteration that skips the MFMAs issues them at once.
-      const bool dma_next = idx + 1 < n_tt && !reuse;
-      const int key0_next = dma_next ? key0_of(idx + 1) : 0;
-      auto stage = [&]() {
-        if (dma_next) dma_tile(key0_next, (idx + 1) & 1);
-      };
-      if (key0 >= nk) {  // block tail beyond the band (uniform over the workgroup)
-        stage();
-        continue;
-      }
 
-      // ---- does this wave need the tile at all (window), and does it need the element mask
-      const int key_hi = key0 + KT - 1;
-      bool need = true, need_mask = key_hi >= nk;
-      if (kind == 2) {
-        need = !(key_hi < r0 - w || key0 > r0 + WROWS - 1 + w);
-        need_mask = need_mask || (key0 < r0 + WROWS - 1 - w) || (key_hi > r0 + w);
-      }
-      if (!need) {  // uniform per wave; the tile's barrier sits in the loop increment, which `continue` still runs
-        stage();
-        continue;
-      }
-
-      // ---- S^T = K Q^T for the two 32-key halves of the tile
-      // The accumulators start at minus the lane's reference maximum, so the matrix core delivers the scores already
-      // shifted: in the common case (no new maximum) they go into exp2 without a subtraction.
-      float16v S[2];
-      const float s_init = (m_run == -INFINITY) ? 0.f : -m_run;
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) S[t2][r] = s_init;
-      // K operands are requested PF steps ahead of the MFMA that consumes them, so LDS latency overlaps the matrix core
-      constexpr int PF = 8;
-      {
-        constexpr int NS = 2 * DK;
-        auto kptr = [&](int i) -> const half8* {
-          return (const half8*)(Ks + (i / DK) * 32 * D + koff_row + kx[i % DK]);   // fK(t2*32 + nn) = fK(nn)
-        };
-        half8 Abuf[PF];
-#pragma unroll
-        for (int i = 0; i < PF; ++i) Abuf[i] = *kptr(i);
-#pragma unroll
-        for (int i = 0; i < NS; ++i) {
-          const int t2 = i / DK, ks = i % DK;
-          const half8 A = Abuf[i % PF];
-          if (i + PF < NS)
-            Abuf[i % PF] = *kptr(i + PF);
-          S[t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Qr[ks], S[t2], 0, 0, 0);
-          if (dma_next) {
-#pragma unroll
-            for (int pi = i * (2 * NIW) / NS; pi < (i + 1) * (2 * NIW) / NS; ++pi) dma_piece(key0_next, (idx + 1) & 1, pi);
-          }
-        }
-        // pin the order: PF reads up front, then one read per MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
-#pragma unroll
-        for (int i = 0; i < NS - PF; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, PF, 0);
-      }
-      // ---- mask, running softmax (lane = query row; registers = keys).  m_run is a reference maximum, not the exact
-      // one: it moves only when a score exceeds it by more than 2^kBump (or when the row sees its first valid key), so
-      // probabilities stay within [0, 2^kBump] - exact in the ratio P / sum(P) - and the rescale is rare.
-      constexpr float kBump = 8.f;
-      half8 P[2][2];
-      if (need_mask) {
-        // valid keys of this lane's row form one interval [lo, hi]; relative to the lane's first key of the tile,
-        // register r holds key offset c_r (a compile-time constant), valid iff (unsigned)(c_r - lo') <= (unsigned)(hi' - lo')
-        const int row = r0 + nn;
-        int lo = 0, hi = nk - 1;
-        if (kind == 2) { lo = row - w > 0 ? row - w : 0; hi = row + w < nk - 1 ? row + w : nk - 1; }
-        const int base = key0 + 4 * g;
-        int dlo = lo - base, dhi = hi - base;
-        dlo = dlo < -1 ? -1 : (dlo > 65 ? 65 : dlo);    // clamped: only the range of c_r matters
-        dhi = dhi < -1 ? -1 : (dhi > 65 ? 65 : dhi);
-        unsigned range = (unsigned)(dhi - dlo);
-        if (dhi < dlo) { dlo = 1000; range = 0u; }      // empty interval: no c_r passes
-        const unsigned ndlo = (unsigned)(-dlo);
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const unsigned cr = (unsigned)(t2 * 32 + 8 * (r >> 2) + (r & 3));
-            S[t2][r] = (cr + ndlo <= range) ? S[t2][r] : -INFINITY;
-          }
-      }
-      // row maximum: four independent chains (short dependency depth), then the other lane half through a register
-      // swap (v_permlane32_swap leaves [lo, lo] / [hi, hi] in the two registers; no trip through the LDS pipe)
-      float mc[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-        for (int r = 0; r < 16; r += 2)
-          mc[(r >> 1) & 3] = __builtin_fmaxf(__builtin_fmaxf(mc[(r >> 1) & 3], S[t2][r]), S[t2][r + 1]);
-      float mx = fmaxf(fmaxf(mc[0], mc[1]), fmaxf(mc[2], mc[3]));
-      {
-        const uint32_t mb = __float_as_uint(mx);
-        const auto sw = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
-        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-      }
-      const bool bump = (m_run == -INFINITY) ? (mx > -INFINITY) : (mx > kBump);
-      // Probabilities, two per register, rounded toward zero; the row sum is taken over the rounded values (the ones
-      // the matrix core multiplies), so the rounding direction cancels in P / sum(P).  They are formed before the
-      // (rare) reference bump is known, so that the exponentials overlap the maximum's dependency chain.
-      auto probabilities = [&]() -> float {
-        float ps[4] = {0.f, 0.f, 0.f, 0.f};
-        const half2v ones = {(_Float16)1.f, (_Float16)1.f};
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            uint4v pk;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const half2v h2 = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(
-                  __builtin_amdgcn_exp2f(S[t2][s2 * 8 + 2 * j]), __builtin_amdgcn_exp2f(S[t2][s2 * 8 + 2 * j + 1])));
-              ps[j] = __builtin_amdgcn_fdot2(h2, ones, ps[j], false);
-              pk[j] = __builtin_bit_cast(uint32_t, h2);
-            }
-            P[t2][s2] = __builtin_bit_cast(half8, pk);
-          }
-        return (ps[0] + ps[1]) + (ps[2] + ps[3]);
-      };
-      float psum = probabilities();
-      if (__builtin_amdgcn_ballot_w64(bump) != 0) {
-        const bool fresh = m_run == -INFINITY;
-        const float delta = bump ? mx : 0.f;
-        const float alpha = (bump && !fresh) ? __builtin_amdgcn_exp2f(-delta) : 1.f;
-        if (bump) m_run = fresh ? delta : m_run + delta;
-        l_run *= alpha;
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) S[t2][r] -= delta;
+    // An item runs one or two phases over the same query rows.  Phase 0 is the band operator.  Phase 1 (items marked
+    // for it: every other band of the slice passes V~ through, so the summary tokens this band attends to were pooled
+    // before the launch) is the cross-band exchange of section 3.6, with the phase-0 result - rounded to fp16 exactly as
+    // it would have been stored - as the query and as the residual, and the <= 2m summary tokens as keys and values.
+    const int n_phases = 1 + (item.kind_band >> 16 & 1);
+    const uint16_t* Cp = (const uint16_t*)p.C + ((slice * 3 + band) * p.m2) * (int64_t)D;
+    uint4v yres[DK];     // phase 1: the residual rows, channels 16 ks + 8 g .. + 8 of this lane's row (fp16)
+    int tile_base = 0;   // tiles staged so far in this item: tile i of the item lives in LDS copy i & 1
+    bool staged = false; // the first tile of the coming phase is already in its LDS copy
+    for (int phase = 0; phase < n_phases; ++phase) {
+      const int kind_p = phase ? 0 : kind;
+      const uint16_t* Kq = phase ? Cp : Kp;
+      const uint16_t* Vq = phase ? Cp : Vp;
+      const int nkp = phase ? p.n_c[band] : nk;
+      if (phase) {
+        // phase-0 output -> fp16 (what the band operator alone would store) -> query operand and residual
+        const float l_tot = l_run + __shfl_xor(l_run, 32);
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
-        psum = probabilities();   // again, against the moved reference
-      }
-      l_run += psum;
-      // ---- O^T += V^T P^T
-      {
-        constexpr int NS = 4 * DT;   // (t2, s2, dt) flattened, dt fastest
-        // V is row-major in LDS; the operand (lane = channel, 8 keys in the order of P's registers) comes from two
-        // transposing reads, each delivering 4 consecutive keys: keys 16 ts + 8 h + 4 g + 0..3 for read h
-        auto vread = [&](int i) -> half8 {
-          const int dt = i % DT, ts = i / DT;   // ts = t2 * 2 + s2
-          uint4v r4;
+          for (int j = 0; j < 2; ++j) {
+            uint4v y4;
+            half8 qh;
+            float o[8];
 #pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            const half_t* ptr = Vt + (ts * 16 + 8 * h) * D + voff_row + vx[dt];   // fV only sees row & 3 = sl / 4
-            const fp16x4 t4 = __builtin_amdgcn_ds_read_tr16_b64_v4f16((fp16x4 __attribute__((address_space(3)))*)ptr);
-            const uint2v u2 = __builtin_bit_cast(uint2v, t4);
-            r4[2 * h] = u2[0]; r4[2 * h + 1] = u2[1];
+            for (int b = 0; b < 4; ++b) {
+              const uint32_t lo = __float_as_uint(O[dt][(2 * j) * 4 + b] * inv);
+              const uint32_t hi = __float_as_uint(O[dt][(2 * j + 1) * 4 + b] * inv);
+              const auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
+              o[b] = __uint_as_float(sw[0]);
+              o[4 + b] = __uint_as_float(sw[1]);
+            }
+#pragma unroll
+            for (int b = 0; b < 4; ++b) y4[b] = pack_h2(o[2 * b], o[2 * b + 1]);
+            const half8 yh = __builtin_bit_cast(half8, y4);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) qh[b] = (_Float16)((float)yh[b] * c2);
+            yres[dt * 2 + j] = y4;
+            Qr[dt * 2 + j] = qh;
           }
-          return __builtin_bit_cast(half8, r4);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
+        m_run = -INFINITY; l_run = 0.f;
+      }
+
+      // tile iteration space of the phase
+      int n_outer = 1, e0 = 0, sub_n = 1, t_lo = 0, t_hi = 0;
+      if (kind_p == 1) {
+        const int I = q0 / p.mid_block;
+        e0 = p.mid_row_ptr[I];
+        n_outer = p.mid_row_ptr[I + 1] - e0;
+        sub_n = p.mid_block / KT;
+      } else if (kind_p == 2) {
+        const int klo = q0 - w > 0 ? q0 - w : 0;
+        int khi = q0 + ROWS - 1 + w;
+        if (khi > nkp - 1) khi = nkp - 1;
+        t_lo = klo / KT; t_hi = khi / KT;
+        n_outer = t_hi - t_lo + 1;
+      } else {
+        n_outer = (nkp + KT - 1) / KT;
+      }
+      const int n_tt = n_outer * sub_n;
+      auto key0_of = [&](int idx) -> int {
+        if (kind_p == 1) return (p.mid_col_idx[e0 + idx / sub_n] * sub_n + idx % sub_n) * KT;
+        return (t_lo + idx) * KT;
+      };
+      // Exchange items of one (slice, band) all see the same <= 2 tiles of summary tokens: a workgroup that has them in
+      // its two LDS copies from its previous item keeps them (no loads, no stores for this item).
+      const int lds_key = (kind == 3 && n_tt <= 2) ? (int)(slice * 4 + band) : -1;
+      const bool reuse = lds_key >= 0 && lds_key == lds_holds;
+      lds_holds = lds_key;
+      if (!staged) {
+        if (n_tt > 0 && !reuse) {
+#pragma unroll
+          for (int pi = 0; pi < 2 * NIW; ++pi) dma_piece(Kq, Vq, nkp, key0_of(0), tile_base & 1, pi);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+      }
+      staged = false;
+      for (int idx = 0; idx < n_tt; ++idx, __builtin_amdgcn_s_waitcnt(0x0070), __syncthreads()) {
+        const int key0 = key0_of(idx);
+        const int buf = (tile_base + idx) & 1;
+        const half_t* Ks = Ks2[buf];
+        const half_t* Vt = Vt2[buf];
+        // The next tile goes straight into the other LDS copy (free since the barrier that ended the previous iteration);
+        // the wait for it sits in front of the barrier that ends this iteration.  Its copy instructions are spread over the
+        // score MFMAs below (a wave issues in order, and a burst of them right behind the barrier holds every wave of the
+        // CU in the memory pipeline's queue); an iteration that skips the MFMAs issues them at once.  The last tile of
+        // phase 0 fetches the first summary tile of phase 1 the same way.
+        const bool next_in_phase = idx + 1 < n_tt;
+        const bool next_phase = !next_in_phase && phase + 1 < n_phases;
+        const bool dma_next = (next_in_phase && !reuse) || next_phase;
+        const uint16_t* Kn = next_phase ? Cp : Kq;
+        const uint16_t* Vn = next_phase ? Cp : Vq;
+        const int nkn = next_phase ? p.n_c[band] : nkp;
+        const int key0_next = next_in_phase ? key0_of(idx + 1) : 0;
+        if (next_phase) staged = true;
+        auto stage = [&]() {
+          if (dma_next) {
+#pragma unroll
+            for (int pi = 0; pi < 2 * NIW; ++pi) dma_piece(Kn, Vn, nkn, key0_next, buf ^ 1, pi);
+          }
         };
-        half8 Abuf[PF];
+        if (key0 >= nkp) {  // block tail beyond the band (uniform over the workgroup)
+          stage();
+          continue;
+        }
+
+        // ---- does this wave need the tile at all (window), and does it need the element mask
+        const int key_hi = key0 + KT - 1;
+        bool need = true, need_mask = key_hi >= nkp;
+        if (kind_p == 2) {
+          need = !(key_hi < r0 - w || key0 > r0 + WROWS - 1 + w);
+          need_mask = need_mask || (key0 < r0 + WROWS - 1 - w) || (key_hi > r0 + w);
+        }
+        if (!need) {  // uniform per wave; the tile's barrier sits in the loop increment, which `continue` still runs
+          stage();
+          continue;
+        }
+
+        // ---- S^T = K Q^T for the two 32-key halves of the tile
+        // The accumulators start at minus the lane's reference maximum, so the matrix core delivers the scores already
+        // shifted: in the common case (no new maximum) they go into exp2 without a subtraction.
+        float16v S[2];
+        const float s_init = (m_run == -INFINITY) ? 0.f : -m_run;
 #pragma unroll
-        for (int i = 0; i < PF; ++i) Abuf[i] = vread(i);
+        for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-        for (int i = 0; i < NS; ++i) {
-          const int dt = i % DT, ts = i / DT;
-          const half8 A = Abuf[i % PF];
-          if (i + PF < NS) Abuf[i % PF] = vread(i + PF);
-          O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[ts >> 1][ts & 1], O[dt], 0, 0, 0);
+          for (int r = 0; r < 16; ++r) S[t2][r] = s_init;
+        // K operands are requested PF steps ahead of the MFMA that consumes them, so LDS latency overlaps the matrix core
+        constexpr int PF = 8;
+        {
+          constexpr int NS = 2 * DK;
+          auto kptr = [&](int i) -> const half8* {
+            return (const half8*)(Ks + (i / DK) * 32 * D + koff_row + kx[i % DK]);   // fK(t2*32 + nn) = fK(nn)
+          };
+          half8 Abuf[PF];
+#pragma unroll
+          for (int i = 0; i < PF; ++i) Abuf[i] = *kptr(i);
+#pragma unroll
+          for (int i = 0; i < NS; ++i) {
+            const int t2 = i / DK, ks = i % DK;
+            const half8 A = Abuf[i % PF];
+            if (i + PF < NS)
+              Abuf[i % PF] = *kptr(i + PF);
+            S[t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Qr[ks], S[t2], 0, 0, 0);
+            if (dma_next) {
+#pragma unroll
+              for (int pi = i * (2 * NIW) / NS; pi < (i + 1) * (2 * NIW) / NS; ++pi) dma_piece(Kn, Vn, nkn, key0_next, buf ^ 1, pi);
+            }
+          }
+          // pin the order: PF reads up front, then one read per MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
+#pragma unroll
+          for (int i = 0; i < NS - PF; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, PF, 0);
+        }
+        // ---- mask, running softmax (lane = query row; registers = keys).  m_run is a reference maximum, not the exact
+        // one: it moves only when a score exceeds it by more than 2^kBump (or when the row sees its first valid key), so
+        // probabilities stay within [0, 2^kBump] - exact in the ratio P / sum(P) - and the rescale is rare.
+        constexpr float kBump = 8.f;
+        half8 P[2][2];
+        if (need_mask) {
+          // valid keys of this lane's row form one interval [lo, hi]; relative to the lane's first key of the tile,
+          // register r holds key offset c_r (a compile-time constant), valid iff (unsigned)(c_r - lo') <= (unsigned)(hi' - lo')
+          const int row = r0 + nn;
+          int lo = 0, hi = nkp - 1;
+          if (kind_p == 2) { lo = row - w > 0 ? row - w : 0; hi = row + w < nkp - 1 ? row + w : nkp - 1; }
+          const int base = key0 + 4 * g;
+          int dlo = lo - base, dhi = hi - base;
+          dlo = dlo < -1 ? -1 : (dlo > 65 ? 65 : dlo);    // clamped: only the range of c_r matters
+          dhi = dhi < -1 ? -1 : (dhi > 65 ? 65 : dhi);
+          unsigned range = (unsigned)(dhi - dlo);
+          if (dhi < dlo) { dlo = 1000; range = 0u; }      // empty interval: no c_r passes
+          const unsigned ndlo = (unsigned)(-dlo);
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const unsigned cr = (unsigned)(t2 * 32 + 8 * (r >> 2) + (r & 3));
+              S[t2][r] = (cr + ndlo <= range) ? S[t2][r] : -INFINITY;
+            }
+        }
+        // row maximum: four independent chains (short dependency depth), then the other lane half through a register
+        // swap (v_permlane32_swap leaves [lo, lo] / [hi, hi] in the two registers; no trip through the LDS pipe)
+        float mc[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+          for (int r = 0; r < 16; r += 2)
+            mc[(r >> 1) & 3] = __builtin_fmaxf(__builtin_fmaxf(mc[(r >> 1) & 3], S[t2][r]), S[t2][r + 1]);
+        float mx = fmaxf(fmaxf(mc[0], mc[1]), fmaxf(mc[2], mc[3]));
+        {
+          const uint32_t mb = __float_as_uint(mx);
+          const auto sw = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+          mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        }
+        const bool bump = (m_run == -INFINITY) ? (mx > -INFINITY) : (mx > kBump);
+        // Probabilities, two per register, rounded toward zero; the row sum is taken over the rounded values (the ones
+        // the matrix core multiplies), so the rounding direction cancels in P / sum(P).  They are formed before the
+        // (rare) reference bump is known, so that the exponentials overlap the maximum's dependency chain.
+        auto probabilities = [&]() -> float {
+          float ps[4] = {0.f, 0.f, 0.f, 0.f};
+          const half2v ones = {(_Float16)1.f, (_Float16)1.f};
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+              uint4v pk;
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const half2v h2 = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(
+                    __builtin_amdgcn_exp2f(S[t2][s2 * 8 + 2 * j]), __builtin_amdgcn_exp2f(S[t2][s2 * 8 + 2 * j + 1])));
+                ps[j] = __builtin_amdgcn_fdot2(h2, ones, ps[j], false);
+                pk[j] = __builtin_bit_cast(uint32_t, h2);
+              }
+              P[t2][s2] = __builtin_bit_cast(half8, pk);
+            }
+          return (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        };
+        float psum = probabilities();
+        if (__builtin_amdgcn_ballot_w64(bump) != 0) {
+          const bool fresh = m_run == -INFINITY;
+          const float delta = bump ? mx : 0.f;
+          const float alpha = (bump && !fresh) ? __builtin_amdgcn_exp2f(-delta) : 1.f;
+          if (bump) m_run = fresh ? delta : m_run + delta;
+          l_run *= alpha;
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) S[t2][r] -= delta;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+          psum = probabilities();   // again, against the moved reference
+        }
+        l_run += psum;
+        // ---- O^T += V^T P^T
+        {
+          constexpr int NS = 4 * DT;   // (t2, s2, dt) flattened, dt fastest
+          // V is row-major in LDS; the operand (lane = channel, 8 keys in the order of P's registers) comes from two
+          // transposing reads, each delivering 4 consecutive keys: keys 16 ts + 8 h + 4 g + 0..3 for read h
+          auto vread = [&](int i) -> half8 {
+            const int dt = i % DT, ts = i / DT;   // ts = t2 * 2 + s2
+            uint4v r4;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const half_t* ptr = Vt + (ts * 16 + 8 * h) * D + voff_row + vx[dt];   // fV only sees row & 3 = sl / 4
+              const fp16x4 t4 = __builtin_amdgcn_ds_read_tr16_b64_v4f16((fp16x4 __attribute__((address_space(3)))*)ptr);
+              const uint2v u2 = __builtin_bit_cast(uint2v, t4);
+              r4[2 * h] = u2[0]; r4[2 * h + 1] = u2[1];
+            }
+            return __builtin_bit_cast(half8, r4);
+          };
+          half8 Abuf[PF];
+#pragma unroll
+          for (int i = 0; i < PF; ++i) Abuf[i] = vread(i);
+#pragma unroll
+          for (int i = 0; i < NS; ++i) {
+            const int dt = i % DT, ts = i / DT;
+            const half8 A = Abuf[i % PF];
+            if (i + PF < NS) Abuf[i % PF] = vread(i + PF);
+            O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[ts >> 1][ts & 1], O[dt], 0, 0, 0);
+          }
         }
       }
+      tile_base += n_tt;
     }
 
     // ---- epilogue: normalise, optional residual, store.  A lane holds, per 16 channels, two groups of four that
@@ -394,6 +457,11 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
             const auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
             o[b] = __uint_as_float(sw[0]);
             o[4 + b] = __uint_as_float(sw[1]);
+          }
+          if (n_phases == 2) {   // residual of the in-item exchange: the phase-0 rows kept in registers
+            const half8 yh = __builtin_bit_cast(half8, yres[dt * 2 + j]);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) o[b] += (float)yh[b];
           }
           if (row < nq) {
             const int dd = dt * 32 + j * 16 + g * 8;

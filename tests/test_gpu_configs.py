@@ -267,3 +267,27 @@ def test_projected_forward_matches_oracle(name, heads, alloc):
     mx, rl = U.errors(U.to_host64(out), want2)
     print(f"projected {name} second allocation: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
     assert mx <= 2e-2 and rl <= 5e-3
+
+
+@pytest.mark.parametrize("name,heads,alloc", [("16k", [0, 1, 2, 3, 4, 5, 6], (1, 2, 4, 3, 5, 7, 0)), ("256k", [0, 7, 19], (1, 2, 4))])
+def test_exchange_inside_the_band_items_is_bit_identical(name, heads, alloc):
+    """Slices that run one band carry the cross-band exchange inside their band items (the output tile never leaves the
+    registers between the band operator and the exchange); slices that run several bands use the separate launch.  Same
+    arithmetic on the same fp16 values: the outputs must equal those of the all-separate route bit for bit, in both
+    launch modes; m = 5 gives a ragged summary tile."""
+    import torch
+    wl = WL.WORKLOADS[name]
+    q, k, v = (U.to_device(WL.round_to_io(x, "bf16"), "bf16") for x in WL.qkv_numpy(wl, heads=heads)) if name == "16k" else \
+        [t[:, heads].contiguous() for t in WL.qkv_torch(wl, "cuda")]
+    for extra in (dict(), dict(n_summary=5)):
+        ctx, _ = U.make_ctx(wl, heads=len(heads), **extra)
+        a, b, c2 = (torch.empty_like(q) for _ in range(3))
+        ctx.forward(q, k, v, alloc, a)
+        ctx.set_exchange_fusion(False)
+        ctx.forward(q, k, v, alloc, b)
+        ctx.set_exchange_fusion(True)
+        ctx.set_launch_mode(B.LAUNCH_SEPARATE)
+        ctx.forward(q, k, v, alloc, c2)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b) and torch.equal(a, c2), (name, extra)
+        ctx.destroy()
