@@ -235,6 +235,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-256k", action="store_true", help="skip the dense comparison at 256K tokens")
     ap.add_argument("--no-projected", action="store_true", help="skip the folded-projection comparison")
+    ap.add_argument("--separate-exchange", action="store_true",
+                    help="cross-band exchange as a launch of its own for every slice (A/B of the in-item exchange)")
     ap.add_argument("--t", type=float, default=None, help="timestep for the MLP head allocator (default: the workload's)")
     ap.add_argument("--transform", choices=("dct", "haar"), default="dct",
                     help="per-axis transform: the reference design's DCT-II or the Haar wavelet variant")
@@ -265,6 +267,8 @@ def main():
     ctx = B.Context(wl.batch, wl.heads, wl.head_dim, wl.grid, B.BF16, cfg)
     if args.separate:
         ctx.set_launch_mode(B.LAUNCH_SEPARATE)
+    if args.separate_exchange:
+        ctx.set_exchange_fusion(False)
     router = None
     if wl.alloc["kind"] == "mlp":
         router = WL.router_weights(wl.alloc["hidden"], wl.alloc["seed"])

@@ -167,7 +167,6 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
     // it would have been stored - as the query and as the residual, and the <= 2m summary tokens as keys and values.
     const int n_phases = 1 + (item.kind_band >> 16 & 1);
     const uint16_t* Cp = (const uint16_t*)p.C + ((slice * 3 + band) * p.m2) * (int64_t)D;
-    uint4v yres[DK];     // phase 1: the residual rows, channels 16 ks + 8 g .. + 8 of this lane's row (fp16)
     int tile_base = 0;   // tiles staged so far in this item: tile i of the item lives in LDS copy i & 1
     bool staged = false; // the first tile of the coming phase is already in its LDS copy
     for (int phase = 0; phase < n_phases; ++phase) {
@@ -199,7 +198,9 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
             const half8 yh = __builtin_bit_cast(half8, y4);
 #pragma unroll
             for (int b = 0; b < 8; ++b) qh[b] = (_Float16)((float)yh[b] * c2);
-            yres[dt * 2 + j] = y4;
+            // The rows are parked in the output tensor - exactly what the band operator alone would have stored - and
+            // come back as the residual in the epilogue (same lane, same address: no other reader in this launch).
+            if (r0 + nn < nq) *(uint4v*)(Op + (int64_t)(r0 + nn) * D + dt * 32 + j * 16 + g * 8) = y4;
             Qr[dt * 2 + j] = qh;
           }
 #pragma unroll
@@ -458,16 +459,11 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
             o[b] = __uint_as_float(sw[0]);
             o[4 + b] = __uint_as_float(sw[1]);
           }
-          if (n_phases == 2) {   // residual of the in-item exchange: the phase-0 rows kept in registers
-            const half8 yh = __builtin_bit_cast(half8, yres[dt * 2 + j]);
-#pragma unroll
-            for (int b = 0; b < 8; ++b) o[b] += (float)yh[b];
-          }
           if (row < nq) {
             const int dd = dt * 32 + j * 16 + g * 8;
             uint16_t* dst = Op + (int64_t)row * D + dd;
-            if (kind == 3) {
-              const uint4v y = *(const uint4v*)(Qp + (int64_t)row * D + dd);
+            if (kind == 3 || n_phases == 2) {   // residual: the exchange's query rows (parked in the output by phase 1's start)
+              const uint4v y = *(const volatile uint4v*)((kind == 3 ? Qp : (const uint16_t*)Op) + (int64_t)row * D + dd);
               const half8 yh = __builtin_bit_cast(half8, y);
 #pragma unroll
               for (int b = 0; b < 8; ++b) o[b] += (float)yh[b];
