@@ -291,3 +291,31 @@ def test_exchange_inside_the_band_items_is_bit_identical(name, heads, alloc):
         torch.cuda.synchronize()
         assert torch.equal(a, b) and torch.equal(a, c2), (name, extra)
         ctx.destroy()
+
+
+def test_forward_replays_from_a_hip_graph():
+    """The plain forward enqueues kernels only (no synchronisation, no allocation, no memset nodes) once its allocation
+    is known, so it can be captured in a HIP graph - what a launch-bound sampling loop at 16K-64K tokens wants.  The
+    graph is replayed several times with eager work and synchronisations in between; every replay must give the eager
+    result bit for bit."""
+    import torch
+    wl = WL.WORKLOADS["16k"]
+    q, k, v = (U.to_device(WL.round_to_io(x, "bf16"), "bf16") for x in WL.qkv_numpy(wl))
+    alloc = B.route_fixed(wl.heads, *wl.alloc["counts"])
+    ctx, _ = U.make_ctx(wl)
+    eager = torch.empty_like(q)
+    ctx.forward(q, k, v, alloc, eager)           # also uploads the work lists of this allocation
+    torch.cuda.synchronize()
+    out = torch.empty_like(q)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        ctx.forward(q, k, v, alloc, out)
+    for rep in range(4):
+        out.zero_()
+        q2 = (q.float() * (1.0 + 0.25 * rep)).to(torch.bfloat16)     # eager work between the replays, new inputs
+        q.copy_(q2)
+        ctx.forward(q, k, v, alloc, eager)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
