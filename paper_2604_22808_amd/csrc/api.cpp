@@ -270,8 +270,9 @@ static hipError_t device_setup(freqattn_ctx* c, hipStream_t st) {
   A(dev_alloc(*c, &c->d_range_flag, 64));
   if (e == hipSuccess) e = launch_fill_zero((float*)c->d_range_flag, 64, st);   // (a zero float is a zero int)
   if (mf && g.n_summary > 0 && g.n_summary < 64) A(dev_alloc(*c, &c->d_pool_part, (size_t)c->slices * 3 * 128 * c->d));
-  if (mf) A(dev_alloc(*c, &c->d_energy_part, (size_t)6 * DCT_MAX_WAVES * 3 * 64));
-  if (mf) A(dev_alloc(*c, &c->d_tot_part, (size_t)3 * DCT_MAX_WAVES * 64));
+  // (partial sums of the router statistics: the routed entry points do not run on an arena context)
+  if (mf && !arena) A(dev_alloc(*c, &c->d_energy_part, (size_t)6 * DCT_MAX_WAVES * 3 * 64));
+  if (mf && !arena) A(dev_alloc(*c, &c->d_tot_part, (size_t)3 * DCT_MAX_WAVES * 64));
   {
     auto box = [](int64_t num, int64_t den, int n) { return (int)((num * n + den - 1) / den); };  // #k with k*den < num*n
     const int dims[3] = {s.T, s.H, s.W};
@@ -682,7 +683,8 @@ static hipError_t forward_transform_mfma(Ctx& c, const void* x, void* spec, hipS
   a.in = x; a.slice_list = slice_list; a.list_in = 1; a.out = c.tmp0; a.M = c.d_F16[2]; a.ldm = W; a.n = W; a.n_out = kw;
   a.inner = d; a.outer = (int64_t)T * H; a.nslab = (int64_t)ns * T * H; a.in_bf16 = 1;
   if (tot_slot >= 0) a.tot_part = c.d_tot_part + (size_t)tot_slot * DCT_MAX_WAVES * 64;
-  if ((e = launch_mfma_dct_pass(a, c.num_cu, st, &c.tot_waves)) != hipSuccess) return e;
+  int w_dummy = 0;
+  if ((e = launch_mfma_dct_pass(a, c.num_cu, st, tot_slot >= 0 ? &c.tot_waves[tot_slot] : &w_dummy)) != hipSuccess) return e;
 
   DctPassArgs b{};
   b.d = d; b.Ntok = c.N;
@@ -702,7 +704,7 @@ static hipError_t forward_transform_mfma(Ctx& c, const void* x, void* spec, hipS
     t.low_u = c.low_box[1]; t.low_v = c.low_box[2]; t.low_a = c.low_box[0];
     t.mid_u = c.mid_box[1]; t.mid_v = c.mid_box[2]; t.mid_a = c.mid_box[0];
   }
-  return launch_mfma_dct_pass(t, c.num_cu, st, &c.energy_waves);
+  return launch_mfma_dct_pass(t, c.num_cu, st, energy_slot >= 0 ? &c.energy_waves[energy_slot] : &w_dummy);
 }
 
 // MFMA path, inverse (section 3.7) for `ns` slices: the T axis pass gathers band-major rows into tmp1 in [h][t]
@@ -853,12 +855,12 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
     bool pruned = false;
     for (int a = 0; a < 3; ++a) { mid[a] = keep_rows(c->mid_box[a], full[a]); pruned = pruned || mid[a] < full[a]; }
     if (whole_grid) pruned = false;   // every statistic taken directly from whole-grid transforms
-    c->energy_waves = 0; c->tot_waves = 0; c->qk_on_mid_box = pruned;
+    for (int i = 0; i < 6; ++i) c->energy_waves[i] = 0;
+    for (int i = 0; i < 3; ++i) c->tot_waves[i] = 0;
+    c->qk_on_mid_box = pruned;
     c->qk_full.assign((size_t)c->slices, pruned ? 0 : 1);
     // statistics slots: 0..2 = Q, K, V on the box (high band by Parseval when pruned), 3..5 = the same on the whole grid
     const bool vbox = pruned && c->v_box_ok;
-    HIP_TRY(c, launch_fill_zero(c->d_energy_part, (int64_t)6 * DCT_MAX_WAVES * 3 * 64, st));
-    if (pruned) HIP_TRY(c, launch_fill_zero(c->d_tot_part, (int64_t)3 * DCT_MAX_WAVES * 64, st));
     c->v_full.assign((size_t)c->slices, vbox ? 0 : 1);
     if (pruned && predict && c->alloc_valid && c->n_cls[2] > 0) {
       const int32_t* L = c->d_lists;
@@ -876,8 +878,10 @@ static freqattn_status transforms_phase(freqattn_ctx* c, const void* q, const vo
       if (vbox) HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, mid, 2, 2));
     }
     if (!vbox) HIP_TRY(c, forward_transform_mfma(*c, v, c->specV, st, nullptr, c->slices, full, pruned ? 5 : 2, -1));
-    HIP_TRY(c, launch_energy_reduce(c->d_energy_part, pruned ? c->d_tot_part : nullptr, c->d_stats, c->d, c->energy_waves,
-                                    c->tot_waves, st));
+    EnergyWaves nw;
+    for (int i = 0; i < 6; ++i) nw.en[i] = c->energy_waves[i];
+    for (int i = 0; i < 3; ++i) nw.tot[i] = c->tot_waves[i];
+    HIP_TRY(c, launch_energy_reduce(c->d_energy_part, pruned ? c->d_tot_part : nullptr, c->d_stats, c->d, nw, st));
     return FREQATTN_OK;
   }
   if (c->path == FREQATTN_PATH_MFMA && !with_stats) {

@@ -90,9 +90,9 @@ struct Ctx {
   float* d_stats = nullptr;                       // router statistics [3][d] (+ partial sums of the generic kernel)
   float* d_energy_part = nullptr;                 // per-wave partial sums of the fused statistics (MFMA path)
   float* d_tot_part = nullptr;                    // per-wave partial sums of the inputs' squares (Q, K), MFMA path
-  int tot_waves = 0;
+  int tot_waves[3] = {0, 0, 0};                   // waves that stored sums of squares in the last W-axis pass, per statistics slot
   bool qk_on_mid_box = false;                     // the last routed transforms left Q~, K~ on the low+mid box only
-  int energy_waves = 0;                           // waves that wrote partial sums in the last fused pass
+  int energy_waves[6] = {0, 0, 0, 0, 0, 0};       // waves that stored band statistics in the last T-axis pass, per statistics slot
   int low_box[3] = {0, 0, 0}, mid_box[3] = {0, 0, 0};  // extent of the low / low+mid box per axis
   float* h_stats = nullptr;                       // pinned mirror
 
@@ -221,9 +221,10 @@ hipError_t launch_probe_mfma(float* out, int blocks, int iters, hipStream_t st);
 hipError_t launch_convert_16(const void* in, void* out, int64_t n, int to_bf16, hipStream_t st);
 hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_list, int n_slices, int64_t slice_bytes,
                               hipStream_t st);
+struct EnergyWaves { int en[6]; int tot[3]; };   // waves whose slots hold this forward's partial sums, per statistics slot
 hipError_t launch_energy_reduce(const float* energy_part /*[6][DCT_MAX_WAVES][3][64]: Q, K, V (box), Q, K, V (whole grid)*/,
                                 const float* tot_part /*[3][DCT_MAX_WAVES][64] or NULL*/, float* stats, int d,
-                                int n_waves, int n_waves_tot, hipStream_t st);
+                                const EnergyWaves& nw, hipStream_t st);
 
 // ---- MFMA kernels (mfma_dct.hip, mfma_attn.hip) -------------------------------------------------------------------
 struct DctPassArgs {
@@ -259,7 +260,7 @@ struct DctPassArgs {
   int32_t* range_flag;
   int en_omul, en_div, low_u, low_v, low_a, mid_u, mid_v, mid_a;  // flat index of the tile = o*en_omul + col0/d
 };
-#define DCT_MAX_WAVES 4096   // upper bound of waves in one launch of the DCT pass (sizes energy_part)
+#define DCT_MAX_WAVES 65536   // upper bound of waves in one launch of the DCT pass (sizes energy_part)
 hipError_t launch_mfma_dct_pass(const DctPassArgs& a, int num_cu, hipStream_t st, int* waves_out = nullptr);
 bool mfma_dct_supported(int n_in, int n_out);
 hipError_t launch_gemm_nt(const GemmProblem* d_probs, const GemmSeg* d_segs, int per, int m, int n, hipStream_t st);

@@ -534,28 +534,27 @@ hipError_t launch_convert_16(const void* in, void* out, int64_t n, int to_bf16, 
 // the (tensor, wave) terms round-robin and a fixed tree adds their partial sums.
 // With tot_part set, the tensors in slots 0..2 were only computed on the low+mid box: their high-band energy is the
 // energy of the input (Parseval, the transform is orthonormal) minus their low and mid energies.
-__global__ void __launch_bounds__(256) k_energy_reduce(const float* part, const float* tot_part, float* stats, int d,
-                                                       int n_waves, int n_waves_tot) {
+__global__ void __launch_bounds__(256) k_energy_reduce(const float* part, const float* tot_part, float* stats, int d, EnergyWaves nw) {
   __shared__ float red[256];
   const int idx = blockIdx.x, tid = threadIdx.x;
   const int band = idx / d, ch = idx % d;
   const int chunks = d / 64, chunk = ch / 64, col = ch % 64;
-  const int per = (n_waves - chunk + chunks - 1) / chunks;   // waves of this chunk
   const bool parseval = tot_part != nullptr && band == 2;
   float t = 0.f;
-  for (int i = tid; i < 6 * per; i += 256) {   // slots: Q, K, V on the box (Parseval for the high band), Q, K, V on the whole grid
-    const int tensor = i / per, w = chunk + (i % per) * chunks;
-    const float* p3 = part + (((size_t)tensor * DCT_MAX_WAVES + w) * 3) * 64 + col;
-    if (parseval && tensor < 3) t -= p3[0] + p3[64];
-    else t += p3[band * 64];
-  }
-  if (parseval) {
-    const int per_t = (n_waves_tot - chunk + chunks - 1) / chunks;
-    for (int i = tid; i < 3 * per_t; i += 256) {
-      const int tensor = i / per_t, w = chunk + (i % per_t) * chunks;
-      t += tot_part[((size_t)tensor * DCT_MAX_WAVES + w) * 64 + col];
+  for (int tensor = 0; tensor < 6; ++tensor) {   // slots: Q, K, V on the box (Parseval for the high band), Q, K, V on the whole grid
+    const int per = (nw.en[tensor] - chunk + chunks - 1) / chunks;   // waves of this chunk that stored sums into this slot
+    for (int i = tid; i < per; i += 256) {
+      const int w = chunk + i * chunks;
+      const float* p3 = part + (((size_t)tensor * DCT_MAX_WAVES + w) * 3) * 64 + col;
+      if (parseval && tensor < 3) t -= p3[0] + p3[64];
+      else t += p3[band * 64];
     }
   }
+  if (parseval)
+    for (int tensor = 0; tensor < 3; ++tensor) {
+      const int per_t = (nw.tot[tensor] - chunk + chunks - 1) / chunks;
+      for (int i = tid; i < per_t; i += 256) t += tot_part[((size_t)tensor * DCT_MAX_WAVES + chunk + (size_t)i * chunks) * 64 + col];
+    }
   red[tid] = t;
   __syncthreads();
   for (int sft = 128; sft > 0; sft >>= 1) {
@@ -567,9 +566,9 @@ __global__ void __launch_bounds__(256) k_energy_reduce(const float* part, const 
   if (tid == 0) stats[idx] = (parseval && red[0] < 0.f) ? 0.f : red[0];   // (a NaN stays a NaN: the host reports it)
 }
 
-hipError_t launch_energy_reduce(const float* energy_part, const float* tot_part, float* stats, int d, int n_waves,
-                                int n_waves_tot, hipStream_t st) {
-  hipLaunchKernelGGL(k_energy_reduce, dim3(3 * d), dim3(256), 0, st, energy_part, tot_part, stats, d, n_waves, n_waves_tot);
+hipError_t launch_energy_reduce(const float* energy_part, const float* tot_part, float* stats, int d, const EnergyWaves& nw,
+                                hipStream_t st) {
+  hipLaunchKernelGGL(k_energy_reduce, dim3(3 * d), dim3(256), 0, st, energy_part, tot_part, stats, d, nw);
   return hipGetLastError();
 }
 

@@ -160,6 +160,8 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
     return *(const uint4v*)(t.in_base + (int64_t)j * t.in_stride + lcol);
   };
 
+  // A wave strides over the tile list by the size of the grid: at any time the resident waves work on one narrow,
+  // advancing range of tiles.
   const uint32_t tile_step = gridDim.x * DCT_WAVES;
   uint32_t tile = blockIdx.x * DCT_WAVES + wave;
   const uint32_t n_tiles32 = (uint32_t)n_tiles;
@@ -350,7 +352,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
           const float mine = b == 0 ? en[0][nt] : b == 1 ? en[1][nt] - en[0][nt] : en[2][nt] - en[1][nt];
           const float tot = mine + __shfl_xor(mine, 32);
           float* slot = a.energy_part + ((size_t)gwave * 3 + b) * 64 + nt * 32 + nn;
-          if (g == 0) *slot = *slot + tot;   // launches on one stream are ordered: no other writer of this slot
+          if (g == 0) *slot = tot;   // this wave is the only writer of the slot (waves without a tile store zeros)
         }
     }
     if (TOT) {
@@ -359,7 +361,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
         float t = te[j];
         t += __shfl_xor(t, 8); t += __shfl_xor(t, 16); t += __shfl_xor(t, 32);   // lanes that share lane & 7
         float* slot = a.tot_part + (size_t)gwave * 64 + lcol + j;
-        if (lane < 8) *slot = *slot + t;
+        if (lane < 8) *slot = t;
       }
     }
   }
@@ -381,14 +383,35 @@ static hipError_t launch_n(const DctPassArgs& a, int num_cu, hipStream_t st, int
   int64_t blocks = (n_tiles + DCT_WAVES - 1) / DCT_WAVES;
   int64_t cap = (int64_t)num_cu * occ;
   if (cap * DCT_WAVES > DCT_MAX_WAVES) cap = DCT_MAX_WAVES / DCT_WAVES;
-  if (blocks > cap) blocks = cap;
+  // Grid size: not the resident capacity but about two tiles per wave.  A wave still strides over the tile list by the
+  // size of the grid, so the waves in flight work on one narrow, advancing range of tiles, and with fresh workgroups
+  // arriving all the time the loads of new tiles do not queue behind the stores of finished ones (measured: 7.9 instead of
+  // 8.5 ms for the forward transforms of the 1M-token workload; one tile per wave loses the prefetch across tiles,
+  // contiguous runs of tiles per workgroup are slower than either).  FREQATTN_DCT_TPW overrides; 0 = resident grid.
+  static int tpw_env = -1;
+  if (tpw_env < 0) { const char* e = getenv("FREQATTN_DCT_TPW"); tpw_env = e ? atoi(e) : 2; }
+  int tpw = tpw_env;
+  if (tpw > 0) {
+    // statistics modes keep one partial-sum slot per wave: the grid must fit DCT_MAX_WAVES
+    if (MODE == DCT_SCATTER_EN || MODE == DCT_PLAIN_TOT) {
+      static int tpw_stats = -1;
+      if (tpw_stats < 0) { const char* e = getenv("FREQATTN_DCT_TPW_STATS"); tpw_stats = e ? atoi(e) : 16; }   // (these passes measured best with longer-lived waves)
+      tpw = std::max(tpw, tpw_stats);
+      tpw = (int)std::max<int64_t>(tpw, (n_tiles + DCT_MAX_WAVES - 1) / DCT_MAX_WAVES);
+    }
+    blocks = std::max<int64_t>(1, (n_tiles + (int64_t)tpw * DCT_WAVES - 1) / ((int64_t)tpw * DCT_WAVES));
+    if (blocks < cap) blocks = std::min<int64_t>(cap, (n_tiles + DCT_WAVES - 1) / DCT_WAVES);   // small launches: fill the machine first
+  } else if (blocks > cap) {
+    blocks = cap;
+  }
   if (MODE == DCT_SCATTER_EN || MODE == DCT_PLAIN_TOT) {
     // every wave must keep one column chunk for all its tiles: the tile stride has to be a multiple of the chunks
-    // per head_dim (columns of a token).  The partial-sum slots are accumulated into; the caller zeroes them first.
+    // per head_dim (columns of a token).  Every wave of the grid stores its partial sums into its own slots; the caller
+    // gets the number of waves back and sums exactly those.
     const int cpt = a.d / 64;
     if ((blocks * DCT_WAVES) % cpt != 0 || !waves_out || (a.energy_part && !a.perm_out) || (a.tot_part && a.inner != a.d))
       return hipErrorInvalidValue;
-    if ((int)(blocks * DCT_WAVES) > *waves_out) *waves_out = (int)(blocks * DCT_WAVES);
+    *waves_out = (int)(blocks * DCT_WAVES);
   }
   hipLaunchKernelGGL((k_dct_pass<NI, MT, MODE>), dim3((unsigned)blocks), dim3(64 * DCT_WAVES), 0, st, a, n_tiles, chunks);
   return hipGetLastError();
