@@ -372,10 +372,17 @@ def main():
     if any(one_band):
         n_l = ctx.band_sizes()
         m_eff = [min(wl.band["n_summary"], n) for n in n_l]
-        moved = sum(4.0 * wl.head_dim * n_l[(m.bit_length() - 1)] * (sum(m_eff) - m_eff[m.bit_length() - 1])
-                    for m, ob in zip(masks, one_band) if ob) * wl.batch
-        work["band_attention_fused"] = ("mfma", work["band_attention_fused"][1] + moved, 1)
-        work["exchange"] = ("mfma", max(work["exchange"][1] - moved, 0.0), 1)
+        moved_band = [0.0, 0.0, 0.0]
+        for m, ob in zip(masks, one_band):
+            if ob:
+                l = m.bit_length() - 1
+                moved_band[l] += 4.0 * wl.head_dim * n_l[l] * (sum(m_eff) - m_eff[l]) * wl.batch
+        moved = sum(moved_band) if not args.separate_exchange else 0.0
+        if moved:
+            work["band_attention_fused"] = ("mfma", work["band_attention_fused"][1] + moved, 1)
+            for l, name in enumerate(("low_attention", "mid_attention", "high_attention")):
+                work[name] = ("mfma", work[name][1] + moved_band[l], 1)
+            work["exchange"] = ("mfma", max(work["exchange"][1] - moved, 0.0), 1)
     work["forward_transform"] = (work["forward_transform"][0], work["forward_transform"][1], fwd_launches)
     work["inverse_transform"] = (work["inverse_transform"][0], work["inverse_transform"][1], max(1, inv_launches))
     stage_report = {}

@@ -20,6 +20,10 @@
  *                          low+mid box only (default: from 64K tokens on; see freqattn_get_v_box)
  *   FREQATTN_DCT_OCC=n     read at the first transform launch of each pass shape: resident workgroups per compute unit
  *                          of the transform passes (default: what 160 KB of LDS allow, at most 4)
+ *   FREQATTN_DCT_TPW=n     read at the first transform launch of each pass shape: tiles per wave that size the grids of
+ *                          the transform passes (default 2; 0 = a resident grid of FREQATTN_DCT_OCC workgroups per unit)
+ *   FREQATTN_DCT_TPW_PERM=n   the same for the passes that scatter into / gather from band-major rows (default: as above)
+ *   FREQATTN_DCT_TPW_STATS=n  the same for the passes that add up router statistics (default 16)
  */
 #ifndef FREQATTN_H
 #define FREQATTN_H

@@ -393,6 +393,11 @@ static hipError_t launch_n(const DctPassArgs& a, int num_cu, hipStream_t st, int
   int tpw = tpw_env;
   if (tpw > 0) {
     // statistics modes keep one partial-sum slot per wave: the grid must fit DCT_MAX_WAVES
+    if (MODE == DCT_SCATTER || MODE == DCT_GATHER) {
+      static int tpw_perm = -1;
+      if (tpw_perm < 0) { const char* e = getenv("FREQATTN_DCT_TPW_PERM"); tpw_perm = e ? atoi(e) : tpw; }
+      tpw = tpw_perm;
+    }
     if (MODE == DCT_SCATTER_EN || MODE == DCT_PLAIN_TOT) {
       static int tpw_stats = -1;
       if (tpw_stats < 0) { const char* e = getenv("FREQATTN_DCT_TPW_STATS"); tpw_stats = e ? atoi(e) : 16; }   // (these passes measured best with longer-lived waves)
