@@ -24,6 +24,9 @@
  *                          the transform passes (default 2; 0 = a resident grid of FREQATTN_DCT_OCC workgroups per unit)
  *   FREQATTN_DCT_TPW_PERM=n   the same for the passes that scatter into / gather from band-major rows (default: as above)
  *   FREQATTN_DCT_TPW_STATS=n  the same for the passes that add up router statistics (default 16)
+ *   FREQATTN_DCT_WGS=n, FREQATTN_DCT_WGS_128=n   read at the first launch of each pass shape: most workgroups of a transform
+ *                          pass per compute unit, for passes over fewer than 128 rows / over 128 rows (0 = whatever fits;
+ *                          defaults 0 and 2)
  */
 #ifndef FREQATTN_H
 #define FREQATTN_H

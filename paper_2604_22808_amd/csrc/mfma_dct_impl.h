@@ -26,11 +26,17 @@ namespace fa {
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+typedef __fp16 fp16x4 __attribute__((__vector_size__(4 * sizeof(__fp16))));
 
 #define DCT_WAVES 4
-#define DCT_XS_STRIDE 72  // halfs per staged row: 64 columns + 8 pad (144 bytes keeps 16-byte alignment)
+#define DCT_XS_STRIDE 96  // halfs per staged input row: 64 columns + 32 pad.  192 bytes = 3/4 of the 256 bytes the LDS banks
+                          // span, so the four rows x two 32-byte column groups that half a wave's transposing read touches
+                          // fall on all banks once
+#define DCT_XO_STRIDE 72  // halfs per staged output row (144 bytes: the two lane halves, four rows apart, hit different banks)
 
 __device__ __forceinline__ uint16_t dct_f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);
@@ -57,8 +63,16 @@ __device__ __forceinline__ uint4v bf16x8_to_f16x8(uint4v v) {
 // 3 scatter + router statistics, 4 gather from the band-major buffers.
 enum { DCT_PLAIN = 0, DCT_PLAIN_TOT = 1, DCT_SCATTER = 2, DCT_SCATTER_EN = 3, DCT_GATHER = 4 };
 
+// Waves per SIMD the register allocation aims at: three (168 registers) for the variants with at most 64 accumulator
+// registers, whose tiles are small enough that a third wave's loads in flight matter more than spare registers.
+template <int NI, int MT, int MODE> constexpr int dct_min_waves() {
+  int w = MT == 1 ? 4 : MT == 2 ? 3 : 2;
+  if (MODE == 4 && NI > 64 && w > 2) --w;   // the gather pass also holds the looked-up rows of two tiles
+  return w;
+}
+
 template <int NI, int MT, int MODE>
-__global__ void __launch_bounds__(64 * DCT_WAVES) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ void __launch_bounds__(64 * DCT_WAVES) __attribute__((amdgpu_waves_per_eu(dct_min_waves<NI, MT, MODE>())))
 k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
   // NI input rows are contracted into up to 32*MT output rows, of which the first a.n_out are stored.
   constexpr int RC = (NI % 32 == 0) ? 32 : 16;  // rows staged per step
@@ -86,17 +100,29 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
 
   half_t* Xs = Xs_all[wave];
   const int lrow = lane >> 3, lcol = (lane & 7) * 8;  // this lane's row (within 8) and first column of a row segment
+  // Transposing LDS read (ds_read_b64_tr_b16): lane i of a group of 16 receives, for k = 0..3, element i % 4 of the 8-byte
+  // piece that lane 4 k + i / 4 of the group names.  With lane j naming row j / 4, columns 4 (j % 4) .. + 3, lane i ends up
+  // with column i of four consecutive rows.  The two groups of a wave half take columns 0-15 and 16-31, the upper half
+  // of the wave the rows eight further down.
+  const int boff = (((lane & 15) >> 2) + 8 * g) * DCT_XS_STRIDE + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   float en[3][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};  // band x column tile, this lane's rows only
-  float te[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // sum of squares of the input, this lane's 8 columns
+  float te[2] = {0.f, 0.f};  // sum of squares of the input: column tile x this lane's rows
   bool out_of_range = false;   // scatter passes: a spectral coefficient that fp16 cannot hold (or a non-finite one)
 
-  // Per-tile addressing, computed once per tile: rows of a tile are `stride` elements apart from `base`, except on the
-  // band-major side where every row is looked up through the permutation.
+  // Addressing.  Everything that depends on the tile is wave-uniform and lives in scalar registers; a lane adds one
+  // 32-bit offset of its own (its row within a group of 8 and its 16-byte piece of the row segment), fixed for the whole
+  // launch.  Rows of a tile are `stride` elements apart from the tile's base, except on the band-major side, where every
+  // row is looked up through the permutation.  (The host side checks that the per-lane offsets fit 32 bits.)
+  const int64_t in_stride = a.in_swap ? (int64_t)a.sw_total * a.inner : a.inner;
+  const int64_t out_stride = a.out_swap ? (int64_t)a.sw_total * a.inner : a.inner;
+  const uint32_t lane_in = (uint32_t)(lrow * in_stride + lcol) * 2u;     // bytes
+  const uint32_t lane_out = (uint32_t)(lrow * out_stride + lcol) * 2u;   // bytes
+  const uint32_t lane_perm = (uint32_t)(lrow * a.perm_k) * 4u;           // bytes into the permutation table
   struct TileAddr {
-    const uint16_t* in_base; int64_t in_stride;   // regular / swapped input
-    int64_t out_off, out_stride;                  // regular / swapped output (element offset into out / resid)
-    int64_t bm_off;                               // band-major side: slice*Ntok (rows), and
-    int32_t pidx, dcol, mask;                     // o*perm_o + col0/d, col0 % d, band mask of the slice
+    const char* in_base;                          // regular / swapped input: first row of the tile, column col0
+    int64_t out_off;                              // regular / swapped output (element offset into out / resid)
+    int64_t bm_off;                               // band-major side: (slice*Ntok*d + col0 % d) elements, and
+    int32_t pidx, mask;                           // o*perm_o + col0/d, band mask of the slice
   };
   auto tile_addr = [&](uint32_t tile) -> TileAddr {
     TileAddr t;
@@ -105,59 +131,52 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
     const uint32_t sl = s / (uint32_t)a.outer;              // slice within this launch
     const int32_t o = (int32_t)(s % (uint32_t)a.outer);     // slab within the slice
     const int64_t slice = a.slice_list ? a.slice_list[sl] : (int64_t)sl;   // slice of the caller's tensors
-    t.dcol = 0; t.pidx = 0; t.bm_off = 0; t.mask = 7; t.in_base = nullptr; t.in_stride = 0; t.out_off = 0; t.out_stride = 0;
+    t.pidx = 0; t.bm_off = 0; t.mask = 7; t.in_base = nullptr; t.out_off = 0;
     if (PERM_IN || PERM_OUT) {
       const int32_t ctok = col0 / a.d;
-      t.dcol = col0 - ctok * a.d;
       t.pidx = o * (int32_t)a.perm_o + ctok;
-      t.bm_off = slice * a.Ntok;
+      t.bm_off = slice * a.Ntok * a.d + (col0 - ctok * a.d);
       if (PERM_IN) t.mask = a.masks[slice];
     }
     if (PERM_IN) {
     } else if (a.in_swap) {
       const uint32_t sa = s / (uint32_t)a.sw, sb = s % (uint32_t)a.sw;
-      t.in_base = (const uint16_t*)a.in + (((int64_t)sa * NI * a.sw_total + sb + a.sw_off) * a.inner + col0);
-      t.in_stride = (int64_t)a.sw_total * a.inner;
+      t.in_base = (const char*)((const uint16_t*)a.in + (((int64_t)sa * NI * a.sw_total + sb + a.sw_off) * a.inner + col0));
     } else if (a.list_in) {
-      t.in_base = (const uint16_t*)a.in + (slice * a.slice_elems + (int64_t)o * NI * a.inner + col0);
-      t.in_stride = a.inner;
+      t.in_base = (const char*)((const uint16_t*)a.in + (slice * a.slice_elems + (int64_t)o * NI * a.inner + col0));
     } else {
-      t.in_base = (const uint16_t*)a.in + ((int64_t)s * NI * a.inner + col0);
-      t.in_stride = a.inner;
+      t.in_base = (const char*)((const uint16_t*)a.in + ((int64_t)s * NI * a.inner + col0));
     }
     if (PERM_OUT) {
     } else if (a.out_swap) {
       const uint32_t sa = s / (uint32_t)a.sw, sb = s % (uint32_t)a.sw;
       t.out_off = ((int64_t)sa * NO * a.sw_total + sb + a.sw_off) * a.inner + col0;
-      t.out_stride = (int64_t)a.sw_total * a.inner;
     } else if (a.list_out) {
       t.out_off = slice * a.slice_elems + (int64_t)o * NO * a.inner + col0;
-      t.out_stride = a.inner;
     } else {
       t.out_off = (int64_t)s * NO * a.inner + col0;
-      t.out_stride = a.inner;
     }
     return t;
   };
-  // this lane's 16-byte piece of input row j
-  // (gather: `row` is the band-major row of input row j, looked up one tile ahead by perm_rows)
-  auto load_piece = [&](const TileAddr& t, int j, int32_t row) -> uint4v {
+  // this lane's 16-byte piece of input row j0 + lrow (j0 a multiple of 8)
+  // (gather: `row` is the band-major row of that input row, looked up one tile ahead by perm_rows)
+  auto load_piece = [&](const TileAddr& t, int j0, int32_t row) -> uint4v {
     if (PERM_IN) {
       const int band = row < a.band_off1 ? 0 : (row < a.band_off2 ? 1 : 2);
       const bool active = (t.mask >> band) & 1;
-      const int64_t off = (t.bm_off + row) * a.d + t.dcol + lcol;
+      const uint32_t lane_off = ((uint32_t)row * (uint32_t)a.d + (uint32_t)lcol) * 2u;   // bytes within the slice
       if (a.delta) {   // change of the active bands against V~ (zero elsewhere)
         uint4v r = {0u, 0u, 0u, 0u};
         if (active) {
-          const half8 y = *(const half8*)((const uint16_t*)a.in + off);
-          const half8 v = *(const half8*)((const uint16_t*)a.in_alt + off);
+          const half8 y = *(const half8*)((const char*)((const uint16_t*)a.in + t.bm_off) + lane_off);
+          const half8 v = *(const half8*)((const char*)((const uint16_t*)a.in_alt + t.bm_off) + lane_off);
           r = __builtin_bit_cast(uint4v, y - v);
         }
         return r;
       }
-      return *(const uint4v*)((const uint16_t*)(active ? a.in : a.in_alt) + off);
+      return *(const uint4v*)((const char*)((const uint16_t*)(active ? a.in : a.in_alt) + t.bm_off) + lane_off);
     }
-    return *(const uint4v*)(t.in_base + (int64_t)j * t.in_stride + lcol);
+    return *(const uint4v*)(t.in_base + (int64_t)j0 * in_stride * 2 + lane_in);
   };
 
   // A wave strides over the tile list by the size of the grid: at any time the resident waves work on one narrow,
@@ -177,7 +196,8 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
   auto perm_rows = [&](const TileAddr& t, int32_t (&pr)[NPR]) {
     if (PERM_IN) {
 #pragma unroll
-      for (int i = 0; i < NPR; ++i) pr[i] = a.perm_in[(int64_t)((i / LPC) * RC + (i % LPC) * 8 + lrow) * a.perm_k + (int64_t)t.pidx * pscale];
+      for (int i = 0; i < NPR; ++i)
+        pr[i] = *(const int32_t*)((const char*)(a.perm_in + ((int64_t)((i / LPC) * RC + (i % LPC) * 8) * a.perm_k + (int64_t)t.pidx * pscale)) + lane_perm);
     }
   };
   if (tile < n_tiles32) {
@@ -186,7 +206,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
 #pragma unroll
     for (int ch = 0; ch < PD; ++ch)
 #pragma unroll
-      for (int it = 0; it < LPC; ++it) R[ch][it] = load_piece(cur, ch * RC + it * 8 + lrow, pcur[PERM_IN ? ch * LPC + it : 0]);
+      for (int it = 0; it < LPC; ++it) R[ch][it] = load_piece(cur, ch * RC + it * 8, pcur[PERM_IN ? ch * LPC + it : 0]);
   }
 
   for (; tile < n_tiles32; tile += tile_step) {
@@ -194,14 +214,19 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
     if (has_next) { nxt = tile_addr(tile + tile_step); perm_rows(nxt, pnxt); }
 
     // band-major rows of this lane's output rows, requested now so that the stores of the epilogue do not wait for them
+    // (the row index goes through an empty asm once per tile so that what depends on it - the "row exists" tests of every
+    // group of 8 rows - is recomputed where it is used instead of being kept in registers for the whole launch)
+    int lrow_t = lrow;
+    asm volatile("" : "+v"(lrow_t));
     int32_t prow[MT][4];
     if (PERM_OUT) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-          const int k = mt * 32 + it * 8 + lrow;
-          prow[mt][it] = k < NO ? a.perm_out[(int64_t)k * a.perm_k + (int64_t)cur.pidx * pscale] : 0;
+          const int k0 = mt * 32 + it * 8;
+          prow[mt][it] = k0 + lrow_t < NO
+              ? *(const int32_t*)((const char*)(a.perm_out + ((int64_t)k0 * a.perm_k + (int64_t)cur.pidx * pscale)) + lane_perm) : 0;
         }
     }
     float16v acc[MT][2];
@@ -219,32 +244,46 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
       for (int it = 0; it < LPC; ++it) {
         uint4v v = R[ch % PD][it];
         if (a.in_bf16) v = bf16x8_to_f16x8(v);
-        if (TOT) {
-          const half8 h = __builtin_bit_cast(half8, v);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) te[j] = fmaf((float)h[j], (float)h[j], te[j]);
-        }
         *(uint4v*)(Xs + (it * 8 + lrow) * DCT_XS_STRIDE + lcol) = v;
       }
       if (ch + PD < NCH) {
 #pragma unroll
         for (int it = 0; it < LPC; ++it)
-          R[ch % PD][it] = load_piece(cur, (ch + PD) * RC + it * 8 + lrow, pcur[PERM_IN ? (ch + PD) * LPC + it : 0]);
+          R[ch % PD][it] = load_piece(cur, (ch + PD) * RC + it * 8, pcur[PERM_IN ? (ch + PD) * LPC + it : 0]);
       } else if (has_next) {
 #pragma unroll
         for (int it = 0; it < LPC; ++it)
-          R[ch % PD][it] = load_piece(nxt, (ch + PD - NCH) * RC + it * 8 + lrow, pnxt[PERM_IN ? (ch + PD - NCH) * LPC + it : 0]);
+          R[ch % PD][it] = load_piece(nxt, (ch + PD - NCH) * RC + it * 8, pnxt[PERM_IN ? (ch + PD - NCH) * LPC + it : 0]);
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
       for (int ks = 0; ks < RC / 16; ++ks) {
+        // B operand (lane = column nn, rows 16 ks + 8 g + 0..7) out of the row-major staging buffer by two transposing
+        // reads of four rows each
         half8 B[2];
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < 2; ++nt) {
+          uint4v b4;
 #pragma unroll
-          for (int jj = 0; jj < 8; ++jj) B[nt][jj] = Xs[(ks * 16 + g * 8 + jj) * DCT_XS_STRIDE + nt * 32 + nn];
+          for (int h = 0; h < 2; ++h) {
+            const half_t* ptr = Xs + boff + (ks * 16 + 4 * h) * DCT_XS_STRIDE + nt * 32;
+            const fp16x4 t4 = __builtin_amdgcn_ds_read_tr16_b64_v4f16((fp16x4 __attribute__((address_space(3)))*)ptr);
+            const uint2v u2 = __builtin_bit_cast(uint2v, t4);
+            b4[2 * h] = u2[0]; b4[2 * h + 1] = u2[1];
+          }
+          B[nt] = __builtin_bit_cast(half8, b4);
+          if (TOT) {   // squares of the input, summed in fp32: this lane's column, its 8 rows of the step
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const half2v h2 = {B[nt][2 * q], B[nt][2 * q + 1]};
+              te[nt] = __builtin_amdgcn_fdot2(h2, h2, te[nt], false);
+            }
+            asm volatile("" : "+v"(te[nt]));   // take the sum here: left to itself the compiler postpones all of a tile's
+                                               // sums to its end and keeps every operand alive until then
+          }
+        }
         const int kglob = ch * RC + ks * 16 + g * 8;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -257,29 +296,17 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     }
 
+    // Router statistics (ENERGY): en[0] collects the squares of rows below t1, en[1] of rows below t2, en[2] of all rows;
+    // the bands are differences of these.  The sums are taken inside the epilogue below, group of 32 rows by group, where
+    // each accumulator register is read anyway and dies right after.
+    float f1 = 0.f, f2 = 0.f;
     if (ENERGY) {
       // flat index over the two axes the pass does not transform (perm_o == tokens per slab row on this pass)
       const int32_t other = cur.pidx;
       const int u = other / a.en_div, v = other % a.en_div;
       const int t1 = (u < a.low_u && v < a.low_v) ? a.low_a : 0;
       const int t2 = (u < a.mid_u && v < a.mid_v) ? a.mid_a : 0;
-      const float f1 = (float)(t1 - 4 * g), f2 = (float)(t2 - 4 * g);
-      // en[0] collects rows below t1, en[1] rows below t2, en[2] all rows; the bands are differences of these
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          // row = rc + 4*g; row < t  <=>  clamp(t - row, 0, 1) == 1 for integers (kept in floats: no lane masks to hold)
-          const float rc = (float)(mt * 32 + 8 * (r >> 2) + (r & 3));
-          const float w1 = __builtin_amdgcn_fmed3f(f1 - rc, 0.f, 1.f), w2 = __builtin_amdgcn_fmed3f(f2 - rc, 0.f, 1.f);
-#pragma unroll
-          for (int nt = 0; nt < 2; ++nt) {
-            const float v2 = acc[mt][nt][r] * acc[mt][nt][r];   // rows >= n_out hold exact zeros
-            en[0][nt] = fmaf(v2, w1, en[0][nt]);
-            en[1][nt] = fmaf(v2, w2, en[1][nt]);
-            en[2][nt] += v2;
-          }
-        }
+      f1 = (float)(t1 - 4 * g); f2 = (float)(t2 - 4 * g);
     }
 
     // epilogue: 32 output rows at a time through the staging buffer
@@ -293,8 +320,8 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
       if (!PERM_OUT && a.resid) {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-          const int k = mt * 32 + it * 8 + lrow;
-          if (k < NO) rsd[it] = *(const uint4v*)((const uint16_t*)a.resid + cur.out_off + (int64_t)k * cur.out_stride + lcol);
+          const int k0 = mt * 32 + it * 8;
+          if (k0 + lrow_t < NO) rsd[it] = *(const uint4v*)((const char*)((const uint16_t*)a.resid + cur.out_off + (int64_t)k0 * out_stride) + lane_out);
         }
       }
       __builtin_amdgcn_wave_barrier();
@@ -304,23 +331,33 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
         for (int r = 0; r < 16; ++r) {
           const int row = 8 * (r >> 2) + 4 * g + (r & 3);
           const float val = acc[mt][nt][r];
+          if (ENERGY) {
+            // row = rc + 4*g; row < t  <=>  clamp(t - row, 0, 1) == 1 for integers (kept in floats: no lane masks to hold);
+            // rows >= n_out hold exact zeros
+            const float rc = (float)(mt * 32 + 8 * (r >> 2) + (r & 3));
+            const float w1 = __builtin_amdgcn_fmed3f(f1 - rc, 0.f, 1.f), w2 = __builtin_amdgcn_fmed3f(f2 - rc, 0.f, 1.f);
+            const float v2 = val * val;
+            en[0][nt] = fmaf(v2, w1, en[0][nt]);
+            en[1][nt] = fmaf(v2, w2, en[1][nt]);
+            en[2][nt] += v2;
+          }
           if (PERM_OUT) out_of_range = out_of_range || !(__builtin_fabsf(val) <= 65504.f);
           uint16_t bits;
           if (stage_bf16) bits = dct_f32_to_bf16(val);
           else { const _Float16 hv = (_Float16)val; bits = __builtin_bit_cast(uint16_t, hv); }
-          Xo[row * DCT_XS_STRIDE + nt * 32 + nn] = bits;
+          Xo[row * DCT_XO_STRIDE + nt * 32 + nn] = bits;
         }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
-        const int k = mt * 32 + it * 8 + lrow;
-        if (k < NO) {
-          uint4v v = *(const uint4v*)(Xo + (it * 8 + lrow) * DCT_XS_STRIDE + lcol);
-          int64_t off;
-          if (PERM_OUT) off = (cur.bm_off + prow[mt][it]) * a.d + cur.dcol;
-          else off = cur.out_off + (int64_t)k * cur.out_stride;
+        const int k0 = mt * 32 + it * 8;
+        if (k0 + lrow_t < NO) {
+          uint4v v = *(const uint4v*)(Xo + (it * 8 + lrow) * DCT_XO_STRIDE + lcol);
+          char* dst;   // wave-uniform base plus this lane's 32-bit offset
+          if (PERM_OUT) dst = (char*)((uint16_t*)a.out + cur.bm_off) + ((uint32_t)prow[mt][it] * (uint32_t)a.d + (uint32_t)lcol) * 2u;
+          else dst = (char*)((uint16_t*)a.out + cur.out_off + (int64_t)k0 * out_stride) + lane_out;
           if (!PERM_OUT && a.resid) {   // out = resid + result, both bf16 in memory, the sum formed in fp32
             const uint4v rs = rsd[it];
             const half8 h = __builtin_bit_cast(half8, v);
@@ -331,7 +368,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
               v[i] = (uint32_t)dct_f32_to_bf16(lo) | ((uint32_t)dct_f32_to_bf16(hi) << 16);
             }
           }
-          *(uint4v*)((uint16_t*)a.out + off + lcol) = v;
+          *(uint4v*)dst = v;
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -357,11 +394,10 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
     }
     if (TOT) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        float t = te[j];
-        t += __shfl_xor(t, 8); t += __shfl_xor(t, 16); t += __shfl_xor(t, 32);   // lanes that share lane & 7
-        float* slot = a.tot_part + (size_t)gwave * 64 + lcol + j;
-        if (lane < 8) *slot = t;
+      for (int nt = 0; nt < 2; ++nt) {
+        const float tot = te[nt] + __shfl_xor(te[nt], 32);   // the two lane halves hold different rows of the same column
+        float* slot = a.tot_part + (size_t)gwave * 64 + nt * 32 + nn;
+        if (g == 0) *slot = tot;
       }
     }
   }
@@ -373,6 +409,13 @@ static hipError_t launch_n(const DctPassArgs& a, int num_cu, hipStream_t st, int
   const int64_t n_tiles = a.nslab * chunks;
   if (n_tiles == 0) return hipSuccess;
   if (n_tiles > 0x7fffffff) return hipErrorInvalidValue;
+  {
+    // the kernel adds per-lane byte offsets as unsigned 32-bit numbers: 8 rows of the larger row stride, a band-major
+    // row times head_dim, 8 rows of the permutation table
+    const int64_t stride = (a.in_swap || a.out_swap) ? (int64_t)a.sw_total * a.inner : a.inner;
+    if (stride * 8 * 2 + 128 > 0xffffffffLL) return hipErrorInvalidValue;
+    if ((a.perm_in || a.perm_out) && (a.Ntok * a.d * 2 > 0xffffffffLL || a.perm_k * 8 * 4 > 0xffffffffLL)) return hipErrorInvalidValue;
+  }
   // workgroups per CU: bounded by the 160 KB of LDS of a gfx950 CU (the runtime's occupancy query assumes 64 KB)
   constexpr int lds_bytes = (32 * MT * (NI + 8) + DCT_WAVES * 32 * DCT_XS_STRIDE) * 2;
   static int occ = 0;
@@ -418,7 +461,25 @@ static hipError_t launch_n(const DctPassArgs& a, int num_cu, hipStream_t st, int
       return hipErrorInvalidValue;
     *waves_out = (int)(blocks * DCT_WAVES);
   }
-  hipLaunchKernelGGL((k_dct_pass<NI, MT, MODE>), dim3((unsigned)blocks), dim3(64 * DCT_WAVES), 0, st, a, n_tiles, chunks);
+  // Workgroups per compute unit.  The passes over 64 rows and fewer run best with all the waves their registers allow
+  // (three or four per SIMD: a tile is 8 KB, and the loads in flight are what keeps the memory system busy); the passes
+  // over 128 rows measured 3 % faster held to two workgroups per unit, which is enforced by asking for LDS the kernel does
+  // not use.  FREQATTN_DCT_WGS / FREQATTN_DCT_WGS_128 override (0 = no limit).
+  static int dyn_lds = -1;
+  if (dyn_lds < 0) {
+    const char* e = getenv(NI >= 128 ? "FREQATTN_DCT_WGS_128" : "FREQATTN_DCT_WGS");
+    const int wgs = e ? atoi(e) : (NI >= 128 ? 2 : 0);
+    dyn_lds = 0;
+    if (wgs > 0) {
+      const int per = (160 * 1024 / wgs) / 1024 * 1024;
+      if (per > lds_bytes) dyn_lds = per - lds_bytes;
+      if (dyn_lds > 0) {
+        const hipError_t e2 = hipFuncSetAttribute((const void*)k_dct_pass<NI, MT, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn_lds);
+        if (e2 != hipSuccess) { dyn_lds = -1; return e2; }
+      }
+    }
+  }
+  hipLaunchKernelGGL((k_dct_pass<NI, MT, MODE>), dim3((unsigned)blocks), dim3(64 * DCT_WAVES), (size_t)dyn_lds, st, a, n_tiles, chunks);
   return hipGetLastError();
 }
 
