@@ -27,6 +27,8 @@
  *   FREQATTN_DCT_WGS=n, FREQATTN_DCT_WGS_128=n   read at the first launch of each pass shape: most workgroups of a transform
  *                          pass per compute unit, for passes over fewer than 128 rows / over 128 rows (0 = whatever fits;
  *                          defaults 0 and 2)
+ *   FREQATTN_GEMM_WIDE=0|1  read at the first product launch of freqattn_forward_projected: 0 keeps every product on the
+ *                          128 x 128-tile kernel (default 1: 256 x 256 tiles where a launch has that many rows and columns)
  */
 #ifndef FREQATTN_H
 #define FREQATTN_H

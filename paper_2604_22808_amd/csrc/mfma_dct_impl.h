@@ -66,7 +66,7 @@ enum { DCT_PLAIN = 0, DCT_PLAIN_TOT = 1, DCT_SCATTER = 2, DCT_SCATTER_EN = 3, DC
 // Waves per SIMD the register allocation aims at: three (168 registers) for the variants with at most 64 accumulator
 // registers, whose tiles are small enough that a third wave's loads in flight matter more than spare registers.
 template <int NI, int MT, int MODE> constexpr int dct_min_waves() {
-  int w = MT == 1 ? 4 : MT == 2 ? 3 : 2;
+  int w = MT <= 2 ? 3 : 2;
   if (MODE == 4 && NI > 64 && w > 2) --w;   // the gather pass also holds the looked-up rows of two tiles
   return w;
 }
@@ -164,7 +164,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
     if (PERM_IN) {
       const int band = row < a.band_off1 ? 0 : (row < a.band_off2 ? 1 : 2);
       const bool active = (t.mask >> band) & 1;
-      const uint32_t lane_off = ((uint32_t)row * (uint32_t)a.d + (uint32_t)lcol) * 2u;   // bytes within the slice
+      const uint64_t lane_off = ((uint64_t)(uint32_t)row * (uint32_t)a.d + (uint32_t)lcol) * 2u;   // bytes within the slice
       if (a.delta) {   // change of the active bands against V~ (zero elsewhere)
         uint4v r = {0u, 0u, 0u, 0u};
         if (active) {
@@ -356,7 +356,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
         if (k0 + lrow_t < NO) {
           uint4v v = *(const uint4v*)(Xo + (it * 8 + lrow) * DCT_XO_STRIDE + lcol);
           char* dst;   // wave-uniform base plus this lane's 32-bit offset
-          if (PERM_OUT) dst = (char*)((uint16_t*)a.out + cur.bm_off) + ((uint32_t)prow[mt][it] * (uint32_t)a.d + (uint32_t)lcol) * 2u;
+          if (PERM_OUT) dst = (char*)((uint16_t*)a.out + cur.bm_off) + ((uint64_t)(uint32_t)prow[mt][it] * (uint32_t)a.d + (uint32_t)lcol) * 2u;
           else dst = (char*)((uint16_t*)a.out + cur.out_off + (int64_t)k0 * out_stride) + lane_out;
           if (!PERM_OUT && a.resid) {   // out = resid + result, both bf16 in memory, the sum formed in fp32
             const uint4v rs = rsd[it];
@@ -410,11 +410,11 @@ static hipError_t launch_n(const DctPassArgs& a, int num_cu, hipStream_t st, int
   if (n_tiles == 0) return hipSuccess;
   if (n_tiles > 0x7fffffff) return hipErrorInvalidValue;
   {
-    // the kernel adds per-lane byte offsets as unsigned 32-bit numbers: 8 rows of the larger row stride, a band-major
-    // row times head_dim, 8 rows of the permutation table
+    // the kernel adds per-lane byte offsets as unsigned 32-bit numbers: 8 rows of the larger row stride, 8 rows of the
+    // permutation table (band-major rows times the row width are formed in 64 bits)
     const int64_t stride = (a.in_swap || a.out_swap) ? (int64_t)a.sw_total * a.inner : a.inner;
     if (stride * 8 * 2 + 128 > 0xffffffffLL) return hipErrorInvalidValue;
-    if ((a.perm_in || a.perm_out) && (a.Ntok * a.d * 2 > 0xffffffffLL || a.perm_k * 8 * 4 > 0xffffffffLL)) return hipErrorInvalidValue;
+    if ((a.perm_in || a.perm_out) && (a.Ntok > 0x7fffffffLL || a.perm_k * 8 * 4 > 0xffffffffLL)) return hipErrorInvalidValue;
   }
   // workgroups per CU: bounded by the 160 KB of LDS of a gfx950 CU (the runtime's occupancy query assumes 64 KB)
   constexpr int lds_bytes = (32 * MT * (NI + 8) + DCT_WAVES * 32 * DCT_XS_STRIDE) * 2;

@@ -16,6 +16,8 @@
 // of C and its accumulator registers run over columns - the same register layout as the attention kernel's output.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "ctx.h"
 
 namespace fa {
@@ -143,6 +145,146 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(const GemmProblem* __restric
     }
 }
 
+// The same product with a 256 x 256 tile per workgroup of eight waves (a wave owns 64 rows x 128 columns: per K step of 16
+// it reads 2 + 4 operands from LDS for 8 MFMAs, and the tile brings half the bytes per flop into LDS that the 128 x 128
+// tile above does).  One workgroup per compute unit; K advances in steps of 64 through two LDS buffers of 64 KB (a
+// variant with steps of 32 through four buffers - three steps in flight - measured 6 % slower, and so did touching the
+// lines of later steps ahead of time to have them in L2, and so did spreading a step's copies between its MFMAs: the
+// copies' latency is not what holds this kernel back; its LDS reads and copy writes together keep the LDS about as busy
+// as the MFMAs keep the matrix cores).
+// The columns of a launch run over all its problems back to back (problem p owns columns [p n, (p + 1) n), n a
+// multiple of 32), so that a tile can span several narrow problems - the per-head projections are 64 or 128 columns
+// wide.  All problems of a launch must have the same A segments (pointers, strides and K); B and C are the problem's own.
+constexpr int WM = 256, WN = 256, WK = 64, WST = 2;
+
+__global__ void __launch_bounds__(512, 1) k_gemm_nt_wide(const GemmProblem* __restrict__ probs, const GemmSeg* __restrict__ segs,
+                                                         int per, int n, int tiles_m, int tiles_n) {
+  static_assert((WM + WN) * WK * 2 * WST <= 160 * 1024, "LDS budget");
+  __shared__ __attribute__((aligned(16))) half_t As[WST][WM * WK];
+  __shared__ __attribute__((aligned(16))) half_t Bs[WST][WN * WK];
+  const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+  const int mt = (seq / tiles_n) * 8 + xcd;
+  if (mt >= tiles_m) return;   // (uniform over the workgroup: the grid is padded to whole rounds of 8 row tiles)
+  const int m0 = mt * WM, gc0 = (seq % tiles_n) * WN;   // first row / first column (over all problems) of the tile
+  const int n_total = per * n;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nn = lane & 31, g = lane >> 5;
+  const int wm = wave & 3, wn = wave >> 2;              // this wave's 64 rows and 128 columns of the tile
+  // Rows are WK halfs in LDS; the 16-byte chunks of row r are permuted through the source address so that the operand
+  // reads of 16 consecutive rows fall on 16 different 16-byte bank groups
+  constexpr int CPR = WK / 8;                           // chunks per row
+  constexpr int RPI = 64 / CPR;                         // rows per copy instruction (64 lanes x 16 bytes)
+  constexpr int IPW = 32 / RPI;                         // copy instructions per wave, step and matrix
+  auto fK = [](int r) -> int { return (r >> 1) & 7; };
+  const int lr = lane / CPR, lc = lane % CPR;
+
+  // the copies: wave w moves rows [32 w, 32 w + 32) of the A tile and of the B tile
+  const int bcol0 = gc0 + 32 * wave;                                    // first B row (= column of C) this wave copies
+  const int pb = min(bcol0, n_total - 1) / n;                           // its problem (n % 32 == 0: one problem per wave)
+  const GemmProblem prb = probs[pb];
+  const int m = prb.m;
+  int a_row[IPW], b_row[IPW];   // row within the tile's A rows / within the problem's B rows, clamped to what exists
+#pragma unroll
+  for (int i = 0; i < IPW; ++i) {
+    const int r = 32 * wave + RPI * i + lr;
+    a_row[i] = min(m0 + r, m - 1) - m0;
+    b_row[i] = min(bcol0 + RPI * i + lr, n_total - 1) - pb * n;
+  }
+  auto stage = [&](const GemmSeg& sg, int k0, int buf) {
+    const half_t* abase = sg.A + (int64_t)m0 * sg.lda + k0;   // wave-uniform
+    const half_t* bbase = sg.B + k0;
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+      const int r = 32 * wave + RPI * i + lr;
+      const int chunk = (lc ^ fK(r)) << 3;
+      gemm_dma16(abase + (uint32_t)(a_row[i] * sg.lda + chunk), As[buf] + (32 * wave + RPI * i) * WK);
+      gemm_dma16(bbase + (uint32_t)(b_row[i] * sg.ldb + chunk), Bs[buf] + (32 * wave + RPI * i) * WK);
+    }
+  };
+
+  float16v acc[4][2];   // [column tile][row tile]
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ct][rt][r] = 0.f;
+
+  int seg_i = 0, k_i = 0;   // position of the step that is copied next
+  GemmSeg sg = segs[prb.seg0];
+  int total_steps = 0;
+  for (int s2 = 0; s2 < prb.nseg; ++s2) total_steps += segs[prb.seg0 + s2].K / WK;
+  auto advance = [&]() {
+    k_i += WK;
+    if (k_i >= sg.K) {
+      k_i = 0;
+      ++seg_i;
+      if (seg_i < prb.nseg) sg = segs[prb.seg0 + seg_i];
+    }
+  };
+  if (total_steps > 0) { stage(sg, k_i, 0); advance(); }
+  for (int step = 0; step < total_steps; ++step) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of step `step` has landed
+    __syncthreads();   // step `step` is in LDS for every wave, and nobody reads the buffer of step - 1 any more
+    if (step + 1 < total_steps) { stage(sg, k_i, (step + 1) % WST); advance(); }
+    const int buf = step % WST;
+    const half_t* Ab = As[buf] + (64 * wm + nn) * WK;
+    const half_t* Bb = Bs[buf] + (128 * wn + nn) * WK;
+    constexpr int NKS = WK / 16;
+    half8 rows[2][2], cols[2][4];
+    auto operands = [&](int ks, int set) {
+      const int pos = ((2 * ks + g) ^ fK(nn)) << 3;        // fK(32 t + nn) = fK(nn)
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) rows[set][rt] = *(const half8*)(Ab + rt * 32 * WK + pos);
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) cols[set][ct] = *(const half8*)(Bb + ct * 32 * WK + pos);
+    };
+    operands(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      if (ks + 1 < NKS) operands(ks + 1, (ks + 1) & 1);
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+          acc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(cols[ks & 1][ct], rows[ks & 1][rt], acc[ct][rt], 0, 0, 0);
+    }
+  }
+
+  // store: lane = row of C, registers = columns; a register swap with the partner lane (lane ^ 32, same row) leaves
+  // every lane with 8 consecutive columns, i.e. 16-byte stores.  Every 32-column tile looks up its own problem.
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct) {
+    const int gc = gc0 + 128 * wn + 32 * ct;
+    if (gc >= n_total) break;
+    const int pc = gc / n;
+    const GemmProblem pr = probs[pc];
+    const int col0 = gc - pc * n;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      const int row = m0 + 64 * wm + 32 * rt + nn;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        float o[8];   // columns col0 + j*16 + g*8 + 0..7
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const uint32_t lo = __float_as_uint(acc[ct][rt][(2 * j) * 4 + b]);
+          const uint32_t hi = __float_as_uint(acc[ct][rt][(2 * j + 1) * 4 + b]);
+          const auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
+          o[b] = __uint_as_float(sw[0]);
+          o[4 + b] = __uint_as_float(sw[1]);
+        }
+        if (row < pr.m) {
+          uint4v st4;
+#pragma unroll
+          for (int b = 0; b < 4; ++b) st4[b] = gemm_pack_h2(o[2 * b], o[2 * b + 1]);
+          *(uint4v*)(pr.C + (int64_t)row * pr.ldc + col0 + j * 16 + g * 8) = st4;
+        }
+      }
+    }
+  }
+}
+
 // out[c][r] = (fp16) in[r][c] for a bf16 matrix [R][Cc]: the weights arrive [k][n] (n contiguous) and the product wants
 // them K-contiguous.  32 x 32 tiles through LDS.
 __global__ void __launch_bounds__(256) k_transpose_bf16_to_f16(const uint16_t* __restrict__ in, half_t* __restrict__ out, int R, int Cc) {
@@ -167,6 +309,16 @@ __global__ void __launch_bounds__(256) k_transpose_bf16_to_f16(const uint16_t* _
 // `per` problems d_probs[0 .. per) of identical m and n (host-checked by the caller).
 hipError_t launch_gemm_nt(const GemmProblem* d_probs, const GemmSeg* d_segs, int per, int m, int n, hipStream_t st) {
   if (per <= 0 || m <= 0 || n <= 0) return hipSuccess;
+  static int wide = -1;
+  if (wide < 0) { const char* e = getenv("FREQATTN_GEMM_WIDE"); wide = e ? atoi(e) : 1; }
+  if (wide && n % 32 == 0 && m >= WM && (int64_t)per * n >= WN) {
+    // (the callers' launches share their A segments between problems, which the wide kernel relies on)
+    const int tiles_m = (m + WM - 1) / WM, tiles_n = (int)(((int64_t)per * n + WN - 1) / WN);
+    const int64_t blocks = (int64_t)((tiles_m + 7) / 8) * 8 * tiles_n;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_gemm_nt_wide, dim3((unsigned)blocks), dim3(512), 0, st, d_probs, d_segs, per, n, tiles_m, tiles_n);
+    return hipGetLastError();
+  }
   const int tiles_m = (m + GM - 1) / GM, tiles_n = (n + GN - 1) / GN;
   const int64_t blocks = (int64_t)((tiles_m + 7) / 8) * 8 * tiles_n * per;
   if (blocks > 0x7fffffff) return hipErrorInvalidValue;
