@@ -388,7 +388,7 @@ def main():
     stage_report = {}
     for name, ms in stages:
         entry = {"ms": round(ms, 4)}
-        if name in work and ms > 0:
+        if name in work and ms > 0 and work[name][1] > 0:   # (a stage with nothing left to do carries only its time)
             bound, amount, launches = work[name]
             if bound == "hbm":
                 entry.update(bound="hbm", achieved_GBs=round(amount / (ms * 1e-3) / 1e9, 1), launches=launches)
