@@ -212,7 +212,6 @@ hipError_t launch_vsum(const void* V, const void* Wsum, float* part, void* C, co
 hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, float* stats /*[3][d], zeroed inside*/,
                               int slices, int64_t N, int d, const int64_t band_off[3], const int64_t band_n[3],
                               int is_half, hipStream_t st);
-// Adds up the per-wave partial sums of the three fused W-axis passes in a fixed order: stats[band][channel].
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 hipError_t launch_probe_copy(const void* in, void* out, int64_t bytes, int num_cu, hipStream_t st);
 hipError_t launch_probe_mfma(float* out, int blocks, int iters, hipStream_t st);
@@ -223,7 +222,7 @@ hipError_t launch_copy_slices(const void* in, void* out, const int32_t* slice_li
                               hipStream_t st);
 struct EnergyWaves { int en[6]; int tot[3]; };   // waves whose slots hold this forward's partial sums, per statistics slot
 hipError_t launch_energy_reduce(const float* energy_part /*[6][DCT_MAX_WAVES][3][64]: Q, K, V (box), Q, K, V (whole grid)*/,
-                                const float* tot_part /*[3][DCT_MAX_WAVES][64] or NULL*/, float* stats, int d,
+                                const float* tot_part /*[3][DCT_MAX_WAVES][64] or NULL*/, float* stats /*[3][d] + 3*d*64 floats of scratch*/, int d,
                                 const EnergyWaves& nw, hipStream_t st);
 
 // ---- MFMA kernels (mfma_dct.hip, mfma_attn.hip) -------------------------------------------------------------------

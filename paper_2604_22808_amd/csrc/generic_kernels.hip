@@ -530,45 +530,67 @@ hipError_t launch_convert_16(const void* in, void* out, int64_t n, int to_bf16, 
 }
 
 // Fixed-order sum of the per-wave partial statistics written by the fused forward passes of Q, K and V.
-// Wave w of a launch worked on column chunk w % (d/64) only.  One workgroup per (band, channel): 256 threads take
-// the (tensor, wave) terms round-robin and a fixed tree adds their partial sums.
+// Wave w of a launch worked on column chunk w % (d/64) only, and left [3 bands][64 columns] floats behind (768 bytes).
+// Two stages.  Stage 1: d workgroups of 4 x 192 threads (thread = band, column); workgroup b takes the waves w = b, b + d,
+// ... of every slot (d is a multiple of d/64, so all of them belong to chunk b % (d/64)) and reads their 768 bytes
+// whole.  Stage 2: one thread per (band, channel) adds the stage-1 sums of its chunk in ascending workgroup order.
 // With tot_part set, the tensors in slots 0..2 were only computed on the low+mid box: their high-band energy is the
 // energy of the input (Parseval, the transform is orthonormal) minus their low and mid energies.
-__global__ void __launch_bounds__(256) k_energy_reduce(const float* part, const float* tot_part, float* stats, int d, EnergyWaves nw) {
-  __shared__ float red[256];
-  const int idx = blockIdx.x, tid = threadIdx.x;
-  const int band = idx / d, ch = idx % d;
-  const int chunks = d / 64, chunk = ch / 64, col = ch % 64;
+__global__ void __launch_bounds__(768) k_energy_reduce1(const float* __restrict__ part, const float* __restrict__ tot_part,
+                                                        float* __restrict__ part1 /*[d][3][64]*/, int d, EnergyWaves nw) {
+  // four groups of 192 threads share a workgroup's waves (group q takes every fourth of them), four loads in flight each
+  __shared__ float red[4][192];
+  const int b = blockIdx.x, q = threadIdx.x / 192, tid = threadIdx.x % 192, band = tid >> 6, col = tid & 63;
   const bool parseval = tot_part != nullptr && band == 2;
-  float t = 0.f;
+  const int first = b + q * d, step = 4 * d;
+  float t[4] = {0.f, 0.f, 0.f, 0.f};
   for (int tensor = 0; tensor < 6; ++tensor) {   // slots: Q, K, V on the box (Parseval for the high band), Q, K, V on the whole grid
-    const int per = (nw.en[tensor] - chunk + chunks - 1) / chunks;   // waves of this chunk that stored sums into this slot
-    for (int i = tid; i < per; i += 256) {
-      const int w = chunk + i * chunks;
-      const float* p3 = part + (((size_t)tensor * DCT_MAX_WAVES + w) * 3) * 64 + col;
-      if (parseval && tensor < 3) t -= p3[0] + p3[64];
-      else t += p3[band * 64];
+    const float* base = part + (size_t)tensor * DCT_MAX_WAVES * 192;
+    const int n = nw.en[tensor];
+    if (parseval && tensor < 3) {
+      for (int w = first; w < n; w += 4 * step)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (w + u * step < n) t[u] -= base[(size_t)(w + u * step) * 192 + col] + base[(size_t)(w + u * step) * 192 + 64 + col];
+    } else {
+      for (int w = first; w < n; w += 4 * step)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (w + u * step < n) t[u] += base[(size_t)(w + u * step) * 192 + tid];
     }
   }
   if (parseval)
     for (int tensor = 0; tensor < 3; ++tensor) {
-      const int per_t = (nw.tot[tensor] - chunk + chunks - 1) / chunks;
-      for (int i = tid; i < per_t; i += 256) t += tot_part[((size_t)tensor * DCT_MAX_WAVES + chunk + (size_t)i * chunks) * 64 + col];
+      const int n = nw.tot[tensor];
+      for (int w = first; w < n; w += 4 * step)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (w + u * step < n) t[u] += tot_part[((size_t)tensor * DCT_MAX_WAVES + w + u * step) * 64 + col];
     }
-  red[tid] = t;
+  red[q][tid] = (t[0] + t[1]) + (t[2] + t[3]);
   __syncthreads();
-  for (int sft = 128; sft > 0; sft >>= 1) {
-    if (tid < sft) red[tid] += red[tid + sft];
-    __syncthreads();
-  }
-  // The Parseval difference of a band that holds (almost) no energy can come out slightly negative (the low and mid
-  // sums carry the rounding of the fp16 transform): an energy is never below zero.
-  if (tid == 0) stats[idx] = (parseval && red[0] < 0.f) ? 0.f : red[0];   // (a NaN stays a NaN: the host reports it)
+  if (q == 0) part1[(size_t)b * 192 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
 }
 
+__global__ void __launch_bounds__(384) k_energy_reduce2(const float* __restrict__ part1, float* __restrict__ stats, int d, int parseval) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= 3 * d) return;
+  const int band = idx / d, ch = idx % d;
+  const int chunks = d / 64, chunk = ch / 64, col = ch % 64;
+  float t = 0.f;
+  for (int b = chunk; b < d; b += chunks) t += part1[(size_t)b * 192 + band * 64 + col];
+  // The Parseval difference of a band that holds (almost) no energy can come out slightly negative (the low and mid
+  // sums carry the rounding of the fp16 transform): an energy is never below zero.
+  stats[idx] = (parseval && band == 2 && t < 0.f) ? 0.f : t;   // (a NaN stays a NaN: the host reports it)
+}
+
+// stats: [3][d] results followed by at least 3 * d * 64 floats of scratch (the stage-1 sums)
 hipError_t launch_energy_reduce(const float* energy_part, const float* tot_part, float* stats, int d, const EnergyWaves& nw,
                                 hipStream_t st) {
-  hipLaunchKernelGGL(k_energy_reduce, dim3(3 * d), dim3(256), 0, st, energy_part, tot_part, stats, d, nw);
+  if (d % 64 != 0 || d <= 0) return hipErrorInvalidValue;
+  float* part1 = stats + 3 * d;
+  hipLaunchKernelGGL(k_energy_reduce1, dim3(d), dim3(768), 0, st, energy_part, tot_part, part1, d, nw);
+  hipLaunchKernelGGL(k_energy_reduce2, dim3((3 * d + 383) / 384), dim3(384), 0, st, part1, stats, d, tot_part != nullptr ? 1 : 0);
   return hipGetLastError();
 }
 
