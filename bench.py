@@ -410,6 +410,9 @@ def main():
                 "avg_launch_ms": round(per_launch_s * 1e3, 4), "achieved": round(achieved, 2), "peak": peak, "unit": unit,
                 "frac": round(achieved / peak, 4), "traffic": traffic, "traffic_measured_at_commit": traffic_commit,
                 "measured_peak": round(measured, 1), "frac_of_measured": round(achieved / measured, 4)}
+    if traffic and bound == "hbm":   # what the stage's kernels really move (counter bytes of the committed profile) per second
+        roofline["hbm_rate_at_measured_traffic"] = round(traffic / per_launch_s / 1e9, 1)
+        roofline["frac_at_measured_traffic"] = round(traffic / per_launch_s / 1e9 / peak, 4)
     if dom[0] in work_min:   # the same stage against the bytes the pruned scheme strictly needs
         ach_min = work_min[dom[0]] / (dom[1] * 1e-3) / 1e9
         roofline["achieved_pruned_minimum"] = round(ach_min, 2)
