@@ -5,8 +5,8 @@
 //
 // Work decomposition: a wave owns a tile of all n rows x 64 contiguous columns.  Rows arrive as coalesced 128-byte
 // segments, are parked row-major in a wave-private LDS buffer 32 rows at a time, and are read back column-wise as
-// the B operand of v_mfma_f32_32x32x16_f16 (lane = column, 8 consecutive j per lane); the A operand is the fp16
-// transform matrix, staged once per workgroup in LDS.  The next 32 rows (of this tile or of the wave's next tile)
+// the B operand of v_mfma_f32_32x32x16_f16 (lane = column, 8 consecutive j per lane: two transposing LDS reads of
+// four rows each); the A operand is the fp16 transform matrix, staged once per workgroup in LDS.  The next 32 rows (of this tile or of the wave's next tile)
 // are fetched while the current 32 are multiplied.  Accumulators are fp32; results go back through the same LDS
 // buffer so that global stores are again full 128-byte rows.  The kernel is bandwidth-bound by design: every element
 // is read once and written once per axis.
