@@ -116,8 +116,10 @@ freqattn_status freqattn_create(const freqattn_shape* shape /*HOST*/, const freq
  * and the output of such a forward is not defined.  FREQATTN_F32 contexts and FREQATTN_PATH_GENERIC have no such limit.
  * Asynchronous: work is enqueued on `stream` and the call returns.  The one exception is a call whose head_alloc
  * differs from the previous call's on this context: it first waits for `stream` so that the work lists of earlier
- * calls are no longer in use.  Allocates nothing.  EINVAL: NULL pointer, head_alloc entry outside 0..7, band_cfg
- * mismatch.  EHIP: a launch failed. */
+ * calls are no longer in use.  Allocates nothing.  To capture the call into a HIP graph, run it once eagerly with the
+ * same head_alloc first: the first launch of a kernel variant reads the environment switches and sets its launch
+ * attributes, and a changed head_alloc waits for the stream - neither belongs under capture.  EINVAL: NULL pointer,
+ * head_alloc entry outside 0..7, band_cfg mismatch.  EHIP: a launch failed. */
 freqattn_status freqattn_forward(freqattn_ctx* ctx, const void* q, const void* k, const void* v,
                                  const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out, void* stream);
 
