@@ -319,3 +319,92 @@ def test_forward_replays_from_a_hip_graph():
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, eager), rep
+
+
+def test_batch_of_two_router_in_the_loop():
+    """batch 2 x 4 heads on the 16K grid, router in the loop: the statistics are means over both batch entries (section
+    3.5), the allocation repeats per batch entry, and the routed output must equal the plain forward with it bit for bit
+    and the oracle within the tolerance."""
+    import torch
+    wl = WL.WORKLOADS["16k"]
+    d, N = wl.head_dim, wl.n_tokens
+    q, k, v = (np.stack([np.stack([WL.field_numpy(wl.grid, d, 40 + b, s, h) for h in range(4)]) for b in range(2)]).reshape(2, 4, N, d)
+               for s in range(3))
+    q, k, v = (WL.round_to_io(x, "bf16") for x in (q, k, v))
+    band = dict(wl.band)
+    cfg = O.BandConfig(**band)
+    w = WL.router_weights(64, 1)
+    ctx = B.Context(2, 4, d, wl.grid, B.BF16, B.make_cfg(**band))
+    assert ctx.get_path() == B.PATH_MFMA
+    dq, dk, dv = (U.to_device(x, "bf16") for x in (q, k, v))
+    out = torch.empty_like(dq); plain = torch.empty_like(dq)
+    for t in (0.8, 0.2):
+        for _ in range(2):     # second call: the prediction from the first
+            alloc, pi = ctx.forward_routed(dq, dk, dv, t, *w, out)
+        torch.cuda.synchronize()
+        alloc = [int(a) for a in alloc]
+        stats = U.band_statistics_library_transform(q, k, v, wl.grid, band)
+        want_alloc, want_pi = U.expected_route(stats, t, w, 4)
+        print(f"batch 2 routed t={t}: allocation {alloc} pi {pi} oracle {list(want_alloc)} {want_pi}", flush=True)
+        assert np.abs(pi - want_pi).max() < 2e-3 and alloc == [int(a) for a in want_alloc]
+        ctx.forward(dq, dk, dv, alloc, plain)
+        torch.cuda.synchronize()
+        assert torch.equal(out, plain)
+        want = O.forward(q, k, v, wl.grid, cfg, alloc)
+        mx, rl = U.errors(U.to_host64(out), want)
+        print(f"batch 2 routed t={t}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+        assert mx <= 2e-2 and rl <= 5e-3
+
+
+def test_projected_forward_batch_of_two():
+    """The folded layer with batch 2 (the product launches group by batch entry)."""
+    import torch
+    wl = WL.WORKLOADS["16k"]
+    heads, alloc = 4, (1, 2, 4, 6)
+    d, N = wl.head_dim, wl.n_tokens
+    dm = heads * d
+    rng = np.random.default_rng(29)
+    xs = np.stack([np.stack([WL.field_numpy(wl.grid, d, 50 + b, 0, h) for h in range(heads)], axis=1).reshape(N, dm) for b in range(2)])
+    x = WL.round_to_io(xs, "bf16")
+    wq, wk, wv, wo = (WL.round_to_io(rng.standard_normal((dm, dm)) / np.sqrt(dm), "bf16") for _ in range(4))
+    band = dict(wl.band)
+    ctx = B.Context(2, heads, d, wl.grid, B.BF16, B.make_cfg(**band))
+    dev = lambda a: U.to_device(a, "bf16")
+    dx, dwq, dwk, dwv, dwo = dev(x), dev(wq), dev(wk), dev(wv), dev(wo)
+    out = torch.empty_like(dx)
+    ctx.forward_projected(dx, dwq, dwk, dwv, dwo, alloc, out)
+    torch.cuda.synchronize()
+    assert ctx.check_range() == 0
+    want = O.forward_projected(x, wq, wk, wv, wo, wl.grid, O.BandConfig(**band), alloc)
+    assert np.abs(want[0] - want[1]).max() > 1e-3
+    mx, rl = U.errors(U.to_host64(out), want)
+    print(f"projected batch 2: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+    assert mx <= 2e-2 and rl <= 5e-3
+
+
+def test_projected_forward_on_a_ragged_grid():
+    """Grid 16 x 48 x 80 (61,440 tokens; bands of 960 / 6,720 / 53,760 rows, none a multiple of the products' 256-row
+    tiles), head_dim 128, 3 heads: the last row tile of every product launch is partly empty."""
+    import torch
+    grid, d, heads, alloc = (16, 48, 80), 128, 3, (1, 2, 4)
+    N = int(np.prod(grid))
+    dm = heads * d
+    rng = np.random.default_rng(31)
+    xs = np.stack([WL.field_numpy(grid, d, 60, 0, h) for h in range(heads)], axis=1).reshape(1, N, dm)
+    x = WL.round_to_io(xs, "bf16")
+    wq, wk, wv, wo = (WL.round_to_io(rng.standard_normal((dm, dm)) / np.sqrt(dm), "bf16") for _ in range(4))
+    band = dict(WL.WORKLOADS["16k"].band)
+    band.update(mid_block=128, mid_diag=1, mid_stride=5, high_window=200, n_summary=7, low_compress=4)
+    ctx = B.Context(1, heads, d, grid, B.BF16, B.make_cfg(**band))
+    assert ctx.get_path() == B.PATH_MFMA
+    assert any(n % 256 for n in ctx.band_sizes())
+    dev = lambda a: U.to_device(a, "bf16")
+    dx, dwq, dwk, dwv, dwo = dev(x), dev(wq), dev(wk), dev(wv), dev(wo)
+    out = torch.empty_like(dx)
+    ctx.forward_projected(dx, dwq, dwk, dwv, dwo, alloc, out)
+    torch.cuda.synchronize()
+    assert ctx.check_range() == 0
+    want = O.forward_projected(x, wq, wk, wv, wo, grid, O.BandConfig(**band), alloc)
+    mx, rl = U.errors(U.to_host64(out), want)
+    print(f"projected ragged grid: bands {ctx.band_sizes()} max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+    assert mx <= 2e-2 and rl <= 5e-3
