@@ -202,15 +202,19 @@ freqattn_status freqattn_route_mlp(freqattn_ctx* ctx, const void* q, const void*
 
 /* The path with the projections of sections 3.1 and 3.7 folded around it: Q = X W_Q, K = X W_K, V = X W_V per head, the
  * per-head path, then concat(heads) W_O.  The transform acts on the token axes and the projections on channels, so they
- * commute: X is transformed once instead of Q, K and V, the projections run on spectral rows (Q~ and K~ only on the
- * rows of the bands a head runs), W_O is applied to the band outputs and one inverse transform of model width follows.
+ * commute: X is transformed once instead of Q, K and V, the projections run on spectral rows (Q~, K~ and V~ only on
+ * the rows of the bands a head runs), W_O is applied to the band outputs and one inverse transform of model width
+ * follows.  On a band a head passes through, its V~ only reaches the output projection and the summary tokens: the
+ * first as X~ times the sum over the passing heads of W_V,h W_O,h (one more K segment of the band's output product), the
+ * second as chunk means of X~ rows times W_V,h.  (With more than 256 slices, or FREQATTN_PROJ_FOLD=0 - read at every
+ * call - V~ is projected on every row instead.)
  *   x, out   DEVICE, contiguous [batch, N, d_model] bf16; out must not overlap x
  *   wq, wk, wv  DEVICE bf16 [d_model, heads * head_dim] row-major (head h owns columns h*head_dim ..)
  *   wo       DEVICE bf16 [heads * head_dim, d_model] row-major
  *   d_model  multiple of 64, at most heads * head_dim
  * BF16 contexts on the matrix-core path only (FREQATTN_EUNSUPPORTED otherwise).  The first call for a d_model allocates
- * the model-width buffers (two of batch * N * d_model fp16, the transposed weights) and synchronises; later calls
- * allocate nothing.  Asynchronous otherwise, like freqattn_forward; the range contract stated there applies to x. */
+ * the model-width buffers (two of batch * N * d_model fp16, the transposed weights, 3 * d_model^2 for the pass-through
+ * weights) and synchronises; later calls allocate nothing.  Asynchronous otherwise, like freqattn_forward; the range contract stated there applies to x. */
 freqattn_status freqattn_forward_projected(freqattn_ctx* ctx, const void* x, int32_t d_model, const void* wq,
                                            const void* wk, const void* wv, const void* wo,
                                            const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out,

@@ -84,6 +84,7 @@ static void free_all(Ctx* c) {
   F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_range_flag); F(c->d_lists); F(c->d_energy_part);
   F(c->d_tot_part); F(c->d_wsum); F(c->d_vsum_part); F(c->d_pool_part);
   F(c->projX); F(c->projZ); F(c->projWq); F(c->projWk); F(c->projWv); F(c->projWo); F(c->proj_ones);
+  F(c->projWvN); F(c->projM); F(c->projPool); F(c->projCtmp);
   F(c->d_gemm_prob); F(c->d_gemm_seg);
   if (c->h_gemm_prob) (void)hipHostFree(c->h_gemm_prob);
   if (c->h_gemm_seg) (void)hipHostFree(c->h_gemm_seg);
@@ -947,7 +948,8 @@ static freqattn_status complete_qk_for_high(freqattn_ctx* c, const void* q, cons
 // Sections 3.3-3.6 on the band-major buffers: compression, band operators, expansion, summaries, exchange.  `v_in` is
 // the untransformed V (for the high-band summaries of slices whose V~ stops at the low+mid box), or NULL when V~ exists
 // on the whole grid for every slice.
-static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in, hipStream_t st, StageTimer& tm) {
+static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in, hipStream_t st, StageTimer& tm,
+                                   bool passed_bands_done = false) {
   const bool mf = c->path == FREQATTN_PATH_MFMA;
   const int is_half = mf ? 1 : 0;
   const int32_t* L = c->d_lists;
@@ -977,6 +979,7 @@ static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in
         for (int l = 0; l < 3; ++l) {
           const bool active = (mask >> l) & 1;
           bool skp = (mask & ~(1 << l) & 7) == 0 || (which == 1 && active) || (which == 2 && !active);
+          if (passed_bands_done && !active) skp = true;   // (projected forward: those tokens are in their slots already, and V~ does not exist there)
           if (l == 2 && mf && c->v_box_ok && v_in && !(mask & 4)) {
             skp = true;
             if (mask != 0 && which != 2) { sel[s >> 6] |= 1ull << (s & 63); ++nsel; }
@@ -1204,6 +1207,7 @@ static freqattn_status ensure_projection_buffers(freqattn_ctx* c, int d_model, h
   HIP_TRY(c, hipStreamSynchronize(st));
   auto F = [&](auto*& p) { if (p) { (void)hipFree((void*)p); p = nullptr; } };
   F(c->projX); F(c->projZ); F(c->projWq); F(c->projWk); F(c->projWv); F(c->projWo); F(c->proj_ones);
+  F(c->projWvN); F(c->projM); F(c->projPool); F(c->projCtmp);
   F(c->d_gemm_prob); F(c->d_gemm_seg);
   if (c->h_gemm_prob) { (void)hipHostFree(c->h_gemm_prob); c->h_gemm_prob = nullptr; }
   if (c->h_gemm_seg) { (void)hipHostFree(c->h_gemm_seg); c->h_gemm_seg = nullptr; }
@@ -1220,8 +1224,15 @@ static freqattn_status ensure_projection_buffers(freqattn_ctx* c, int d_model, h
   A(dev_alloc(*c, &c->projWv, (size_t)hd * d_model));
   A(dev_alloc(*c, &c->projWo, (size_t)hd * d_model));
   A(dev_alloc(*c, &c->proj_ones, (size_t)B));
-  c->gemm_cap_prob = 3 * B * heads + 3 * B;
-  c->gemm_cap_seg = 3 * B * heads + 3 * B * heads;
+  const size_t mrows = (size_t)std::max(c->cfg.n_summary, 1);
+  A(dev_alloc(*c, &c->projWvN, (size_t)hd * d_model));
+  A(dev_alloc(*c, &c->projM, (size_t)3 * d_model * d_model));
+  A(dev_alloc(*c, &c->projPool, (size_t)B * 3 * mrows * d_model));
+  A(dev_alloc(*c, &c->projCtmp, (size_t)c->slices * 3 * mrows * c->d));
+  // problems: Q~, K~, V~ per slice; output projection per (batch entry, band); pass-through weights per band; pooled rows
+  // per slice.  Segments: one per projection; heads + 1 per output projection; heads per pass-through weight.
+  c->gemm_cap_prob = 3 * B * heads + 3 * B + 3 + B * heads;
+  c->gemm_cap_seg = 3 * B * heads + 3 * B * (heads + 1) + 3 * heads + B * heads;
   A(dev_alloc(*c, &c->d_gemm_prob, (size_t)c->gemm_cap_prob));
   A(dev_alloc(*c, &c->d_gemm_seg, (size_t)c->gemm_cap_seg));
   if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_gemm_prob, (size_t)c->gemm_cap_prob * sizeof(GemmProblem), hipHostMallocDefault);
@@ -1240,10 +1251,14 @@ static freqattn_status ensure_projection_buffers(freqattn_ctx* c, int d_model, h
 }
 
 // Problem tables of the product launches for the current allocation.  A launch takes problems with the same rows of
-// A: [Q~ and K~ of all heads with the same hull of active bands, per batch entry] [V~ of all heads on every row, per
-// batch entry] [output projection per (batch, band), K running over the heads: band output where the head runs the
-// band, V~ where it passes through].
-static int build_gemm_tables(Ctx& c) {
+// A.  Stage 0: [Q~, K~ (and, with `fold`, V~) of all heads with the same hull of active bands, per batch entry]
+// [without `fold`: V~ of all heads on every row, per batch entry].  Stage 1: output projection per (batch, band), K
+// running over the heads.  Without `fold` a head contributes the band output where it runs the band and V~ where it
+// passes through.  With `fold` only the heads that run the band contribute their output; the passing heads' share
+// X~ W_V,h W_O,h is one more segment, X~ times the band's pass-through weight (stage 2: the sum over the passing heads
+// of W_V,h W_O,h, transposed, one product per band), so their V~ is never formed on that band; their summary tokens
+// there (section 3.6) are the pooled rows of X~ times W_V,h (stage 3, per batch entry).
+static int build_gemm_tables(Ctx& c, bool fold) {
   const int B = c.shape.batch, heads = c.shape.heads, d = c.d, dm = c.proj_d_model, hd = heads * d;
   half_t* X = (half_t*)c.projX;
   int np = 0, ns = 0;
@@ -1268,22 +1283,50 @@ static int build_gemm_tables(Ctx& c) {
         if (done[(size_t)h] || !hull(h, q0, q1) || q0 != r0 || q1 != r1) continue;
         done[(size_t)h] = 1;
         const int64_t slice = (int64_t)b * heads + h;
-        for (int which = 0; which < 2; ++which) {
-          const half_t* Wt = (which == 0 ? c.projWq : c.projWk) + (size_t)h * d * dm;
-          half_t* spec = (half_t*)(which == 0 ? c.specQ : c.specK) + (slice * c.N + r0) * d;
+        for (int which = 0; which < (fold ? 3 : 2); ++which) {
+          const half_t* Wt = (which == 0 ? c.projWq : which == 1 ? c.projWk : c.projWv) + (size_t)h * d * dm;
+          half_t* spec = (half_t*)(which == 0 ? c.specQ : which == 1 ? c.specK : c.specV) + (slice * c.N + r0) * d;
           c.h_gemm_seg[ns] = GemmSeg{X + ((int64_t)b * c.N + r0) * dm, Wt, dm, dm, dm, 0};
           c.h_gemm_prob[np++] = GemmProblem{spec, d, (int)(r1 - r0), d, ns++, 1, 0};
         }
       }
       c.gemm_groups.push_back({first, np - first, (int)(r1 - r0), d, 0});
     }
-    const int first = np;
-    for (int h = 0; h < heads; ++h) {
-      const int64_t slice = (int64_t)b * heads + h;
-      c.h_gemm_seg[ns] = GemmSeg{X + (int64_t)b * c.N * dm, c.projWv + (size_t)h * d * dm, dm, dm, dm, 0};
-      c.h_gemm_prob[np++] = GemmProblem{(half_t*)c.specV + slice * c.N * d, d, (int)c.N, d, ns++, 1, 0};
+    if (!fold) {
+      const int first = np;
+      for (int h = 0; h < heads; ++h) {
+        const int64_t slice = (int64_t)b * heads + h;
+        c.h_gemm_seg[ns] = GemmSeg{X + (int64_t)b * c.N * dm, c.projWv + (size_t)h * d * dm, dm, dm, dm, 0};
+        c.h_gemm_prob[np++] = GemmProblem{(half_t*)c.specV + slice * c.N * d, d, (int)c.N, d, ns++, 1, 0};
+      }
+      c.gemm_groups.push_back({first, heads, (int)c.N, d, 0});
     }
-    c.gemm_groups.push_back({first, heads, (int)c.N, d, 0});
+  }
+  bool passing[3] = {false, false, false};
+  if (fold)
+    for (int l = 0; l < 3; ++l) {
+      if (c.band_n[l] <= 0) continue;
+      const int seg0 = ns;
+      for (int h = 0; h < heads; ++h)
+        if (!((c.h_alloc[(size_t)h] >> l) & 1))   // (W_V,h W_O,h)^T[i][j] = sum_c W_O^T[i][h d + c] W_V[j][h d + c]
+          c.h_gemm_seg[ns++] = GemmSeg{c.projWo + (size_t)h * d, c.projWvN + (size_t)h * d, hd, hd, d, 0};
+      if (ns == seg0) continue;
+      passing[l] = true;
+      c.h_gemm_prob[np] = GemmProblem{c.projM + (size_t)l * dm * dm, dm, dm, dm, seg0, ns - seg0, 0};
+      c.gemm_groups.push_back({np, 1, dm, dm, 2});
+      ++np;
+    }
+  if (fold && c.cfg.n_summary > 0) {
+    const int mrows = c.cfg.n_summary;
+    for (int b = 0; b < B; ++b) {
+      const int first = np;
+      for (int h = 0; h < heads; ++h) {
+        const int64_t slice = (int64_t)b * heads + h;
+        c.h_gemm_seg[ns] = GemmSeg{c.projPool + (size_t)b * 3 * mrows * dm, c.projWv + (size_t)h * d * dm, dm, dm, dm, 0};
+        c.h_gemm_prob[np++] = GemmProblem{c.projCtmp + (size_t)slice * 3 * mrows * d, d, 3 * mrows, d, ns++, 1, 0};
+      }
+      c.gemm_groups.push_back({first, heads, 3 * mrows, d, 3});
+    }
   }
   for (int b = 0; b < B; ++b)
     for (int l = 0; l < 3; ++l) {
@@ -1292,10 +1335,13 @@ static int build_gemm_tables(Ctx& c) {
       for (int h = 0; h < heads; ++h) {
         const int64_t slice = (int64_t)b * heads + h;
         const bool active = (c.h_alloc[(size_t)h] >> l) & 1;
+        if (fold && !active) continue;
         const half_t* src = (const half_t*)(active ? c.Y : c.specV) + (slice * c.N + c.band_off[l]) * d;
         c.h_gemm_seg[ns++] = GemmSeg{src, c.projWo + (size_t)h * d, d, hd, d, 0};
       }
-      c.h_gemm_prob[np] = GemmProblem{(half_t*)c.projZ + ((int64_t)b * c.N + c.band_off[l]) * dm, dm, (int)c.band_n[l], dm, seg0, heads, 0};
+      if (fold && passing[l])
+        c.h_gemm_seg[ns++] = GemmSeg{X + ((int64_t)b * c.N + c.band_off[l]) * dm, c.projM + (size_t)l * dm * dm, dm, dm, dm, 0};
+      c.h_gemm_prob[np] = GemmProblem{(half_t*)c.projZ + ((int64_t)b * c.N + c.band_off[l]) * dm, dm, (int)c.band_n[l], dm, seg0, ns - seg0, 0};
       c.gemm_groups.push_back({np, 1, (int)c.band_n[l], dm, 1});
       ++np;
     }
@@ -1327,9 +1373,18 @@ extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const voi
     if (fs != FREQATTN_OK) return fs;
     fs = ensure_projection_buffers(c, d_model, st);
     if (fs != FREQATTN_OK) return fs;
+    // Pass-through folding (see build_gemm_tables): on by default wherever the summaries' per-slice bookkeeping reaches
+    // (256 slices); FREQATTN_PROJ_FOLD=0, read at every call, keeps V~ on every row instead.
+    const char* fold_env = getenv("FREQATTN_PROJ_FOLD");
+    const bool fold = c->slices <= 256 && !(fold_env && atoi(fold_env) == 0);
+    if (fold != c->proj_fold) {
+      if (c->gemm_tables_valid) HIP_TRY(c, hipStreamSynchronize(st));   // the tables of the other mode may still be read
+      c->proj_fold = fold;
+      c->gemm_tables_valid = false;
+    }
     if (!c->gemm_tables_valid) {
       // (ensure_lists or ensure_projection_buffers waited for the stream when they invalidated the tables)
-      const int np = build_gemm_tables(*c);
+      const int np = build_gemm_tables(*c, fold);
       int ns = 0;
       for (int i = 0; i < np; ++i) ns = std::max(ns, c->h_gemm_prob[i].seg0 + c->h_gemm_prob[i].nseg);
       if (np > 0) HIP_TRY(c, hipMemcpyAsync(c->d_gemm_prob, c->h_gemm_prob, (size_t)np * sizeof(GemmProblem), hipMemcpyHostToDevice, st));
@@ -1342,18 +1397,38 @@ extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const voi
     HIP_TRY(c, launch_transpose_bf16_to_f16(wk, c->projWk, d_model, hd, st));
     HIP_TRY(c, launch_transpose_bf16_to_f16(wv, c->projWv, d_model, hd, st));
     HIP_TRY(c, launch_transpose_bf16_to_f16(wo, c->projWo, hd, d_model, st));
+    auto products = [&](int stage) -> freqattn_status {
+      for (const Ctx::GemmGroup& gg : c->gemm_groups)
+        if (gg.stage == stage) HIP_TRY(c, launch_gemm_nt(c->d_gemm_prob + gg.first, c->d_gemm_seg, gg.per, gg.m, gg.n, st));
+      return FREQATTN_OK;
+    };
+    if (fold) {
+      HIP_TRY(c, launch_convert_16(wv, c->projWvN, (int64_t)d_model * hd, 0, st));
+      fs = products(2);   // pass-through weights per band
+      if (fs != FREQATTN_OK) return fs;
+    }
     tm.done("weights");
     const int full[3] = {c->shape.T, c->shape.H, c->shape.W};
     HIP_TRY(c, forward_transform_mfma(*c, x, c->projX, st, nullptr, B, full, -1, -1, d_model));
     tm.done("x_transform");
-    for (const Ctx::GemmGroup& gg : c->gemm_groups)
-      if (gg.stage == 0) HIP_TRY(c, launch_gemm_nt(c->d_gemm_prob + gg.first, c->d_gemm_seg, gg.per, gg.m, gg.n, st));
-    tm.done("qkv_projection");
-    c->v_full.assign((size_t)c->slices, 1);
-    fs = bands_core(c, scale, nullptr, st, tm);
+    fs = products(0);
     if (fs != FREQATTN_OK) return fs;
-    for (const Ctx::GemmGroup& gg : c->gemm_groups)
-      if (gg.stage == 1) HIP_TRY(c, launch_gemm_nt(c->d_gemm_prob + gg.first, c->d_gemm_seg, gg.per, gg.m, gg.n, st));
+    tm.done("qkv_projection");
+    if (fold && c->cfg.n_summary > 0) {
+      // summary tokens of the bands a head passes through: chunk means of X~, times every head's W_V, into the slots
+      const int mrows = c->cfg.n_summary;
+      HIP_TRY(c, launch_pool_wide(c->projX, c->projPool, B, c->N, d_model, c->band_off, c->band_n, c->m_eff, mrows, st));
+      fs = products(3);
+      if (fs != FREQATTN_OK) return fs;
+      HIP_TRY(c, launch_place_summaries(c->projCtmp, c->Cbuf, c->d_lists + c->off_masks, c->slices, c->d, c->m_eff, mrows,
+                                        2 * std::max(c->cfg.n_summary, 1), st));
+      tm.done("summaries_passed_bands");
+    }
+    c->v_full.assign((size_t)c->slices, 1);
+    fs = bands_core(c, scale, nullptr, st, tm, fold);
+    if (fs != FREQATTN_OK) return fs;
+    fs = products(1);
+    if (fs != FREQATTN_OK) return fs;
     tm.done("o_projection");
     HIP_TRY(c, inverse_transform_mfma(*c, out, nullptr, st, nullptr, B, full, false, c->projZ, d_model, c->proj_ones));
     tm.done("inverse_transform");

@@ -142,6 +142,13 @@ struct Ctx {
   void* projX = nullptr; void* projZ = nullptr;           // X~ and the projected spectral output, [batch][N][d_model] fp16, band-major rows
   half_t* projWq = nullptr; half_t* projWk = nullptr; half_t* projWv = nullptr;   // [heads*d][d_model]: W^T, K-contiguous
   half_t* projWo = nullptr;                               // [d_model][heads*d]: W_O^T
+  // Pass-through folding: on a band a head does not run, its V~ only feeds the output projection and the summary
+  // tokens; both are taken from X~ directly (X~ (W_V,h W_O,h) summed over the passing heads; pooled X~ times W_V,h)
+  bool proj_fold = false;                                 // this call's tables use the folding (decided per call)
+  half_t* projWvN = nullptr;                              // [d_model][heads*d]: W_V as given, fp16
+  half_t* projM = nullptr;                                // [3][d_model][d_model]: (sum over passing heads of W_V,h W_O,h)^T per band
+  half_t* projPool = nullptr;                             // [batch][3][m][d_model]: chunk means of X~
+  half_t* projCtmp = nullptr;                             // [slices][3][m][d]: the same projected with every head's W_V
   int32_t* proj_ones = nullptr;                           // [batch] band masks "every band from the first source" of the wide inverse
   GemmProblem* d_gemm_prob = nullptr; GemmProblem* h_gemm_prob = nullptr;   // device table + pinned mirror
   GemmSeg* d_gemm_seg = nullptr; GemmSeg* h_gemm_seg = nullptr;
@@ -208,6 +215,12 @@ hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t
 // High-band summary tokens of the slices in `sel` (bit set, nsel of them) from the untransformed bf16 V.
 hipError_t launch_vsum(const void* V, const void* Wsum, float* part, void* C, const uint64_t sel[4], int nsel, int64_t N,
                        int d, int nsplit, int64_t n_high, const int m_eff[3], int m2rows, hipStream_t st);
+// Projected forward: P[batch][3][mrows][dm] = per-chunk means of the band rows of X~ [batch][N][dm] (fp16), and the
+// placement of the projected pooled rows T[slices][3][mrows][d] into the C slots of the bands a slice passes through.
+hipError_t launch_pool_wide(const void* X, void* P, int batch, int64_t N, int dm, const int64_t band_off[3],
+                            const int64_t band_n[3], const int m_eff[3], int mrows, hipStream_t st);
+hipError_t launch_place_summaries(const void* T, void* C, const int32_t* masks, int slices, int d, const int m_eff[3],
+                                  int mrows, int m2rows, hipStream_t st);
 // Router statistics: per band and channel, sum of squares over slices and the three spectral buffers.
 hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, float* stats /*[3][d], zeroed inside*/,
                               int slices, int64_t N, int d, const int64_t band_off[3], const int64_t band_n[3],

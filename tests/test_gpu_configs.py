@@ -233,9 +233,11 @@ def test_ablation_speed_sweep_helper():
 
 
 @pytest.mark.parametrize("name,heads,alloc", [("16k", 8, (1, 1, 2, 2, 2, 4, 4, 7)), ("64k", 6, (1, 2, 4, 3, 0, 6))])
-def test_projected_forward_matches_oracle(name, heads, alloc):
-    """Projections folded around the path (sections 3.1, 3.7): X transformed once, Q~/K~/V~ projected from spectral rows,
-    W_O applied before one inverse transform of model width - against the oracle's project-then-forward definition."""
+def test_projected_forward_matches_oracle(name, heads, alloc, monkeypatch):
+    """Projections folded around the path (sections 3.1, 3.7): X transformed once, Q~/K~/V~ projected from spectral rows
+    of the bands a head runs (what it passes through goes from X~ straight into the output projection, its summary tokens
+    from pooled rows of X~), W_O applied before one inverse transform of model width - against the oracle's
+    project-then-forward definition."""
     import torch
     wl = WL.WORKLOADS[name]
     d, N = wl.head_dim, wl.n_tokens
@@ -259,6 +261,14 @@ def test_projected_forward_matches_oracle(name, heads, alloc):
     mx, rl = U.errors(got, want)
     print(f"projected {name}: max-abs {mx:.3e} rel-L2 {rl:.3e} (|want| max {np.abs(want).max():.2f})", flush=True)
     assert mx <= 2e-2 and rl <= 5e-3
+    # the same without the pass-through folding (V~ projected on every row, pooled and sent through W_O per head)
+    monkeypatch.setenv("FREQATTN_PROJ_FOLD", "0")
+    ctx.forward_projected(dx, dwq, dwk, dwv, dwo, alloc, out)
+    torch.cuda.synchronize()
+    mx, rl = U.errors(U.to_host64(out), want)
+    print(f"projected {name} without pass-through folding: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+    assert mx <= 2e-2 and rl <= 5e-3
+    monkeypatch.delenv("FREQATTN_PROJ_FOLD")
     # another allocation on the same context: new product tables
     alloc2 = tuple(reversed(alloc))
     ctx.forward_projected(dx, dwq, dwk, dwv, dwo, alloc2, out)
