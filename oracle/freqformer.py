@@ -50,8 +50,8 @@ import math
 
 import numpy as np
 
-LOW, MID, HIGH = 0, 1, 2
-BAND_BITS = (1, 2, 4)  # bit l of a head's mask switches band l on
+LOW, MID, HIGH, MID2 = 0, 1, 2, 3
+BAND_BITS = (1, 2, 4, 8)  # bit l of a head's mask switches band l on (band 3 only exists in four-band layouts)
 
 
 @dataclass(frozen=True)
@@ -61,6 +61,12 @@ class BandConfig:
     Band edges are rationals so that membership is decided in integers:
     low  <=> k_axis * low_den < low_num * n_axis on all three axes,
     low or mid <=> the same with (mid_num, mid_den), high = the rest.
+
+    Four bands (the L = 4 of the ablation list in section 8; reading: the paper names no fourth operator, so the mid
+    range is cut in two and both halves get the block-sparse operator with the same parameters, each inside its own
+    band order): mid2_num > 0 adds a third edge; coefficients inside it but outside the mid edge form band 3
+    ("mid2"), and high is what lies outside the mid2 edge.  Band indices and mask bits stay 0 low, 1 mid, 2 high; the
+    second mid band is index 3 / bit 8.
     """
     low_num: int = 1
     low_den: int = 4
@@ -75,6 +81,8 @@ class BandConfig:
     n_summary: int = 16        # m summary tokens per band (0 switches the exchange off)
     softmax_scale: float = 0.0  # 0 -> 1/sqrt(d_k)
     transform: int = 0         # per-axis transform: 0 orthonormal DCT-II (reference design), 1 orthonormal Haar wavelet
+    mid2_num: int = 0          # third band edge (four bands) when > 0
+    mid2_den: int = 1
 
 
 # --------------------------------------------------------------------------- section 3.2
@@ -162,8 +170,11 @@ def band_partition(T: int, H: int, W: int, cfg: BandConfig) -> list[np.ndarray]:
     low = inside(cfg.low_num, cfg.low_den)
     lowmid = inside(cfg.mid_num, cfg.mid_den)
     mid = lowmid & ~low
-    high = ~lowmid
     flat = np.arange(T * H * W, dtype=np.int64).reshape(T, H, W)
+    if cfg.mid2_num > 0:   # four bands: [low, mid, high, mid2]
+        inner = inside(cfg.mid2_num, cfg.mid2_den)
+        return [flat[low], flat[mid], flat[~inner], flat[inner & ~lowmid]]
+    high = ~lowmid
     return [flat[low], flat[mid], flat[high]]  # boolean indexing keeps row-major (ascending) order
 
 
@@ -304,7 +315,7 @@ def head_forward(q, k, v, cfg: BandConfig, mask: int, return_parts: bool = False
             Y.append(Vl.copy())
         elif l == LOW:
             Y.append(low_band_attention(Ql, Kl, Vl, cfg.low_compress, scale))
-        elif l == MID:
+        elif l == MID or l == MID2:
             Y.append(mid_band_attention(Ql, Kl, Vl, cfg, scale))
         else:
             Y.append(high_band_attention(Ql, Kl, Vl, cfg.high_window, scale))
@@ -312,9 +323,9 @@ def head_forward(q, k, v, cfg: BandConfig, mask: int, return_parts: bool = False
     Yhat = [y.copy() for y in Y]
     if cfg.n_summary > 0:
         S = [summary_tokens(y, cfg.n_summary) if len(y) else np.zeros((0, d)) for y in Y]
-        for l in range(3):
+        for l in range(len(bands)):
             if (mask & BAND_BITS[l]) and len(Y[l]):
-                C = np.concatenate([S[o] for o in range(3) if o != l], axis=0)
+                C = np.concatenate([S[o] for o in range(len(bands)) if o != l], axis=0)
                 if len(C):
                     Yhat[l] = Y[l] + cross_band_exchange(Y[l], C, scale)
 
@@ -373,7 +384,8 @@ def dense_reference(q, k, v, scale: float | None = None) -> np.ndarray:
 def interaction_count(T, H, W, cfg: BandConfig, mask: int = 7) -> int:
     """Query-key pairs evaluated by the band operators of one head, counted pair by pair
     (section 4.2: I = Nlow_bar^2 + N_mid k_mid + N_high w, with the exact degrees of this pattern)."""
-    n_low, n_mid, n_high = (len(ix) for ix in band_partition(T, H, W, cfg))
+    sizes = [len(ix) for ix in band_partition(T, H, W, cfg)]
+    n_low, n_mid, n_high = sizes[:3]
     total = 0
     if mask & 1:
         nbar = -(-n_low // cfg.low_compress)
@@ -388,6 +400,13 @@ def interaction_count(T, H, W, cfg: BandConfig, mask: int = 7) -> int:
         w = cfg.high_window
         for i in range(n_high):
             total += min(i + w, n_high - 1) - max(i - w, 0) + 1
+    if len(sizes) > 3 and (mask & 8):
+        B = cfg.mid_block
+        n2 = sizes[3]
+        nb = -(-n2 // B)
+        m = mid_block_mask(nb, cfg.mid_diag, cfg.mid_stride, cfg.mid_block0)
+        size = np.minimum(B, n2 - np.arange(nb) * B)
+        total += int((m * size[:, None] * size[None, :]).sum())
     return total
 
 
@@ -418,6 +437,7 @@ def band_statistics(q, k, v, grid, cfg: BandConfig) -> np.ndarray:
     T, H, W = grid
     Bsz, nh, N, d = q.shape
     assert d % ROUTER_DR == 0
+    assert cfg.mid2_num == 0, "the router of section 3.5 is defined for three bands"
     bands = band_partition(T, H, W, cfg)
     acc = np.zeros((3, d), dtype=np.float64)
     for x in (q, k, v):

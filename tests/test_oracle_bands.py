@@ -118,3 +118,42 @@ def test_two_band_layouts_are_the_three_band_rule_with_an_empty_band():
     assert np.abs(O.forward(q, k, v, grid, two, [7]) - O.forward(q, k, v, grid, two, [5])).max() < 1e-12
     assert np.abs(O.forward(q, k, v, grid, two, [5]) - v).max() > 1e-3
     assert np.abs(O.forward(q, k, v, grid, no_high, [4]) - v).max() < 1e-10
+
+
+def _cfg4(**kw):
+    base = dict(low_num=1, low_den=4, mid_num=1, mid_den=2, mid2_num=3, mid2_den=4)
+    base.update(kw)
+    return O.BandConfig(**base)
+
+
+@pytest.mark.parametrize("grid", [(4, 8, 8), (8, 12, 20), (16, 16, 16)])
+def test_four_band_partition_brute_force_and_counts(grid):
+    """Four bands (section 8's L = 4; the reading cuts the range between the mid edge and the new edge out of the high
+    band): a triple loop over the max-norm rule, a disjoint cover, closed-form counts, public order low, mid, high, mid2."""
+    T, H, W = grid
+    cfg = _cfg4()
+    bands = O.band_partition(T, H, W, cfg)
+    assert len(bands) == 4
+    want = [[], [], [], []]
+    for kt in range(T):
+        for kh in range(H):
+            for kw in range(W):
+                r = max(kt / T, kh / H, kw / W)
+                l = 0 if r < 0.25 else 1 if r < 0.5 else 3 if r < 0.75 else 2
+                want[l].append((kt * H + kh) * W + kw)
+    for l in range(4):
+        assert bands[l].tolist() == want[l]
+    allidx = np.sort(np.concatenate(bands))
+    assert np.array_equal(allidx, np.arange(T * H * W))
+    box = lambda num, den: int(np.prod([-(-num * n // den) for n in grid]))
+    assert [len(b) for b in bands] == [box(1, 4), box(1, 2) - box(1, 4), T * H * W - box(3, 4), box(3, 4) - box(1, 2)]
+
+
+def test_four_band_layout_with_an_empty_fourth_band_is_the_three_band_layout():
+    three = O.band_partition(8, 8, 16, O.BandConfig())
+    four = O.band_partition(8, 8, 16, _cfg4(mid2_num=1, mid2_den=2))     # third edge on the mid edge: band 3 is empty
+    assert len(four) == 4 and len(four[3]) == 0
+    for a, b in zip(three, four[:3]):
+        assert np.array_equal(a, b)
+    four = O.band_partition(8, 8, 16, _cfg4(mid2_num=1, mid2_den=1))     # third edge at 1: the high band is empty
+    assert len(four[2]) == 0 and np.array_equal(np.sort(np.concatenate([four[0], four[1], four[3]])), np.arange(8 * 8 * 16))

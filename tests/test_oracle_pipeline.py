@@ -166,3 +166,64 @@ def test_projected_forward_pins():
             want[b] += O.head_forward(f(wq), f(wk), f(wv), cfg, alloc[h]).reshape(N, d) @ wo[sl]
     assert np.abs(got - want).max() < 1e-10
     assert np.abs(got - x @ wv @ wo).max() > 1e-3
+
+
+def cfg_four(**kw):
+    return cfg_tiny(mid2_num=3, mid2_den=4, **kw)
+
+
+def test_four_band_pipeline_by_hand_from_parts():
+    """Four bands (the L = 4 of section 8): the output re-assembled from independently computed pieces - library DCT,
+    the band operators (the block-sparse one on both middle bands), the exchange against the 3 m summary tokens of the
+    other three bands - for all bands active and for a head that runs the second middle band alone."""
+    from scipy.fft import dctn, idctn
+    grid = (4, 8, 16)
+    q, k, v = rand_head(14, grid=grid)
+    cfg = cfg_four()
+    scale = 1 / np.sqrt(D)
+    N = int(np.prod(grid))
+    spec = lambda x: dctn(x, type=2, norm="ortho", axes=(0, 1, 2)).reshape(N, D)
+    qs, ks, vs = spec(q), spec(k), spec(v)
+    bands = O.band_partition(*grid, cfg)
+    assert [len(b) for b in bands] == [8, 56, 296, 152]     # 2*... boxes 1/4, 1/2, 3/4 of (4, 8, 16): 8, 64, 216 coefficients
+    op = [lambda i: O.low_band_attention(qs[i], ks[i], vs[i], 4, scale),
+          lambda i: O.mid_band_attention(qs[i], ks[i], vs[i], cfg, scale),
+          lambda i: O.high_band_attention(qs[i], ks[i], vs[i], 32, scale),
+          lambda i: O.mid_band_attention(qs[i], ks[i], vs[i], cfg, scale)]
+    for mask in (15, 8, 9):
+        Y = [op[l](bands[l]) if (mask >> l) & 1 else vs[bands[l]] for l in range(4)]
+        S = [O.summary_tokens(y, 4) for y in Y]
+        full = np.zeros((N, D))
+        for l in range(4):
+            if (mask >> l) & 1:
+                C = np.concatenate([S[o] for o in range(4) if o != l])
+                assert C.shape[0] == 12
+                full[bands[l]] = Y[l] + O.dense_attention(Y[l], C, C, scale)
+            else:
+                full[bands[l]] = Y[l]
+        want = idctn(full.reshape(grid + (D,)), type=2, norm="ortho", axes=(0, 1, 2))
+        got = O.head_forward(q, k, v, cfg, mask)
+        assert np.abs(got - want).max() < 1e-10, mask
+
+
+def test_four_band_layout_with_an_empty_band_equals_three_bands():
+    q, k, v = rand_head(15)
+    three = O.head_forward(q, k, v, cfg_tiny(), 7)
+    four = O.head_forward(q, k, v, cfg_tiny(mid2_num=1, mid2_den=2), 7 | 8)    # band 3 empty: its bit changes nothing
+    assert np.abs(three - four).max() < 1e-12
+    # the second middle band covering everything outside the mid edge, window wide enough to be dense, one block: both are
+    # dense attention over the same rows
+    a = O.head_forward(q, k, v, cfg_tiny(high_window=10**6, n_summary=0), 4)
+    b = O.head_forward(q, k, v, cfg_tiny(mid2_num=1, mid2_den=1, mid_block=10**6, n_summary=0), 8)
+    assert np.abs(a - b).max() < 1e-10
+
+
+def test_four_band_interaction_count():
+    cfg = cfg_four()
+    n = [len(b) for b in O.band_partition(4, 8, 16, cfg)]
+    both = O.interaction_count(4, 8, 16, cfg, mask=2 | 8)
+    assert both == O.interaction_count(4, 8, 16, cfg, mask=2) + O.interaction_count(4, 8, 16, cfg, mask=8)
+    nb = -(-n[3] // 16)                                  # 152 rows: nine full blocks of 16 and one of 8
+    m = O.mid_block_mask(nb, 1, 4, 1)
+    size = np.array([16] * 9 + [8])
+    assert n[3] == 152 and O.interaction_count(4, 8, 16, cfg, mask=8) == int((m * np.outer(size, size)).sum())
