@@ -73,6 +73,11 @@ typedef struct {
   int32_t n_summary;    /* m summary tokens per band; 0 switches the cross-band exchange off                        */
   float softmax_scale;  /* <= 0 selects 1/sqrt(head_dim)                                                            */
   int32_t transform;    /* freqattn_transform: the 1-D transform applied along each grid axis (section 3.2)         */
+  int32_t mid2_num, mid2_den; /* four bands (the L = 4 of section 8's ablation list) when mid2_num > 0: a third edge,
+                           mid <= mid2 <= 1.  The paper names no fourth operator; here the coefficients between the
+                           mid edge and this edge form a second block-sparse band (band 3, mask bit 8: same block
+                           pattern parameters, inside its own band order) and the high band is what lies outside.
+                           mid2_num <= 0: three bands.                                                               */
 } freqattn_band_cfg;
 
 /* Per-axis transform of section 3.2: the reference design's orthonormal DCT-II, or the orthonormal Haar wavelet (the
@@ -95,8 +100,11 @@ typedef enum {
  * then uploaded) and allocates all device scratch on the current HIP device.  `path` is a freqattn_path.
  * Band count (the L of the ablation list in section 8): three bands is the reference design; mid edge == low edge leaves
  * the mid band empty, i.e. two bands (compressed dense low band, windowed high band); mid edge == 1 leaves the high
- * band empty (low + block-sparse rest).  Four bands are not built.
- * Returns EINVAL for non-positive dimensions, edges not satisfying 0 < low <= mid <= 1, low_compress < 1,
+ * band empty (low + block-sparse rest); mid2_num > 0 adds a second block-sparse band between the mid band and the high
+ * band (four bands: band indices and mask bits 0 low, 1 mid, 2 high, 3 second mid band).  Four-band contexts take
+ * freqattn_forward, freqattn_forward_static and the introspection calls; the router entry points (section 3.5 is
+ * written for three bands) and freqattn_forward_projected return FREQATTN_EUNSUPPORTED on them.
+ * Returns EINVAL for non-positive dimensions, edges not satisfying 0 < low <= mid (<= mid2) <= 1, low_compress < 1,
  * mid_block < 1, mid_stride < 1, mid_diag < 0, high_window < 0, n_summary < 0, unknown dtype or NULL pointers;
  * EUNSUPPORTED if FREQATTN_PATH_MFMA is forced on a shape it cannot run; ENOMEM / EHIP on allocation failure. */
 freqattn_status freqattn_create(const freqattn_shape* shape /*HOST*/, const freqattn_band_cfg* cfg /*HOST*/,
@@ -105,8 +113,9 @@ freqattn_status freqattn_create(const freqattn_shape* shape /*HOST*/, const freq
 /* Whole hot path (sections 3.2-3.7) for all batches and heads.
  *   q, k, v   DEVICE, contiguous [batch, heads, N, head_dim] of shape.dtype, read only
  *   band_cfg  HOST; must equal the configuration given to freqattn_create in every field except softmax_scale
- *   head_alloc HOST [heads]; bit 0 / 1 / 2 of entry h switch the low / mid / high operator of head h on.  A band whose
- *             bit is clear passes V~ through unchanged on that band (it still contributes summary tokens).
+ *   head_alloc HOST [heads]; bit 0 / 1 / 2 of entry h switch the low / mid / high operator of head h on (bit 3 the second
+ *             mid band of a four-band context).  A band whose bit is clear passes V~ through unchanged on that band
+ *             (it still contributes summary tokens).
  *   out       DEVICE, same shape and type as q; must not overlap q, k, v
  *   stream    hipStream_t (NULL = default stream)
  * Range contract of BF16 contexts on the matrix-core path: spectral coefficients are kept in fp16, and an orthonormal
@@ -119,7 +128,7 @@ freqattn_status freqattn_create(const freqattn_shape* shape /*HOST*/, const freq
  * calls are no longer in use.  Allocates nothing.  To capture the call into a HIP graph, run it once eagerly with the
  * same head_alloc first: the first launch of a kernel variant reads the environment switches and sets its launch
  * attributes, and a changed head_alloc waits for the stream - neither belongs under capture.  EINVAL: NULL pointer,
- * head_alloc entry outside 0..7, band_cfg mismatch.  EHIP: a launch failed. */
+ * head_alloc entry outside 0..7 (0..15 on a four-band context), band_cfg mismatch.  EHIP: a launch failed. */
 freqattn_status freqattn_forward(freqattn_ctx* ctx, const void* q, const void* k, const void* v,
                                  const freqattn_band_cfg* band_cfg, const int32_t* head_alloc, void* out, void* stream);
 
@@ -161,13 +170,16 @@ int32_t freqattn_get_path(const freqattn_ctx* ctx);
 int32_t freqattn_get_v_box(const freqattn_ctx* ctx);
 
 /* ---- introspection of the integer tables (section 3.3 band lists, section 3.4.2 block pattern) ---------------- */
-/* n[l] = number of coefficients in band l (0 low, 1 mid, 2 high); HOST out. */
-freqattn_status freqattn_band_sizes(const freqattn_ctx* ctx, int64_t n[3]);
+/* n[l] = number of coefficients in band l (0 low, 1 mid, 2 high, 3 second mid band: 0 on a three-band context); HOST
+ * out, four entries. */
+freqattn_status freqattn_band_sizes(const freqattn_ctx* ctx, int64_t n[4]);
 /* Flat coefficient indices (kt*H + kh)*W + kw of band `band`, ascending; host_out HOST [n[band]]. */
 freqattn_status freqattn_band_index(const freqattn_ctx* ctx, int32_t band, int32_t* host_out);
 /* Block list of the mid band in CSR form, columns ascending in a row.  *nnz is always written; row_ptr (HOST
  * [nb+1], nb = ceil(n_mid / mid_block)) and col_idx (HOST [nnz]) are filled when not NULL. */
 freqattn_status freqattn_mid_blocks(const freqattn_ctx* ctx, int32_t* row_ptr, int32_t* col_idx, int64_t* nnz);
+/* The same for the second mid band of a four-band context (nb = ceil(n[3] / mid_block); nnz = 0 otherwise). */
+freqattn_status freqattn_mid2_blocks(const freqattn_ctx* ctx, int32_t* row_ptr, int32_t* col_idx, int64_t* nnz);
 /* Section 3.6 with U = I, read through the transform's linearity: summary token u of band `band` of a tensor whose
  * coefficients pass through unchanged is (1 / |chunk u|) * sum_n w[u][n] x[n], with w[u][n] the sum of the transform's
  * rows of chunk u (band rows [floor(u n_l / m), floor((u+1) n_l / m)), m = min(n_summary, n_l)).  host_out HOST

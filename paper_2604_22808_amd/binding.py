@@ -27,7 +27,7 @@ class Shape(C.Structure):
 class BandCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("low_num", "low_den", "mid_num", "mid_den", "low_compress", "mid_block",
                                          "mid_diag", "mid_stride", "mid_block0", "high_window", "n_summary")] + \
-               [("softmax_scale", C.c_float), ("transform", C.c_int32)]
+               [("softmax_scale", C.c_float), ("transform", C.c_int32), ("mid2_num", C.c_int32), ("mid2_den", C.c_int32)]
 
 
 EXPORTS = {
@@ -47,6 +47,7 @@ EXPORTS = {
     "freqattn_band_sizes": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "freqattn_band_index": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
     "freqattn_mid_blocks": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
+    "freqattn_mid2_blocks": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
     "freqattn_dct_matrix": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
     "freqattn_get_v_box": (C.c_int32, [C.c_void_p]),
     "freqattn_summary_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]),
@@ -109,7 +110,7 @@ def _stream():
 
 def make_cfg(**kw) -> BandCfg:
     base = dict(low_num=1, low_den=4, mid_num=1, mid_den=2, low_compress=4, mid_block=64, mid_diag=1, mid_stride=8,
-                mid_block0=1, high_window=256, n_summary=16, softmax_scale=0.0, transform=0)
+                mid_block0=1, high_window=256, n_summary=16, softmax_scale=0.0, transform=0, mid2_num=0, mid2_den=1)
     base.update(kw)
     return BandCfg(**base)
 
@@ -268,25 +269,37 @@ class Context:
         self._check(lib().freqattn_measure_peaks(self._h, C.byref(cp), C.byref(mf), _stream()))
         return cp.value, mf.value
 
+    @property
+    def n_bands(self):
+        return 4 if self.cfg.mid2_num > 0 else 3
+
     def band_sizes(self):
-        n = (C.c_int64 * 3)()
+        n = (C.c_int64 * 4)()
         self._check(lib().freqattn_band_sizes(self._h, n))
-        return [int(x) for x in n]
+        return [int(x) for x in n][:self.n_bands]
 
     def band_index(self, band):
         out = np.zeros(self.band_sizes()[band], np.int32)
         self._check(lib().freqattn_band_index(self._h, band, out.ctypes.data_as(C.POINTER(C.c_int32))))
         return out
 
-    def mid_blocks(self):
+    def _blocks(self, fn, band):
         nnz = C.c_int64()
-        self._check(lib().freqattn_mid_blocks(self._h, None, None, C.byref(nnz)))
-        nb = -(-self.band_sizes()[1] // self.cfg.mid_block)
+        self._check(fn(self._h, None, None, C.byref(nnz)))
+        nb = -(-self.band_sizes()[band] // self.cfg.mid_block)
         rp = np.zeros(nb + 1, np.int32)
         ci = np.zeros(nnz.value, np.int32)
-        self._check(lib().freqattn_mid_blocks(self._h, rp.ctypes.data_as(C.POINTER(C.c_int32)),
-                                              ci.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nnz)))
+        self._check(fn(self._h, rp.ctypes.data_as(C.POINTER(C.c_int32)), ci.ctypes.data_as(C.POINTER(C.c_int32)),
+                       C.byref(nnz)))
         return rp, ci
+
+    def mid_blocks(self):
+        return self._blocks(lib().freqattn_mid_blocks, 1)
+
+    def mid2_blocks(self):
+        if self.n_bands < 4:
+            return np.zeros(1, np.int32), np.zeros(0, np.int32)
+        return self._blocks(lib().freqattn_mid2_blocks, 3)
 
     def get_v_box(self):
         return int(lib().freqattn_get_v_box(self._h))

@@ -78,7 +78,7 @@ static void free_all(Ctx* c) {
     return;
   }
   auto F = [](void* p) { if (p) (void)hipFree(p); };
-  F(c->d_perm); F(c->d_perm_t); F(c->d_row_ptr); F(c->d_col_idx);
+  F(c->d_perm); F(c->d_perm_t); F(c->d_row_ptr); F(c->d_col_idx); F(c->d_row_ptr2); F(c->d_col_idx2);
   for (int a = 0; a < 3; ++a) { F(c->d_F32[a]); F(c->d_Ft32[a]); F(c->d_F16[a]); F(c->d_Ft16[a]); }
   F(c->specQ); F(c->specK); F(c->specV); F(c->Y); F(c->tmp0); F(c->tmp1);
   F(c->lowQ); F(c->lowK); F(c->lowV); F(c->lowY); F(c->Cbuf); F(c->d_stats); F(c->d_range_flag); F(c->d_lists); F(c->d_energy_part);
@@ -97,7 +97,7 @@ static void free_all(Ctx* c) {
 
 static int items_per_slice_max(const Ctx& c, int rows) {
   auto cd = [](int64_t a, int64_t b) { return (int)((a + b - 1) / b); };
-  return cd(c.nbar, rows) + cd(c.band_n[MID], rows) + cd(c.band_n[HIGH], rows) + 3;
+  return cd(c.nbar, rows) + cd(c.band_n[MID], rows) + cd(c.band_n[HIGH], rows) + cd(c.band_n[MID2], rows) + 4;
 }
 
 static int keep_rows(int box, int n);
@@ -121,6 +121,9 @@ static freqattn_status host_setup(const freqattn_shape* shape, const freqattn_ba
   if (g.low_num < 1 || g.low_den < 1 || g.mid_num < 1 || g.mid_den < 1 ||
       !((int64_t)g.low_num * g.mid_den <= (int64_t)g.mid_num * g.low_den) || g.mid_num > g.mid_den)
     return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: band edges must satisfy 0 < low <= mid <= 1");
+  if (g.mid2_num > 0 && (g.mid2_den < 1 || g.mid2_num > g.mid2_den ||
+                         !((int64_t)g.mid_num * g.mid2_den <= (int64_t)g.mid2_num * g.mid_den)))
+    return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: the third band edge must satisfy mid <= mid2 <= 1");
   if (g.low_compress < 1 || g.mid_block < 1 || g.mid_stride < 1 || g.mid_diag < 0 || g.high_window < 0 ||
       g.n_summary < 0)
     return fail(nullptr, FREQATTN_EINVAL, "freqattn_create: band operator parameter out of range");
@@ -161,15 +164,16 @@ static freqattn_status host_setup(const freqattn_shape* shape, const freqattn_ba
     return fail(nullptr, FREQATTN_ENOMEM, "freqattn_create: host allocation failed");
   }
   c->nbar = (c->band_n[LOW] + g.low_compress - 1) / g.low_compress;
-  for (int l = 0; l < 3; ++l) c->m_eff[l] = (int)std::min<int64_t>(g.n_summary, c->band_n[l]);
-  for (int l = 0; l < 3; ++l) {
+  for (int l = 0; l < NBMAX; ++l) c->m_eff[l] = c->n_c[l] = 0;
+  for (int l = 0; l < c->nb; ++l) c->m_eff[l] = (int)std::min<int64_t>(g.n_summary, c->band_n[l]);
+  for (int l = 0; l < c->nb; ++l) {
     c->n_c[l] = 0;
-    for (int o = 0; o < 3; ++o)
+    for (int o = 0; o < c->nb; ++o)
       if (o != l) c->n_c[l] += c->m_eff[o];
   }
-  if (c->path == FREQATTN_PATH_MFMA && 2 * g.n_summary > 1024) {
+  if (c->path == FREQATTN_PATH_MFMA && (c->nb - 1) * g.n_summary > 1024) {
     delete c;
-    return fail(nullptr, FREQATTN_EUNSUPPORTED, "freqattn_create: n_summary > 512 on the MFMA path");
+    return fail(nullptr, FREQATTN_EUNSUPPORTED, "freqattn_create: (bands - 1) * n_summary > 1024 on the MFMA path");
   }
   c->attn_rows = (g.mid_block % 128 == 0) ? 128 : 64;
   c->uid = g_next_uid.fetch_add(1);
@@ -217,6 +221,10 @@ static hipError_t device_setup(freqattn_ctx* c, hipStream_t st) {
   up(c->d_row_ptr, c->h_row_ptr.data(), c->h_row_ptr.size() * 4);
   A(dev_alloc(*c, &c->d_col_idx, c->h_col_idx.size()));
   up(c->d_col_idx, c->h_col_idx.data(), c->h_col_idx.size() * 4);
+  A(dev_alloc(*c, &c->d_row_ptr2, c->h_row_ptr2.size()));
+  up(c->d_row_ptr2, c->h_row_ptr2.data(), c->h_row_ptr2.size() * 4);
+  A(dev_alloc(*c, &c->d_col_idx2, c->h_col_idx2.size()));
+  up(c->d_col_idx2, c->h_col_idx2.data(), c->h_col_idx2.size() * 4);
   {
     const int dims[3] = {s.T, s.H, s.W};
     for (int a = 0; a < 3 && e == hipSuccess; ++a) {
@@ -265,12 +273,12 @@ static hipError_t device_setup(freqattn_ctx* c, hipStream_t st) {
   A(dev_alloc_bytes(*c, &c->lowK, lowb));
   A(dev_alloc_bytes(*c, &c->lowV, lowb));
   A(dev_alloc_bytes(*c, &c->lowY, lowb));
-  A(dev_alloc_bytes(*c, &c->Cbuf, (size_t)c->slices * 3 * 2 * (size_t)std::max(g.n_summary, 1) * c->d * es));
+  A(dev_alloc_bytes(*c, &c->Cbuf, (size_t)c->slices * c->nb * (c->nb - 1) * (size_t)std::max(g.n_summary, 1) * c->d * es));
   const size_t stats_floats = (size_t)3 * c->d * (1 + 64);
   A(dev_alloc(*c, &c->d_stats, stats_floats));
   A(dev_alloc(*c, &c->d_range_flag, 64));
   if (e == hipSuccess) e = launch_fill_zero((float*)c->d_range_flag, 64, st);   // (a zero float is a zero int)
-  if (mf && g.n_summary > 0 && g.n_summary < 64) A(dev_alloc(*c, &c->d_pool_part, (size_t)c->slices * 3 * 128 * c->d));
+  if (mf && g.n_summary > 0 && g.n_summary < 64) A(dev_alloc(*c, &c->d_pool_part, (size_t)c->slices * c->nb * 128 * c->d));
   // (partial sums of the router statistics: the routed entry points do not run on an arena context)
   if (mf && !arena) A(dev_alloc(*c, &c->d_energy_part, (size_t)6 * DCT_MAX_WAVES * 3 * 64));
   if (mf && !arena) A(dev_alloc(*c, &c->d_tot_part, (size_t)3 * DCT_MAX_WAVES * 64));
@@ -292,7 +300,8 @@ static hipError_t device_setup(freqattn_ctx* c, hipStream_t st) {
     // whole-grid V~: the extra launches cost more there than the smaller passes save)
     const char* env = getenv("FREQATTN_V_BOX");
     const bool wanted = env ? atoi(env) != 0 : c->N >= 65536;
-    c->v_box_ok = mf && smaller && c->N % 64 == 0 && c->slices <= 256 && c->band_n[HIGH] > 0 &&
+    // (three bands only: with a second mid band outside the box its summary tokens would need the same treatment)
+    c->v_box_ok = mf && smaller && c->N % 64 == 0 && c->slices <= 256 && c->band_n[HIGH] > 0 && c->nb == 3 &&
                   (g.n_summary == 0 || c->m_eff[HIGH] <= 64) && wanted;
     if (c->v_box_ok && g.n_summary > 0 && e == hipSuccess) {
       try {
@@ -322,10 +331,10 @@ static hipError_t device_setup(freqattn_ctx* c, hipStream_t st) {
   {
     const int rows = c->attn_rows;
     const size_t per_slice = (size_t)items_per_slice_max(*c, rows);
-    const size_t xchg_per_slice = (size_t)((c->N + rows - 1) / rows + 3);
+    const size_t xchg_per_slice = (size_t)((c->N + rows - 1) / rows + NBMAX);
     size_t ints = 0;
     c->off_masks = ints; ints += (size_t)c->slices;
-    for (int l = 0; l < 3; ++l) { c->off_list[l] = ints; ints += (size_t)c->slices; }
+    for (int l = 0; l < NBMAX; ++l) { c->off_list[l] = ints; ints += (size_t)c->slices; }
     for (int k = 0; k < 4; ++k) { c->off_cls[k] = ints; ints += (size_t)c->slices; }
     c->off_nonhigh = ints; ints += (size_t)c->slices;
     c->off_fix = ints; ints += (size_t)c->slices;
@@ -467,20 +476,20 @@ extern "C" freqattn_status freqattn_check_range(freqattn_ctx* c, int32_t* out_of
 
 extern "C" int64_t freqattn_workspace_bytes(const freqattn_ctx* c) { return c ? c->dev_bytes : 0; }
 
-extern "C" freqattn_status freqattn_band_sizes(const freqattn_ctx* c, int64_t n[3]) {
+extern "C" freqattn_status freqattn_band_sizes(const freqattn_ctx* c, int64_t n[4]) {
   if (!c || !n) return FREQATTN_EINVAL;
-  for (int l = 0; l < 3; ++l) n[l] = c->band_n[l];
+  for (int l = 0; l < NBMAX; ++l) n[l] = l < c->nb ? c->band_n[l] : 0;
   return FREQATTN_OK;
 }
 extern "C" freqattn_status freqattn_band_index(const freqattn_ctx* c, int32_t band, int32_t* host_out) {
-  if (!c || !host_out || band < 0 || band > 2) return FREQATTN_EINVAL;
+  if (!c || !host_out || band < 0 || band >= c->nb) return FREQATTN_EINVAL;
   std::memcpy(host_out, c->h_band_index[band].data(), c->h_band_index[band].size() * sizeof(int32_t));
   return FREQATTN_OK;
 }
 extern "C" int32_t freqattn_get_v_box(const freqattn_ctx* c) { return (c && c->v_box_ok) ? 1 : 0; }
 
 extern "C" freqattn_status freqattn_summary_weights(const freqattn_ctx* c, int32_t band, float* host_out) {
-  if (!c || !host_out || band < 0 || band > 2) return FREQATTN_EINVAL;
+  if (!c || !host_out || band < 0 || band >= c->nb) return FREQATTN_EINVAL;
   try {
     std::vector<float> w;
     build_summary_weights(*c, band, w);
@@ -496,6 +505,13 @@ extern "C" freqattn_status freqattn_mid_blocks(const freqattn_ctx* c, int32_t* r
   *nnz = (int64_t)c->h_col_idx.size();
   if (row_ptr) std::memcpy(row_ptr, c->h_row_ptr.data(), c->h_row_ptr.size() * sizeof(int32_t));
   if (col_idx) std::memcpy(col_idx, c->h_col_idx.data(), c->h_col_idx.size() * sizeof(int32_t));
+  return FREQATTN_OK;
+}
+extern "C" freqattn_status freqattn_mid2_blocks(const freqattn_ctx* c, int32_t* row_ptr, int32_t* col_idx, int64_t* nnz) {
+  if (!c || !nnz) return FREQATTN_EINVAL;
+  *nnz = (int64_t)c->h_col_idx2.size();
+  if (row_ptr) std::memcpy(row_ptr, c->h_row_ptr2.data(), c->h_row_ptr2.size() * sizeof(int32_t));
+  if (col_idx) std::memcpy(col_idx, c->h_col_idx2.data(), c->h_col_idx2.size() * sizeof(int32_t));
   return FREQATTN_OK;
 }
 extern "C" freqattn_status freqattn_dct_matrix(const freqattn_ctx* c, int32_t axis, double* host_out) {
@@ -533,7 +549,8 @@ static bool same_cfg(const freqattn_band_cfg& a, const freqattn_band_cfg& b) {
   return a.low_num == b.low_num && a.low_den == b.low_den && a.mid_num == b.mid_num && a.mid_den == b.mid_den &&
          a.low_compress == b.low_compress && a.mid_block == b.mid_block && a.mid_diag == b.mid_diag &&
          a.mid_stride == b.mid_stride && (a.mid_block0 != 0) == (b.mid_block0 != 0) &&
-         a.high_window == b.high_window && a.n_summary == b.n_summary && a.transform == b.transform;
+         a.high_window == b.high_window && a.n_summary == b.n_summary && a.transform == b.transform &&
+         std::max(a.mid2_num, 0) == std::max(b.mid2_num, 0) && (a.mid2_num <= 0 || a.mid2_den == b.mid2_den);
 }
 
 // Fills the pinned host mirror of the per-forward lists.  The item lists are only read by the MFMA attention kernel;
@@ -542,19 +559,20 @@ static bool same_cfg(const freqattn_band_cfg& a, const freqattn_band_cfg& b) {
 static bool build_lists(Ctx& c, const int32_t* head_alloc) {
   int32_t* L = c.h_lists;
   const int heads = c.shape.heads;
-  for (int l = 0; l < 3; ++l) c.n_list[l] = 0;
+  for (int l = 0; l < NBMAX; ++l) c.n_list[l] = 0;
   for (int k = 0; k < 4; ++k) c.n_cls[k] = 0;
   c.n_nonhigh = 0;
   for (int s = 0; s < c.slices; ++s) {
     const int mask = head_alloc[s % heads];
     L[c.off_masks + s] = mask;
     int eff = 0;   // bands that really run (a band without coefficients runs nothing)
-    for (int l = 0; l < 3; ++l)
+    for (int l = 0; l < c.nb; ++l)
       if (((mask >> l) & 1) && c.band_n[l] > 0) eff |= 1 << l;
-    const int cls = (eff & 4) ? 2 : (eff & 2) ? 1 : (eff & 1) ? 0 : 3;
+    // (the second mid band lies outside the low+mid box, like the high band: its slices take the whole-grid transforms)
+    const int cls = (eff & (4 | 8)) ? 2 : (eff & 2) ? 1 : (eff & 1) ? 0 : 3;
     L[c.off_cls[cls] + c.n_cls[cls]++] = s;
     if (cls != 2) L[c.off_nonhigh + c.n_nonhigh++] = s;
-    for (int l = 0; l < 3; ++l)
+    for (int l = 0; l < c.nb; ++l)
       if (((mask >> l) & 1) && c.band_n[l] > 0) L[c.off_list[l] + c.n_list[l]++] = s;
   }
   c.n_items_branch = 0;
@@ -572,7 +590,7 @@ static bool build_lists(Ctx& c, const int32_t* head_alloc) {
   auto fused_xchg = [&](int mask, int l) -> bool {
     if (!fusion || c.n_c[l] <= 0) return false;
     int eff = 0;
-    for (int o = 0; o < 3; ++o)
+    for (int o = 0; o < c.nb; ++o)
       if (((mask >> o) & 1) && c.band_n[o] > 0) eff |= 1 << o;
     return eff == (1 << l);
   };
@@ -588,19 +606,21 @@ static bool build_lists(Ctx& c, const int32_t* head_alloc) {
     if ((mask & 1) && c.band_n[LOW] > 0)
       for (int64_t q0 = 0; q0 < c.nbar; q0 += rows)
         push(c.off_items_kind[0], c.n_items_kind[0], cap_kind, {0 | (LOW << 8) | (fused_xchg(mask, LOW) ? 1 << 16 : 0), s, (int32_t)q0, (int32_t)cd(c.nbar, KT)});
-    if ((mask & 2) && c.band_n[MID] > 0) {
+    for (int l = MID; l < c.nb; l += MID2 - MID) {   // the block-sparse bands: mid, and the second mid band if there is one
+      if (!((mask >> l) & 1) || c.band_n[l] <= 0) continue;
       // Query blocks I with the same I mod stride share all their strided key blocks (J = I mod stride): they are listed
       // together, so that workgroups running at the same time fetch those K/V tiles into their L2 once.
+      const std::vector<int32_t>& row_ptr = l == MID ? c.h_row_ptr : c.h_row_ptr2;
       const int64_t tiles_per_block = std::max<int64_t>(1, c.cfg.mid_block / rows);   // items per query block
-      const int64_t nblocks = (c.band_n[MID] + c.cfg.mid_block - 1) / c.cfg.mid_block;
+      const int64_t nblocks = (c.band_n[l] + c.cfg.mid_block - 1) / c.cfg.mid_block;
       const int64_t stride = std::min<int64_t>(c.cfg.mid_stride, nblocks);
       for (int64_t r = 0; r < stride; ++r)
         for (int64_t I = r; I < nblocks; I += stride)
           for (int64_t u = 0; u < tiles_per_block; ++u) {
             const int64_t q0 = I * c.cfg.mid_block + u * rows;
-            if (q0 >= c.band_n[MID]) break;
-            const int nblk = c.h_row_ptr[I + 1] - c.h_row_ptr[I];
-            push(c.off_items_kind[1], c.n_items_kind[1], cap_kind, {1 | (MID << 8) | (fused_xchg(mask, MID) ? 1 << 16 : 0), s, (int32_t)q0, (int32_t)(nblk * cd(c.cfg.mid_block, KT))});
+            if (q0 >= c.band_n[l]) break;
+            const int nblk = row_ptr[I + 1] - row_ptr[I];
+            push(c.off_items_kind[1], c.n_items_kind[1], cap_kind, {1 | (l << 8) | (fused_xchg(mask, l) ? 1 << 16 : 0), s, (int32_t)q0, (int32_t)(nblk * cd(c.cfg.mid_block, KT))});
           }
     }
     if ((mask & 4) && c.band_n[HIGH] > 0)
@@ -610,7 +630,7 @@ static bool build_lists(Ctx& c, const int32_t* head_alloc) {
         push(c.off_items_kind[2], c.n_items_kind[2], cap_kind, {2 | (HIGH << 8) | (fused_xchg(mask, HIGH) ? 1 << 16 : 0), s, (int32_t)q0, (int32_t)(k1 / KT - k0 / KT + 1)});
       }
     if (c.cfg.n_summary > 0)
-      for (int l = 0; l < 3; ++l)
+      for (int l = 0; l < c.nb; ++l)
         if (((mask >> l) & 1) && c.band_n[l] > 0 && c.n_c[l] > 0 && !fused_xchg(mask, l))
           for (int64_t q0 = 0; q0 < c.band_n[l]; q0 += rows)
             push(c.off_items_xchg, c.n_items_xchg, cap_x, {3 | (l << 8), s, (int32_t)q0, (int32_t)cd(c.n_c[l], KT)});
@@ -728,6 +748,7 @@ static hipError_t inverse_transform_mfma(Ctx& c, void* out, const void* v_in, hi
   a.in = wide ? wide : c.Y; a.in_alt = wide ? wide : c.specV; a.masks = wide ? wide_masks : c.d_lists + c.off_masks;
   a.slice_list = slice_list; a.delta = delta ? 1 : 0;
   a.band_off1 = (int32_t)c.band_off[1]; a.band_off2 = (int32_t)c.band_off[2];
+  a.band_off3 = (int32_t)(c.nb > 3 ? c.band_off[3] : c.N);
   a.perm_in = c.d_perm_t; a.perm_k = 1; a.perm_o = W; a.perm_scale = T;
   a.out = c.tmp1; a.M = c.d_Ft16[0]; a.ldm = T; a.n = kt; a.n_out = T; a.inner = (int64_t)kw * d;
   a.nslab = (int64_t)ns * kh; a.outer = kh;
@@ -792,7 +813,7 @@ static hipError_t inverse_transform(Ctx& c, void* out, const void* v_in, hipStre
   AxisPassArgs a{};
   a.Ntok = c.N; a.slice_mod = c.slices;
   a.in = c.Y; a.in_alt = c.specV; a.masks = masks; a.band_off1 = (int32_t)c.band_off[1];
-  a.band_off2 = (int32_t)c.band_off[2]; a.perm_in = c.d_perm;
+  a.band_off2 = (int32_t)c.band_off[2]; a.band_off3 = (int32_t)(c.nb > 3 ? c.band_off[3] : c.N); a.perm_in = c.d_perm;
   a.out = c.tmp0; a.M = c.d_Ft32[2]; a.n = a.n_out = W; a.inner = d; a.outer = (int64_t)T * H;
   a.nslab = (int64_t)c.slices * T * H; a.in_kind = 0; a.out_kind = 0;
   if ((e = launch_generic_axis_pass(a, st)) != hipSuccess) return e;
@@ -810,12 +831,14 @@ static void fill_attn_params(const Ctx& c, AttnParams& p, float scale) {
   p.specQ = c.specQ; p.specK = c.specK; p.specV = c.specV; p.Y = c.Y;
   p.lowQ = c.lowQ; p.lowK = c.lowK; p.lowV = c.lowV; p.lowY = c.lowY; p.C = c.Cbuf;
   p.mid_row_ptr = c.d_row_ptr; p.mid_col_idx = c.d_col_idx;
-  for (int l = 0; l < 3; ++l) {
+  p.mid2_row_ptr = c.d_row_ptr2; p.mid2_col_idx = c.d_col_idx2;
+  p.nb = c.nb;
+  for (int l = 0; l < c.nb; ++l) {
     p.band_off[l] = (int32_t)c.band_off[l];
     p.band_n[l] = (int32_t)c.band_n[l];
     p.n_c[l] = c.n_c[l];
   }
-  p.N = (int32_t)c.N; p.d = c.d; p.nbar = (int32_t)c.nbar; p.m2 = 2 * std::max(c.cfg.n_summary, 1);
+  p.N = (int32_t)c.N; p.d = c.d; p.nbar = (int32_t)c.nbar; p.m2 = (c.nb - 1) * std::max(c.cfg.n_summary, 1);
   p.mid_block = c.cfg.mid_block; p.high_window = c.cfg.high_window; p.scale = scale;
 }
 
@@ -971,14 +994,15 @@ static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in
   AttnParams ap;
   fill_attn_params(*c, ap, scale);
   auto summaries = [&](int which) -> freqattn_status {
-    uint64_t skip[3][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}}, sel[4] = {0, 0, 0, 0};
+    uint64_t skip[NBMAX][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}}, sel[4] = {0, 0, 0, 0};
+    const int all_bands = (1 << c->nb) - 1;
     int nsel = 0, npool = 0;
     if (c->slices <= 256) {
       for (int s = 0; s < c->slices; ++s) {
         const int mask = c->h_alloc[(size_t)(s % c->shape.heads)];
-        for (int l = 0; l < 3; ++l) {
+        for (int l = 0; l < c->nb; ++l) {
           const bool active = (mask >> l) & 1;
-          bool skp = (mask & ~(1 << l) & 7) == 0 || (which == 1 && active) || (which == 2 && !active);
+          bool skp = (mask & ~(1 << l) & all_bands) == 0 || (which == 1 && active) || (which == 2 && !active);
           if (passed_bands_done && !active) skp = true;   // (projected forward: those tokens are in their slots already, and V~ does not exist there)
           if (l == 2 && mf && c->v_box_ok && v_in && !(mask & 4)) {
             skp = true;
@@ -992,7 +1016,7 @@ static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in
       npool = 1;
     }
     if (npool > 0)
-      HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, &skip[0][0], c->d_pool_part, st));
+      HIP_TRY(c, launch_summaries(c->Y, c->specV, c->Cbuf, L + c->off_masks, c->slices, c->N, c->d, c->nb, c->band_off, c->band_n, c->m_eff, ap.m2, is_half, &skip[0][0], c->d_pool_part, st));
     if (nsel > 0) {
       int nsplit = std::max(1, c->vsum_nsplit / nsel);   // nsel * nsplit <= 2 CUs' worth + nsel, what the scratch holds
       nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(nsplit, c->N / 64 / 8));   // at least eight tiles per range
@@ -1040,6 +1064,14 @@ static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in
       g.row_ptr = c->d_row_ptr; g.col_idx = c->d_col_idx; g.block = c->cfg.mid_block;
       HIP_TRY(c, launch_generic_attn(g, st));
     }
+    if (c->nb > 3 && c->n_list[MID2] > 0) {   // the second mid band: the same operator on its own rows and block list
+      const int64_t o = c->band_off[MID2] * c->d;
+      g.Q = (const float*)c->specQ + o; g.K = (const float*)c->specK + o; g.V = (const float*)c->specV + o;
+      g.O = (float*)c->Y + o; g.slice_list = L + c->off_list[MID2]; g.n_slices = c->n_list[MID2];
+      g.slice_stride = g.kv_slice_stride = Nd; g.nq = g.nk = (int)c->band_n[MID2]; g.mode = 1;
+      g.row_ptr = c->d_row_ptr2; g.col_idx = c->d_col_idx2; g.block = c->cfg.mid_block;
+      HIP_TRY(c, launch_generic_attn(g, st));
+    }
     tm.done("mid_attention");
     if (c->n_list[HIGH] > 0) {
       const int64_t o = c->band_off[HIGH] * c->d;
@@ -1064,14 +1096,14 @@ static freqattn_status bands_core(freqattn_ctx* c, float scale, const void* v_in
     if (mf) {
       HIP_TRY(c, launch_mfma_attn(ap, (const AttnItem*)(L + c->off_items_xchg), c->n_items_xchg, c->attn_rows, c->num_cu, st));
     } else {
-      for (int l = 0; l < 3; ++l) {
+      for (int l = 0; l < c->nb; ++l) {
         if (c->n_list[l] == 0 || c->n_c[l] == 0) continue;
         GenericAttnArgs g{};
         g.d = c->d; g.scale = scale; g.mode = 0; g.residual = 1;
         g.Q = (const float*)c->Y + c->band_off[l] * c->d; g.O = (float*)c->Y + c->band_off[l] * c->d;
         g.K = g.V = (const float*)c->Cbuf + (int64_t)l * ap.m2 * c->d;
         g.slice_list = L + c->off_list[l]; g.n_slices = c->n_list[l];
-        g.slice_stride = c->N * c->d; g.kv_slice_stride = (int64_t)3 * ap.m2 * c->d;
+        g.slice_stride = c->N * c->d; g.kv_slice_stride = (int64_t)c->nb * ap.m2 * c->d;
         g.nq = (int)c->band_n[l]; g.nk = c->n_c[l];
         HIP_TRY(c, launch_generic_attn(g, st));
       }
@@ -1108,7 +1140,8 @@ static freqattn_status forward_impl(freqattn_ctx* c, const void* q, const void* 
   freqattn_status fs = check_forward_args(c, q, k, v, band_cfg, out, who);
   if (fs != FREQATTN_OK) return fs;
   for (int h = 0; h < c->shape.heads; ++h)
-    if (head_alloc[h] < 0 || head_alloc[h] > 7) return fail(c, FREQATTN_EINVAL, std::string(who) + ": head_alloc entry outside 0..7");
+    if (head_alloc[h] < 0 || head_alloc[h] >= (1 << c->nb))
+      return fail(c, FREQATTN_EINVAL, std::string(who) + (c->nb > 3 ? ": head_alloc entry outside 0..15" : ": head_alloc entry outside 0..7"));
   const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
   fs = ensure_lists(c, head_alloc, st);
   if (fs != FREQATTN_OK) return fs;
@@ -1358,6 +1391,7 @@ extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const voi
       return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: NULL argument");
     if (c->path != FREQATTN_PATH_MFMA)
       return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_projected: needs a context on the matrix-core path");
+    if (c->nb != 3) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_projected: three-band contexts only");
     if (!same_cfg(*band_cfg, c->cfg))
       return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: band_cfg differs from the one given to freqattn_create");
     if (out == x) return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: out aliases x");
@@ -1451,6 +1485,7 @@ extern "C" freqattn_status freqattn_forward_routed(freqattn_ctx* c, const void* 
   freqattn_status fs = check_forward_args(c, q, k, v, band_cfg, out, "freqattn_forward_routed");
   if (fs != FREQATTN_OK) return fs;
   if (c->d % 64 != 0) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_routed: head_dim must be a multiple of 64");
+  if (c->nb != 3) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_routed: the router scores three bands (section 3.5); a four-band context takes its allocation from the caller");
   hipStream_t st = (hipStream_t)stream;
   const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
   StageTimer tm(*c, st);
@@ -1512,7 +1547,7 @@ extern "C" freqattn_status freqattn_dense_forward(freqattn_ctx* c, const void* q
 extern "C" freqattn_status freqattn_read_spectral(freqattn_ctx* c, int32_t which, int32_t slice, int32_t band,
                                                   float* host_out, void* stream) {
   return guarded(c, "freqattn_read_spectral", [&]() -> freqattn_status {
-  if (!c || !host_out || which < 0 || which > 3 || slice < 0 || slice >= c->slices || band < 0 || band > 2)
+  if (!c || !host_out || which < 0 || which > 3 || slice < 0 || slice >= c->slices || band < 0 || band >= c->nb)
     return FREQATTN_EINVAL;
   if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_read_spectral: tables-only context");
   HIP_TRY(c, hipStreamSynchronize((hipStream_t)stream));
@@ -1640,6 +1675,7 @@ extern "C" freqattn_status freqattn_route_mlp(freqattn_ctx* c, const void* q, co
     return fail(c, FREQATTN_EINVAL, "freqattn_route_mlp: NULL argument or hidden < 1");
   if (c->path == FREQATTN_PATH_TABLES_ONLY) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: tables-only context");
   if (c->d % 64 != 0) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: head_dim must be a multiple of 64");
+  if (c->nb != 3) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_route_mlp: the router scores three bands (section 3.5); a four-band context takes its allocation from the caller");
   hipStream_t st = (hipStream_t)stream;
   freqattn_status fs = transforms_phase(c, q, k, v, st, true);
   if (fs != FREQATTN_OK) return fs;

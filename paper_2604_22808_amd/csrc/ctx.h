@@ -11,7 +11,8 @@ namespace fa {
 
 typedef _Float16 half_t;
 
-enum { LOW = 0, MID = 1, HIGH = 2 };
+enum { LOW = 0, MID = 1, HIGH = 2, MID2 = 3 };   // MID2: the second block-sparse band of a four-band layout (its rows follow the high band's)
+enum { NBMAX = 4 };
 
 // Work item of the attention kernels: a tile of query rows of one branch of one (batch*heads) slice.
 // kind: 0 low (compressed tokens), 1 mid (block list), 2 high (window), 3 exchange on band `band`, 4 dense baseline.
@@ -32,13 +33,16 @@ struct AttnParams {
   const void* lowK;
   const void* lowV;
   void* lowY;
-  const void* C;      // [slices][3][2m][d] summary tokens seen by band l
+  const void* C;      // [slices][nb][(nb-1) m][d] summary tokens seen by band l
   const int32_t* mid_row_ptr;
   const int32_t* mid_col_idx;
-  int32_t band_off[3];
-  int32_t band_n[3];
-  int32_t n_c[3];     // valid rows of C per band
-  int32_t N, d, nbar, m2;  // m2 = 2m = rows reserved per band in C
+  const int32_t* mid2_row_ptr;   // block list of band MID2
+  const int32_t* mid2_col_idx;
+  int32_t band_off[NBMAX];
+  int32_t band_n[NBMAX];
+  int32_t n_c[NBMAX]; // valid rows of C per band
+  int32_t nb;         // bands: 3 or 4
+  int32_t N, d, nbar, m2;  // m2 = (nb-1) m = rows reserved per band in C
   int32_t mid_block, high_window;
   float scale;
   // dense baseline
@@ -58,15 +62,17 @@ struct Ctx {
   int slices;       // batch*heads
   int64_t N;
   int d;
-  int64_t band_n[3], band_off[3];
-  int64_t nbar, nb_mid;
-  int m_eff[3], n_c[3];
+  int nb = 3;       // bands: 3, or 4 with cfg.mid2_num > 0
+  int64_t band_n[NBMAX] = {0, 0, 0, 0}, band_off[NBMAX] = {0, 0, 0, 0};
+  int64_t nbar, nb_mid, nb_mid2 = 0;
+  int m_eff[NBMAX] = {0, 0, 0, 0}, n_c[NBMAX] = {0, 0, 0, 0};
   std::string err;
 
   // host tables
-  std::vector<int32_t> h_band_index[3];
+  std::vector<int32_t> h_band_index[NBMAX];
   std::vector<int32_t> h_perm;       // flat coefficient index -> band-major row
   std::vector<int32_t> h_row_ptr, h_col_idx;
+  std::vector<int32_t> h_row_ptr2, h_col_idx2;   // block list of band MID2
   std::vector<double> h_F[3];        // per-axis DCT matrices as rounded for the device, [n][n]
   std::vector<int32_t> h_alloc;      // last head_alloc seen (size heads), empty before the first forward
   bool alloc_valid = false;
@@ -76,6 +82,8 @@ struct Ctx {
   int32_t* d_perm_t = nullptr;   // the same map stored [kh*W + kw][kt]: the 64..128 rows a T-axis tile looks up are adjacent (MFMA path)
   int32_t* d_row_ptr = nullptr;
   int32_t* d_col_idx = nullptr;
+  int32_t* d_row_ptr2 = nullptr;
+  int32_t* d_col_idx2 = nullptr;
   float* d_F32[3] = {nullptr, nullptr, nullptr};    // F  [n][n] fp32 (generic path)
   float* d_Ft32[3] = {nullptr, nullptr, nullptr};   // F^T
   half_t* d_F16[3] = {nullptr, nullptr, nullptr};   // F  fp16 (MFMA path)
@@ -100,9 +108,9 @@ struct Ctx {
   int32_t* d_lists = nullptr; int32_t* h_lists = nullptr; size_t lists_bytes = 0;
   // layout inside lists (int32 units)
   size_t off_masks = 0;               // [slices] band mask per slice
-  size_t off_list[3] = {0, 0, 0};     // [slices] slices with band l active
-  int n_list[3] = {0, 0, 0};
-  size_t off_cls[4] = {0, 0, 0, 0};   // [slices] slices by class: 0 low only, 1 mid (no high), 2 high, 3 nothing active
+  size_t off_list[NBMAX] = {0, 0, 0, 0};     // [slices] slices with band l active
+  int n_list[NBMAX] = {0, 0, 0, 0};
+  size_t off_cls[4] = {0, 0, 0, 0};   // [slices] slices by class: 0 low only, 1 mid (no high, no second mid band), 2 high or second mid band, 3 nothing active
   int n_cls[4] = {0, 0, 0, 0};
   size_t off_nonhigh = 0;             // [slices] classes 0, 1 and 3 together (every slice that does not run the high band)
   int n_nonhigh = 0;
@@ -167,7 +175,7 @@ struct Ctx {
 void build_dct_matrix(int n, std::vector<double>& F);  // [n][n], row = frequency
 void build_haar_matrix(int n, std::vector<double>& F); // [n][n], row = scale (coarse to fine), n a power of two
 void build_bands(Ctx& c);
-void build_mid_blocks(Ctx& c);
+void build_mid_blocks(Ctx& c);   // both block-sparse bands
 void build_summary_weights(const Ctx& c, int band, std::vector<float>& out);   // [m_eff[band]][N]
 void pack_vsum_weights(const std::vector<float>& w, int m, int64_t N, std::vector<uint16_t>& out);  // bf16 [N/64][64][64], see mfma_vsum.hip
 
@@ -183,7 +191,7 @@ struct AxisPassArgs {
   int64_t Ntok;
   // input source selection per band for the first inverse pass (perm_in set): rows of band l of slice hb come from
   // `in` when bit l of masks[hb] is set, else from `in_alt`.
-  const void* in_alt; const int32_t* masks; int32_t band_off1, band_off2;
+  const void* in_alt; const int32_t* masks; int32_t band_off1, band_off2, band_off3;   // first rows of bands 1, 2, 3 (band_off3 = Ntok without a fourth band)
   int in_kind, out_kind;    // 0 float, 1 bf16, 2 fp16
   int slice_mod;            // number of slices the masks array covers (slab slice index is taken modulo this)
 };
@@ -210,11 +218,11 @@ hipError_t launch_expand_low(const void* lowY, void* Y, const int32_t* slice_lis
 // skip_bits[l][..]: bit s set = band l of slice s is not pooled here (no active band of the slice looks at it, or - high
 // band only - its V~ rows do not exist and launch_vsum supplies it).
 hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
-                            const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2, int is_half,
-                            const uint64_t* skip_bits /*[3][4] or NULL*/, float* split_part /*[slices][3][128][d] or NULL*/, hipStream_t st);
+                            int nb, const int64_t band_off[NBMAX], const int64_t band_n[NBMAX], const int m_eff[NBMAX], int m2, int is_half,
+                            const uint64_t* skip_bits /*[NBMAX][4] or NULL*/, float* split_part /*[slices][nb][128][d] or NULL*/, hipStream_t st);
 // High-band summary tokens of the slices in `sel` (bit set, nsel of them) from the untransformed bf16 V.
 hipError_t launch_vsum(const void* V, const void* Wsum, float* part, void* C, const uint64_t sel[4], int nsel, int64_t N,
-                       int d, int nsplit, int64_t n_high, const int m_eff[3], int m2rows, hipStream_t st);
+                       int d, int nsplit, int64_t n_high, const int m_eff[NBMAX], int m2rows, hipStream_t st);   // (three-band contexts only)
 // Projected forward: P[batch][3][mrows][dm] = per-chunk means of the band rows of X~ [batch][N][dm] (fp16), and the
 // placement of the projected pooled rows T[slices][3][mrows][d] into the C slots of the bands a slice passes through.
 hipError_t launch_pool_wide(const void* X, void* P, int batch, int64_t N, int dm, const int64_t band_off[3],
@@ -255,7 +263,7 @@ struct DctPassArgs {
   // first column col0 is the band-major row perm[j*perm_k + o*perm_o + col0/d] of slice `slice`.
   const int32_t* perm_in; const int32_t* perm_out; int64_t Ntok, perm_k, perm_o;
   int32_t perm_scale;       // 0/1: index = k*perm_k + tile index; otherwise k*perm_k + tile index*perm_scale (transposed table)
-  const void* in_alt; const int32_t* masks; int32_t band_off1, band_off2;
+  const void* in_alt; const int32_t* masks; int32_t band_off1, band_off2, band_off3;
   int in_bf16, out_bf16;    // element type of in / out: bf16 when set, else fp16
   int d;
   // Swapped scratch layout: with out_swap (in_swap) set, slab s = a*sw + b writes (reads) row k at

@@ -48,7 +48,7 @@ __global__ void k_axis_pass(AxisPassArgs a, int64_t total) {
     if (a.perm_in) {
       const int32_t row = a.perm_in[o * a.n + j];
       if (a.masks) {
-        const int band = row < a.band_off1 ? 0 : (row < a.band_off2 ? 1 : 2);
+        const int band = row < a.band_off1 ? 0 : (row < a.band_off2 ? 1 : (row < a.band_off3 ? 2 : 3));
         if (!((a.masks[slice % a.slice_mod] >> band) & 1)) src = a.in_alt;
       }
       e = (slice * a.Ntok + row) * a.inner + i;
@@ -222,20 +222,27 @@ hipError_t launch_expand_low(const void* lowY, void* Y, const int32_t* slice_lis
 
 // Summary tokens (section 3.6, U = I): chunk u of band l covers band rows [floor(u n / m), floor((u+1) n / m)).
 // One workgroup per (slice, band, chunk); threads split the chunk's rows 256/d ways and the partial sums are added in
-// a fixed order, so the result does not depend on scheduling.  The mean is written to the C rows of the two other
-// bands (band l sees the summaries of the other bands, ascending band order).
-struct SkipBits { uint64_t w[3][4]; };   // per band: slices whose summaries of that band are not pooled here (unused, or summed from the untransformed V)
+// a fixed order, so the result does not depend on scheduling.  The mean is written to the C rows of the other
+// bands (band l sees the summaries of the other bands, ascending band index).
+struct SkipBits { uint64_t w[NBMAX][4]; };   // per band: slices whose summaries of that band are not pooled here (unused, or summed from the untransformed V)
+struct BandGeom { int64_t off[NBMAX], n[NBMAX]; int m[NBMAX]; int nb; };   // first row, rows and summary tokens per band; nb bands
+
+// row of band `band`'s token u among the tokens band b != band looks at
+__device__ __forceinline__ int summary_pos(const BandGeom& g, int band, int b, int u) {
+  int pos = u;
+  for (int o = 0; o < band; ++o)
+    if (o != b) pos += g.m[o];
+  return pos;
+}
 
 template <typename T>
 __global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C, const int32_t* masks, int64_t N, int d,
-                                                   int64_t off0, int64_t off1, int64_t off2, int64_t n0, int64_t n1,
-                                                   int64_t n2, int m0, int m1, int m2e, int mmax, int m2rows, SkipBits skip) {
+                                                   BandGeom g, int m2rows, SkipBits skip) {
   __shared__ float part[256];
   const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x;
   if (slice < 256 && ((skip.w[band][slice >> 6] >> (slice & 63)) & 1)) return;
-  const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
-  const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
-  const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
+  const int64_t off = g.off[band], n = g.n[band];
+  const int me = g.m[band];
   if (u >= me) return;
   const T* src = ((masks[slice] >> band) & 1) ? Y : V;
   const int64_t r0 = ((int64_t)u * n) / me, r1 = ((int64_t)(u + 1) * n) / me;
@@ -251,31 +258,24 @@ __global__ void __launch_bounds__(256) k_summaries(const T* Y, const T* V, T* C,
     float t = 0.f;
     for (int g2 = 0; g2 < groups; ++g2) t += part[g2 * d + ch];
     const T mean = (T)(t / (float)(r1 - r0));
-    // destination rows: in C of band b != band, the summaries of the lower other band come first
-    for (int b = 0; b < 3; ++b) {
+    for (int b = 0; b < g.nb; ++b) {
       if (b == band) continue;
-      int pos = u;
-      for (int o = 0; o < band; ++o)
-        if (o != b) pos += (o == 0 ? m0 : o == 1 ? m1 : m2e);
-      C[(((int64_t)slice * 3 + b) * m2rows + pos) * d + ch] = mean;
+      C[(((int64_t)slice * g.nb + b) * m2rows + summary_pos(g, band, b, u)) * d + ch] = mean;
     }
   }
-  (void)mmax;
 }
 
 // fp16 variant with 16-byte loads: a thread owns 8 adjacent channels, 256 / (d/8) row groups per workgroup, sixteen
 // rows in flight per thread.  Same chunk rule, same fixed summation order per (row group, then groups ascending).
 __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const half_t* V, half_t* C, const int32_t* masks,
-                                                      int64_t N, int d, int64_t off0, int64_t off1, int64_t off2,
-                                                      int64_t n0, int64_t n1, int64_t n2, int m0, int m1, int m2e,
-                                                      int m2rows, SkipBits skip, int nsplit, float* split_part) {
+                                                      int64_t N, int d, BandGeom g, int m2rows, SkipBits skip, int nsplit,
+                                                      float* split_part) {
   typedef _Float16 h8 __attribute__((ext_vector_type(8)));
   __shared__ float part[256 * 8];
   const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x / nsplit, sp = blockIdx.x % nsplit;
   if (slice < 256 && ((skip.w[band][slice >> 6] >> (slice & 63)) & 1)) return;
-  const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
-  const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
-  const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
+  const int64_t off = g.off[band], n = g.n[band];
+  const int me = g.m[band];
   if (u >= me) return;
   const half_t* src = (((masks[slice] >> band) & 1) ? Y : V) + ((int64_t)slice * N + off) * d;
   const int64_t c0 = ((int64_t)u * n) / me, c1 = ((int64_t)(u + 1) * n) / me;   // the chunk
@@ -320,71 +320,64 @@ __global__ void __launch_bounds__(256) k_summaries_h8(const half_t* Y, const hal
       mean[j] = (_Float16)(t * inv);
     }
     if (nsplit > 1) {   // [slice][band][u][split][d]
-      float* dst = split_part + ((((int64_t)slice * 3 + band) * gridDim.x + blockIdx.x) * d) + c8 * 8;
+      float* dst = split_part + ((((int64_t)slice * g.nb + band) * gridDim.x + blockIdx.x) * d) + c8 * 8;
 #pragma unroll
       for (int j = 0; j < 8; ++j) dst[j] = sum[j];
       return;
     }
-    for (int b = 0; b < 3; ++b) {
+    for (int b = 0; b < g.nb; ++b) {
       if (b == band) continue;
-      int pos = u;
-      for (int o = 0; o < band; ++o)
-        if (o != b) pos += (o == 0 ? m0 : o == 1 ? m1 : m2e);
-      *(h8*)(C + (((int64_t)slice * 3 + b) * m2rows + pos) * d + c8 * 8) = mean;
+      *(h8*)(C + (((int64_t)slice * g.nb + b) * m2rows + summary_pos(g, band, b, u)) * d + c8 * 8) = mean;
     }
   }
 }
 
 // Second stage of the split pooling: adds the nsplit partial sums of a chunk in order and writes the mean rows.
-__global__ void __launch_bounds__(256) k_summaries_finish(const float* split_part, half_t* C, int d, int64_t n0, int64_t n1,
-                                                          int64_t n2, int m0, int m1, int m2e, int m2rows, SkipBits skip,
-                                                          int nsplit, int mmax) {
+__global__ void __launch_bounds__(256) k_summaries_finish(const float* split_part, half_t* C, int d, BandGeom g, int m2rows,
+                                                          SkipBits skip, int nsplit, int mmax) {
   const int slice = blockIdx.z, band = blockIdx.y, u = blockIdx.x, ch = threadIdx.x;
   if (slice < 256 && ((skip.w[band][slice >> 6] >> (slice & 63)) & 1)) return;
-  const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
-  const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
+  const int64_t n = g.n[band];
+  const int me = g.m[band];
   if (u >= me || ch >= d) return;
   const int64_t c0 = ((int64_t)u * n) / me, c1 = ((int64_t)(u + 1) * n) / me;
-  const float* src = split_part + ((((int64_t)slice * 3 + band) * (mmax * nsplit) + (int64_t)u * nsplit) * d) + ch;
+  const float* src = split_part + ((((int64_t)slice * g.nb + band) * (mmax * nsplit) + (int64_t)u * nsplit) * d) + ch;
   float t = 0.f;
   for (int sp = 0; sp < nsplit; ++sp) t += src[(int64_t)sp * d];
   const half_t mean = (half_t)(t / (float)(c1 - c0));
-  for (int b = 0; b < 3; ++b) {
+  for (int b = 0; b < g.nb; ++b) {
     if (b == band) continue;
-    int pos = u;
-    for (int o = 0; o < band; ++o)
-      if (o != b) pos += (o == 0 ? m0 : o == 1 ? m1 : m2e);
-    C[(((int64_t)slice * 3 + b) * m2rows + pos) * d + ch] = mean;
+    C[(((int64_t)slice * g.nb + b) * m2rows + summary_pos(g, band, b, u)) * d + ch] = mean;
   }
 }
 
 hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t* masks, int slices, int64_t N, int d,
-                            const int64_t band_off[3], const int64_t band_n[3], const int m_eff[3], int m2rows,
-                            int is_half, const uint64_t* skip_bits /*[3][4] or NULL*/, float* split_part, hipStream_t st) {
+                            int nb, const int64_t band_off[NBMAX], const int64_t band_n[NBMAX], const int m_eff[NBMAX], int m2rows,
+                            int is_half, const uint64_t* skip_bits /*[NBMAX][4] or NULL*/, float* split_part, hipStream_t st) {
   SkipBits skip;
-  for (int l = 0; l < 3; ++l)
+  BandGeom g;
+  g.nb = nb;
+  int mmax = 0;
+  for (int l = 0; l < NBMAX; ++l) {
     for (int i = 0; i < 4; ++i) skip.w[l][i] = skip_bits ? skip_bits[l * 4 + i] : 0;
-  int mmax = m_eff[0] > m_eff[1] ? m_eff[0] : m_eff[1];
-  if (m_eff[2] > mmax) mmax = m_eff[2];
+    g.off[l] = band_off[l]; g.n[l] = l < nb ? band_n[l] : 0; g.m[l] = l < nb ? m_eff[l] : 0;
+    if (g.m[l] > mmax) mmax = g.m[l];
+  }
   if (mmax == 0 || slices == 0) return hipSuccess;
-  dim3 grid((unsigned)mmax, 3, (unsigned)slices);
+  dim3 grid((unsigned)mmax, (unsigned)nb, (unsigned)slices);
   if (is_half && d % 8 == 0 && 256 % (d / 8) == 0) {
     // at least 64 workgroups per (slice, band): with few chunks each is cut into row ranges (scratch: 128 rows per pair)
     const int nsplit = (split_part && mmax < 64) ? (64 + mmax - 1) / mmax : 1;
-    hipLaunchKernelGGL(k_summaries_h8, dim3((unsigned)(mmax * nsplit), 3, (unsigned)slices), dim3(256), 0, st, (const half_t*)Y,
-                       (const half_t*)V, (half_t*)C, masks, N, d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1],
-                       band_n[2], m_eff[0], m_eff[1], m_eff[2], m2rows, skip, nsplit, split_part);
+    hipLaunchKernelGGL(k_summaries_h8, dim3((unsigned)(mmax * nsplit), (unsigned)nb, (unsigned)slices), dim3(256), 0, st, (const half_t*)Y,
+                       (const half_t*)V, (half_t*)C, masks, N, d, g, m2rows, skip, nsplit, split_part);
     if (nsplit > 1)
-      hipLaunchKernelGGL(k_summaries_finish, grid, dim3(256), 0, st, split_part, (half_t*)C, d, band_n[0], band_n[1], band_n[2],
-                         m_eff[0], m_eff[1], m_eff[2], m2rows, skip, nsplit, mmax);
+      hipLaunchKernelGGL(k_summaries_finish, grid, dim3(256), 0, st, split_part, (half_t*)C, d, g, m2rows, skip, nsplit, mmax);
   } else if (is_half)
     hipLaunchKernelGGL(k_summaries<half_t>, grid, dim3(256), 0, st, (const half_t*)Y, (const half_t*)V, (half_t*)C,
-                       masks, N, d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0],
-                       m_eff[1], m_eff[2], mmax, m2rows, skip);
+                       masks, N, d, g, m2rows, skip);
   else
     hipLaunchKernelGGL(k_summaries<float>, grid, dim3(256), 0, st, (const float*)Y, (const float*)V, (float*)C, masks, N,
-                       d, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2], m_eff[0], m_eff[1],
-                       m_eff[2], mmax, m2rows, skip);
+                       d, g, m2rows, skip);
   return hipGetLastError();
 }
 

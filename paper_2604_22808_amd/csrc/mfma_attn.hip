@@ -116,7 +116,7 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
     } else if (kind == 3) {
       const int64_t o = (slice * p.N + p.band_off[band]) * D;
       Qp = (const uint16_t*)p.Y + o; Op = (uint16_t*)p.Y + o; nq = p.band_n[band];
-      Kp = Vp = (const uint16_t*)p.C + ((slice * 3 + band) * p.m2) * (int64_t)D; nk = p.n_c[band];
+      Kp = Vp = (const uint16_t*)p.C + ((slice * p.nb + band) * p.m2) * (int64_t)D; nk = p.n_c[band];
     } else {
       const int64_t o = slice * p.N * D;
       Qp = (const uint16_t*)p.denseQ + o; Kp = (const uint16_t*)p.denseK + o; Vp = (const uint16_t*)p.denseV + o;
@@ -166,7 +166,7 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
     // before the launch) is the cross-band exchange of section 3.6, with the phase-0 result - rounded to fp16 exactly as
     // it would have been stored - as the query and as the residual, and the <= 2m summary tokens as keys and values.
     const int n_phases = 1 + (item.kind_band >> 16 & 1);
-    const uint16_t* Cp = (const uint16_t*)p.C + ((slice * 3 + band) * p.m2) * (int64_t)D;
+    const uint16_t* Cp = (const uint16_t*)p.C + ((slice * p.nb + band) * p.m2) * (int64_t)D;
     int tile_base = 0;   // tiles staged so far in this item: tile i of the item lives in LDS copy i & 1
     bool staged = false; // the first tile of the coming phase is already in its LDS copy
     for (int phase = 0; phase < n_phases; ++phase) {
@@ -214,8 +214,9 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
       int n_outer = 1, e0 = 0, sub_n = 1, t_lo = 0, t_hi = 0;
       if (kind_p == 1) {
         const int I = q0 / p.mid_block;
-        e0 = p.mid_row_ptr[I];
-        n_outer = p.mid_row_ptr[I + 1] - e0;
+        const int32_t* rp = band == MID2 ? p.mid2_row_ptr : p.mid_row_ptr;   // each block-sparse band has its own list
+        e0 = rp[I];
+        n_outer = rp[I + 1] - e0;
         sub_n = p.mid_block / KT;
       } else if (kind_p == 2) {
         const int klo = q0 - w > 0 ? q0 - w : 0;
@@ -228,7 +229,7 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
       }
       const int n_tt = n_outer * sub_n;
       auto key0_of = [&](int idx) -> int {
-        if (kind_p == 1) return (p.mid_col_idx[e0 + idx / sub_n] * sub_n + idx % sub_n) * KT;
+        if (kind_p == 1) return ((band == MID2 ? p.mid2_col_idx : p.mid_col_idx)[e0 + idx / sub_n] * sub_n + idx % sub_n) * KT;
         return (t_lo + idx) * KT;
       };
       // Exchange items of one (slice, band) all see the same <= 2 tiles of summary tokens: a workgroup that has them in

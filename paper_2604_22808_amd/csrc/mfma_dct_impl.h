@@ -162,7 +162,7 @@ k_dct_pass(DctPassArgs a, int64_t n_tiles, int chunks_per_slab) {
   // (gather: `row` is the band-major row of that input row, looked up one tile ahead by perm_rows)
   auto load_piece = [&](const TileAddr& t, int j0, int32_t row) -> uint4v {
     if (PERM_IN) {
-      const int band = row < a.band_off1 ? 0 : (row < a.band_off2 ? 1 : 2);
+      const int band = row < a.band_off1 ? 0 : (row < a.band_off2 ? 1 : (row < a.band_off3 ? 2 : 3));
       const bool active = (t.mask >> band) & 1;
       const uint64_t lane_off = ((uint64_t)(uint32_t)row * (uint32_t)a.d + (uint32_t)lcol) * 2u;   // bytes within the slice
       if (a.delta) {   // change of the active bands against V~ (zero elsewhere)

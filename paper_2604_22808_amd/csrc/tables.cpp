@@ -36,12 +36,15 @@ void build_haar_matrix(int n, std::vector<double>& F) {
 
 // Band membership of section 3.3 with rational edges, decided in 64-bit integers; band-major order is the order of
 // the ascending flat index (kt*H + kh)*W + kw inside each band.  perm maps a flat index to its band-major row, where
-// the low band occupies rows [0, n_low), the mid band the next n_mid rows and the high band the rest.
+// the low band occupies rows [0, n_low), the mid band the next n_mid rows, the high band the rows after that and - in a
+// four-band layout (cfg.mid2_num > 0: coefficients inside the third edge but outside the mid edge) - the second mid
+// band the rest: the bands lie in the order of their indices, and a three-band layout is a four-band one without its
+// last band.
 void build_bands(Ctx& c) {
   const int T = c.shape.T, H = c.shape.H, W = c.shape.W;
   const freqattn_band_cfg& g = c.cfg;
-  for (int l = 0; l < 3; ++l) c.h_band_index[l].clear();
-  std::vector<int8_t> band((size_t)c.N);
+  c.nb = g.mid2_num > 0 ? 4 : 3;
+  for (int l = 0; l < NBMAX; ++l) c.h_band_index[l].clear();
   for (int kt = 0; kt < T; ++kt)
     for (int kh = 0; kh < H; ++kh)
       for (int kw = 0; kw < W; ++kw) {
@@ -49,40 +52,43 @@ void build_bands(Ctx& c) {
         auto inside = [&](int64_t num, int64_t den) {
           return kt * den < num * T && kh * den < num * H && kw * den < num * W;
         };
-        const int l = inside(g.low_num, g.low_den) ? LOW : inside(g.mid_num, g.mid_den) ? MID : HIGH;
-        band[flat] = (int8_t)l;
+        int l = inside(g.low_num, g.low_den) ? LOW : inside(g.mid_num, g.mid_den) ? MID : HIGH;
+        if (l == HIGH && c.nb == 4 && inside(g.mid2_num, g.mid2_den)) l = MID2;
         c.h_band_index[l].push_back((int32_t)flat);
       }
   int64_t off = 0;
-  for (int l = 0; l < 3; ++l) {
+  for (int l = 0; l < NBMAX; ++l) {
     c.band_n[l] = (int64_t)c.h_band_index[l].size();
     c.band_off[l] = off;
     off += c.band_n[l];
   }
   c.h_perm.assign((size_t)c.N, 0);
-  for (int l = 0; l < 3; ++l)
+  for (int l = 0; l < NBMAX; ++l)
     for (size_t r = 0; r < c.h_band_index[l].size(); ++r)
       c.h_perm[c.h_band_index[l][r]] = (int32_t)(c.band_off[l] + (int64_t)r);
 }
 
 // Block list of the mid-band pattern (section 3.4.2): query block I sees key block J iff |I-J| <= diag, or
-// (I-J) mod stride == 0, or J == 0 when block0 is on.  Columns ascend within a row.
-void build_mid_blocks(Ctx& c) {
-  const freqattn_band_cfg& g = c.cfg;
-  const int64_t nb = (c.band_n[MID] + g.mid_block - 1) / g.mid_block;
-  c.nb_mid = nb;
-  c.h_row_ptr.assign((size_t)nb + 1, 0);
-  c.h_col_idx.clear();
+// (I-J) mod stride == 0, or J == 0 when block0 is on.  Columns ascend within a row.  One list per block-sparse band.
+static int64_t block_list(const freqattn_band_cfg& g, int64_t n_rows, std::vector<int32_t>& row_ptr, std::vector<int32_t>& col_idx) {
+  const int64_t nb = (n_rows + g.mid_block - 1) / g.mid_block;
+  row_ptr.assign((size_t)nb + 1, 0);
+  col_idx.clear();
   for (int64_t I = 0; I < nb; ++I) {
     for (int64_t J = 0; J < nb; ++J) {
       const int64_t diff = I - J;
       const int64_t ad = diff < 0 ? -diff : diff;
       int64_t mod = diff % g.mid_stride;
       if (mod < 0) mod += g.mid_stride;
-      if (ad <= g.mid_diag || mod == 0 || (g.mid_block0 && J == 0)) c.h_col_idx.push_back((int32_t)J);
+      if (ad <= g.mid_diag || mod == 0 || (g.mid_block0 && J == 0)) col_idx.push_back((int32_t)J);
     }
-    c.h_row_ptr[(size_t)I + 1] = (int32_t)c.h_col_idx.size();
+    row_ptr[(size_t)I + 1] = (int32_t)col_idx.size();
   }
+  return nb;
+}
+void build_mid_blocks(Ctx& c) {
+  c.nb_mid = block_list(c.cfg, c.band_n[MID], c.h_row_ptr, c.h_col_idx);
+  c.nb_mid2 = block_list(c.cfg, c.band_n[MID2], c.h_row_ptr2, c.h_col_idx2);
 }
 
 // Weights of a band's summary tokens as functionals of the untransformed input (section 3.6, U = I):

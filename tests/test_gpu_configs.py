@@ -418,3 +418,49 @@ def test_projected_forward_on_a_ragged_grid():
     mx, rl = U.errors(U.to_host64(out), want)
     print(f"projected ragged grid: bands {ctx.band_sizes()} max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
     assert mx <= 2e-2 and rl <= 5e-3
+
+
+def test_four_band_layout_on_both_paths():
+    """Band count L = 4 (the band-count ablation of section 8): a second block-sparse band between the mid edge and a
+    third edge at 3/4 of every axis.  Matrix-core path at 16K tokens (bands of 256 / 1,792 / 9,472 / 4,864 coefficients),
+    one head per mask: each band alone, pairs across the new band, all four, and a head that passes everything through;
+    band outputs of the new band are compared before the inverse transform as well.  Then the generic fp32 path on the
+    tiny grid.  The routed and projected entry points refuse such a context."""
+    wl = WL.WORKLOADS["16k"]
+    alloc = (8, 9, 15, 6, 12, 10, 0, 1, 4)
+    heads = list(range(len(alloc)))
+    q, k, v = (WL.round_to_io(x, "bf16") for x in WL.qkv_numpy(wl, heads=[h % wl.heads for h in heads]))
+    band = dict(wl.band, mid2_num=3, mid2_den=4)
+    cfg = O.BandConfig(**band)
+    ctx = B.Context(1, len(alloc), wl.head_dim, wl.grid, B.BF16, B.make_cfg(**band))
+    assert ctx.get_path() == B.PATH_MFMA and ctx.band_sizes() == [256, 1792, 9472, 4864]
+    T, H, W = wl.grid
+    wants = []
+    for s, mask in enumerate(alloc):
+        host = [x[0, s].astype(np.float64).reshape(T, H, W, wl.head_dim) for x in (q, k, v)]
+        wants.append(O.head_forward(host[0], host[1], host[2], cfg, mask, return_parts=True))
+    for fusion in (1, 0):
+        ctx.set_exchange_fusion(fusion)
+        got = U.run_forward(ctx, q, k, v, "bf16", alloc)
+        for s, mask in enumerate(alloc):
+            want, parts = wants[s]
+            mx, rl = U.errors(got[0, s], want.reshape(-1, wl.head_dim))
+            print(f"four bands fusion={fusion} mask {mask}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+            assert mx <= 2e-2 and rl <= 5e-3, (mask, mx, rl)
+            for l in range(4):
+                if (mask >> l) & 1:
+                    _, rl = U.errors(ctx.read_spectral(3, s, l), parts["Yhat"][l])
+                    assert rl <= 3e-3, (mask, l, rl)
+    with pytest.raises(B.FreqAttnError):
+        U.run_forward(ctx, q, k, v, "bf16", (16,) + alloc[1:])     # a fifth band does not exist
+    tiny = WL.WORKLOADS["tiny_f32"]
+    q, k, v = (WL.round_to_io(x, "f32") for x in WL.qkv_numpy(tiny))
+    bandt = dict(tiny.band, mid2_num=3, mid2_den=4)
+    ctx = B.Context(1, 2, tiny.head_dim, tiny.grid, B.F32, B.make_cfg(**bandt))
+    assert ctx.get_path() == B.PATH_GENERIC and len(ctx.band_sizes()) == 4 and min(ctx.band_sizes()) > 0
+    for allocs in ((15, 9), (8, 14), (5, 10)):
+        got = U.run_forward(ctx, q, k, v, "f32", allocs)
+        want = O.forward(q, k, v, tiny.grid, O.BandConfig(**bandt), allocs)
+        mx, rl = U.errors(got, want)
+        print(f"four bands fp32 {allocs}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+        assert mx <= 1e-5 and rl <= 1e-5

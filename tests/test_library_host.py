@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "freqattn.h")).read()
-    declared = set(re.findall(r"\b(freqattn_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(freqattn_[a-z0-9_]+)\s*\(", header))
     assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
     raw = C.CDLL(B.LIB_PATH)
     for name in declared:
@@ -195,3 +195,29 @@ def test_two_band_tables_and_load_balance_term():
     assert abs(B.load_balance(pi, 0.01) - O.load_balance_loss(pi.astype(np.float32), 0.01)) < 1e-9
     hard = np.eye(3)[[0] * 16 + [1] * 6 + [2] * 2]
     assert abs(B.load_balance(hard, 1.0) - O.load_balance_loss(hard, 1.0)) < 1e-7
+
+
+def test_four_band_tables():
+    """L = 4 (the band-count ablation of section 8): a third edge splits what lies beyond the mid edge into a second
+    block-sparse band (index 3, rows after the high band) and the windowed rest; lists and block patterns are the oracle's,
+    and without the third edge the context is the three-band one."""
+    for grid, kw in [((8, 16, 16), dict(mid2_num=3, mid2_den=4)), ((4, 8, 16), dict(mid2_num=3, mid2_den=4, mid_block=16)),
+                     ((3, 5, 7), dict(mid2_num=2, mid2_den=3, mid_block=5, mid_stride=3)),
+                     ((8, 8, 8), dict(mid2_num=1, mid2_den=1, mid_block=16))]:
+        ctx = tables_ctx(grid, **kw)
+        cfg = O.BandConfig(**kw)
+        want = O.band_partition(*grid, cfg)
+        assert len(want) == 4 and ctx.band_sizes() == [len(w) for w in want]
+        for l in range(4):
+            assert np.array_equal(ctx.band_index(l).astype(np.int64), want[l])
+        for band, (rp, ci) in ((1, ctx.mid_blocks()), (3, ctx.mid2_blocks())):
+            nb = -(-len(want[band]) // cfg.mid_block)
+            wrp, wci = O.mid_block_csr(nb, cfg.mid_diag, cfg.mid_stride, cfg.mid_block0)
+            assert np.array_equal(rp, wrp) and np.array_equal(ci, wci)
+    three = tables_ctx((8, 16, 16))
+    assert three.band_sizes() == [len(w) for w in O.band_partition(8, 16, 16, O.BandConfig())]
+    assert len(three.mid2_blocks()[1]) == 0
+    with pytest.raises(B.FreqAttnError):
+        tables_ctx((8, 16, 16), mid2_num=1, mid2_den=4)      # third edge below the mid edge
+    with pytest.raises(B.FreqAttnError):
+        tables_ctx((8, 16, 16), mid2_num=5, mid2_den=4)      # third edge beyond the grid
