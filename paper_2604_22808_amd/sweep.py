@@ -1,11 +1,12 @@
 """Speed sweep over the ablation dimensions the paper lists (its section on ablation dimensions): transform choice,
-low-band compression ratio, mid-band sparse degree, high-band window, number of summary tokens.  Quality columns stay
+low-band compression ratio, mid-band sparse degree, high-band window, number of summary tokens, number of bands.  Quality columns stay
 empty - there is no trained model here - so this prints time per forward only.
 
     python -m paper_2604_22808_amd.sweep [--workload 256k] [--steps 5]
 
 One parameter is varied at a time around the workload's own configuration; the head allocation is the workload's
-(router in the loop where the workload says so).  Prints one markdown table row per configuration.
+(router in the loop where the workload says so); the band-count rows give every head one band, heads split evenly
+over the bands that exist.  Prints one markdown table row per configuration.
 """
 from __future__ import annotations
 
@@ -14,14 +15,16 @@ import dataclasses
 import time
 
 
-def time_forward(wl, band, steps, warmup=2):
+def time_forward(wl, band, steps, warmup=2, alloc=None):
     import torch
     from . import binding as B
     from . import workloads as WL
     q, k, v = time_forward.inputs
     out = time_forward.out
     ctx = B.Context(wl.batch, wl.heads, wl.head_dim, wl.grid, B.BF16, B.make_cfg(**band))
-    if wl.alloc["kind"] == "mlp":
+    if alloc is not None:
+        step = lambda: ctx.forward(q, k, v, alloc, out)
+    elif wl.alloc["kind"] == "mlp":
         w = WL.router_weights(wl.alloc["hidden"], wl.alloc["seed"])
         step = lambda: ctx.forward_routed(q, k, v, wl.alloc["t"], *w, out)
     else:
@@ -36,7 +39,7 @@ def time_forward(wl, band, steps, warmup=2):
     torch.cuda.synchronize()
     ms = 1e3 * (time.perf_counter() - t0) / steps
     rp, ci = ctx.mid_blocks()
-    n_low, n_mid, n_high = ctx.band_sizes()
+    n_mid = ctx.band_sizes()[1]
     keys_mid = len(ci) * band["mid_block"] ** 2 / max(n_mid, 1)
     del ctx
     return ms, keys_mid
@@ -63,11 +66,19 @@ def main():
     rows += [(f"mid diagonal = +-{dg}", {"mid_diag": dg}) for dg in (1, 4)]
     rows += [(f"high window w_h = {w}", {"high_window": w}) for w in (32, 64, 128, 256, 1024)]
     rows += [(f"summary tokens m = {m}", {"n_summary": m}) for m in (0, 4, 8, 16)]
+    def one_band_per_head(bits):
+        return [bits[h * len(bits) // wl.heads] for h in range(wl.heads)]
+    rows += [("L = 2: low + windowed rest, one band per head", {"mid_num": base["low_num"], "mid_den": base["low_den"], "_alloc": one_band_per_head([1, 4])}),
+             ("L = 2: low + block-sparse rest, one band per head", {"mid_num": 1, "mid_den": 1, "_alloc": one_band_per_head([1, 2])}),
+             ("L = 3, one band per head", {"_alloc": one_band_per_head([1, 2, 4])}),
+             ("L = 4: second block-sparse band up to 3/4 of every axis, one band per head", {"mid2_num": 3, "mid2_den": 4, "_alloc": one_band_per_head([1, 2, 8, 4])})]
     print(f"| configuration ({wl.name}: {wl.n_tokens} tokens, {wl.heads} heads, head_dim {wl.head_dim}) | mid keys per query | ms per forward | tokens/s |")
     print("|---|---|---|---|")
     for name, change in rows:
+        change = dict(change)
+        alloc = change.pop("_alloc", None)
         band = dict(base, **change)
-        ms, keys_mid = time_forward(wl, band, args.steps)
+        ms, keys_mid = time_forward(wl, band, args.steps, alloc=alloc)
         print(f"| {name} | {keys_mid:.0f} | {ms:.3f} | {wl.batch * wl.n_tokens / (ms * 1e-3):.3e} |", flush=True)
 
 

@@ -230,6 +230,9 @@ def test_ablation_speed_sweep_helper():
     ms1, keys1 = sweep.time_forward(wl, dict(wl.band, mid_stride=4, high_window=64), steps=2, warmup=1)
     assert ms0 > 0 and ms1 > 0 and keys1 > keys0 > 0
     assert torch.isfinite(sweep.time_forward.out.float()).all()
+    ms4, _ = sweep.time_forward(wl, dict(wl.band, mid2_num=3, mid2_den=4), steps=2, warmup=1,
+                                alloc=[1, 1, 2, 2, 8, 8, 4, 4])     # the band-count rows: a four-band context, given allocation
+    assert ms4 > 0 and torch.isfinite(sweep.time_forward.out.float()).all()
 
 
 @pytest.mark.parametrize("name,heads,alloc", [("16k", 8, (1, 1, 2, 2, 2, 4, 4, 7)), ("64k", 6, (1, 2, 4, 3, 0, 6))])
