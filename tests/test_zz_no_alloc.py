@@ -76,3 +76,18 @@ def test_forward_static_refuses_shapes_beyond_the_array():
     ref.forward(x, x, x.clone(), (1, 4), b)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+def test_forward_static_on_a_four_band_context():
+    """A context with a second block-sparse band (four bands) through the static entry point: its second block list and
+    the wider summary layout are carved out of the array too."""
+    import torch
+    band = dict(WL.WORKLOADS["16k"].band)
+    band.update(mid_block=64, mid_stride=3, high_window=100, n_summary=6, mid2_num=3, mid2_den=4)
+    alloc = (8, 9, 15, 6)
+    ctx, (q, k, v), want, path = _case((16, 16, 32), 4, 64, B.BF16, band, alloc, 33)
+    assert path == B.PATH_MFMA and len(ctx.band_sizes()) == 4
+    got = torch.full_like(q, float("nan"))
+    ctx.forward_static(q, k, v, alloc, got)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
