@@ -456,6 +456,21 @@ def test_four_band_layout_on_both_paths():
                     assert rl <= 3e-3, (mask, l, rl)
     with pytest.raises(B.FreqAttnError):
         U.run_forward(ctx, q, k, v, "bf16", (16,) + alloc[1:])     # a fifth band does not exist
+    import torch
+    qd, kd, vd = (U.to_device(x, "bf16") for x in (q, k, v))
+    w = WL.router_weights(64, 1)
+    for call in (lambda: ctx.forward_routed(qd, kd, vd, 0.5, *w, torch.empty_like(qd)),
+                 lambda: ctx.route_mlp(qd, kd, vd, 0.5, *w)):
+        with pytest.raises(B.FreqAttnError) as e:
+            call()
+        assert e.value.status == B.EUNSUPPORTED
+    dm = len(alloc) * wl.head_dim
+    x = torch.zeros((1, wl.n_tokens, 64), dtype=torch.bfloat16, device="cuda")
+    wqkv = torch.zeros((64, dm), dtype=torch.bfloat16, device="cuda")
+    wo = torch.zeros((dm, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.FreqAttnError) as e:
+        ctx.forward_projected(x, wqkv, wqkv, wqkv, wo, alloc, torch.empty_like(x))
+    assert e.value.status == B.EUNSUPPORTED
     tiny = WL.WORKLOADS["tiny_f32"]
     q, k, v = (WL.round_to_io(x, "f32") for x in WL.qkv_numpy(tiny))
     bandt = dict(tiny.band, mid2_num=3, mid2_den=4)
