@@ -482,3 +482,31 @@ def test_four_band_layout_on_both_paths():
         mx, rl = U.errors(got, want)
         print(f"four bands fp32 {allocs}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
         assert mx <= 1e-5 and rl <= 1e-5
+
+
+@pytest.mark.parametrize("edges,m", [(dict(mid2_num=3, mid2_den=4), 8), (dict(mid2_num=1, mid2_den=2), 8),
+                                      (dict(mid2_num=1, mid2_den=1), 8), (dict(mid2_num=2, mid2_den=3), 0),
+                                      (dict(mid2_num=3, mid2_den=4), 100)])
+def test_four_band_edge_cases_on_a_ragged_grid(edges, m):
+    """Four-band contexts where the layout degenerates - the second mid band empty (third edge = mid edge), the high band
+    empty (third edge = 1) - without exchange (m = 0), with an edge that cuts the axes at non-integers (2/3 of 16, 32,
+    48) and with m = 100 summary tokens per band (300 summary keys per query: five key tiles in the exchange, chunks of
+    unequal length); head_dim 128 with 128-token
+    blocks (128 query rows per work item) on a grid whose bands are no multiples of the tiles."""
+    grid, d = (16, 32, 48), 128
+    band = dict(low_num=1, low_den=4, mid_num=1, mid_den=2, low_compress=4, mid_block=128, mid_diag=1, mid_stride=4,
+                mid_block0=1, high_window=128, n_summary=m, **edges)
+    alloc = (8, 15, 12, 3, 5)
+    rng = np.random.default_rng(77)
+    N = int(np.prod(grid))
+    q, k, v = (WL.round_to_io(0.5 * rng.standard_normal((1, len(alloc), N, d)), "bf16") for _ in range(3))
+    ctx = B.Context(1, len(alloc), d, grid, B.BF16, B.make_cfg(**band))
+    cfg = O.BandConfig(**band)
+    sizes = [len(ix) for ix in O.band_partition(*grid, cfg)]
+    assert ctx.get_path() == B.PATH_MFMA and ctx.band_sizes() == sizes
+    got = U.run_forward(ctx, q, k, v, "bf16", alloc)
+    want = O.forward(q, k, v, grid, cfg, alloc)
+    for s, mask in enumerate(alloc):
+        mx, rl = U.errors(got[0, s], want[0, s])
+        print(f"four bands {edges} m={m} sizes {sizes} mask {mask}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+        assert mx <= 2e-2 and rl <= 5e-3, (edges, m, mask, mx, rl)
