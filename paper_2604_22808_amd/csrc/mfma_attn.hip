@@ -228,8 +228,22 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
         n_outer = (nkp + KT - 1) / KT;
       }
       const int n_tt = n_outer * sub_n;
+      // The key blocks of a block-sparse item are read once, 64 at a time, one per lane (a wave-wide load in the tile
+      // loop would put a trip through the memory hierarchy in front of every tile's copies); key0_of picks its entry
+      // out of the register.
+      const int32_t* cidx = (band == MID2 ? p.mid2_col_idx : p.mid_col_idx) + e0;
+      int colv = 0, cbase = 0;
+      auto load_cols = [&](int base) {
+        cbase = base;
+        colv = (kind_p == 1 && base + lane < n_outer) ? cidx[base + lane] : 0;
+      };
+      load_cols(0);
       auto key0_of = [&](int idx) -> int {
-        if (kind_p == 1) return ((band == MID2 ? p.mid2_col_idx : p.mid_col_idx)[e0 + idx / sub_n] * sub_n + idx % sub_n) * KT;
+        if (kind_p == 1) {
+          const int blk = idx / sub_n;
+          if (blk < cbase || blk >= cbase + 64) load_cols(blk & ~63);   // (uniform; only items with more than 64 key blocks)
+          return (__builtin_amdgcn_readlane(colv, blk - cbase) * sub_n + (idx - blk * sub_n)) * KT;
+        }
         return (t_lo + idx) * KT;
       };
       // Exchange items of one (slice, band) all see the same <= 2 tiles of summary tokens: a workgroup that has them in

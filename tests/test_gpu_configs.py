@@ -510,3 +510,22 @@ def test_four_band_edge_cases_on_a_ragged_grid(edges, m):
         mx, rl = U.errors(got[0, s], want[0, s])
         print(f"four bands {edges} m={m} sizes {sizes} mask {mask}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
         assert mx <= 2e-2 and rl <= 5e-3, (edges, m, mask, mx, rl)
+
+
+def test_block_sparse_items_with_more_than_64_key_blocks():
+    """The matrix-core kernel holds a work item's key-block list in one register, 64 entries at a time: a pattern
+    dense enough to give every query block about 130 key blocks (the block-sparse band over 63/64 of a 16K grid, every
+    second block strided in) walks through several refills."""
+    wl = WL.WORKLOADS["16k"]
+    band = dict(wl.band, mid_num=1, mid_den=1, mid_stride=2)
+    q, k, v = (WL.round_to_io(x, "bf16") for x in WL.qkv_numpy(wl, heads=[1, 6]))
+    ctx = B.Context(1, 2, wl.head_dim, wl.grid, B.BF16, B.make_cfg(**band))
+    rp, ci = ctx.mid_blocks()
+    assert ctx.get_path() == B.PATH_MFMA and int(np.diff(rp).max()) > 2 * 64
+    alloc = (2, 3)
+    got = U.run_forward(ctx, q, k, v, "bf16", alloc)
+    want = O.forward(q, k, v, wl.grid, O.BandConfig(**band), alloc)
+    for s in range(2):
+        mx, rl = U.errors(got[0, s], want[0, s])
+        print(f"dense block pattern mask {alloc[s]}: max-abs {mx:.3e} rel-L2 {rl:.3e}", flush=True)
+        assert mx <= 2e-2 and rl <= 5e-3
