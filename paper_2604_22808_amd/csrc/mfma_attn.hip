@@ -146,6 +146,12 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
 #pragma unroll
       for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
+    // C operand that starts a score accumulation: minus the lane's reference maximum in every register, so that the
+    // matrix core delivers the scores already shifted (0 while the row has seen no valid key): in the common case (no new
+    // reference) they go into exp2 without a subtraction, and no accumulator is initialised per tile
+    float16v Minit;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) Minit[r] = 0.f;
 
     // Staging: this wave's share of a tile is RPI rows per instruction, NIW instructions per tensor; rows past the
     // end of the key range are clamped to its last row (their scores are masked, and V rows of real data times zero are zero)
@@ -208,6 +214,8 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
 #pragma unroll
           for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
         m_run = -INFINITY; l_run = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) Minit[r] = 0.f;
       }
 
       // tile iteration space of the phase
@@ -302,14 +310,7 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
         }
 
         // ---- S^T = K Q^T for the two 32-key halves of the tile
-        // The accumulators start at minus the lane's reference maximum, so the matrix core delivers the scores already
-        // shifted: in the common case (no new maximum) they go into exp2 without a subtraction.
-        float16v S[2];
-        const float s_init = (m_run == -INFINITY) ? 0.f : -m_run;
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) S[t2][r] = s_init;
+        float16v S[2];   // (each starts from Minit)
         // K operands are requested PF steps ahead of the MFMA that consumes them, so LDS latency overlaps the matrix core
         constexpr int PF = 8;
         {
@@ -326,7 +327,7 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
             const half8 A = Abuf[i % PF];
             if (i + PF < NS)
               Abuf[i % PF] = *kptr(i + PF);
-            S[t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Qr[ks], S[t2], 0, 0, 0);
+            S[t2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Qr[ks], ks == 0 ? Minit : S[t2], 0, 0, 0);
             if (dma_next) {
 #pragma unroll
               for (int pi = i * (2 * NIW) / NS; pi < (i + 1) * (2 * NIW) / NS; ++pi) dma_piece(Kn, Vn, nkn, key0_next, buf ^ 1, pi);
@@ -411,6 +412,12 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
           const float alpha = (bump && !fresh) ? __builtin_amdgcn_exp2f(-delta) : 1.f;
           if (bump) m_run = fresh ? delta : m_run + delta;
           l_run *= alpha;
+          {
+            const float mi = (m_run == -INFINITY) ? 0.f : -m_run;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Minit[r] = mi;
+            asm volatile("" : "+v"(Minit));   // (sixteen registers on purpose, not one value spread again per tile)
+          }
 #pragma unroll
           for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
