@@ -312,6 +312,11 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
         // ---- S^T = K Q^T for the two 32-key halves of the tile
         float16v S[2];   // (each starts from Minit)
         // K operands are requested PF steps ahead of the MFMA that consumes them, so LDS latency overlaps the matrix core
+        // The wave takes the higher issue priority for the score stage (its operand reads, its MFMAs and the next tile's
+        // copies spread between them) and gives it back for the softmax: with two waves per SIMD the one that starts a
+        // tile gets its copies and reads under way while the other is in its vector work (measured: block-sparse branch
+        // 6 % faster, window branch 2 %; priority in the other stages instead, or in all MFMA stages, gains less).
+        __builtin_amdgcn_s_setprio(1);
         constexpr int PF = 8;
         {
           constexpr int NS = 2 * DK;
@@ -342,6 +347,7 @@ __global__ void __launch_bounds__(64 * NW, (D == 64 || NW == 4) ? 2 : 1) k_attn(
           }
           __builtin_amdgcn_sched_group_barrier(0x008, PF, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
         // ---- mask, running softmax (lane = query row; registers = keys).  m_run is a reference maximum, not the exact
         // one: it moves only when a score exceeds it by more than 2^kBump (or when the row sees its first valid key), so
         // probabilities stay within [0, 2^kBump] - exact in the ratio P / sum(P) - and the rescale is rare.
