@@ -102,8 +102,8 @@ typedef enum {
  * the mid band empty, i.e. two bands (compressed dense low band, windowed high band); mid edge == 1 leaves the high
  * band empty (low + block-sparse rest); mid2_num > 0 adds a second block-sparse band between the mid band and the high
  * band (four bands: band indices and mask bits 0 low, 1 mid, 2 high, 3 second mid band).  Four-band contexts take
- * freqattn_forward, freqattn_forward_static and the introspection calls; the router entry points (section 3.5 is
- * written for three bands) and freqattn_forward_projected return FREQATTN_EUNSUPPORTED on them.
+ * freqattn_forward, freqattn_forward_static, freqattn_forward_projected and the introspection calls; the router entry
+ * points (section 3.5 is written for three bands) return FREQATTN_EUNSUPPORTED on them.
  * Returns EINVAL for non-positive dimensions, edges not satisfying 0 < low <= mid (<= mid2) <= 1, low_compress < 1,
  * mid_block < 1, mid_stride < 1, mid_diag < 0, high_window < 0, n_summary < 0, unknown dtype or NULL pointers;
  * EUNSUPPORTED if FREQATTN_PATH_MFMA is forced on a shape it cannot run; ENOMEM / EHIP on allocation failure. */

@@ -1259,19 +1259,19 @@ static freqattn_status ensure_projection_buffers(freqattn_ctx* c, int d_model, h
   A(dev_alloc(*c, &c->proj_ones, (size_t)B));
   const size_t mrows = (size_t)std::max(c->cfg.n_summary, 1);
   A(dev_alloc(*c, &c->projWvN, (size_t)hd * d_model));
-  A(dev_alloc(*c, &c->projM, (size_t)3 * d_model * d_model));
-  A(dev_alloc(*c, &c->projPool, (size_t)B * 3 * mrows * d_model));
-  A(dev_alloc(*c, &c->projCtmp, (size_t)c->slices * 3 * mrows * c->d));
+  A(dev_alloc(*c, &c->projM, (size_t)c->nb * d_model * d_model));
+  A(dev_alloc(*c, &c->projPool, (size_t)B * c->nb * mrows * d_model));
+  A(dev_alloc(*c, &c->projCtmp, (size_t)c->slices * c->nb * mrows * c->d));
   // problems: Q~, K~, V~ per slice; output projection per (batch entry, band); pass-through weights per band; pooled rows
   // per slice.  Segments: one per projection; heads + 1 per output projection; heads per pass-through weight.
-  c->gemm_cap_prob = 3 * B * heads + 3 * B + 3 + B * heads;
-  c->gemm_cap_seg = 3 * B * heads + 3 * B * (heads + 1) + 3 * heads + B * heads;
+  c->gemm_cap_prob = 3 * B * heads + c->nb * B + c->nb + B * heads;
+  c->gemm_cap_seg = 3 * B * heads + c->nb * B * (heads + 1) + c->nb * heads + B * heads;
   A(dev_alloc(*c, &c->d_gemm_prob, (size_t)c->gemm_cap_prob));
   A(dev_alloc(*c, &c->d_gemm_seg, (size_t)c->gemm_cap_seg));
   if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_gemm_prob, (size_t)c->gemm_cap_prob * sizeof(GemmProblem), hipHostMallocDefault);
   if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_gemm_seg, (size_t)c->gemm_cap_seg * sizeof(GemmSeg), hipHostMallocDefault);
   if (e == hipSuccess) {
-    std::vector<int32_t> ones((size_t)B, 7);
+    std::vector<int32_t> ones((size_t)B, (1 << NBMAX) - 1);
     e = hipMemcpy(c->proj_ones, ones.data(), (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice);
   }
   if (e != hipSuccess) {
@@ -1299,7 +1299,7 @@ static int build_gemm_tables(Ctx& c, bool fold) {
   auto hull = [&](int h, int64_t& r0, int64_t& r1) -> bool {
     const int mask = c.h_alloc[(size_t)h];
     int lo = -1, hi = -1;
-    for (int l = 0; l < 3; ++l)
+    for (int l = 0; l < c.nb; ++l)   // (bands lie in the order of their indices: the hull is one run of rows)
       if (((mask >> l) & 1) && c.band_n[l] > 0) { if (lo < 0) lo = l; hi = l; }
     if (lo < 0) return false;
     r0 = c.band_off[lo]; r1 = c.band_off[hi] + c.band_n[hi];
@@ -1335,9 +1335,9 @@ static int build_gemm_tables(Ctx& c, bool fold) {
       c.gemm_groups.push_back({first, heads, (int)c.N, d, 0});
     }
   }
-  bool passing[3] = {false, false, false};
+  bool passing[NBMAX] = {false, false, false, false};
   if (fold)
-    for (int l = 0; l < 3; ++l) {
+    for (int l = 0; l < c.nb; ++l) {
       if (c.band_n[l] <= 0) continue;
       const int seg0 = ns;
       for (int h = 0; h < heads; ++h)
@@ -1355,14 +1355,14 @@ static int build_gemm_tables(Ctx& c, bool fold) {
       const int first = np;
       for (int h = 0; h < heads; ++h) {
         const int64_t slice = (int64_t)b * heads + h;
-        c.h_gemm_seg[ns] = GemmSeg{c.projPool + (size_t)b * 3 * mrows * dm, c.projWv + (size_t)h * d * dm, dm, dm, dm, 0};
-        c.h_gemm_prob[np++] = GemmProblem{c.projCtmp + (size_t)slice * 3 * mrows * d, d, 3 * mrows, d, ns++, 1, 0};
+        c.h_gemm_seg[ns] = GemmSeg{c.projPool + (size_t)b * c.nb * mrows * dm, c.projWv + (size_t)h * d * dm, dm, dm, dm, 0};
+        c.h_gemm_prob[np++] = GemmProblem{c.projCtmp + (size_t)slice * c.nb * mrows * d, d, c.nb * mrows, d, ns++, 1, 0};
       }
-      c.gemm_groups.push_back({first, heads, 3 * mrows, d, 3});
+      c.gemm_groups.push_back({first, heads, c.nb * mrows, d, 3});
     }
   }
   for (int b = 0; b < B; ++b)
-    for (int l = 0; l < 3; ++l) {
+    for (int l = 0; l < c.nb; ++l) {
       if (c.band_n[l] <= 0) continue;
       const int seg0 = ns;
       for (int h = 0; h < heads; ++h) {
@@ -1391,7 +1391,6 @@ extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const voi
       return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: NULL argument");
     if (c->path != FREQATTN_PATH_MFMA)
       return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_projected: needs a context on the matrix-core path");
-    if (c->nb != 3) return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_projected: three-band contexts only");
     if (!same_cfg(*band_cfg, c->cfg))
       return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: band_cfg differs from the one given to freqattn_create");
     if (out == x) return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: out aliases x");
@@ -1400,7 +1399,8 @@ extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const voi
       return fail(c, FREQATTN_EUNSUPPORTED, "freqattn_forward_projected: d_model must be a multiple of 64 and at most "
                                             "heads * head_dim (the transform passes share the context's scratch)");
     for (int h = 0; h < heads; ++h)
-      if (head_alloc[h] < 0 || head_alloc[h] > 7) return fail(c, FREQATTN_EINVAL, "freqattn_forward_projected: head_alloc entry outside 0..7");
+      if (head_alloc[h] < 0 || head_alloc[h] >= (1 << c->nb))
+        return fail(c, FREQATTN_EINVAL, c->nb > 3 ? "freqattn_forward_projected: head_alloc entry outside 0..15" : "freqattn_forward_projected: head_alloc entry outside 0..7");
     hipStream_t st = (hipStream_t)stream;
     const float scale = band_cfg->softmax_scale > 0.f ? band_cfg->softmax_scale : 1.0f / std::sqrt((float)c->d);
     freqattn_status fs = ensure_lists(c, head_alloc, st);
@@ -1451,11 +1451,11 @@ extern "C" freqattn_status freqattn_forward_projected(freqattn_ctx* c, const voi
     if (fold && c->cfg.n_summary > 0) {
       // summary tokens of the bands a head passes through: chunk means of X~, times every head's W_V, into the slots
       const int mrows = c->cfg.n_summary;
-      HIP_TRY(c, launch_pool_wide(c->projX, c->projPool, B, c->N, d_model, c->band_off, c->band_n, c->m_eff, mrows, st));
+      HIP_TRY(c, launch_pool_wide(c->projX, c->projPool, B, c->N, d_model, c->nb, c->band_off, c->band_n, c->m_eff, mrows, st));
       fs = products(3);
       if (fs != FREQATTN_OK) return fs;
-      HIP_TRY(c, launch_place_summaries(c->projCtmp, c->Cbuf, c->d_lists + c->off_masks, c->slices, c->d, c->m_eff, mrows,
-                                        2 * std::max(c->cfg.n_summary, 1), st));
+      HIP_TRY(c, launch_place_summaries(c->projCtmp, c->Cbuf, c->d_lists + c->off_masks, c->slices, c->d, c->nb, c->m_eff, mrows,
+                                        (c->nb - 1) * std::max(c->cfg.n_summary, 1), st));
       tm.done("summaries_passed_bands");
     }
     c->v_full.assign((size_t)c->slices, 1);

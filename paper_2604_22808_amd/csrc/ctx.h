@@ -223,11 +223,11 @@ hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t
 // High-band summary tokens of the slices in `sel` (bit set, nsel of them) from the untransformed bf16 V.
 hipError_t launch_vsum(const void* V, const void* Wsum, float* part, void* C, const uint64_t sel[4], int nsel, int64_t N,
                        int d, int nsplit, int64_t n_high, const int m_eff[NBMAX], int m2rows, hipStream_t st);   // (three-band contexts only)
-// Projected forward: P[batch][3][mrows][dm] = per-chunk means of the band rows of X~ [batch][N][dm] (fp16), and the
-// placement of the projected pooled rows T[slices][3][mrows][d] into the C slots of the bands a slice passes through.
-hipError_t launch_pool_wide(const void* X, void* P, int batch, int64_t N, int dm, const int64_t band_off[3],
-                            const int64_t band_n[3], const int m_eff[3], int mrows, hipStream_t st);
-hipError_t launch_place_summaries(const void* T, void* C, const int32_t* masks, int slices, int d, const int m_eff[3],
+// Projected forward: P[batch][nb][mrows][dm] = per-chunk means of the band rows of X~ [batch][N][dm] (fp16), and the
+// placement of the projected pooled rows T[slices][nb][mrows][d] into the C slots of the bands a slice passes through.
+hipError_t launch_pool_wide(const void* X, void* P, int batch, int64_t N, int dm, int nb, const int64_t band_off[NBMAX],
+                            const int64_t band_n[NBMAX], const int m_eff[NBMAX], int mrows, hipStream_t st);
+hipError_t launch_place_summaries(const void* T, void* C, const int32_t* masks, int slices, int d, int nb, const int m_eff[NBMAX],
                                   int mrows, int m2rows, hipStream_t st);
 // Router statistics: per band and channel, sum of squares over slices and the three spectral buffers.
 hipError_t launch_band_energy(const void* sq, const void* sk, const void* sv, float* stats /*[3][d], zeroed inside*/,

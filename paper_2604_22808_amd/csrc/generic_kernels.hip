@@ -387,17 +387,16 @@ hipError_t launch_summaries(const void* Y, const void* V, void* C, const int32_t
 // of a band it passes through are P times its W_V.  Workgroup = (chunk, band, batch entry) x a block of 256 columns:
 // 32 threads across the columns (8 each), 8 row phases, eight rows in flight per thread; fixed summation order.
 __global__ void __launch_bounds__(256) k_pool_wide(const half_t* __restrict__ X, half_t* __restrict__ P, int64_t N, int dm,
-                                                   int64_t off0, int64_t off1, int64_t off2, int64_t n0, int64_t n1, int64_t n2,
-                                                   int m0, int m1, int m2e, int mrows) {
+                                                   BandGeom g, int mrows) {
   typedef _Float16 h8 __attribute__((ext_vector_type(8)));
   __shared__ float part[8][32][8];
-  const int u = blockIdx.x, band = blockIdx.y % 3, b = blockIdx.y / 3, cb = blockIdx.z;
-  const int64_t off = band == 0 ? off0 : band == 1 ? off1 : off2;
-  const int64_t n = band == 0 ? n0 : band == 1 ? n1 : n2;
-  const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
+  const int u = blockIdx.x, band = blockIdx.y % g.nb, b = blockIdx.y / g.nb, cb = blockIdx.z;
+  const int64_t off = g.off[band];
+  const int64_t n = g.n[band];
+  const int me = g.m[band];
   const int tid = threadIdx.x, cg = tid & 31, ph = tid >> 5;
   const int col = cb * 256 + cg * 8;
-  half_t* dst = P + (((int64_t)b * 3 + band) * mrows + u) * dm + col;
+  half_t* dst = P + (((int64_t)b * g.nb + band) * mrows + u) * dm + col;
   const bool live = col < dm;   // (dm is a multiple of 8: a thread's 8 columns are all inside or all outside)
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   int64_t c0 = 0, c1 = 0;
@@ -436,40 +435,46 @@ __global__ void __launch_bounds__(256) k_pool_wide(const half_t* __restrict__ X,
     *(h8*)dst = mean;
   }
 }
-hipError_t launch_pool_wide(const void* X, void* P, int batch, int64_t N, int dm, const int64_t band_off[3],
-                            const int64_t band_n[3], const int m_eff[3], int mrows, hipStream_t st) {
+static BandGeom band_geom(int nb, const int64_t band_off[NBMAX], const int64_t band_n[NBMAX], const int m_eff[NBMAX]) {
+  BandGeom g;
+  g.nb = nb;
+  for (int l = 0; l < NBMAX; ++l) {
+    g.off[l] = band_off[l]; g.n[l] = l < nb ? band_n[l] : 0; g.m[l] = l < nb ? m_eff[l] : 0;
+  }
+  return g;
+}
+hipError_t launch_pool_wide(const void* X, void* P, int batch, int64_t N, int dm, int nb, const int64_t band_off[NBMAX],
+                            const int64_t band_n[NBMAX], const int m_eff[NBMAX], int mrows, hipStream_t st) {
   if (mrows <= 0 || batch <= 0) return hipSuccess;
   if (dm % 8 != 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(k_pool_wide, dim3((unsigned)mrows, (unsigned)(3 * batch), (unsigned)((dm + 255) / 256)), dim3(256), 0, st,
-                     (const half_t*)X, (half_t*)P, N, dm, band_off[0], band_off[1], band_off[2], band_n[0], band_n[1], band_n[2],
-                     m_eff[0], m_eff[1], m_eff[2], mrows);
+  hipLaunchKernelGGL(k_pool_wide, dim3((unsigned)mrows, (unsigned)(nb * batch), (unsigned)((dm + 255) / 256)), dim3(256), 0, st,
+                     (const half_t*)X, (half_t*)P, N, dm, band_geom(nb, band_off, band_n, m_eff), mrows);
   return hipGetLastError();
 }
 
 // T[slice][band][u][:] (the projected pooled rows, mrows per band) -> the slots of C where the other bands of the slice
 // look for band `band`'s summary tokens, for every band the slice passes through while it runs another one.
 __global__ void __launch_bounds__(256) k_place_summaries(const half_t* __restrict__ T, half_t* __restrict__ C,
-                                                         const int32_t* __restrict__ masks, int d, int m0, int m1, int m2e,
+                                                         const int32_t* __restrict__ masks, int d, BandGeom g,
                                                          int mrows, int m2rows) {
   const int u = blockIdx.x, band = blockIdx.y, slice = blockIdx.z;
-  const int me = band == 0 ? m0 : band == 1 ? m1 : m2e;
-  const int mask = masks[slice] & 7;
+  const int me = g.m[band];
+  const int mask = masks[slice] & ((1 << g.nb) - 1);
   if (u >= me || ((mask >> band) & 1) || (mask & ~(1 << band)) == 0) return;
-  const half_t* src = T + (((int64_t)slice * 3 + band) * mrows + u) * d;
-  for (int b = 0; b < 3; ++b) {
+  const half_t* src = T + (((int64_t)slice * g.nb + band) * mrows + u) * d;
+  for (int b = 0; b < g.nb; ++b) {
     if (b == band) continue;
-    int pos = u;
-    for (int o = 0; o < band; ++o)
-      if (o != b) pos += (o == 0 ? m0 : o == 1 ? m1 : m2e);
-    half_t* dst = C + (((int64_t)slice * 3 + b) * m2rows + pos) * d;
+    const int pos = summary_pos(g, band, b, u);
+    half_t* dst = C + (((int64_t)slice * g.nb + b) * m2rows + pos) * d;
     for (int ch = threadIdx.x; ch < d; ch += 256) dst[ch] = src[ch];
   }
 }
-hipError_t launch_place_summaries(const void* T, void* C, const int32_t* masks, int slices, int d, const int m_eff[3],
+hipError_t launch_place_summaries(const void* T, void* C, const int32_t* masks, int slices, int d, int nb, const int m_eff[NBMAX],
                                   int mrows, int m2rows, hipStream_t st) {
   if (mrows <= 0 || slices <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_place_summaries, dim3((unsigned)mrows, 3, (unsigned)slices), dim3(256), 0, st, (const half_t*)T,
-                     (half_t*)C, masks, d, m_eff[0], m_eff[1], m_eff[2], mrows, m2rows);
+  const int64_t none[NBMAX] = {0, 0, 0, 0};
+  hipLaunchKernelGGL(k_place_summaries, dim3((unsigned)mrows, (unsigned)nb, (unsigned)slices), dim3(256), 0, st, (const half_t*)T,
+                     (half_t*)C, masks, d, band_geom(nb, none, none, m_eff), mrows, m2rows);
   return hipGetLastError();
 }
 

@@ -235,8 +235,9 @@ def test_ablation_speed_sweep_helper():
     assert ms4 > 0 and torch.isfinite(sweep.time_forward.out.float()).all()
 
 
-@pytest.mark.parametrize("name,heads,alloc", [("16k", 8, (1, 1, 2, 2, 2, 4, 4, 7)), ("64k", 6, (1, 2, 4, 3, 0, 6))])
-def test_projected_forward_matches_oracle(name, heads, alloc, monkeypatch):
+@pytest.mark.parametrize("name,heads,alloc,extra", [("16k", 8, (1, 1, 2, 2, 2, 4, 4, 7), {}), ("64k", 6, (1, 2, 4, 3, 0, 6), {}),
+                                                   ("16k", 8, (8, 9, 15, 6, 12, 10, 0, 1), dict(mid2_num=3, mid2_den=4))])
+def test_projected_forward_matches_oracle(name, heads, alloc, extra, monkeypatch):
     """Projections folded around the path (sections 3.1, 3.7): X transformed once, Q~/K~/V~ projected from spectral rows
     of the bands a head runs (what it passes through goes from X~ straight into the output projection, its summary tokens
     from pooled rows of X~), W_O applied before one inverse transform of model width - against the oracle's
@@ -250,7 +251,7 @@ def test_projected_forward_matches_oracle(name, heads, alloc, monkeypatch):
     x = WL.round_to_io(xs, "bf16")
     wq, wk, wv = (WL.round_to_io(rng.standard_normal((dm, dm)) / np.sqrt(dm), "bf16") for _ in range(3))
     wo = WL.round_to_io(rng.standard_normal((dm, dm)) / np.sqrt(dm), "bf16")
-    band = dict(wl.band)
+    band = dict(wl.band, **extra)      # (the third case: a four-band context)
     ctx = B.Context(1, heads, d, wl.grid, B.BF16, B.make_cfg(**band))
     dev = lambda a: U.to_device(a, "bf16")
     dx, dwq, dwk, dwv, dwo = dev(x), dev(wq), dev(wk), dev(wv), dev(wo)
@@ -428,7 +429,7 @@ def test_four_band_layout_on_both_paths():
     third edge at 3/4 of every axis.  Matrix-core path at 16K tokens (bands of 256 / 1,792 / 9,472 / 4,864 coefficients),
     one head per mask: each band alone, pairs across the new band, all four, and a head that passes everything through;
     band outputs of the new band are compared before the inverse transform as well.  Then the generic fp32 path on the
-    tiny grid.  The routed and projected entry points refuse such a context."""
+    tiny grid.  The routed entry points refuse such a context (section 3.5 scores three bands)."""
     wl = WL.WORKLOADS["16k"]
     alloc = (8, 9, 15, 6, 12, 10, 0, 1, 4)
     heads = list(range(len(alloc)))
@@ -464,13 +465,6 @@ def test_four_band_layout_on_both_paths():
         with pytest.raises(B.FreqAttnError) as e:
             call()
         assert e.value.status == B.EUNSUPPORTED
-    dm = len(alloc) * wl.head_dim
-    x = torch.zeros((1, wl.n_tokens, 64), dtype=torch.bfloat16, device="cuda")
-    wqkv = torch.zeros((64, dm), dtype=torch.bfloat16, device="cuda")
-    wo = torch.zeros((dm, 64), dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(B.FreqAttnError) as e:
-        ctx.forward_projected(x, wqkv, wqkv, wqkv, wo, alloc, torch.empty_like(x))
-    assert e.value.status == B.EUNSUPPORTED
     tiny = WL.WORKLOADS["tiny_f32"]
     q, k, v = (WL.round_to_io(x, "f32") for x in WL.qkv_numpy(tiny))
     bandt = dict(tiny.band, mid2_num=3, mid2_den=4)
